@@ -1,0 +1,203 @@
+"""CPU oracle for the AWQ W4A16 linear path -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy/ctypes front end over ``awq_oracle.c`` (plain C, built with gcc).
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package; the product never does, and this package
+never imports the product.
+
+Every function follows the passage of AWQ (arXiv 2306.00978) named in its
+docstring; the arithmetic itself lives in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "awq_oracle.c")
+_LIB = os.path.join(_HERE, "libawq_oracle.so")
+GROUP = 128
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc. No FMA contraction, no fast-math."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+               "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.awq_oracle_f16_to_f32.restype = ctypes.c_float
+        lib.awq_oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
+        lib.awq_oracle_f32_to_f16.restype = ctypes.c_uint16
+        lib.awq_oracle_f32_to_f16.argtypes = [ctypes.c_float]
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i64(v):
+    return ctypes.c_int64(int(v))
+
+
+def _chk(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} rejected its arguments (rc={rc})")
+
+
+def _as_f16_bits(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        return a.view(np.uint16)
+    if a.dtype == np.uint16:
+        return a
+    raise TypeError("expected float16 (or its uint16 bit pattern)")
+
+
+def f16_to_f32_scalar(bits: int) -> float:
+    return float(_load().awq_oracle_f16_to_f32(int(bits)))
+
+
+def f32_to_f16_scalar(v: float) -> int:
+    return int(_load().awq_oracle_f32_to_f16(float(np.float32(v))))
+
+
+def act_scale(X, alpha: float = 0.5, floor: float = 1e-4) -> np.ndarray:
+    """Sec. 3.2, Eq. 5: s = s_X^alpha, s_X = per-input-channel mean |X| (fp64)."""
+    Xb = _as_f16_bits(X)
+    T, K = Xb.shape
+    s = np.empty(K, dtype=np.float64)
+    _chk(_load().awq_oracle_act_scale(_p(Xb), _i64(T), _i64(K), ctypes.c_double(alpha),
+                                      ctypes.c_double(floor), _p(s)), "act_scale")
+    return s
+
+
+def apply_inv_scale(x, s) -> np.ndarray:
+    """Sec. 3.2, Eq. 4: the diag(s)^-1 X factor; x' = fp16(fp32(x) / s)."""
+    xb = _as_f16_bits(x)
+    M, K = xb.shape
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    assert s.shape == (K,)
+    out = np.empty((M, K), dtype=np.uint16)
+    _chk(_load().awq_oracle_apply_inv_scale(_p(xb), _p(s), _i64(M), _i64(K), _p(out)),
+         "apply_inv_scale")
+    return out.view(np.float16)
+
+
+def quantize(W, s=None, group: int = GROUP):
+    """Sec. 3.2, Eq. 1-2: Q(w*s) per group of 128 input channels (asymmetric
+    16-level min/max form).  Returns codes[N,K] u8, scales[N,G] f16, zeros[N,G] u8."""
+    Wb = _as_f16_bits(W)
+    N, K = Wb.shape
+    if K % group:
+        raise ValueError("K must be a multiple of the group size")
+    G = K // group
+    sp = None
+    if s is not None:
+        s = np.ascontiguousarray(s, dtype=np.float32)
+        assert s.shape == (K,)
+        sp = _p(s)
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, G), dtype=np.uint16)
+    zeros = np.empty((N, G), dtype=np.uint8)
+    _chk(_load().awq_oracle_quantize(_p(Wb), sp, _i64(N), _i64(K), ctypes.c_int(group),
+                                     _p(codes), _p(scales), _p(zeros)), "quantize")
+    return codes, scales.view(np.float16), zeros
+
+
+def packed_sizes(N: int, K: int, group: int = GROUP):
+    G = K // group
+    return N * K // 2, N * G * 2, N * G // 2
+
+
+def pack(codes, scales, zeros, group: int = GROUP):
+    """Sec. 4.2 weight packing, in the byte layout of this library (see C file)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, K = codes.shape
+    G = K // group
+    sb = _as_f16_bits(scales)
+    zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+    assert sb.shape == (N, G) and zeros.shape == (N, G)
+    qb, sbytes, zb = packed_sizes(N, K, group)
+    qweight = np.empty(qb, dtype=np.uint8)
+    scales_p = np.empty(sbytes // 2, dtype=np.uint16)
+    zeros_p = np.empty(zb, dtype=np.uint8)
+    _chk(_load().awq_oracle_pack(_p(codes), _p(sb), _p(zeros), _i64(N), _i64(K),
+                                 ctypes.c_int(group), _p(qweight), _p(scales_p), _p(zeros_p)),
+         "pack")
+    return qweight, scales_p, zeros_p
+
+
+def unpack(qweight, scales_p, zeros_p, N: int, K: int, group: int = GROUP):
+    qweight = np.ascontiguousarray(qweight, dtype=np.uint8)
+    scales_p = _as_f16_bits(scales_p).reshape(-1)
+    zeros_p = np.ascontiguousarray(zeros_p, dtype=np.uint8)
+    G = K // group
+    qb, sbytes, zb = packed_sizes(N, K, group)
+    assert qweight.size == qb and scales_p.size * 2 == sbytes and zeros_p.size == zb
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, G), dtype=np.uint16)
+    zeros = np.empty((N, G), dtype=np.uint8)
+    _chk(_load().awq_oracle_unpack(_p(qweight), _p(scales_p), _p(zeros_p), _i64(N), _i64(K),
+                                   ctypes.c_int(group), _p(codes), _p(scales), _p(zeros)),
+         "unpack")
+    return codes, scales.view(np.float16), zeros
+
+
+def dequant(codes, scales, zeros, group: int = GROUP) -> np.ndarray:
+    """Sec. 4.2 on-the-fly dequantization: Wdq = (q - zero) * scale, fp32 (exact)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, K = codes.shape
+    sb = _as_f16_bits(scales)
+    zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+    Wdq = np.empty((N, K), dtype=np.float32)
+    _chk(_load().awq_oracle_dequant(_p(codes), _p(sb), _p(zeros), _i64(N), _i64(K),
+                                    ctypes.c_int(group), _p(Wdq)), "dequant")
+    return Wdq
+
+
+def matmul(x, Wdq, acc32: bool = False) -> np.ndarray:
+    """y[m,n] = sum_k x[m,k] * Wdq[n,k]; fp64 accumulation (fp32 sequential if acc32)."""
+    xb = _as_f16_bits(x)
+    M, K = xb.shape
+    Wdq = np.ascontiguousarray(Wdq, dtype=np.float32)
+    N = Wdq.shape[0]
+    assert Wdq.shape == (N, K)
+    y = np.empty((M, N), dtype=np.float64)
+    _chk(_load().awq_oracle_matmul(_p(xb), _p(Wdq), _i64(M), _i64(N), _i64(K),
+                                   ctypes.c_int(1 if acc32 else 0), _p(y)), "matmul")
+    return y
+
+
+def norm_error(y_gpu, y_ref, x, Wdq) -> np.ndarray:
+    """Acceptance metric: |y_gpu - y_ref| / (||x_row||_2 * max|Wdq| + 1e-6), per element."""
+    yb = _as_f16_bits(y_gpu)
+    xb = _as_f16_bits(x)
+    M, K = xb.shape
+    Wdq = np.ascontiguousarray(Wdq, dtype=np.float32)
+    N = Wdq.shape[0]
+    y_ref = np.ascontiguousarray(y_ref, dtype=np.float64)
+    assert yb.shape == (M, N) and y_ref.shape == (M, N)
+    err = np.empty((M, N), dtype=np.float64)
+    _chk(_load().awq_oracle_norm_error(_p(yb), _p(y_ref), _p(xb), _p(Wdq), _i64(M), _i64(N),
+                                       _i64(K), _p(err)), "norm_error")
+    return err
+
+
+def linear(x, codes, scales, zeros, group: int = GROUP) -> np.ndarray:
+    """The whole layer as the paper states it: dequantize, then matmul (fp64 acc)."""
+    return matmul(x, dequant(codes, scales, zeros, group))

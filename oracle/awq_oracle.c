@@ -1,0 +1,333 @@
+/*
+ * awq_oracle.c -- plain CPU oracle for the W4A16 group-quantized linear layer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct reference
+ * that the GPU library is checked against.  It shares no code, header, table or
+ * helper with the HIP path, and nothing in the product may call it.
+ *
+ * What it computes (AWQ, arXiv 2306.00978):
+ *   - Sec. 3.2, Eq. 1-2: the group quantizer Q applied to w*s, where s is the
+ *     per-input-channel activation-aware scale.  Eq. 1 prints a symmetric
+ *     abs-max form; the build target fixes the asymmetric 16-level min/max
+ *     form used here:  scale = (max-min)/15, zero = clamp(round(-min/scale)),
+ *     q = clamp(round(w/scale)+zero, 0, 15), group = 128 consecutive input
+ *     channels of one output row (Sec. 4.1 "group size of 128").
+ *   - Sec. 3.2, Eq. 4: W x == (W diag(s)) (diag(s)^-1 x); the caller divides x.
+ *   - Sec. 4.2 "on-the-fly weight dequantization": y = x * dequant(q)^T with
+ *     dequant(q) = (q - zero) * scale, written out here as a plain loop.
+ *   - Sec. 4.2 "SIMD-aware weight packing": the packed byte layout is a pure
+ *     index permutation; pack/unpack below are written from the layout text
+ *     in the design document, with plain index arithmetic.
+ *
+ * Arithmetic: the quantizer decides integers, so both sides take those
+ * decisions in IEEE binary32, one operation per statement, no FMA contraction
+ * (build with -ffp-contract=off), round-to-nearest-even.  The matmul
+ * accumulates in binary64.
+ *
+ * Pins (tests/test_oracle_*.py): code range, |w' - dequant| <= scale/2 for
+ * unclipped elements, end-point codes, round-off mean 0.25 (Sec. 3.2,
+ * observation 1), the Eq. 3 error-ratio law, exact-grid round trip, Eq. 4
+ * equivalence in fp64, brute-force dot products, hand-placed pack offsets,
+ * fp16 conversion against an independent implementation (numpy).
+ * Parity unpinned: none of the functions below (the paper prints no worked
+ * numeric example, so all pins are invariants / closed forms / brute force).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#define ORACLE_GROUP 128
+
+/* ---------- binary16 <-> binary32, bit level ---------- */
+
+float awq_oracle_f16_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) << 31;
+    int exp = (h >> 10) & 0x1f;
+    uint32_t man = h & 0x3ffu;
+    uint32_t bits;
+    float f;
+    if (exp == 0x1f) {                      /* inf / nan */
+        bits = sign | 0x7f800000u | (man << 13);
+    } else if (exp != 0) {                  /* normal */
+        bits = sign | ((uint32_t)(exp + 112) << 23) | (man << 13);
+    } else if (man == 0) {                  /* signed zero */
+        bits = sign;
+    } else {                                /* subnormal: man * 2^-24 */
+        float v = (float)man * 5.9604644775390625e-08f;
+        memcpy(&bits, &v, 4);
+        bits |= sign;
+    }
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+/* round-to-nearest-even binary32 -> binary16 */
+uint16_t awq_oracle_f32_to_f16(float f)
+{
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    uint16_t sign = (uint16_t)((bits >> 16) & 0x8000u);
+    uint32_t a = bits & 0x7fffffffu;
+    if (a > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);       /* nan */
+    if (a >= 0x47800000u) {                                        /* >= 65536 or inf */
+        return (uint16_t)(sign | 0x7c00u);
+    }
+    if (a >= 0x38800000u) {                                        /* normal half range */
+        uint32_t m = a - 0x38000000u;      /* rebias exponent by 112 */
+        uint32_t keep = m >> 13;
+        uint32_t rest = m & 0x1fffu;
+        if (rest > 0x1000u || (rest == 0x1000u && (keep & 1u))) keep += 1;
+        /* a carry may walk into the exponent, up to 0x7c00 = inf: correct */
+        return (uint16_t)(sign | keep);
+    }
+    if (a < 0x33000000u) return sign;                              /* < 2^-25 -> 0 */
+    {
+        /* subnormal half: value = m24 * 2^(e-150); target unit 2^-24 */
+        int e = (int)(a >> 23);
+        uint32_t m24 = (a & 0x7fffffu) | 0x800000u;
+        int shift = 126 - e;               /* e in [102,112] -> shift in [14,24] */
+        uint32_t keep = m24 >> shift;
+        uint32_t rest = m24 & ((1u << shift) - 1u);
+        uint32_t half = 1u << (shift - 1);
+        if (rest > half || (rest == half && (keep & 1u))) keep += 1;
+        return (uint16_t)(sign | keep);
+    }
+}
+
+/* ---------- a0: per-input-channel activation statistic (Sec. 3.2, Eq. 5) ----------
+ * s[k] = max(mean_t |X[t,k]|, floor)^alpha, accumulated in binary64.            */
+int awq_oracle_act_scale(const uint16_t *X, int64_t T, int64_t K, double alpha,
+                         double floor_, double *s)
+{
+    if (!X || !s || T <= 0 || K <= 0) return -1;
+    for (int64_t k = 0; k < K; ++k) {
+        double acc = 0.0;
+        for (int64_t t = 0; t < T; ++t)
+            acc += fabs((double)awq_oracle_f16_to_f32(X[t * K + k]));
+        double mean = acc / (double)T;
+        if (mean < floor_) mean = floor_;
+        s[k] = pow(mean, alpha);
+    }
+    return 0;
+}
+
+/* x'[m,k] = fp16( fp32(x[m,k]) / s[k] ) : the inverse scale of Eq. 4 applied to
+ * the activation by the caller ("fused into the previous operator").            */
+int awq_oracle_apply_inv_scale(const uint16_t *x, const float *s, int64_t M,
+                               int64_t K, uint16_t *xs)
+{
+    if (!x || !s || !xs || M <= 0 || K <= 0) return -1;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            float q = awq_oracle_f16_to_f32(x[m * K + k]) / s[k];
+            xs[m * K + k] = awq_oracle_f32_to_f16(q);
+        }
+    return 0;
+}
+
+/* ---------- a1..a4: quantize one matrix ----------
+ * W      [N,K] binary16, row-major (out-features x in-features)
+ * s      [K] binary32 or NULL (= all ones, plain round-to-nearest)
+ * codes  [N,K] one code per byte, 0..15
+ * scales [N,G] binary16 bits, G = K/128
+ * zeros  [N,G] one zero point per byte, 0..15                                   */
+static float clampf(float v, float lo, float hi)
+{
+    if (v < lo) return lo;
+    if (v > hi) return hi;
+    return v;
+}
+
+int awq_oracle_quantize(const uint16_t *W, const float *s, int64_t N, int64_t K,
+                        int group, uint8_t *codes, uint16_t *scales, uint8_t *zeros)
+{
+    if (!W || !codes || !scales || !zeros) return -1;
+    if (group != ORACLE_GROUP || N <= 0 || K <= 0 || K % group) return -2;
+    const int64_t G = K / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float wp[ORACLE_GROUP];
+        for (int64_t g = 0; g < G; ++g) {
+            const int64_t k0 = g * group;
+            /* a1: fold the activation-aware scale (Eq. 2: Q(w*s)) */
+            for (int j = 0; j < group; ++j) {
+                float w = awq_oracle_f16_to_f32(W[n * K + k0 + j]);
+                float sk = s ? s[k0 + j] : 1.0f;
+                wp[j] = w * sk;
+            }
+            /* a2: range of the group */
+            float mx = wp[0], mn = wp[0];
+            for (int j = 1; j < group; ++j) {
+                if (wp[j] > mx) mx = wp[j];
+                if (wp[j] < mn) mn = wp[j];
+            }
+            /* a3: step size, stored as binary16; the codes use the stored value */
+            float range = mx - mn;
+            float sc32 = range / 15.0f;
+            sc32 = clampf(sc32, 6.103515625e-05f /* 2^-14 */, 65504.0f);
+            uint16_t sc_h = awq_oracle_f32_to_f16(sc32);
+            float scale = awq_oracle_f16_to_f32(sc_h);
+            float nmn = -mn;
+            float zr = nmn / scale;
+            float zero = clampf(rintf(zr), 0.0f, 15.0f);
+            scales[n * G + g] = sc_h;
+            zeros[n * G + g] = (uint8_t)zero;
+            /* a4: codes */
+            for (int j = 0; j < group; ++j) {
+                float r = wp[j] / scale;
+                float q = rintf(r);
+                q = q + zero;
+                q = clampf(q, 0.0f, 15.0f);
+                codes[n * K + k0 + j] = (uint8_t)q;
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---------- a5: packed layout (written from the layout text) ----------
+ * qweight: tiles of 16 rows x 128 columns, 1024 bytes each, tile index
+ *          (n/16)*G + (k/128).  Inside a tile, 64 slots of 16 bytes; slot
+ *          l = (n%16) + 16*c owns row n%16 and, in its 32-bit word j (0..3),
+ *          the eight codes of columns 32*j + 8*c + e, e = 0..7.  Element e sits
+ *          in nibble position P[e] of the little-endian word, P = {0,4,1,5,2,6,3,7}
+ *          (so the nibbles, low to high, hold elements 0,2,4,6,1,3,5,7).
+ * scales : [N/16][G][16] binary16  (row n%16 innermost)
+ * zeros  : [N/16][G][8] bytes; byte b holds row 2b in its low nibble and row
+ *          2b+1 in its high nibble.                                              */
+static const int NIB_POS[8] = {0, 4, 1, 5, 2, 6, 3, 7};
+
+int awq_oracle_pack(const uint8_t *codes, const uint16_t *scales, const uint8_t *zeros,
+                    int64_t N, int64_t K, int group, uint8_t *qweight,
+                    uint16_t *scales_p, uint8_t *zeros_p)
+{
+    if (!codes || !scales || !zeros || !qweight || !scales_p || !zeros_p) return -1;
+    if (group != ORACLE_GROUP || N <= 0 || K <= 0 || K % group || N % 16) return -2;
+    const int64_t G = K / group;
+    memset(qweight, 0, (size_t)(N * K / 2));
+    memset(zeros_p, 0, (size_t)(N * G / 2));
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t tile = (n / 16) * G + (k / 128);
+            int kk = (int)(k % 128);
+            int j = kk / 32;
+            int c = (kk % 32) / 8;
+            int e = kk % 8;
+            int slot = (int)(n % 16) + 16 * c;
+            int64_t word_byte = tile * 1024 + slot * 16 + j * 4;
+            int bit = 4 * NIB_POS[e];
+            uint8_t code = codes[n * K + k] & 0xf;
+            qweight[word_byte + bit / 8] |= (uint8_t)(code << (bit % 8));
+        }
+        for (int64_t g = 0; g < G; ++g) {
+            int64_t rb = n / 16;
+            int r = (int)(n % 16);
+            scales_p[(rb * G + g) * 16 + r] = scales[n * G + g];
+            zeros_p[(rb * G + g) * 8 + r / 2] |= (uint8_t)((zeros[n * G + g] & 0xf) << (4 * (r % 2)));
+        }
+    }
+    return 0;
+}
+
+int awq_oracle_unpack(const uint8_t *qweight, const uint16_t *scales_p,
+                      const uint8_t *zeros_p, int64_t N, int64_t K, int group,
+                      uint8_t *codes, uint16_t *scales, uint8_t *zeros)
+{
+    if (!codes || !scales || !zeros || !qweight || !scales_p || !zeros_p) return -1;
+    if (group != ORACLE_GROUP || N <= 0 || K <= 0 || K % group || N % 16) return -2;
+    const int64_t G = K / group;
+    /* walk the packed bytes in storage order and scatter to [n,k] */
+    for (int64_t tile = 0; tile < (N / 16) * G; ++tile) {
+        int64_t rb = tile / G, g = tile % G;
+        for (int slot = 0; slot < 64; ++slot) {
+            int r = slot % 16, c = slot / 16;
+            for (int j = 0; j < 4; ++j) {
+                const uint8_t *wb = qweight + tile * 1024 + slot * 16 + j * 4;
+                uint32_t word = (uint32_t)wb[0] | ((uint32_t)wb[1] << 8) |
+                                ((uint32_t)wb[2] << 16) | ((uint32_t)wb[3] << 24);
+                for (int e = 0; e < 8; ++e) {
+                    int64_t n = rb * 16 + r;
+                    int64_t k = g * 128 + 32 * j + 8 * c + e;
+                    codes[n * K + k] = (uint8_t)((word >> (4 * NIB_POS[e])) & 0xf);
+                }
+            }
+        }
+        for (int r = 0; r < 16; ++r) {
+            int64_t n = rb * 16 + r;
+            scales[n * G + g] = scales_p[tile * 16 + r];
+            zeros[n * G + g] = (uint8_t)((zeros_p[tile * 8 + r / 2] >> (4 * (r % 2))) & 0xf);
+        }
+    }
+    return 0;
+}
+
+/* ---------- dequantize: Wdq[n,k] = (q - zero) * scale  (exact in binary32) ---------- */
+int awq_oracle_dequant(const uint8_t *codes, const uint16_t *scales, const uint8_t *zeros,
+                       int64_t N, int64_t K, int group, float *Wdq)
+{
+    if (!codes || !scales || !zeros || !Wdq) return -1;
+    if (group <= 0 || N <= 0 || K <= 0 || K % group) return -2;
+    const int64_t G = K / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t g = k / group;
+            float d = (float)((int)codes[n * K + k] - (int)zeros[n * G + g]);
+            Wdq[n * K + k] = d * awq_oracle_f16_to_f32(scales[n * G + g]);
+        }
+    return 0;
+}
+
+/* ---------- a6/a7: y[m,n] = sum_k x[m,k] * Wdq[n,k] ----------
+ * x [M,K] binary16; Wdq [N,K] binary32; y [M,N] binary64.
+ * acc32 != 0 switches to sequential binary32 accumulation (reported variant). */
+int awq_oracle_matmul(const uint16_t *x, const float *Wdq, int64_t M, int64_t N,
+                      int64_t K, int acc32, double *y)
+{
+    if (!x || !Wdq || !y || M <= 0 || N <= 0 || K <= 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t m = 0; m < M; ++m) {
+            if (acc32) {
+                float acc = 0.0f;
+                for (int64_t k = 0; k < K; ++k) {
+                    float p = awq_oracle_f16_to_f32(x[m * K + k]) * Wdq[n * K + k];
+                    acc = acc + p;
+                }
+                y[m * N + n] = (double)acc;
+            } else {
+                double acc = 0.0;
+                for (int64_t k = 0; k < K; ++k)
+                    acc += (double)awq_oracle_f16_to_f32(x[m * K + k]) * (double)Wdq[n * K + k];
+                y[m * N + n] = acc;
+            }
+        }
+    return 0;
+}
+
+/* The acceptance metric of the build target, per element:
+ * err[m,n] = |y_gpu - y_ref| / (||x[m,:]||_2 * max|Wdq| + 1e-6)                */
+int awq_oracle_norm_error(const uint16_t *y_gpu, const double *y_ref, const uint16_t *x,
+                          const float *Wdq, int64_t M, int64_t N, int64_t K, double *err)
+{
+    if (!y_gpu || !y_ref || !x || !Wdq || !err) return -1;
+    double wmax = 0.0;
+    for (int64_t i = 0; i < N * K; ++i) {
+        double a = fabs((double)Wdq[i]);
+        if (a > wmax) wmax = a;
+    }
+    for (int64_t m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double v = (double)awq_oracle_f16_to_f32(x[m * K + k]);
+            ss += v * v;
+        }
+        double den = sqrt(ss) * wmax + 1e-6;
+        for (int64_t n = 0; n < N; ++n) {
+            double d = (double)awq_oracle_f16_to_f32(y_gpu[m * N + n]) - y_ref[m * N + n];
+            err[m * N + n] = fabs(d) / den;
+        }
+    }
+    return 0;
+}
