@@ -1,0 +1,112 @@
+/*
+ * awq_mi355x.h -- C ABI of the MI355X (gfx950) W4A16 group-quantized linear library.
+ *
+ * Method: AWQ, arXiv 2306.00978.  Weights W[N,K] (out-features x in-features) are
+ * quantized to 4-bit codes in groups of 128 consecutive input channels with one
+ * fp16 step ("scale") and one uint4 zero point per group, after folding the
+ * per-input-channel activation-aware scale s into them (Sec. 3.2, Eq. 1-2).  The
+ * layer is evaluated as y = x' * dequant(q)^T with dequantization fused into the
+ * matrix-vector / matrix-matrix kernel (Sec. 4.2), where x' = x / s (Eq. 4).
+ *
+ * Conventions for every call below
+ *   - Tensor pointers are DEVICE pointers (HIP global memory) owned by the caller;
+ *     size/out-parameter pointers (size_t*) are HOST pointers.  The library never
+ *     allocates, frees or synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it and may still be running when the call returns.
+ *   - Shapes: N % 16 == 0, K % 128 == 0, group == 128, all sizes > 0.
+ *     Tensor pointers must be 16-byte aligned.
+ *   - Return value: AWQ_OK (0) or a negative awq_status.  Arguments are validated
+ *     before anything is launched, so on a validation error no output is touched.
+ *   - No global mutable state; calls on distinct streams may run concurrently as
+ *     long as their outputs (and workspaces) do not overlap.
+ *
+ * Packed layout, version 1 (what awq_quantize_pack writes and awq_w4a16_linear reads)
+ *   qweight : N*K/2 bytes; tiles of 16 rows x 128 columns (1024 B), tile index
+ *             (n/16)*(K/128) + k/128.  A tile is 64 slots of 16 B; slot
+ *             (n%16) + 16*c holds, in its little-endian 32-bit word j (0..3), the
+ *             codes of columns 32*j + 8*c + e (e = 0..7), element e in nibble
+ *             {0,4,1,5,2,6,3,7}[e].
+ *   scales  : [N/16][K/128][16] fp16, row (n%16) innermost.
+ *   zeros   : [N/16][K/128][8] bytes, byte b = row 2b (low nibble), row 2b+1 (high).
+ */
+#ifndef AWQ_MI355X_H
+#define AWQ_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum awq_status {
+    AWQ_OK = 0,
+    AWQ_ERR_NULL_POINTER = -1,
+    AWQ_ERR_BAD_SHAPE = -2,         /* size <= 0, K % 128 != 0, N % 16 != 0 */
+    AWQ_ERR_UNSUPPORTED_GROUP = -3, /* group != 128 */
+    AWQ_ERR_MISALIGNED = -4,        /* a tensor pointer is not 16-byte aligned */
+    AWQ_ERR_WORKSPACE_TOO_SMALL = -5,
+    AWQ_ERR_HIP = -6,               /* the HIP runtime refused a launch */
+    AWQ_ERR_BAD_ARGUMENT = -7       /* a scalar argument is out of range (e.g. alpha) */
+} awq_status;
+
+/* Version of the packed layout / ABI (currently 1). */
+int awq_version(void);
+
+/* Static, human-readable name of a status code (never NULL). */
+const char *awq_status_string(int status);
+
+/* Bytes of the three packed arrays for an [N,K] weight.  Host pointers; any of
+ * the three may be NULL. */
+int awq_packed_sizes(int64_t N, int64_t K, int group, size_t *qweight_bytes,
+                     size_t *scales_bytes, size_t *zeros_bytes);
+
+/* Sec. 3.2, Eq. 5: s[k] = max(mean_t |X[t,k]|, 1e-4)^alpha, the activation-aware
+ * per-input-channel scale.  X [T,K] fp16 row-major (device), s [K] fp32 (device,
+ * written).  0 <= alpha <= 1.  K % 8 == 0.  fp32 arithmetic. */
+int awq_act_scale(const void *X_f16, int64_t T, int64_t K, float alpha, float *s,
+                  void *stream);
+
+/* Sec. 3.2, Eq. 4: the diag(s)^-1 X factor, applied once by the producer of x:
+ * xs[m,k] = fp16(fp32(x[m,k]) / s[k]) (correctly rounded).  x, xs [M,K] fp16
+ * (device; xs may alias x), s [K] fp32 (device).  K % 8 == 0. */
+int awq_apply_inv_scale(const void *x_f16, const float *s, int64_t M, int64_t K,
+                        void *xs_f16, void *stream);
+
+/* Sec. 3.2, Eq. 1-2 and Sec. 4.2 (weight packing): quantize W*diag(s) per group of
+ * 128 input channels and write the packed layout.
+ *   w' = fp32(W)*s;  scale = fp16(clamp((max-min)/15, 2^-14, 65504));
+ *   zero = clamp(rint(-min/scale), 0, 15);  q = clamp(rint(w'/scale)+zero, 0, 15)
+ * in IEEE binary32, round-half-even, no contraction.
+ * W_f16 [N,K] fp16 row-major (device, read); s [K] fp32 (device) or NULL (= ones);
+ * qweight/scales/zeros: device buffers of awq_packed_sizes() bytes (written). */
+int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K, int group,
+                      void *qweight, void *scales, void *zeros, void *stream);
+
+/* Inverse of the packing (export / test path): codes [N,K] one code per byte,
+ * scales_f16 [N,K/128] fp16, zeros_u8 [N,K/128] one zero point per byte, all
+ * device, row-major, written.  Any of the three outputs may be NULL (skipped). */
+int awq_unpack(const void *qweight, const void *scales, const void *zeros, int64_t N,
+               int64_t K, int group, uint8_t *codes, void *scales_f16, uint8_t *zeros_u8,
+               void *stream);
+
+/* Bytes of scratch awq_w4a16_linear needs for this shape (0 if none).  Returns 0
+ * for invalid shapes as well; awq_w4a16_linear reports those. */
+size_t awq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
+
+/* Sec. 4.2 (on-the-fly dequantization fused into the MV / MM kernel):
+ *   y[m,n] = fp16( sum_k fp32(x[m,k]) * (q[n,k] - zero[n,k/128]) * scale[n,k/128] )
+ * with fp32 accumulation.  x_f16 [M,K] fp16 row-major, already divided by s;
+ * qweight/scales/zeros as written by awq_quantize_pack; y_f16 [M,N] fp16 row-major
+ * (written).  M <= 16 takes the decode path (streams the packed weights once),
+ * larger M the prefill path (MFMA tiles).  `workspace` may be NULL when
+ * awq_linear_workspace_bytes() is 0; its contents are undefined afterwards. */
+int awq_w4a16_linear(const void *x_f16, const void *qweight, const void *scales,
+                     const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,
+                     int group, void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AWQ_MI355X_H */

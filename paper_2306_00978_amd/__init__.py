@@ -1,0 +1,199 @@
+"""ctypes binding of libawq_mi355x.so (see include/awq_mi355x.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of the
+shared library.  PyTorch is used for device memory (``tensor.data_ptr()``) and
+streams (``torch.cuda.current_stream()``).  There is no CPU fallback: if the
+library has not been built, importing a function from it raises.
+
+Function names and argument order mirror the C ABI:
+    awq_act_scale, awq_apply_inv_scale            (AWQ Sec. 3.2, Eq. 4-5)
+    awq_quantize_pack, awq_unpack                 (Sec. 3.2, Eq. 1-2; Sec. 4.2 packing)
+    awq_w4a16_linear                              (Sec. 4.2 fused dequantization)
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # first: its HIP runtime must be the one this process uses
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libawq_mi355x.so")
+GROUP = 128
+
+EXPORTS = [
+    "awq_version", "awq_status_string", "awq_packed_sizes", "awq_act_scale",
+    "awq_apply_inv_scale", "awq_quantize_pack", "awq_unpack", "awq_linear_workspace_bytes",
+    "awq_w4a16_linear",
+]
+
+_lib = None
+
+
+class AwqError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+def load() -> ctypes.CDLL:
+    """Load the shared library (built by ``paper_2306_00978_amd.build``); no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2306_00978_amd.build` "
+            "(there is no CPU or PyTorch fallback for this library)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    lib.awq_version.restype = i32
+    lib.awq_version.argtypes = []
+    lib.awq_status_string.restype = ctypes.c_char_p
+    lib.awq_status_string.argtypes = [i32]
+    lib.awq_packed_sizes.restype = i32
+    lib.awq_packed_sizes.argtypes = [i64, i64, i32, szp, szp, szp]
+    lib.awq_act_scale.restype = i32
+    lib.awq_act_scale.argtypes = [vp, i64, i64, ctypes.c_float, vp, vp]
+    lib.awq_apply_inv_scale.restype = i32
+    lib.awq_apply_inv_scale.argtypes = [vp, vp, i64, i64, vp, vp]
+    lib.awq_quantize_pack.restype = i32
+    lib.awq_quantize_pack.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.awq_unpack.restype = i32
+    lib.awq_unpack.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.awq_linear_workspace_bytes.restype = sz
+    lib.awq_linear_workspace_bytes.argtypes = [i64, i64, i64, i32]
+    lib.awq_w4a16_linear.restype = i32
+    lib.awq_w4a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise AwqError(status, what)
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> torch.Tensor:
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{what}: expected a contiguous {dtype} tensor on the GPU")
+    return t
+
+
+def awq_version() -> int:
+    return load().awq_version()
+
+
+def status_string(status: int) -> str:
+    return load().awq_status_string(int(status)).decode()
+
+
+def awq_packed_sizes(N: int, K: int, group: int = GROUP):
+    q, s, z = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load().awq_packed_sizes(N, K, group, ctypes.byref(q), ctypes.byref(s), ctypes.byref(z)),
+           "awq_packed_sizes")
+    return q.value, s.value, z.value
+
+
+def awq_act_scale(X: torch.Tensor, alpha: float = 0.5, out: torch.Tensor | None = None):
+    """s[k] = max(mean_t |X[t,k]|, 1e-4)^alpha; X [T,K] fp16 -> s [K] fp32."""
+    _dev(X, torch.float16, "X")
+    T, K = X.shape
+    s = out if out is not None else torch.empty(K, dtype=torch.float32, device=X.device)
+    _dev(s, torch.float32, "s")
+    _check(load().awq_act_scale(_ptr(X), T, K, float(alpha), _ptr(s), _stream()), "awq_act_scale")
+    return s
+
+
+def awq_apply_inv_scale(x: torch.Tensor, s: torch.Tensor, out: torch.Tensor | None = None):
+    """xs = fp16(fp32(x) / s); x [M,K] fp16, s [K] fp32."""
+    _dev(x, torch.float16, "x")
+    _dev(s, torch.float32, "s")
+    M, K = x.shape
+    if s.numel() != K:
+        raise ValueError("s must have K elements")
+    xs = out if out is not None else torch.empty_like(x)
+    _dev(xs, torch.float16, "xs")
+    _check(load().awq_apply_inv_scale(_ptr(x), _ptr(s), M, K, _ptr(xs), _stream()),
+           "awq_apply_inv_scale")
+    return xs
+
+
+def awq_quantize_pack(W: torch.Tensor, s: torch.Tensor | None = None, group: int = GROUP,
+                      out=None):
+    """W [N,K] fp16, s [K] fp32 or None -> (qweight u8[N*K/2], scales f16[N*K/128],
+    zeros u8[N*K/256]) in the packed layout."""
+    _dev(W, torch.float16, "W")
+    N, K = W.shape
+    if s is not None:
+        _dev(s, torch.float32, "s")
+        if s.numel() != K:
+            raise ValueError("s must have K elements")
+    qb, sb, zb = awq_packed_sizes(N, K, group)
+    if out is None:
+        qweight = torch.empty(qb, dtype=torch.uint8, device=W.device)
+        scales = torch.empty(sb // 2, dtype=torch.float16, device=W.device)
+        zeros = torch.empty(zb, dtype=torch.uint8, device=W.device)
+    else:
+        qweight, scales, zeros = out
+        if qweight.numel() * qweight.element_size() < qb or scales.numel() * 2 < sb \
+                or zeros.numel() * zeros.element_size() < zb:
+            raise ValueError("output buffers are too small")
+    _check(load().awq_quantize_pack(_ptr(W), _ptr(s), N, K, group, _ptr(qweight), _ptr(scales),
+                                    _ptr(zeros), _stream()), "awq_quantize_pack")
+    return qweight, scales, zeros
+
+
+def awq_unpack(qweight, scales, zeros, N: int, K: int, group: int = GROUP):
+    """Packed arrays -> (codes u8[N,K], scales f16[N,G], zeros u8[N,G])."""
+    qb, sb, zb = awq_packed_sizes(N, K, group)
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+            or zeros.numel() * zeros.element_size() < zb:
+        raise ValueError("packed buffers are too small for this shape")
+    G = K // group
+    dev = qweight.device
+    codes = torch.empty((N, K), dtype=torch.uint8, device=dev)
+    sc = torch.empty((N, G), dtype=torch.float16, device=dev)
+    zr = torch.empty((N, G), dtype=torch.uint8, device=dev)
+    _check(load().awq_unpack(_ptr(qweight), _ptr(scales), _ptr(zeros), N, K, group, _ptr(codes),
+                             _ptr(sc), _ptr(zr), _stream()), "awq_unpack")
+    return codes, sc, zr
+
+
+def awq_linear_workspace_bytes(M: int, N: int, K: int, group: int = GROUP) -> int:
+    return int(load().awq_linear_workspace_bytes(M, N, K, group))
+
+
+def awq_w4a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int = GROUP,
+                     out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """y[M,N] = x[M,K] . dequant(qweight, scales, zeros)^T (fp16 in, fp32 accumulate, fp16 out).
+    x must already be divided by the activation-aware scale s."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    qb, sb, zb = awq_packed_sizes(N, K, group)
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+            or zeros.numel() * zeros.element_size() < zb:
+        raise ValueError("packed buffers are too small for this shape")
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    if y.numel() != M * N:
+        raise ValueError("y must have M*N elements")
+    need = awq_linear_workspace_bytes(M, N, K, group)
+    ws_bytes = 0
+    if need:
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        ws_bytes = workspace.numel() * workspace.element_size()
+    _check(load().awq_w4a16_linear(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(y),
+                                   M, N, K, group, _ptr(workspace) if need else None, ws_bytes,
+                                   _stream()), "awq_w4a16_linear")
+    return y

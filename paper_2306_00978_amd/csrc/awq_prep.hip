@@ -1,0 +1,104 @@
+// awq_act_scale / awq_apply_inv_scale for gfx950.
+//
+// AWQ Sec. 3.2: the saliency of a weight channel is decided by the magnitude of
+// its input activation; Eq. 5 takes s = s_X^alpha with s_X the per-input-channel
+// mean |X| over the calibration rows, and Eq. 4 moves diag(s)^-1 onto the
+// activations.  Both are plain streaming passes over X (HBM-bound).
+#include "awq_common.h"
+
+namespace {
+
+constexpr int ACT_COLS = 64;     // columns per workgroup (8 lanes x 8 halves = 128 B per row)
+constexpr int ACT_PHASES = 128;  // row phases per workgroup (1024 threads)
+
+// Each workgroup owns 64 columns and walks all T rows; thread (phase, oct) sums |x|
+// of rows phase, phase+128, ... for its eight columns.  The 128 partial sums per
+// column are then added in a fixed tree order, so the result is deterministic.
+__global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict__ X,
+                                                         int64_t T, int64_t K, float alpha,
+                                                         float *__restrict__ s)
+{
+    __shared__ float red[ACT_PHASES][ACT_COLS];
+    const int oct = threadIdx.x & 7;
+    const int phase = threadIdx.x >> 3;
+    const int64_t col0 = (int64_t)blockIdx.x * ACT_COLS + oct * 8;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (col0 < K) {
+        const int64_t K8 = K / 8;
+        const uint4 *p = X + col0 / 8;
+        for (int64_t t = phase; t < T; t += ACT_PHASES) {
+            uint4 raw = p[t * K8];
+            const half_t *h = reinterpret_cast<const half_t *>(&raw);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += __builtin_fabsf((float)h[e]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[phase][oct * 8 + e] = acc[e];
+    __syncthreads();
+    for (int half = ACT_PHASES / 2; half >= 1; half >>= 1) {
+        for (int i = threadIdx.x; i < half * ACT_COLS; i += 1024) {
+            const int p = i / ACT_COLS, cidx = i % ACT_COLS;
+            red[p][cidx] += red[p + half][cidx];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < ACT_COLS) {
+        const int64_t col = (int64_t)blockIdx.x * ACT_COLS + threadIdx.x;
+        if (col < K) {
+            float mean = red[0][threadIdx.x] / (float)T;
+            mean = fmaxf(mean, 1e-4f);
+            s[col] = powf(mean, alpha);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void apply_inv_scale_kernel(const uint4 *__restrict__ x,
+                                                              const float4 *__restrict__ s,
+                                                              int64_t runs_total, int64_t K8,
+                                                              uint4 *__restrict__ xs)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= runs_total) return;
+    const int64_t run = i % K8;
+    uint4 raw = x[i];
+    const half_t *h = reinterpret_cast<const half_t *>(&raw);
+    const float4 a = s[2 * run], b = s[2 * run + 1];
+    const float sv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    uint4 out;
+    half_t *o = reinterpret_cast<half_t *>(&out);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (half_t)((float)h[e] / sv[e]);
+    xs[i] = out;
+}
+
+}  // namespace
+
+extern "C" int awq_act_scale(const void *X_f16, int64_t T, int64_t K, float alpha, float *s,
+                             void *stream)
+{
+    if (!X_f16 || !s) return AWQ_ERR_NULL_POINTER;
+    if (T <= 0 || K <= 0 || (K % 8) != 0 || K > (int64_t)1 << 30) return AWQ_ERR_BAD_SHAPE;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return AWQ_ERR_BAD_ARGUMENT;
+    if (!awq_aligned16(X_f16) || !awq_aligned16(s)) return AWQ_ERR_MISALIGNED;
+    const int blocks = (int)((K + ACT_COLS - 1) / ACT_COLS);
+    act_scale_kernel<<<dim3(blocks), dim3(1024), 0, (hipStream_t)stream>>>(
+        (const uint4 *)X_f16, T, K, alpha, s);
+    return awq_launch_status();
+}
+
+extern "C" int awq_apply_inv_scale(const void *x_f16, const float *s, int64_t M, int64_t K,
+                                   void *xs_f16, void *stream)
+{
+    if (!x_f16 || !s || !xs_f16) return AWQ_ERR_NULL_POINTER;
+    if (M <= 0 || K <= 0 || (K % 8) != 0 || M * (K / 8) > (int64_t)1 << 38)
+        return AWQ_ERR_BAD_SHAPE;
+    if (!awq_aligned16(x_f16) || !awq_aligned16(s) || !awq_aligned16(xs_f16))
+        return AWQ_ERR_MISALIGNED;
+    const int64_t runs = M * (K / 8);
+    const int64_t blocks = (runs + 255) / 256;
+    if (blocks > 0x7fffffff) return AWQ_ERR_BAD_SHAPE;
+    apply_inv_scale_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(
+        (const uint4 *)x_f16, (const float4 *)s, runs, K / 8, (uint4 *)xs_f16);
+    return awq_launch_status();
+}

@@ -1,0 +1,182 @@
+// awq_quantize_pack / awq_unpack for gfx950.
+//
+// AWQ Sec. 3.2, Eq. 1-2: the group quantizer applied to w*s, in the asymmetric
+// 16-level min/max form; Sec. 4.2: the codes are written directly in the packed
+// order the linear kernels consume.
+//
+// One wavefront owns one tile (16 rows x 128 columns = one quantization group for
+// 16 rows).  Lane l works on row l%16 and on the four 8-column runs
+// 32*j + 8*(l/16) + 0..7, which is exactly the 16-byte slot it will write, so the
+// packed tile leaves the wave as a single coalesced 1 KB store.  The four lanes
+// l, l^16, l^32, l^48 share a row; its min/max are combined with two xor-shuffles.
+//
+// This file must be compiled with -ffp-contract=off: the integer decisions
+// (zero point, codes) are taken in IEEE binary32 with one rounding per operation,
+// correctly rounded division and round-half-even, bit for bit.
+#include "awq_common.h"
+
+namespace {
+
+__device__ __forceinline__ float clampf(float v, float lo, float hi)
+{
+    if (v < lo) v = lo;
+    if (v > hi) v = hi;
+    return v;
+}
+
+// nibble position of element e inside a packed word: {0,4,1,5,2,6,3,7}
+__device__ __forceinline__ int nib_shift(int e) { return 4 * ((e >> 1) + 4 * (e & 1)); }
+
+__global__ __launch_bounds__(256) void quantize_pack_kernel(
+    const uint4 *__restrict__ W,   // [N, K/8] runs of eight fp16
+    const float4 *__restrict__ s,  // [K/4] or nullptr
+    uint4 *__restrict__ qweight, uint16_t *__restrict__ scales, uint8_t *__restrict__ zeros,
+    int G, int num_tiles)
+{
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= num_tiles) return;                 // whole wave leaves together
+    const int rb = tile / G, g = tile - rb * G;
+    const int r = lane & 15, c = lane >> 4;
+    const int64_t n = (int64_t)rb * 16 + r;
+    const int64_t K8 = (int64_t)G * 16;            // row length in 8-element runs
+
+    float wp[4][8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int run = g * 16 + 4 * j + c;        // 8-column run inside the row
+        uint4 raw = W[n * K8 + run];
+        const half_t *h = reinterpret_cast<const half_t *>(&raw);
+        float sv[8];
+        if (s) {
+            float4 a = s[2 * run], b = s[2 * run + 1];
+            sv[0] = a.x; sv[1] = a.y; sv[2] = a.z; sv[3] = a.w;
+            sv[4] = b.x; sv[5] = b.y; sv[6] = b.z; sv[7] = b.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sv[e] = 1.0f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wp[j][e] = (float)h[e] * sv[e];
+    }
+
+    float mx = wp[0][0], mn = wp[0][0];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            mx = fmaxf(mx, wp[j][e]);
+            mn = fminf(mn, wp[j][e]);
+        }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mn = fminf(mn, __shfl_xor(mn, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mn = fminf(mn, __shfl_xor(mn, 32));
+
+    const float range = mx - mn;
+    float sc32 = range / 15.0f;
+    sc32 = clampf(sc32, 6.103515625e-05f, 65504.0f);
+    const half_t sc_h = (half_t)sc32;              // v_cvt_f16_f32, round-half-even
+    const float scale = (float)sc_h;
+    const float nmn = -mn;
+    const float zr = nmn / scale;
+    const float zero = clampf(__builtin_rintf(zr), 0.0f, 15.0f);
+
+    uint32_t words[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float q = __builtin_rintf(wp[j][e] / scale);
+            q = q + zero;
+            q = clampf(q, 0.0f, 15.0f);
+            w |= (uint32_t)q << nib_shift(e);
+        }
+        words[j] = w;
+    }
+    qweight[(int64_t)tile * 64 + lane] = make_uint4(words[0], words[1], words[2], words[3]);
+
+    const uint32_t z = (uint32_t)zero;
+    const uint32_t z_hi = __shfl_xor(z, 1);        // the odd row of the pair
+    if (c == 0) {
+        scales[(int64_t)tile * 16 + r] = __builtin_bit_cast(uint16_t, sc_h);
+        if ((r & 1) == 0) zeros[(int64_t)tile * 8 + (r >> 1)] = (uint8_t)(z | (z_hi << 4));
+    }
+}
+
+__global__ __launch_bounds__(256) void unpack_kernel(
+    const uint4 *__restrict__ qweight, const uint16_t *__restrict__ scales,
+    const uint8_t *__restrict__ zeros, uint8_t *__restrict__ codes,
+    uint16_t *__restrict__ scales_out, uint8_t *__restrict__ zeros_out, int G, int num_tiles)
+{
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= num_tiles) return;
+    const int rb = tile / G, g = tile - rb * G;
+    const int r = lane & 15, c = lane >> 4;
+    const int64_t n = (int64_t)rb * 16 + r;
+    const int64_t K = (int64_t)G * 128;
+
+    if (codes) {
+        const uint4 q = qweight[(int64_t)tile * 64 + lane];
+        const uint32_t words[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t lo = 0, hi = 0;               // bytes e = 0..3 and 4..7
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                lo |= ((words[j] >> nib_shift(e)) & 0xFu) << (8 * e);
+                hi |= ((words[j] >> nib_shift(e + 4)) & 0xFu) << (8 * e);
+            }
+            uint2 *dst = reinterpret_cast<uint2 *>(codes + n * K + g * 128 + 32 * j + 8 * c);
+            *dst = make_uint2(lo, hi);
+        }
+    }
+    if (c == 0) {
+        if (scales_out) scales_out[n * G + g] = scales[(int64_t)tile * 16 + r];
+        if (zeros_out)
+            zeros_out[n * G + g] = (zeros[(int64_t)tile * 8 + (r >> 1)] >> (4 * (r & 1))) & 0xF;
+    }
+}
+
+}  // namespace
+
+extern "C" int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K,
+                                 int group, void *qweight, void *scales, void *zeros,
+                                 void *stream)
+{
+    if (!W_f16 || !qweight || !scales || !zeros) return AWQ_ERR_NULL_POINTER;
+    int st = awq_check_weight_shape(N, K, group);
+    if (st != AWQ_OK) return st;
+    if (!awq_aligned16(W_f16) || !awq_aligned16(qweight) || !awq_aligned16(scales) ||
+        !awq_aligned16(zeros) || (s && !awq_aligned16(s)))
+        return AWQ_ERR_MISALIGNED;
+    const int G = (int)(K / AWQ_GROUP);
+    const int num_tiles = (int)(N / 16) * G;
+    const int blocks = (num_tiles + 3) / 4;
+    quantize_pack_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
+        (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
+        (uint8_t *)zeros, G, num_tiles);
+    return awq_launch_status();
+}
+
+extern "C" int awq_unpack(const void *qweight, const void *scales, const void *zeros,
+                          int64_t N, int64_t K, int group, uint8_t *codes, void *scales_f16,
+                          uint8_t *zeros_u8, void *stream)
+{
+    if (!qweight || !scales || !zeros) return AWQ_ERR_NULL_POINTER;
+    int st = awq_check_weight_shape(N, K, group);
+    if (st != AWQ_OK) return st;
+    if (!awq_aligned16(qweight) || !awq_aligned16(scales) || !awq_aligned16(zeros) ||
+        (codes && !awq_aligned16(codes)) || (scales_f16 && !awq_aligned16(scales_f16)) ||
+        (zeros_u8 && !awq_aligned16(zeros_u8)))
+        return AWQ_ERR_MISALIGNED;
+    const int G = (int)(K / AWQ_GROUP);
+    const int num_tiles = (int)(N / 16) * G;
+    const int blocks = (num_tiles + 3) / 4;
+    unpack_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
+        (const uint4 *)qweight, (const uint16_t *)scales, (const uint8_t *)zeros, codes,
+        (uint16_t *)scales_f16, zeros_u8, G, num_tiles);
+    return awq_launch_status();
+}

@@ -1,0 +1,115 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad
+arguments before touching the GPU (so these run on a box without one)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "awq_mi355x.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2306_00978_amd as awq
+    if not os.path.exists(awq.LIB_PATH):
+        from paper_2306_00978_amd import build
+        build.build()
+    return awq.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(awq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    import paper_2306_00978_amd as awq
+    assert declared_functions() == sorted(awq.EXPORTS)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(lib):
+    assert lib.awq_version() == 1
+    seen = set()
+    for st in range(0, -8, -1):
+        s = lib.awq_status_string(st).decode()
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert lib.awq_status_string(-99).decode() == "unknown status"
+
+
+def test_packed_sizes(lib):
+    q, s, z = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.awq_packed_sizes(4096, 11008, 128, ctypes.byref(q), ctypes.byref(s), ctypes.byref(z)) == 0
+    assert (q.value, s.value, z.value) == (4096 * 11008 // 2, 4096 * 86 * 2, 4096 * 86 // 2)
+    # 0.51953125 bytes per weight
+    assert (q.value + s.value + z.value) * 128 * 4 == 4096 * 11008 * 266
+    assert lib.awq_packed_sizes(4096, 4096, 64, None, None, None) == -3
+    assert lib.awq_packed_sizes(4096, 4000, 128, None, None, None) == -2
+    assert lib.awq_packed_sizes(4090, 4096, 128, None, None, None) == -2
+    assert lib.awq_packed_sizes(0, 4096, 128, None, None, None) == -2
+    assert lib.awq_packed_sizes(16, 128, 128, None, None, None) == 0
+
+
+def test_argument_validation_happens_before_any_launch(lib):
+    P = ctypes.c_void_p
+    ok = P(0x1000)          # non-null, 16-byte aligned, never dereferenced on these paths
+    odd = P(0x1008)
+    # null pointers
+    assert lib.awq_quantize_pack(None, None, 16, 128, 128, ok, ok, ok, None) == -1
+    assert lib.awq_w4a16_linear(ok, None, ok, ok, ok, 1, 16, 128, 128, None, 0, None) == -1
+    assert lib.awq_unpack(ok, ok, None, 16, 128, 128, ok, ok, ok, None) == -1
+    assert lib.awq_act_scale(None, 4, 128, 0.5, ok, None) == -1
+    assert lib.awq_apply_inv_scale(ok, None, 1, 128, ok, None) == -1
+    # shapes / group
+    assert lib.awq_quantize_pack(ok, None, 16, 100, 128, ok, ok, ok, None) == -2
+    assert lib.awq_quantize_pack(ok, None, 8, 128, 128, ok, ok, ok, None) == -2
+    assert lib.awq_quantize_pack(ok, None, 16, 128, 32, ok, ok, ok, None) == -3
+    assert lib.awq_w4a16_linear(ok, ok, ok, ok, ok, 0, 16, 128, 128, None, 0, None) == -2
+    assert lib.awq_w4a16_linear(ok, ok, ok, ok, ok, -3, 16, 128, 128, None, 0, None) == -2
+    assert lib.awq_w4a16_linear(ok, ok, ok, ok, ok, 1, 16, 128, 64, None, 0, None) == -3
+    assert lib.awq_act_scale(ok, 0, 128, 0.5, ok, None) == -2
+    assert lib.awq_act_scale(ok, 4, 100, 0.5, ok, None) == -2
+    assert lib.awq_apply_inv_scale(ok, ok, 1, 12, ok, None) == -2
+    # scalar range
+    assert lib.awq_act_scale(ok, 4, 128, 1.5, ok, None) == -7
+    assert lib.awq_act_scale(ok, 4, 128, float("nan"), ok, None) == -7
+    # alignment
+    assert lib.awq_quantize_pack(odd, None, 16, 128, 128, ok, ok, ok, None) == -4
+    assert lib.awq_quantize_pack(ok, odd, 16, 128, 128, ok, ok, ok, None) == -4
+    assert lib.awq_w4a16_linear(ok, ok, ok, ok, odd, 1, 16, 128, 128, None, 0, None) == -4
+    assert lib.awq_unpack(ok, ok, ok, 16, 128, 128, odd, None, None, None) == -4
+    # workspace query never fails
+    assert lib.awq_linear_workspace_bytes(1, 4096, 4096, 128) >= 0
+    assert lib.awq_linear_workspace_bytes(-1, 0, 7, 3) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2306_00978_amd as awq
+    with pytest.raises(TypeError):
+        awq.awq_quantize_pack(torch.zeros(16, 128, dtype=torch.float16))
+    with pytest.raises(TypeError):
+        awq.awq_w4a16_linear(torch.zeros(1, 128, dtype=torch.float16), None, None, None, 16)
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2306_00978_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "awq_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2306_00978_amd" not in text and "awq_mi355x" not in text, f

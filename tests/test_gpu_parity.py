@@ -1,0 +1,267 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle.
+
+Bars: codes / steps / zero points / packed bytes bit-exact; outputs within
+|y_gpu - y_ref| / (||x_row||_2 * max|Wdq| + 1e-6) <= 2e-3 for every element.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def awq():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2306_00978_amd as awq
+    awq.load()          # raises if the HIP library is missing: no fallback
+    return awq
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def guarded(nbytes, dtype, fill=0xA5, pad=4096):
+    """A device buffer with canary bytes on both sides; returns (view, check)."""
+    import torch
+    raw = torch.full((nbytes + 2 * pad,), fill, dtype=torch.uint8, device="cuda")
+    view = raw[pad:pad + nbytes].view(dtype)
+
+    def check():
+        torch.cuda.synchronize()
+        assert bool((raw[:pad] == fill).all()) and bool((raw[pad + nbytes:] == fill).all()), \
+            "kernel wrote outside its output buffer"
+    return view, check
+
+
+# ----------------------------------------------------------------------------- quantize
+
+def quantize_both(awq, W, s):
+    import torch
+    import oracle
+    N, K = W.shape
+    codes, scales, zeros = oracle.quantize(W, s)
+    q_ref, s_ref, z_ref = oracle.pack(codes, scales, zeros)
+    qb, sb, zb = awq.awq_packed_sizes(N, K)
+    q_gpu, cq = guarded(qb, torch.uint8)
+    s_gpu, cs = guarded(sb, torch.float16)
+    z_gpu, cz = guarded(zb, torch.uint8)
+    awq.awq_quantize_pack(dev(W), None if s is None else dev(s), out=(q_gpu, s_gpu, z_gpu))
+    cq(); cs(); cz()
+    return (codes, scales, zeros), (q_ref, s_ref, z_ref), (q_gpu, s_gpu, z_gpu)
+
+
+def assert_quantize_bit_exact(awq, W, s):
+    import oracle
+    N, K = W.shape
+    (codes, scales, zeros), (q_ref, s_ref, z_ref), (q_gpu, s_gpu, z_gpu) = quantize_both(awq, W, s)
+    assert np.array_equal(host(s_gpu).view(np.uint16), s_ref), "steps differ"
+    assert np.array_equal(host(z_gpu), z_ref), "zero points differ"
+    qg = host(q_gpu)
+    if not np.array_equal(qg, q_ref):
+        c_gpu, _, _ = oracle.unpack(qg, s_ref, z_ref, N, K)
+        bad = np.argwhere(c_gpu != codes)
+        raise AssertionError(f"{len(bad)} codes differ, first at {bad[:5].tolist()}")
+    # the export path returns the canonical arrays
+    c_u, s_u, z_u = awq.awq_unpack(q_gpu, s_gpu, z_gpu, N, K)
+    assert np.array_equal(host(c_u), codes)
+    assert np.array_equal(host(s_u).view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(host(z_u), zeros)
+    return (codes, scales, zeros), (q_gpu, s_gpu, z_gpu)
+
+
+def make_case(N, K, M, sigma, cfg, proj=0):
+    """Raw inputs from the seeded generator; s and x' through the oracle."""
+    import oracle
+    import workloads
+    case = workloads.linear_case(f"{N}x{K}", N, K, M, sigma, cfg, layer=0, proj=proj)
+    s = oracle.act_scale(case.calib, 0.5).astype(np.float32)
+    xs = oracle.apply_inv_scale(case.x, s)
+    return case, s, xs
+
+
+@pytest.mark.parametrize("N,K", [(16, 128), (48, 640), (80, 1408), (272, 256)])
+def test_quantize_pack_small_shapes(awq, N, K):
+    g = np.random.default_rng(100 + N)
+    W = (g.standard_normal((N, K)) * 0.02).astype(np.float16)
+    s = g.uniform(0.3, 5.0, size=K).astype(np.float32)
+    assert_quantize_bit_exact(awq, W, s)
+    assert_quantize_bit_exact(awq, W, None)
+
+
+def test_quantize_pack_edge_groups(awq):
+    K = 512
+    W = np.zeros((32, K), dtype=np.float16)
+    W[1, :] = 0.5
+    W[2, :] = -0.25
+    W[3, :128] = np.linspace(1.0, 2.5, 128)
+    W[4, :128] = -np.linspace(1.0, 2.5, 128)
+    W[5, 0], W[5, 1] = 65504.0, -65504.0                 # step clamps at the fp16 maximum
+    W[6, :] = np.float16(6e-8)                            # subnormal halves
+    g = np.random.default_rng(7)
+    W[7, :] = (g.standard_normal(K) * 1e-6).astype(np.float16)
+    W[8, :] = (g.standard_normal(K) * 100).astype(np.float16)
+    # exact ties: w/scale lands on .5 -> round-half-even must agree
+    W[9, :128] = (np.arange(128) % 31) * 0.25
+    W[10:, :] = (g.standard_normal((22, K)) * 0.02).astype(np.float16)
+    s = np.full(K, 16.0, dtype=np.float32)
+    assert_quantize_bit_exact(awq, W, s)
+    assert_quantize_bit_exact(awq, W, None)
+    s2 = g.uniform(1e-3, 1e3, size=K).astype(np.float32)
+    assert_quantize_bit_exact(awq, W, s2)
+
+
+CONFIG_SHAPES = [
+    # (N, K, sigma, cfg)
+    (4096, 4096, 0.02, 1), (11008, 4096, 0.02, 1), (4096, 11008, 0.02, 1),
+    (8192, 8192, 0.015, 3), (1024, 8192, 0.015, 3), (28672, 8192, 0.015, 3),
+    (8192, 28672, 0.015, 3),
+]
+_cache = {}
+
+
+def config_case(awq, N, K, sigma, cfg):
+    """Quantize once per distinct shape (bit-exact check included) and reuse."""
+    key = (N, K, cfg)
+    if key not in _cache:
+        _cache.clear()                                   # keep host memory bounded
+        proj = [c[:2] for c in CONFIG_SHAPES].index((N, K))
+        case, s, xs16 = make_case(N, K, 16, sigma, cfg, proj=proj)
+        ref, gpu = assert_quantize_bit_exact(awq, case.W, s)
+        import oracle
+        Wdq = oracle.dequant(*ref)
+        _cache[key] = (case, s, xs16, ref, gpu, Wdq)
+    return _cache[key]
+
+
+def check_linear(awq, xs, Wdq, gpu_packed, N, rows=None):
+    """Run the GPU layer on xs[M,K]; compare rows (all if None) with the oracle."""
+    import torch
+    import oracle
+    M, K = xs.shape
+    y_gpu, cy = guarded(M * N * 2, torch.float16)
+    y_gpu = y_gpu.view(M, N)
+    awq.awq_w4a16_linear(dev(xs), *gpu_packed, N, out=y_gpu)
+    cy()
+    yh = host(y_gpu)
+    sel = np.arange(M) if rows is None else np.asarray(rows)
+    y_ref = oracle.matmul(xs[sel], Wdq)
+    err = oracle.norm_error(yh[sel], y_ref, xs[sel], Wdq)
+    assert np.all(np.isfinite(yh.astype(np.float32)))
+    assert err.max() <= TOL, f"max normalised error {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+    return err.max()
+
+
+@pytest.mark.parametrize("N,K,sigma,cfg", CONFIG_SHAPES)
+def test_config_shapes_quantize_and_decode(awq, N, K, sigma, cfg):
+    """Every distinct (N,K) of the five configs: bit-exact quantize/pack at full size, then
+    the decode path at the M values the configs name (1, 4, 8, 16)."""
+    case, s, xs16, ref, gpu, Wdq = config_case(awq, N, K, sigma, cfg)
+    for M in ((1, 4, 16) if cfg == 1 else (1, 8)):
+        check_linear(awq, xs16[:M], Wdq, gpu, N)
+
+
+@pytest.mark.parametrize("N,K", [(4096, 4096), (11008, 4096), (4096, 11008)])
+def test_config2_prefill_full_size_sampled_rows(awq, N, K):
+    """M = 2048 prefill at full size; 64 seeded rows are checked against the oracle
+    (every output column of those rows)."""
+    import oracle
+    import workloads
+    case, s, xs16, ref, gpu, Wdq = config_case(awq, N, K, 0.02, 1)
+    X = workloads.activations(2048, K, 2, 0, 0, workloads.ROLE_X, case.outliers)
+    xs = oracle.apply_inv_scale(X, s)
+    rows = np.sort(np.random.default_rng(5).choice(2048, size=64, replace=False))
+    check_linear(awq, xs, Wdq, gpu, N, rows=rows)
+
+
+# ------------------------------------------------------------------- decode / prefill, small
+
+@pytest.fixture(scope="module")
+def small(awq):
+    N, K = 176, 1408          # 11 row blocks (not a multiple of 8), 11 groups
+    case, s, xs = make_case(N, K, 300, 0.02, cfg=0)
+    ref, gpu = assert_quantize_bit_exact(awq, case.W, s)
+    import oracle
+    return N, K, xs, oracle.dequant(*ref), gpu
+
+
+@pytest.mark.parametrize("M", list(range(1, 17)))
+def test_decode_every_m(awq, small, M):
+    N, K, xs, Wdq, gpu = small
+    check_linear(awq, xs[:M], Wdq, gpu, N)
+
+
+@pytest.mark.parametrize("M", [17, 64, 127, 128, 129, 300])
+def test_prefill_ragged_m(awq, small, M):
+    N, K, xs, Wdq, gpu = small
+    check_linear(awq, xs[:M], Wdq, gpu, N)
+
+
+@pytest.mark.parametrize("N,K", [(16, 128), (16, 256), (32, 128), (128, 4096), (16, 28672)])
+def test_degenerate_shapes(awq, N, K):
+    case, s, xs = make_case(N, K, 40, 0.02, cfg=0, proj=1)
+    ref, gpu = assert_quantize_bit_exact(awq, case.W, s)
+    import oracle
+    Wdq = oracle.dequant(*ref)
+    for M in (1, 3, 16, 40):
+        check_linear(awq, xs[:M], Wdq, gpu, N)
+
+
+def test_linear_is_deterministic_and_exact_on_integer_data(awq):
+    """Small integers: every product and partial sum is exact in fp32, so the GPU result
+    must equal the oracle bit for bit, and twice in a row."""
+    import oracle
+    g = np.random.default_rng(11)
+    N, K = 64, 512
+    codes = g.integers(0, 16, size=(N, K), dtype=np.uint8)
+    scales = (2.0 ** g.integers(-3, 2, size=(N, K // 128))).astype(np.float16)
+    zeros = g.integers(0, 16, size=(N, K // 128), dtype=np.uint8)
+    q, sp, zp = oracle.pack(codes, scales, zeros)
+    gpu = (dev(q), dev(sp.view(np.float16)), dev(zp))
+    Wdq = oracle.dequant(codes, scales, zeros)
+    for M in (1, 5, 16, 33):
+        x = g.integers(-4, 5, size=(M, K)).astype(np.float16)
+        y_ref = oracle.matmul(x, Wdq)
+        assert np.abs(y_ref).max() < 60000          # finite in fp16; partial sums exact in fp32
+        y1 = host(awq.awq_w4a16_linear(dev(x), *gpu, N))
+        y2 = host(awq.awq_w4a16_linear(dev(x), *gpu, N))
+        assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+        assert np.array_equal(y1.astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
+
+
+# ----------------------------------------------------------------------------- a0 / a0'
+
+@pytest.mark.parametrize("T,K", [(64, 4096), (5, 136), (1000, 11008)])
+def test_act_scale_and_inverse_scale(awq, T, K):
+    import oracle
+    import workloads
+    out = workloads.outlier_channels(K, 0, 0, 2)
+    X = workloads.activations(T, K, 0, 0, 2, workloads.ROLE_CALIB, out)
+    for alpha in (0.5, 0.0, 1.0):
+        s_ref = oracle.act_scale(X, alpha)
+        s_gpu = host(awq.awq_act_scale(dev(X), alpha)).astype(np.float64)
+        assert np.abs(s_gpu / s_ref - 1.0).max() <= 2e-6
+    s = oracle.act_scale(X, 0.5).astype(np.float32)
+    x = X[: min(T, 16)]
+    xs_ref = oracle.apply_inv_scale(x, s)
+    xs_gpu = host(awq.awq_apply_inv_scale(dev(x), dev(s)))
+    assert np.array_equal(xs_gpu.view(np.uint16), xs_ref.view(np.uint16))
+
+
+def test_errors_surface_as_exceptions(awq):
+    import torch
+    W = torch.zeros((16, 100), dtype=torch.float16, device="cuda")
+    with pytest.raises(awq.AwqError) as e:
+        awq.awq_quantize_pack(W)
+    assert e.value.status == -2
