@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the AWQ W4A16 hot path on one MI355X.
+
+Headline workload (`config.workload`): the seven projections of one Llama-2-7B-shaped
+decoder layer (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), INT4 group-128
+weights, decode at M = 1.  One *step* is one pass over the seven linears of one layer; steps
+cycle through `--layers` distinct layers (> 800 MB of packed weights by default) so that
+every weight byte really comes from HBM and not from the 256 MB Infinity Cache.
+`value` is algorithmic bytes per step / time per step, in GB/s.
+
+Also measured in the same run and reported as sub-objects of the same JSON line:
+decode at M = 4 and 16, the M = 2048 prefill GEMM (TFLOP/s), awq_quantize_pack (GB/s), and
+the CPU oracle on the host cores (`cpu_baseline`).
+
+Everything timed goes through the C ABI (paper_2306_00978_amd -> libawq_mi355x.so).
+Only the cpu_baseline leg imports the oracle.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2516.6
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--layers", type=int, default=8, help="distinct layers cycled (cold cache)")
+    ap.add_argument("--no-graph", action="store_true", help="plain stream launches only")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="only the headline decode measurement (used under rocprofv3)")
+    ap.add_argument("--skip-cpu", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import workloads
+    import paper_2306_00978_amd as awq
+
+    awq.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    shapes = workloads.LLAMA2_7B_LAYER
+    L = max(1, args.layers)
+
+    # ------------------------------------------------------------------ inputs (resident in HBM)
+    # activations / calibration rows per distinct input width, from the seeded generator
+    s_by_k, x_by_k, calib_by_k = {}, {}, {}
+    for K in (4096, 11008):
+        out = workloads.outlier_channels(K, 1, 0, 0)
+        calib = workloads.activations(workloads.CALIB_TOKENS, K, 1, 0, 0, workloads.ROLE_CALIB, out)
+        x = workloads.activations(workloads.PREFILL_M, K, 1, 0, 0, workloads.ROLE_X, out)
+        calib_by_k[K] = calib
+        s = awq.awq_act_scale(torch.from_numpy(calib).to(dev), 0.5)
+        s_by_k[K] = s
+        x_by_k[K] = awq.awq_apply_inv_scale(torch.from_numpy(x).to(dev), s)
+
+    # weights: layer 0 from the numpy generator (also feeds the CPU baseline), the other
+    # layers from a seeded device generator with the same distribution
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(workloads.BASE_SEED)
+    layers = []
+    W0 = {}
+    quant_bytes = 0
+    quant_ms = 0.0
+    for l in range(L):
+        packed = []
+        for p, (name, N, K) in enumerate(shapes):
+            if l == 0:
+                Wh = workloads.weights(N, K, workloads.SIGMA_7B, 1, 0, p)
+                W0[p] = Wh
+                W = torch.from_numpy(Wh).to(dev)
+            else:
+                W = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
+                     * workloads.SIGMA_7B).to(torch.float16)
+            qb, sb, zb = awq.awq_packed_sizes(N, K)
+            out = (torch.empty(qb, dtype=torch.uint8, device=dev),
+                   torch.empty(sb // 2, dtype=torch.float16, device=dev),
+                   torch.empty(zb, dtype=torch.uint8, device=dev))
+            if l == 0:
+                awq.awq_quantize_pack(W, s_by_k[K], out=out)       # warm-up of the kernel
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            awq.awq_quantize_pack(W, s_by_k[K], out=out)
+            e1.record()
+            torch.cuda.synchronize()
+            quant_ms += e0.elapsed_time(e1)
+            quant_bytes += 2 * N * K + qb + sb + zb + 4 * K
+            packed.append(out)
+            del W
+        layers.append(packed)
+
+    plans = {}
+
+    def run_layer(l, M, ys):
+        key = (l, M)
+        if key not in plans:       # arguments marshalled once; the call itself is one C call
+            plans[key] = [awq.prepare_linear(x_by_k[K][:M], *layers[l][p], ys[p], N)
+                          for p, (name, N, K) in enumerate(shapes)]
+        for call in plans[key]:
+            call()
+
+    ys_by_m = {}
+
+    def step_bytes(M):
+        return sum(workloads.algorithmic_bytes(M, N, K) for _, N, K in shapes)
+
+    def time_decode(M, steps, warmup, use_graph):
+        ys = ys_by_m.setdefault(M, [torch.empty((M, N), dtype=torch.float16, device=dev)
+                                    for _, N, K in shapes])
+        graphs = None
+        if use_graph:
+            graphs = []
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run_layer(0, M, ys)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            for l in range(L):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    run_layer(l, M, ys)
+                graphs.append(g)
+
+        def one(i):
+            if graphs is not None:
+                graphs[i % L].replay()
+            else:
+                run_layer(i % L, M, ys)
+
+        for i in range(warmup):
+            one(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(steps):
+            one(warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        ev_ms = e0.elapsed_time(e1)
+        return wall_ms / steps, ev_ms / steps
+
+    use_graph = not args.no_graph
+    wall_ms, ev_ms = time_decode(1, args.steps, args.warmup, use_graph)
+    bytes_m1 = step_bytes(1)
+    value = bytes_m1 / (wall_ms * 1e-3) / 1e9
+    launches = len(shapes)
+    kernel_us = ev_ms * 1e3 / launches                     # average per launch, HIP events
+    achieved = bytes_m1 / launches / (kernel_us * 1e-6) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("decode_gemv_7b_m1_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "W4A16 decode GEMV HBM GB/s (Llama-2-7B layer shapes, M=1)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int4 weights, f16 activations, f32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": "configs[1]: 7 projections of one Llama-2-7B-shaped layer, M=1, "
+                        f"group 128, {L} distinct layers cycled (cold cache)",
+            "launch": "hipGraph replay of 7 launches per step" if use_graph else "plain stream",
+            "bytes_per_step": bytes_m1,
+            "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        },
+        "roofline": {
+            "kernel": "gemv_kernel (decode, M=1)",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": traffic,
+            "avg_launch_us": round(kernel_us, 3),
+            "algorithmic_bytes_per_launch": bytes_m1 // launches,
+        },
+    }
+
+    if not args.skip_extras:
+        extras = {}
+        if use_graph:
+            w2, e2 = time_decode(1, args.steps, args.warmup, False)
+            extras["decode_m1_plain_stream"] = {"ms_per_step": round(w2, 5),
+                                                "GB/s": round(bytes_m1 / (w2 * 1e-3) / 1e9, 1)}
+        for M in (4, 16):
+            w, e = time_decode(M, args.steps, args.warmup, use_graph)
+            b = step_bytes(M)
+            extras[f"decode_m{M}"] = {"ms_per_step": round(w, 5),
+                                      "GB/s": round(b / (w * 1e-3) / 1e9, 1),
+                                      "pct_of_hbm_peak": round(100 * b / (w * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+        # prefill GEMM, M = 2048, the three distinct shapes
+        M = workloads.PREFILL_M
+        pre = {}
+        tot_fl, tot_ms = 0, 0.0
+        for p in (0, 4, 6):
+            name, N, K = shapes[p]
+            y = torch.empty((M, N), dtype=torch.float16, device=dev)
+            q, sc, zp = layers[0][p]
+            for _ in range(3):
+                awq.awq_w4a16_linear(x_by_k[K], q, sc, zp, N, out=y)
+            torch.cuda.synchronize()
+            reps = 20
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(reps):
+                q, sc, zp = layers[i % L][p]
+                awq.awq_w4a16_linear(x_by_k[K], q, sc, zp, N, out=y)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            fl = workloads.flops(M, N, K)
+            pre[f"{N}x{K}"] = {"us": round(ms * 1e3, 2), "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1)}
+            tot_fl += fl
+            tot_ms += ms
+        tf = tot_fl / (tot_ms * 1e-3) / 1e12
+        extras["prefill_m2048"] = {"shapes": pre, "TFLOP/s": round(tf, 1),
+                                   "roofline": {"kernel": "gemm_kernel (prefill, M=2048)",
+                                                "bound": "mfma", "achieved": round(tf, 1),
+                                                "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                                "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}}
+        extras["quantize_pack"] = {"matrices": L * len(shapes), "ms_total": round(quant_ms, 3),
+                                   "GB/s": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
+                                   "pct_of_hbm_peak": round(100 * quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+        result["extras"] = extras
+
+    if not args.skip_cpu:
+        result["cpu_baseline"] = cpu_baseline(W0, calib_by_k, x_by_k, shapes)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(W0, calib_by_k, x_by_k, shapes):
+    """The oracle as it stands, on the host cores: one decode step (7 linears, M = 1) from the
+    packed arrays (unpack -> dequantize -> matmul), repeated for a bounded time."""
+    import numpy as np
+    import oracle
+    import workloads
+
+    cores = len(os.sched_getaffinity(0))
+    packed = []
+    for p, (name, N, K) in enumerate(shapes):
+        s = oracle.act_scale(calib_by_k[K], 0.5).astype(np.float32)
+        c, sc, z = oracle.quantize(W0[p], s)
+        packed.append(oracle.pack(c, sc, z))
+    xs = {K: x_by_k[K][:1].cpu().numpy() for K in x_by_k}
+    bytes_step = sum(workloads.algorithmic_bytes(1, N, K) for _, N, K in shapes)
+    reps, t_total = 0, 0.0
+    while reps < 2 or (t_total < 10.0 and reps < 50):
+        t0 = time.perf_counter()
+        for p, (name, N, K) in enumerate(shapes):
+            c, sc, z = oracle.unpack(*packed[p], N, K)
+            oracle.matmul(xs[K], oracle.dequant(c, sc, z))
+        t_total += time.perf_counter() - t0
+        reps += 1
+    omp = int(os.environ.get("OMP_NUM_THREADS", cores))
+    return {
+        "value": round(bytes_step * reps / t_total / 1e9, 3),
+        "unit": "GB/s",
+        "cores": min(cores, omp),
+        "kind": "oracle",
+        "sample": f"{reps} decode steps (7 projections of layer 0, M=1): unpack (1 thread) + "
+                  f"dequantize + fp64 matmul (OpenMP), {t_total:.1f} s of CPU time",
+    }
+
+
+if __name__ == "__main__":
+    main()

@@ -169,6 +169,36 @@ def awq_unpack(qweight, scales, zeros, N: int, K: int, group: int = GROUP):
     return codes, sc, zr
 
 
+def prepare_linear(x: torch.Tensor, qweight, scales, zeros, y: torch.Tensor, N: int,
+                   group: int = GROUP, workspace: torch.Tensor | None = None):
+    """Marshal the arguments of awq_w4a16_linear once and return a zero-argument callable
+    that enqueues the layer on the then-current stream (tight decode loops, graph capture).
+    The tensors must stay alive and in place for as long as the callable is used."""
+    _dev(x, torch.float16, "x")
+    _dev(y, torch.float16, "y")
+    M, K = x.shape
+    qb, sb, zb = awq_packed_sizes(N, K, group)
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+            or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
+        raise ValueError("buffer sizes do not match the shape")
+    need = awq_linear_workspace_bytes(M, N, K, group)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        raise ValueError(f"this shape needs a workspace of {need} bytes")
+    fn = load().awq_w4a16_linear
+    c = ctypes
+    fixed = (c.c_void_p(x.data_ptr()), c.c_void_p(qweight.data_ptr()), c.c_void_p(scales.data_ptr()),
+             c.c_void_p(zeros.data_ptr()), c.c_void_p(y.data_ptr()), c.c_int64(M), c.c_int64(N),
+             c.c_int64(K), c.c_int(group), c.c_void_p(workspace.data_ptr() if need else None),
+             c.c_size_t(workspace.numel() * workspace.element_size() if need else 0))
+    keep = (x, qweight, scales, zeros, y, workspace)
+
+    def call(_keep=keep):
+        st = fn(*fixed, c.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_w4a16_linear")
+    return call
+
+
 def awq_linear_workspace_bytes(M: int, N: int, K: int, group: int = GROUP) -> int:
     return int(load().awq_linear_workspace_bytes(M, N, K, group))
 
