@@ -2,7 +2,10 @@
 //
 // AWQ Sec. 4.2: generation is memory-bound and weight traffic dominates, so the
 // 4-bit weights are streamed once and dequantized on the fly inside the
-// matrix-vector kernel; nothing dequantized is written back to memory.
+// matrix-vector kernel; nothing dequantized is written back to memory.  The same
+// passage warns that dequantization (shift, AND, FMA per weight) costs more ALU
+// work than the product it feeds; the scheme below brings it to 5 vector
+// instructions per 8 weights.
 //
 // Mapping.  A workgroup owns one 16-row block of W (its tiles are contiguous along
 // K); its waves split the K/128 groups between them.  Per tile a lane issues one
@@ -13,12 +16,14 @@
 // tokens at the cost of one, and the k-reduction across lanes happens inside the
 // matrix core instead of through shuffles.
 //
-// Dequantization in registers: the nibble order of a word makes
-// (w >> {0,8}) & 0x000F000F | 0x6400.. the half pair (1024+q, 1024+q') and
-// & 0x00F000F0 | 0x5400.. the pair (64+q, 64+q'); subtracting (1024+z) / (64+z)
-// with one packed-half add each gives q - z exactly.  The MFMA accumulates
-// sum_k x*(q-z) per group in fp32 and the group's step is applied once per group
-// in fp32, so the only roundings are those of the fp32 accumulation.
+// Dequantization.  The nibble order of a word makes
+//   (w >> {0,8}) & 0x000F000F | 0x64006400  the half pair (1024+q, 1024+q')  and
+//   (w >> {0,8}) & 0x00F000F0 | 0x54005400  the half pair (  64+q,   64+q'),
+// one v_and_or_b32 each.  These biased halves go to the matrix core as they are, and
+// a second MFMA with the constant fragment -(1024+z), -(64+z) takes the bias and the
+// zero point out again:  sum_k x_k (1024 + q_k) - sum_k x_k (1024 + z) = sum_k x_k (q_k - z).
+// All products are exact in fp32; the two chains alternate so the running sum stays
+// small.  The group's step is applied once per group in fp32.
 //
 // The partial sums of the waves are combined through LDS in a fixed order
 // (deterministic output), rounded once to fp16 and stored.
@@ -28,32 +33,75 @@
 
 namespace {
 
-__device__ __forceinline__ half8_t expand_word(uint32_t w, uint32_t zA, uint32_t zB)
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t bits)
 {
-    const uint32_t w8 = w >> 8;
-    const uint32_t t0 = (w & 0x000F000Fu) | 0x64006400u;
-    const uint32_t t1 = (w & 0x00F000F0u) | 0x54005400u;
-    const uint32_t t2 = (w8 & 0x000F000Fu) | 0x64006400u;
-    const uint32_t t3 = (w8 & 0x00F000F0u) | 0x54005400u;
-    const half2_t a = __builtin_bit_cast(half2_t, zA), b = __builtin_bit_cast(half2_t, zB);
-    const half2_t d0 = __builtin_bit_cast(half2_t, t0) - a;
-    const half2_t d1 = __builtin_bit_cast(half2_t, t1) - b;
-    const half2_t d2 = __builtin_bit_cast(half2_t, t2) - a;
-    const half2_t d3 = __builtin_bit_cast(half2_t, t3) - b;
-    half8_t out;
-    out[0] = d0[0]; out[1] = d0[1]; out[2] = d1[0]; out[3] = d1[1];
-    out[4] = d2[0]; out[5] = d2[1]; out[6] = d3[0]; out[7] = d3[1];
-    return out;
+    uint32_t d;   // the mask sits in an SGPR, the OR-ed bits in a VGPR (one constant-bus read)
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(bits));
+    return d;
 }
 
-// U = tiles (groups) a wave keeps in flight per loop trip.
+// Eight codes of one packed word -> eight biased halves, in k order.
+__device__ __forceinline__ half8_t biased_halves(uint32_t w, uint32_t magA, uint32_t magB)
+{
+    const uint32_t w8 = w >> 8;
+    uint4 t;
+    t.x = and_or(w, 0x000F000Fu, magA);    // 1024 + (e0, e1)
+    t.y = and_or(w, 0x00F000F0u, magB);    //   64 + (e2, e3)
+    t.z = and_or(w8, 0x000F000Fu, magA);   // 1024 + (e4, e5)
+    t.w = and_or(w8, 0x00F000F0u, magB);   //   64 + (e6, e7)
+    return __builtin_bit_cast(half8_t, t);
+}
+
+// One batch of U tiles of a wave, as loaded from global memory.  The step and zero point
+// are fetched with ONE 2-byte and ONE 1-byte load per lane for the whole batch: lane
+// (r, c) fetches those of row r of group base+c, turns them into the three per-tile
+// constants, and tile u later takes them from lane r + 16u with cross-lane permutes.
 template <int U>
+struct TileBatch {
+    uint4 q[U];
+    uint32_t s_raw, z_raw;
+};
+
+template <int U>
+__device__ __forceinline__ void load_batch(TileBatch<U> &b, const uint4 *qt, const uint16_t *sc,
+                                           const uint8_t *zp, int base, int g1, int c)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int g = base + u < g1 ? base + u : g1 - 1;
+        b.q[u] = qt[g * 64];
+    }
+    const int gl = base + c < g1 ? base + c : g1 - 1;
+    b.s_raw = sc[gl * 16];
+    b.z_raw = zp[gl * 8];
+}
+
+constexpr int GEMV_STAGE_MAX_M = 4;   // activations of up to this many rows go through LDS
+
+// Decode kernel.  U = tiles (groups) a wave keeps in flight per loop trip (<= 4).
+//
+// MS > 0 (M <= MS <= 4): each wave copies the slice of x that its batch of U tiles needs
+// (MS rows x U*128 halves; rows >= M repeat row M-1) into a private LDS area with ONE
+// coalesced 16-byte load per lane and row, issued before the weight loads so that it
+// returns first, and then reads its A fragments from LDS.  No workgroup barrier is
+// involved, so a wave starts computing as soon as its own weights arrive.  With few rows
+// most lanes of an A fragment are duplicates, which is why this is cheaper than loading
+// fragments from global memory.
+// MS == 0 (M > 4): A fragments are loaded straight from global memory (L2 hits).
+//
+// Dynamic LDS: [W][MS rows x (U*256 + 16) bytes], then 16*M outputs x 16 wave slots of
+// fp32 for the cross-wave reduction.
+template <int U, int MS>
 __global__ __launch_bounds__(1024) void gemv_kernel(
     const half_t *__restrict__ x, const uint4 *__restrict__ qweight,
     const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
     half_t *__restrict__ y, int M, int N, int K, int G)
 {
-    __shared__ float red[16][4][64];
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr bool STAGE = MS > 0;
+    constexpr int NS = STAGE ? MS : 1;
+    constexpr int ROW_BYTES = U * 256 + 16;           // +16: rows land on different banks
+    constexpr int WAVE_BYTES = MS * ROW_BYTES;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int W = blockDim.x >> 6;
@@ -65,70 +113,115 @@ __global__ __launch_bounds__(1024) void gemv_kernel(
     const uint16_t *sc = scales + (int64_t)rb * G * 16 + r;
     const uint8_t *zp = zeros + (int64_t)rb * G * 8 + (r >> 1);
     const int zshift = (r & 1) * 4;
-    // A-operand row m = lane%16.  Rows >= M read a valid row instead of zeros: row m of
-    // the MFMA result depends on row m of A only, and rows >= M are never stored.
-    const uint4 *xr = reinterpret_cast<const uint4 *>(x + (int64_t)(r < M ? r : M - 1) * K + 8 * c);
 
+    // A-operand row m = lane%16.  Rows >= M use row M-1 instead of zeros: row m of the MFMA
+    // result depends on row m of A only, and rows >= M are never stored.
+    const int mrow = r < M ? r : M - 1;
+    unsigned char *xw = smem + (size_t)wave * WAVE_BYTES;                 // this wave's x slice
+    const uint4 *xl = reinterpret_cast<const uint4 *>(xw + mrow * ROW_BYTES) + c;
+    const uint4 *xg = reinterpret_cast<const uint4 *>(x + (int64_t)mrow * K) + c;
+    const int K8 = K >> 3;
+
+    // staging source of this lane: row m (clamped to M-1), 16-byte chunk `lane` of the batch
+    const uint4 *xsrc[NS];
+#pragma unroll
+    for (int m = 0; m < NS; ++m)
+        xsrc[m] = reinterpret_cast<const uint4 *>(x + (int64_t)(m < M ? m : M - 1) * K);
+    // lanes past the end of K (last, short batch) re-read the last chunk of the row
+#define AWQ_STAGE_LOAD(base_)                                                   \
+    if (STAGE && (U == 4 || lane < U * 16)) {                                   \
+        int chunk_ = (base_) * 16 + lane;                                       \
+        chunk_ = chunk_ < K8 ? chunk_ : K8 - 1;                                 \
+        _Pragma("unroll") for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][chunk_]; \
+    }
+
+    TileBatch<U> cur;
+    uint4 xs[NS];
+#pragma unroll
+    for (int m = 0; m < NS; ++m) xs[m] = make_uint4(0, 0, 0, 0);
+    if (g0 < g1) {
+        AWQ_STAGE_LOAD(g0)                         // first: it must not wait for the weights
+        load_batch<U>(cur, qt, sc, zp, g0, g1, c);
+    }
+
+    const uint32_t magA = 0x64006400u, magB = 0x54005400u;
     floatx4 total = {0.f, 0.f, 0.f, 0.f};
     for (int base = g0; base < g1; base += U) {
-        uint4 q[U];
-        float sv[U];
-        uint32_t zv[U];
-        int gi[U];
+        if (STAGE && (U == 4 || lane < U * 16)) {  // LDS ops of one wave execute in order
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int g = base + u;
-            gi[u] = g < g1 ? g : g1 - 1;
-            q[u] = qt[(int64_t)gi[u] * 64];
+            for (int m = 0; m < NS; ++m) reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[lane] = xs[m];
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const half_t sh = __builtin_bit_cast(half_t, sc[gi[u] * 16]);
-            sv[u] = (base + u < g1) ? (float)sh : 0.0f;
-            zv[u] = (zp[gi[u] * 8] >> zshift) & 0xFu;
+        TileBatch<U> nxt;
+        const bool more = base + U < g1;
+        if (more) {
+            AWQ_STAGE_LOAD(base + U)
+            load_batch<U>(nxt, qt, sc, zp, base + U, g1, c);
         }
+        // constants of (group base+c, row r), computed once per batch by their owner lane
+        const uint32_t z = (cur.z_raw >> zshift) & 0xFu;
+        const uint32_t own_nzA = 0xE400E400u | (z * 0x00010001u);      // -(1024 + z) twice
+        const uint32_t own_nzB = 0xD400D400u | (z * 0x00100010u);      // -(  64 + z) twice
+        const float own_sv = (base + c < g1)
+            ? (float)__builtin_bit_cast(half_t, (uint16_t)cur.s_raw) : 0.0f;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            const int g = base + u < g1 ? base + u : g1 - 1;
             uint4 xa[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                // k = 128*g + 32*j + 8*c + 0..7  ->  16-byte run index 16*g + 4*j (+c folded in xr)
-                xa[j] = xr[gi[u] * 16 + 4 * j];
+                // k = 128g + 32j + 8c + 0..7 -> 16-byte chunk 16g + 4j (+c folded into xl/xg)
+                xa[j] = STAGE ? xl[u * 16 + 4 * j] : xg[g * 16 + 4 * j];
             }
-            const uint32_t zA = 0x64006400u | (zv[u] * 0x00010001u);
-            const uint32_t zB = 0x54005400u | (zv[u] * 0x00100010u);
-            const uint32_t words[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+            const int src = r + 16 * u;
+            const uint32_t nzA = __shfl(own_nzA, src);
+            const uint32_t nzB = __shfl(own_nzB, src);
+            const float sv = __shfl(own_sv, src);
+            const half8_t nb = __builtin_bit_cast(half8_t, make_uint4(nzA, nzB, nzA, nzB));
+            const uint32_t words[4] = {cur.q[u].x, cur.q[u].y, cur.q[u].z, cur.q[u].w};
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const half8_t b = expand_word(words[j], zA, zB);
                 const half8_t a = __builtin_bit_cast(half8_t, xa[j]);
+                const half8_t b = biased_halves(words[j], magA, magB);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, nb, acc, 0, 0, 0);
             }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) total[v] += sv[u] * acc[v];
+            for (int v = 0; v < 4; ++v) total[v] += sv * acc[v];
         }
+        if (more) cur = nxt;
     }
+#undef AWQ_STAGE_LOAD
 
-    // lane holds y[m = 4*c + v][n = 16*rb + r] partials; combine the waves in order
+    // lane holds the partial y[m = 4c + v][n = 16 rb + r]; combine the waves in fixed order.
+    // red[t][w], t = 16 m + n: the 16 partials of one output are contiguous.
+    float *red = reinterpret_cast<float *>(smem + (size_t)W * WAVE_BYTES);
+    if (4 * c < M) {
 #pragma unroll
-    for (int v = 0; v < 4; ++v) red[wave][v][lane] = total[v];
-    __syncthreads();
-    for (int t = threadIdx.x; t < 256; t += blockDim.x) {
-        const int v = t >> 6, l = t & 63;
-        float sum = 0.f;
-        for (int w = 0; w < W; ++w) sum += red[w][v][l];
-        const int m = 4 * (l >> 4) + v;
-        if (m < M) y[(int64_t)m * N + rb * 16 + (l & 15)] = (half_t)sum;
+        for (int v = 0; v < 4; ++v) red[((4 * c + v) * 16 + r) * 16 + wave] = total[v];
     }
+    __syncthreads();
+    for (int t = threadIdx.x; t < 16 * M; t += blockDim.x) {
+        const float4 *p = reinterpret_cast<const float4 *>(red + t * 16);
+        const float4 a0 = p[0], a1 = p[1], a2 = p[2], a3 = p[3];
+        const float part[16] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w,
+                                a2.x, a2.y, a2.z, a2.w, a3.x, a3.y, a3.z, a3.w};
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) sum += (w < W) ? part[w] : 0.f;
+        y[(int64_t)(t >> 4) * N + rb * 16 + (t & 15)] = (half_t)sum;
+    }
+}
+
+int env_int(const char *name)
+{
+    const char *e = getenv(name);
+    return e ? atoi(e) : 0;
 }
 
 int pick_waves(int G)
 {
-    static const int forced = [] {
-        const char *e = getenv("AWQ_GEMV_WAVES");
-        return e ? atoi(e) : 0;
-    }();
+    static const int forced = env_int("AWQ_GEMV_WAVES");
     if (forced >= 1 && forced <= 16) return forced;
     int w = (G + 3) / 4;
     if (w < 4) w = 4;
@@ -138,10 +231,7 @@ int pick_waves(int G)
 
 int pick_unroll(int G, int W)
 {
-    static const int forced = [] {
-        const char *e = getenv("AWQ_GEMV_UNROLL");
-        return e ? atoi(e) : 0;
-    }();
+    static const int forced = env_int("AWQ_GEMV_UNROLL");
     if (forced >= 2 && forced <= 4) return forced;
     const int cnt = (G + W - 1) / W;
     int best = 4, waste = 1 << 30;
@@ -162,13 +252,25 @@ int awq_gemv_launch(const void *x, const void *qweight, const void *scales, cons
     const int W = pick_waves(G);
     const int U = pick_unroll(G, W);
     const dim3 grid(N / 16), block(W * 64);
+    const int MS = M > GEMV_STAGE_MAX_M ? 0 : (M == 1 ? 1 : (M == 2 ? 2 : 4));
+    // reduction area: 16*M outputs x 16 wave slots x 4 bytes, after the staging areas
+    const size_t lds = (size_t)M * 1024 + (size_t)W * MS * (U * 256 + 16);
 #define AWQ_GEMV_ARGS (const half_t *)x, (const uint4 *)qweight, (const uint16_t *)scales, \
                       (const uint8_t *)zeros, (half_t *)y, M, N, K, G
+#define AWQ_GEMV_CASE(UU)                                                                   \
+    case UU:                                                                                \
+        if (MS == 1) gemv_kernel<UU, 1><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS);       \
+        else if (MS == 2) gemv_kernel<UU, 2><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS);  \
+        else if (MS == 4) gemv_kernel<UU, 4><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS);  \
+        else gemv_kernel<UU, 0><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS);               \
+        break;
     switch (U) {
-    case 2: gemv_kernel<2><<<grid, block, 0, stream>>>(AWQ_GEMV_ARGS); break;
-    case 3: gemv_kernel<3><<<grid, block, 0, stream>>>(AWQ_GEMV_ARGS); break;
-    default: gemv_kernel<4><<<grid, block, 0, stream>>>(AWQ_GEMV_ARGS); break;
+    AWQ_GEMV_CASE(2)
+    AWQ_GEMV_CASE(3)
+    default:
+    AWQ_GEMV_CASE(4)
     }
+#undef AWQ_GEMV_CASE
 #undef AWQ_GEMV_ARGS
     return awq_launch_status();
 }
