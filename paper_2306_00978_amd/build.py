@@ -49,7 +49,12 @@ def build(verbose: bool = False, save_temps: bool = False) -> str:
         objs.append(obj)
     failed = False
     for src, p in procs:
-        out, _ = p.communicate()
+        try:
+            out, _ = p.communicate(timeout=900)
+        except subprocess.TimeoutExpired:
+            p.kill()
+            out, _ = p.communicate()
+            out += "\n[build] compiler timed out after 900 s"
         out = "\n".join(l for l in out.splitlines()
                         if "packed-fp32-ops" not in l and l.strip())
         if p.returncode != 0:

@@ -33,22 +33,33 @@
 
 namespace {
 
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t bits)
+// The four constants of the expansion, held in registers.  They are made opaque to the
+// optimizer so that (w & mask) | bits is selected as ONE v_and_or_b32 (mask in an SGPR,
+// bits in a VGPR) instead of a v_and_b32 and a v_or_b32 with literal operands.
+struct ExpandConsts {
+    uint32_t mask_lo, mask_hi;   // 0x000F000F, 0x00F000F0  (SGPR)
+    uint32_t magA, magB;         // 0x64006400, 0x54005400  (VGPR)
+};
+
+__device__ __forceinline__ ExpandConsts expand_consts()
 {
-    uint32_t d;   // the mask sits in an SGPR, the OR-ed bits in a VGPR (one constant-bus read)
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(bits));
-    return d;
+    ExpandConsts k = {0x000F000Fu, 0x00F000F0u, 0x64006400u, 0x54005400u};
+    asm("" : "+s"(k.mask_lo));
+    asm("" : "+s"(k.mask_hi));
+    asm("" : "+v"(k.magA));
+    asm("" : "+v"(k.magB));
+    return k;
 }
 
 // Eight codes of one packed word -> eight biased halves, in k order.
-__device__ __forceinline__ half8_t biased_halves(uint32_t w, uint32_t magA, uint32_t magB)
+__device__ __forceinline__ half8_t biased_halves(uint32_t w, const ExpandConsts &k)
 {
     const uint32_t w8 = w >> 8;
     uint4 t;
-    t.x = and_or(w, 0x000F000Fu, magA);    // 1024 + (e0, e1)
-    t.y = and_or(w, 0x00F000F0u, magB);    //   64 + (e2, e3)
-    t.z = and_or(w8, 0x000F000Fu, magA);   // 1024 + (e4, e5)
-    t.w = and_or(w8, 0x00F000F0u, magB);   //   64 + (e6, e7)
+    t.x = (w & k.mask_lo) | k.magA;    // 1024 + (e0, e1)
+    t.y = (w & k.mask_hi) | k.magB;    //   64 + (e2, e3)
+    t.z = (w8 & k.mask_lo) | k.magA;   // 1024 + (e4, e5)
+    t.w = (w8 & k.mask_hi) | k.magB;   //   64 + (e6, e7)
     return __builtin_bit_cast(half8_t, t);
 }
 
@@ -66,14 +77,16 @@ template <int U>
 __device__ __forceinline__ void load_batch(TileBatch<U> &b, const uint4 *qt, const uint16_t *sc,
                                            const uint8_t *zp, int base, int g1, int c)
 {
+    // the two small loads go first: loads return in order, and the first tile can only be
+    // consumed once its step and zero point are there
+    const int gl = base + c < g1 ? base + c : g1 - 1;
+    b.s_raw = sc[gl * 16];
+    b.z_raw = zp[gl * 8];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int g = base + u < g1 ? base + u : g1 - 1;
         b.q[u] = qt[g * 64];
     }
-    const int gl = base + c < g1 ? base + c : g1 - 1;
-    b.s_raw = sc[gl * 16];
-    b.z_raw = zp[gl * 8];
 }
 
 constexpr int GEMV_STAGE_MAX_M = 4;   // activations of up to this many rows go through LDS
@@ -91,13 +104,14 @@ constexpr int GEMV_STAGE_MAX_M = 4;   // activations of up to this many rows go 
 //
 // Dynamic LDS: [W][MS rows x (U*256 + 16) bytes], then 16*M outputs x 16 wave slots of
 // fp32 for the cross-wave reduction.
-template <int U, int MS>
+template <int U, int MS, bool PIPE>
 __global__ __launch_bounds__(1024) void gemv_kernel(
     const half_t *__restrict__ x, const uint4 *__restrict__ qweight,
     const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
     half_t *__restrict__ y, int M, int N, int K, int G)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    const ExpandConsts kc = expand_consts();
     constexpr bool STAGE = MS > 0;
     constexpr int NS = STAGE ? MS : 1;
     constexpr int ROW_BYTES = U * 256 + 16;           // +16: rows land on different banks
@@ -144,15 +158,16 @@ __global__ __launch_bounds__(1024) void gemv_kernel(
         load_batch<U>(cur, qt, sc, zp, g0, g1, c);
     }
 
-    const uint32_t magA = 0x64006400u, magB = 0x54005400u;
     floatx4 total = {0.f, 0.f, 0.f, 0.f};
     for (int base = g0; base < g1; base += U) {
         if (STAGE && (U == 4 || lane < U * 16)) {  // LDS ops of one wave execute in order
 #pragma unroll
             for (int m = 0; m < NS; ++m) reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[lane] = xs[m];
         }
+        // PIPE: the next batch is requested before this one is consumed (waves with more
+        // than one batch); otherwise the single batch was requested above.
         TileBatch<U> nxt;
-        const bool more = base + U < g1;
+        const bool more = PIPE && base + U < g1;
         if (more) {
             AWQ_STAGE_LOAD(base + U)
             load_batch<U>(nxt, qt, sc, zp, base + U, g1, c);
@@ -182,7 +197,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const half8_t a = __builtin_bit_cast(half8_t, xa[j]);
-                const half8_t b = biased_halves(words[j], magA, magB);
+                const half8_t b = biased_halves(words[j], kc);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, nb, acc, 0, 0, 0);
             }
@@ -190,6 +205,10 @@ __global__ __launch_bounds__(1024) void gemv_kernel(
             for (int v = 0; v < 4; ++v) total[v] += sv * acc[v];
         }
         if (more) cur = nxt;
+        if (!PIPE && base + U < g1) {
+            AWQ_STAGE_LOAD(base + U)
+            load_batch<U>(cur, qt, sc, zp, base + U, g1, c);
+        }
     }
 #undef AWQ_STAGE_LOAD
 
@@ -252,17 +271,26 @@ int awq_gemv_launch(const void *x, const void *qweight, const void *scales, cons
     const int W = pick_waves(G);
     const int U = pick_unroll(G, W);
     const dim3 grid(N / 16), block(W * 64);
+    const bool pipe = (G + W - 1) / W > U;          // some wave has more than one batch
     const int MS = M > GEMV_STAGE_MAX_M ? 0 : (M == 1 ? 1 : (M == 2 ? 2 : 4));
     // reduction area: 16*M outputs x 16 wave slots x 4 bytes, after the staging areas
     const size_t lds = (size_t)M * 1024 + (size_t)W * MS * (U * 256 + 16);
 #define AWQ_GEMV_ARGS (const half_t *)x, (const uint4 *)qweight, (const uint16_t *)scales, \
                       (const uint8_t *)zeros, (half_t *)y, M, N, K, G
+#define AWQ_GEMV_LAUNCH(UU, MM, PP) gemv_kernel<UU, MM, PP><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS)
 #define AWQ_GEMV_CASE(UU)                                                                   \
     case UU:                                                                                \
-        if (MS == 1) gemv_kernel<UU, 1><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS);       \
-        else if (MS == 2) gemv_kernel<UU, 2><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS);  \
-        else if (MS == 4) gemv_kernel<UU, 4><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS);  \
-        else gemv_kernel<UU, 0><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS);               \
+        if (pipe) {                                                                         \
+            if (MS == 1) AWQ_GEMV_LAUNCH(UU, 1, true);                                      \
+            else if (MS == 2) AWQ_GEMV_LAUNCH(UU, 2, true);                                 \
+            else if (MS == 4) AWQ_GEMV_LAUNCH(UU, 4, true);                                 \
+            else AWQ_GEMV_LAUNCH(UU, 0, true);                                              \
+        } else {                                                                            \
+            if (MS == 1) AWQ_GEMV_LAUNCH(UU, 1, false);                                     \
+            else if (MS == 2) AWQ_GEMV_LAUNCH(UU, 2, false);                                \
+            else if (MS == 4) AWQ_GEMV_LAUNCH(UU, 4, false);                                \
+            else AWQ_GEMV_LAUNCH(UU, 0, false);                                             \
+        }                                                                                   \
         break;
     switch (U) {
     AWQ_GEMV_CASE(2)
@@ -271,6 +299,7 @@ int awq_gemv_launch(const void *x, const void *qweight, const void *scales, cons
     AWQ_GEMV_CASE(4)
     }
 #undef AWQ_GEMV_CASE
+#undef AWQ_GEMV_LAUNCH
 #undef AWQ_GEMV_ARGS
     return awq_launch_status();
 }
