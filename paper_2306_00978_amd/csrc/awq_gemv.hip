@@ -63,10 +63,12 @@ __device__ __forceinline__ half8_t biased_halves(uint32_t w, const ExpandConsts 
     return __builtin_bit_cast(half8_t, t);
 }
 
-// One batch of U tiles of a wave, as loaded from global memory.  The step and zero point
-// are fetched with ONE 2-byte and ONE 1-byte load per lane for the whole batch: lane
-// (r, c) fetches those of row r of group base+c, turns them into the three per-tile
-// constants, and tile u later takes them from lane r + 16u with cross-lane permutes.
+// One batch of U consecutive tiles (groups) of a wave, as loaded from global memory.  The
+// tiles of a row block are contiguous along K, so the U loads differ by a constant 1 KB.
+// The step and zero point are fetched with ONE 2-byte and ONE 1-byte load per lane for the
+// whole batch: lane (r, c) fetches those of row r of group base + min(c, U-1), turns them
+// into the three per-tile constants, and tile u later takes them from lane r + 16u with
+// cross-lane permutes.
 template <int U>
 struct TileBatch {
     uint4 q[U];
@@ -75,40 +77,39 @@ struct TileBatch {
 
 template <int U>
 __device__ __forceinline__ void load_batch(TileBatch<U> &b, const uint4 *qt, const uint16_t *sc,
-                                           const uint8_t *zp, int base, int g1, int c)
+                                           const uint8_t *zp, int base)
 {
     // the two small loads go first: loads return in order, and the first tile can only be
     // consumed once its step and zero point are there
-    const int gl = base + c < g1 ? base + c : g1 - 1;
-    b.s_raw = sc[gl * 16];
-    b.z_raw = zp[gl * 8];
+    b.s_raw = sc[base * 16];
+    b.z_raw = zp[base * 8];
+    const uint4 *p = qt + base * 64;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int g = base + u < g1 ? base + u : g1 - 1;
-        b.q[u] = qt[g * 64];
-    }
+    for (int u = 0; u < U; ++u) b.q[u] = p[u * 64];
 }
 
 constexpr int GEMV_STAGE_MAX_M = 4;   // activations of up to this many rows go through LDS
 
-// Decode kernel.  U = tiles (groups) a wave keeps in flight per loop trip (<= 4).
-//
-// MS > 0 (M <= MS <= 4): each wave copies the slice of x that its batch of U tiles needs
-// (MS rows x U*128 halves; rows >= M repeat row M-1) into a private LDS area with ONE
-// coalesced 16-byte load per lane and row, issued before the weight loads so that it
-// returns first, and then reads its A fragments from LDS.  No workgroup barrier is
-// involved, so a wave starts computing as soon as its own weights arrive.  With few rows
-// most lanes of an A fragment are duplicates, which is why this is cheaper than loading
-// fragments from global memory.
+// Decode kernel.
+// U     = tiles (groups) per batch, a divisor of G: 1, 2 or 4.  A wave owns whole batches.
+// PIPE  = double-buffer the batches (only worth its registers when a wave has several).
+// MS > 0 (M <= MS <= 4): each wave copies the slice of x that its batch needs (MS rows x
+//   U*128 halves; rows >= M repeat row M-1) into a private LDS area with ONE coalesced
+//   16-byte load per lane and row, issued before the weight loads so that it returns first,
+//   and then reads its A fragments from LDS.  No workgroup barrier is involved, so a wave
+//   starts computing as soon as its own weights arrive.  With few rows most lanes of an A
+//   fragment are duplicates, which is why this is cheaper than loading fragments from
+//   global memory.
 // MS == 0 (M > 4): A fragments are loaded straight from global memory (L2 hits).
 //
+// The workgroup has W = 2^logW waves; wave w owns batches [NB*w/W, NB*(w+1)/W), NB = G/U.
 // Dynamic LDS: [W][MS rows x (U*256 + 16) bytes], then 16*M outputs x 16 wave slots of
 // fp32 for the cross-wave reduction.
 template <int U, int MS, bool PIPE>
-__global__ __launch_bounds__(1024) void gemv_kernel(
+__global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void gemv_kernel(
     const half_t *__restrict__ x, const uint4 *__restrict__ qweight,
     const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
-    half_t *__restrict__ y, int M, int N, int K, int G)
+    half_t *__restrict__ y, int M, int N, int K, int G, int logW)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const ExpandConsts kc = expand_consts();
@@ -118,14 +119,16 @@ __global__ __launch_bounds__(1024) void gemv_kernel(
     constexpr int WAVE_BYTES = MS * ROW_BYTES;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
-    const int W = blockDim.x >> 6;
+    const int W = 1 << logW;
     const int rb = blockIdx.x;
     const int r = lane & 15, c = lane >> 4;
+    const int cu = c < U ? c : U - 1;                 // group of the batch this lane fetches meta for
 
-    const int g0 = (G * wave) / W, g1 = (G * (wave + 1)) / W;
+    const int NB = G / U;
+    const int g0 = ((NB * wave) >> logW) * U, g1 = ((NB * (wave + 1)) >> logW) * U;
     const uint4 *qt = qweight + (int64_t)rb * G * 64 + lane;
-    const uint16_t *sc = scales + (int64_t)rb * G * 16 + r;
-    const uint8_t *zp = zeros + (int64_t)rb * G * 8 + (r >> 1);
+    const uint16_t *sc = scales + (int64_t)rb * G * 16 + cu * 16 + r;
+    const uint8_t *zp = zeros + (int64_t)rb * G * 8 + cu * 8 + (r >> 1);
     const int zshift = (r & 1) * 4;
 
     // A-operand row m = lane%16.  Rows >= M use row M-1 instead of zeros: row m of the MFMA
@@ -134,58 +137,54 @@ __global__ __launch_bounds__(1024) void gemv_kernel(
     unsigned char *xw = smem + (size_t)wave * WAVE_BYTES;                 // this wave's x slice
     const uint4 *xl = reinterpret_cast<const uint4 *>(xw + mrow * ROW_BYTES) + c;
     const uint4 *xg = reinterpret_cast<const uint4 *>(x + (int64_t)mrow * K) + c;
-    const int K8 = K >> 3;
+    const bool stager = STAGE && (U == 4 || lane < U * 16);
 
     // staging source of this lane: row m (clamped to M-1), 16-byte chunk `lane` of the batch
     const uint4 *xsrc[NS];
 #pragma unroll
     for (int m = 0; m < NS; ++m)
-        xsrc[m] = reinterpret_cast<const uint4 *>(x + (int64_t)(m < M ? m : M - 1) * K);
-    // lanes past the end of K (last, short batch) re-read the last chunk of the row
-#define AWQ_STAGE_LOAD(base_)                                                   \
-    if (STAGE && (U == 4 || lane < U * 16)) {                                   \
-        int chunk_ = (base_) * 16 + lane;                                       \
-        chunk_ = chunk_ < K8 ? chunk_ : K8 - 1;                                 \
-        _Pragma("unroll") for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][chunk_]; \
-    }
+        xsrc[m] = reinterpret_cast<const uint4 *>(x + (int64_t)(m < M ? m : M - 1) * K) + lane;
 
     TileBatch<U> cur;
     uint4 xs[NS];
 #pragma unroll
     for (int m = 0; m < NS; ++m) xs[m] = make_uint4(0, 0, 0, 0);
     if (g0 < g1) {
-        AWQ_STAGE_LOAD(g0)                         // first: it must not wait for the weights
-        load_batch<U>(cur, qt, sc, zp, g0, g1, c);
+        if (stager) {                              // first: it must not wait for the weights
+#pragma unroll
+            for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][g0 * 16];
+        }
+        load_batch<U>(cur, qt, sc, zp, g0);
     }
 
     floatx4 total = {0.f, 0.f, 0.f, 0.f};
     for (int base = g0; base < g1; base += U) {
-        if (STAGE && (U == 4 || lane < U * 16)) {  // LDS ops of one wave execute in order
+        if (stager) {                              // LDS ops of one wave execute in order
 #pragma unroll
             for (int m = 0; m < NS; ++m) reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[lane] = xs[m];
         }
-        // PIPE: the next batch is requested before this one is consumed (waves with more
-        // than one batch); otherwise the single batch was requested above.
+        // PIPE: the next batch is requested before this one is consumed
         TileBatch<U> nxt;
-        const bool more = PIPE && base + U < g1;
-        if (more) {
-            AWQ_STAGE_LOAD(base + U)
-            load_batch<U>(nxt, qt, sc, zp, base + U, g1, c);
+        const bool more = base + U < g1;
+        if (PIPE && more) {
+            if (stager) {
+#pragma unroll
+                for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][(base + U) * 16];
+            }
+            load_batch<U>(nxt, qt, sc, zp, base + U);
         }
-        // constants of (group base+c, row r), computed once per batch by their owner lane
+        // constants of (group base + cu, row r), computed once per batch by their owner lane
         const uint32_t z = (cur.z_raw >> zshift) & 0xFu;
         const uint32_t own_nzA = 0xE400E400u | (z * 0x00010001u);      // -(1024 + z) twice
         const uint32_t own_nzB = 0xD400D400u | (z * 0x00100010u);      // -(  64 + z) twice
-        const float own_sv = (base + c < g1)
-            ? (float)__builtin_bit_cast(half_t, (uint16_t)cur.s_raw) : 0.0f;
+        const float own_sv = (float)__builtin_bit_cast(half_t, (uint16_t)cur.s_raw);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int g = base + u < g1 ? base + u : g1 - 1;
             uint4 xa[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 // k = 128g + 32j + 8c + 0..7 -> 16-byte chunk 16g + 4j (+c folded into xl/xg)
-                xa[j] = STAGE ? xl[u * 16 + 4 * j] : xg[g * 16 + 4 * j];
+                xa[j] = STAGE ? xl[u * 16 + 4 * j] : xg[(base + u) * 16 + 4 * j];
             }
             const int src = r + 16 * u;
             const uint32_t nzA = __shfl(own_nzA, src);
@@ -204,13 +203,16 @@ __global__ __launch_bounds__(1024) void gemv_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) total[v] += sv * acc[v];
         }
-        if (more) cur = nxt;
-        if (!PIPE && base + U < g1) {
-            AWQ_STAGE_LOAD(base + U)
-            load_batch<U>(cur, qt, sc, zp, base + U, g1, c);
+        if (PIPE) {
+            if (more) cur = nxt;
+        } else if (more) {
+            if (stager) {
+#pragma unroll
+                for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][(base + U) * 16];
+            }
+            load_batch<U>(cur, qt, sc, zp, base + U);
         }
     }
-#undef AWQ_STAGE_LOAD
 
     // lane holds the partial y[m = 4c + v][n = 16 rb + r]; combine the waves in fixed order.
     // red[t][w], t = 16 m + n: the 16 partials of one output are contiguous.
@@ -238,27 +240,23 @@ int env_int(const char *name)
     return e ? atoi(e) : 0;
 }
 
-int pick_waves(int G)
+// log2 of the waves per workgroup: about four tiles per wave, 4..16 waves
+int pick_log_waves(int G)
 {
     static const int forced = env_int("AWQ_GEMV_WAVES");
-    if (forced >= 1 && forced <= 16) return forced;
-    int w = (G + 3) / 4;
-    if (w < 4) w = 4;
-    if (w > 16) w = 16;
-    return w;
+    if (forced == 1 || forced == 2 || forced == 4 || forced == 8 || forced == 16)
+        return forced == 1 ? 0 : forced == 2 ? 1 : forced == 4 ? 2 : forced == 8 ? 3 : 4;
+    if (G >= 64) return 4;
+    if (G >= 24) return 3;
+    return 2;
 }
 
-int pick_unroll(int G, int W)
+// tiles per batch: the largest of 4, 2, 1 that divides G
+int pick_unroll(int G)
 {
     static const int forced = env_int("AWQ_GEMV_UNROLL");
-    if (forced >= 2 && forced <= 4) return forced;
-    const int cnt = (G + W - 1) / W;
-    int best = 4, waste = 1 << 30;
-    for (int u = 4; u >= 2; --u) {
-        const int wst = (cnt + u - 1) / u * u - cnt;
-        if (wst < waste) { waste = wst; best = u; }
-    }
-    return best;
+    if ((forced == 1 || forced == 2 || forced == 4) && G % forced == 0) return forced;
+    return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
 }
 
 }  // namespace
@@ -268,15 +266,16 @@ int awq_gemv_launch(const void *x, const void *qweight, const void *scales, cons
                     void *y, int M, int N, int K, hipStream_t stream)
 {
     const int G = K / AWQ_GROUP;
-    const int W = pick_waves(G);
-    const int U = pick_unroll(G, W);
+    const int logW = pick_log_waves(G);
+    const int W = 1 << logW;
+    const int U = pick_unroll(G);
     const dim3 grid(N / 16), block(W * 64);
-    const bool pipe = (G + W - 1) / W > U;          // some wave has more than one batch
+    const bool pipe = (G / U + W - 1) / W > 1;      // some wave has more than one batch
     const int MS = M > GEMV_STAGE_MAX_M ? 0 : (M == 1 ? 1 : (M == 2 ? 2 : 4));
     // reduction area: 16*M outputs x 16 wave slots x 4 bytes, after the staging areas
     const size_t lds = (size_t)M * 1024 + (size_t)W * MS * (U * 256 + 16);
 #define AWQ_GEMV_ARGS (const half_t *)x, (const uint4 *)qweight, (const uint16_t *)scales, \
-                      (const uint8_t *)zeros, (half_t *)y, M, N, K, G
+                      (const uint8_t *)zeros, (half_t *)y, M, N, K, G, logW
 #define AWQ_GEMV_LAUNCH(UU, MM, PP) gemv_kernel<UU, MM, PP><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS)
 #define AWQ_GEMV_CASE(UU)                                                                   \
     case UU:                                                                                \
@@ -293,8 +292,8 @@ int awq_gemv_launch(const void *x, const void *qweight, const void *scales, cons
         }                                                                                   \
         break;
     switch (U) {
+    AWQ_GEMV_CASE(1)
     AWQ_GEMV_CASE(2)
-    AWQ_GEMV_CASE(3)
     default:
     AWQ_GEMV_CASE(4)
     }
