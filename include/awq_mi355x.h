@@ -106,6 +106,30 @@ int awq_w4a16_linear(const void *x_f16, const void *qweight, const void *scales,
                      const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,
                      int group, void *workspace, size_t workspace_bytes, void *stream);
 
+/* One linear of a grouped decode call: the arguments of awq_w4a16_linear without M. */
+typedef struct awq_linear_desc {
+    const void *x_f16;     /* [M,K] fp16 row-major, device */
+    const void *qweight;   /* packed arrays of this linear, device */
+    const void *scales;
+    const void *zeros;
+    void *y_f16;           /* [M,N] fp16 row-major, device, written */
+    int64_t N, K;
+} awq_linear_desc;
+
+#define AWQ_MULTI_MAX 16
+
+/* Sec. 4.2 (kernel fusion: several projections in one kernel, because a decode
+ * kernel is about as short as a launch): the same computation as `count` calls of
+ * awq_w4a16_linear with the same M <= 16, in ONE kernel launch.  The linears are
+ * independent (none may read another's output; outputs must not overlap); they may
+ * share x (Q/K/V, gate/up) or not.  `descs` is a HOST array of 1..AWQ_MULTI_MAX
+ * entries, read before the call returns.  Workspace as for awq_w4a16_linear
+ * (currently none needed).  Results obey the same tolerance as the single calls but
+ * need not be bit-identical to them (the summation order differs); a given call is
+ * deterministic. */
+int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

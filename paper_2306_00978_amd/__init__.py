@@ -8,7 +8,7 @@ library has not been built, importing a function from it raises.
 Function names and argument order mirror the C ABI:
     awq_act_scale, awq_apply_inv_scale            (AWQ Sec. 3.2, Eq. 4-5)
     awq_quantize_pack, awq_unpack                 (Sec. 3.2, Eq. 1-2; Sec. 4.2 packing)
-    awq_w4a16_linear                              (Sec. 4.2 fused dequantization)
+    awq_w4a16_linear, awq_w4a16_linear_multi      (Sec. 4.2 fused dequantization, kernel fusion)
 """
 from __future__ import annotations
 
@@ -24,8 +24,16 @@ GROUP = 128
 EXPORTS = [
     "awq_version", "awq_status_string", "awq_packed_sizes", "awq_act_scale",
     "awq_apply_inv_scale", "awq_quantize_pack", "awq_unpack", "awq_linear_workspace_bytes",
-    "awq_w4a16_linear",
+    "awq_w4a16_linear", "awq_w4a16_linear_multi",
 ]
+MULTI_MAX = 16
+
+
+class LinearDesc(ctypes.Structure):
+    """awq_linear_desc of the C ABI."""
+    _fields_ = [("x_f16", ctypes.c_void_p), ("qweight", ctypes.c_void_p),
+                ("scales", ctypes.c_void_p), ("zeros", ctypes.c_void_p),
+                ("y_f16", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64)]
 
 _lib = None
 
@@ -66,6 +74,8 @@ def load() -> ctypes.CDLL:
     lib.awq_linear_workspace_bytes.argtypes = [i64, i64, i64, i32]
     lib.awq_w4a16_linear.restype = i32
     lib.awq_w4a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
+    lib.awq_w4a16_linear_multi.restype = i32
+    lib.awq_w4a16_linear_multi.argtypes = [ctypes.POINTER(LinearDesc), i32, i64, i32, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -227,3 +237,42 @@ def awq_w4a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int
                                    M, N, K, group, _ptr(workspace) if need else None, ws_bytes,
                                    _stream()), "awq_w4a16_linear")
     return y
+
+
+def prepare_linear_multi(linears, group: int = GROUP):
+    """Marshal one grouped decode call.  `linears` is a list of (x, qweight, scales, zeros, y, N)
+    with the same M <= 16 everywhere.  Returns a zero-argument callable that enqueues ONE
+    awq_w4a16_linear_multi on the then-current stream; the tensors must stay alive."""
+    if not 1 <= len(linears) <= MULTI_MAX:
+        raise ValueError(f"1..{MULTI_MAX} linears per grouped call")
+    descs = (LinearDesc * len(linears))()
+    M = None
+    for i, (x, qweight, scales, zeros, y, N) in enumerate(linears):
+        _dev(x, torch.float16, "x")
+        _dev(y, torch.float16, "y")
+        m, K = x.shape
+        if M is None:
+            M = m
+        if m != M:
+            raise ValueError("all linears of a grouped call share M")
+        qb, sb, zb = awq_packed_sizes(N, K, group)
+        if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+                or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
+            raise ValueError("buffer sizes do not match the shape")
+        descs[i] = LinearDesc(x.data_ptr(), qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
+                              y.data_ptr(), N, K)
+    fn = load().awq_w4a16_linear_multi
+    count = len(linears)
+    keep = list(linears)
+
+    def call(_keep=keep):
+        st = fn(descs, count, M, group, None, 0, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_w4a16_linear_multi")
+    return call
+
+
+def awq_w4a16_linear_multi(linears, group: int = GROUP):
+    """The linears of `linears` = [(x, qweight, scales, zeros, y, N), ...] in one kernel launch."""
+    prepare_linear_multi(linears, group)()
+    return [l[4] for l in linears]

@@ -1,0 +1,31 @@
+// Host/device interface of the streaming decode kernel (awq_gemv_stream.hip).
+#pragma once
+
+#include "awq_common.h"
+
+constexpr int GEMV_MAX_PROBLEMS = 16;
+constexpr int AWQ_GEMV_STREAM_UNFIT = 1;    // internal: shape not covered, use the batch kernel
+
+// One linear of a grouped decode launch.  The caller fills the pointers and N, K; the
+// launcher fills the planning fields.
+struct GemvProblem {
+    const half_t *x;          // [M,K]
+    const uint4 *q;           // packed codes
+    const uint16_t *sc;       // steps
+    const uint8_t *zp;        // zero points
+    half_t *y;                // [M,N]
+    int N, K;
+    int wg_begin;             // first workgroup of this linear in the grid
+    int ks_log;               // log2 of the waves that split K for one row block
+    int iters;                // row-block iterations per workgroup
+};
+
+struct GemvLaunch {
+    GemvProblem p[GEMV_MAX_PROBLEMS];
+    int count;
+    int M;
+    int logW;                 // log2 of the waves per workgroup
+    int mlog;                 // log2 of M rounded up to a power of two
+};
+
+int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream);

@@ -1,0 +1,461 @@
+// Streaming decode kernel of awq_w4a16_linear / awq_w4a16_linear_multi (M <= 16) for gfx950.
+//
+// AWQ Sec. 4.2: generation is memory-bound, the weights are the traffic, and each
+// decode kernel is so short that launch overhead is comparable to its run time;
+// the paper's answer is on-the-fly dequantization inside the matrix-vector kernel
+// plus kernel fusion (e.g. one kernel for the Q, K and V projections).  This kernel
+// does both: it dequantizes in registers, and one launch can run a list of
+// independent linears (a "grouped" launch), each on its own share of the grid.
+//
+// Work decomposition of one linear (W[N,K], G = K/128 groups, tiles of 16 rows x 128
+// columns = 1 KB, all tiles of a 16-row block contiguous along K):
+//   * a batch is four consecutive tiles of one row block (4 KB) plus their 128 B of
+//     steps and 32 B of zero points; NBT = ceil(G/4) batches per row block;
+//   * a workgroup has W = KS * RW waves: wave w works on K-slice ks = w % KS (a
+//     contiguous range of batches, the same for its whole life) of row block
+//     ri = w / KS of the RW row blocks the workgroup handles per iteration, for
+//     `iters` iterations over consecutive row blocks.  The jobs (iteration, batch) of a
+//     wave form one flat pipeline.
+//
+// Memory pipeline.  Weights never pass through registers on their way in: every job is
+// fetched with global_load_lds (HBM -> LDS directly, 16 bytes per lane, a 1 KB tile lands
+// contiguously) into one of STAGES private ring slots of the wave, STAGES-1 jobs ahead of
+// the job being consumed.  That keeps (STAGES-1) * 4.2 KB in flight per wave at no
+// register cost; a job is read back with one ds_read_b128 per tile when its turn comes.
+// vmcnt counts these loads in order, so "at most 6*(STAGES-1) outstanding" means the
+// oldest job has landed.  The ring is private to a wave: no barrier is involved.
+//
+// Activations.  x stays in registers for the whole kernel.  A-operand row r of the MFMA
+// is token (r % Mpad) of "slot" r / Mpad (Mpad = M rounded up to a power of two), and
+// slot s carries the activations of batch b0 + s of the wave's K-slice.  A tile of batch
+// b0 + s therefore yields its valid sums in output rows s * Mpad + m; the other rows are
+// finite garbage and are masked out when the batch is added to the running sums.  With
+// M = 1 one wave covers 16 batches (K = 8192) with 64 registers and no per-tile
+// activation traffic of any kind.
+//
+// Arithmetic per tile.  (w & 0x000F000F) and (w & 0x00F000F0) read as fp16 pairs are the
+// SUBNORMAL halves q * 2^-24 and q * 2^-20: exact, no bias, one v_and_b32 per pair.  The matrix
+// core of gfx950 takes subnormal inputs at full precision, so the codes go to
+// v_mfma_f32_16x16x32_f16 as they are.  The 2^-20 positions are evened out on the activation
+// side (those fragment elements are multiplied by 2^-4 once, when the fragments are loaded),
+// and the zero point is taken out per tile in fp32:
+//     sum_k x_k (q_k - z) = acc - z * S,   S = sum_k x_k  (once per wave, by an MFMA of the
+// fragments against the constant code 1).  The step and the common factor 2^24 are applied
+// once per group in fp32.  Every product and, for integer-valued data, every sum is exact.
+//
+// Output.  The running sums are folded across slots with cross-lane permutes; waves that
+// share a row block (KS > 1) meet in LDS (one barrier per iteration), are added in a
+// fixed order (deterministic), rounded once to fp16 and stored.
+#include "awq_common.h"
+#include "awq_gemv_stream.h"
+
+#include <stdlib.h>
+#include <algorithm>
+#include <cmath>
+
+namespace {
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef const __attribute__((address_space(1))) void gbl_void_t;
+
+constexpr int STAGE_BYTES = 4480;        // 4 tiles, 256 B steps, 128 B zero points
+constexpr int STAGE_SC = 4096, STAGE_ZP = 4352;
+constexpr int LOADS_PER_JOB = 6;
+
+// HBM -> LDS without a register in between.  Lane l's 16 bytes land at lds + OFF + 16 l (OFF is
+// added to the global address as well); 2- and 1-byte loads land zero-extended at lds + 4 l.
+template <int OFF>
+__device__ __forceinline__ void dma16_to_lds(const void *g, uint32_t lds_addr)
+{
+    __builtin_amdgcn_global_load_lds((gbl_void_t *)(uintptr_t)g, (lds_void_t *)(uintptr_t)lds_addr,
+                                     16, OFF, 0);
+}
+__device__ __forceinline__ void dma2_to_lds(const void *g, uint32_t lds_addr)
+{
+    __builtin_amdgcn_global_load_lds((gbl_void_t *)(uintptr_t)g, (lds_void_t *)(uintptr_t)lds_addr,
+                                     2, 0, 0);
+}
+__device__ __forceinline__ void dma1_to_lds(const void *g, uint32_t lds_addr)
+{
+    __builtin_amdgcn_global_load_lds((gbl_void_t *)(uintptr_t)g, (lds_void_t *)(uintptr_t)lds_addr,
+                                     1, 0, 0);
+}
+
+// What a wave reads back from a landed ring slot: the four tiles (one 16-byte word group
+// per lane and tile) and, for its row r, the four steps (fp16 bits) and the four zero-point
+// bytes (rows 2*(r/2) and 2*(r/2)+1 in the low and high nibble).
+struct Landed {
+    uint4 q[4];
+    uint4 s, z;
+};
+
+template <int PENDING>
+__device__ __forceinline__ void wait_loads()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
+}
+
+__device__ __forceinline__ void read_slot(Landed &d, uint32_t tile_addr, uint32_t sc_addr,
+                                          uint32_t zp_addr)
+{
+    asm volatile(
+        "ds_read_b128 %4, %7 offset:4096\n"
+        "ds_read_b128 %5, %8 offset:4352\n"
+        "ds_read_b128 %0, %6\n"
+        "ds_read_b128 %1, %6 offset:1024\n"
+        "ds_read_b128 %2, %6 offset:2048\n"
+        "ds_read_b128 %3, %6 offset:3072\n"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(d.q[0]), "=&v"(d.q[1]), "=&v"(d.q[2]), "=&v"(d.q[3]), "=&v"(d.s), "=&v"(d.z)
+        : "v"(tile_addr), "v"(sc_addr), "v"(zp_addr)
+        : "memory");
+}
+
+// (w & mask) as fp16 pairs: q * 2^-24 for the low-nibble mask, q * 2^-20 for the high one
+__device__ __forceinline__ half8_t subnormal_halves(uint32_t w, uint32_t mask_lo, uint32_t mask_hi)
+{
+    const uint32_t w8 = w >> 8;
+    return __builtin_bit_cast(half8_t, make_uint4(w & mask_lo, w & mask_hi, w8 & mask_lo, w8 & mask_hi));
+}
+
+// One batch (four tiles) against the register-resident activation fragments xa[4u + j];
+// xsum[u] is 2^-24 * (sum of the activations of tile u) per output row.  Returns, per lane,
+// the four partial sums of output rows 4c + v for column r.
+__device__ __forceinline__ floatx4 consume_batch(const Landed &b, const uint4 (&xa)[16],
+                                                 const floatx4 (&xsum)[4], uint32_t mask_lo,
+                                                 uint32_t mask_hi, int zshift)
+{
+    floatx4 bacc = {0.f, 0.f, 0.f, 0.f};
+    const uint32_t sraw[4] = {b.s.x, b.s.y, b.s.z, b.s.w};
+    const uint32_t zraw[4] = {b.z.x, b.z.y, b.z.z, b.z.w};
+#pragma unroll
+    for (int u = 0; u < 4; u += 2) {
+        // two tiles at a time: their accumulation chains interleave in the matrix pipe
+        const uint32_t wa[4] = {b.q[u].x, b.q[u].y, b.q[u].z, b.q[u].w};
+        const uint32_t wb[4] = {b.q[u + 1].x, b.q[u + 1].y, b.q[u + 1].z, b.q[u + 1].w};
+        floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa[4 * u + j]),
+                                                          subnormal_halves(wa[j], mask_lo, mask_hi), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa[4 * u + 4 + j]),
+                                                          subnormal_halves(wb[j], mask_lo, mask_hi), acc1, 0, 0, 0);
+        }
+        const float z0 = (float)((zraw[u] >> zshift) & 0xFu), z1 = (float)((zraw[u + 1] >> zshift) & 0xFu);
+        const float s0 = (float)__builtin_bit_cast(half_t, (uint16_t)sraw[u]) * 16777216.f;
+        const float s1 = (float)__builtin_bit_cast(half_t, (uint16_t)sraw[u + 1]) * 16777216.f;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            bacc[v] += s0 * (acc0[v] - z0 * xsum[u][v]);
+            bacc[v] += s1 * (acc1[v] - z1 * xsum[u + 1][v]);
+        }
+    }
+    return bacc;
+}
+
+template <int STAGES>
+__global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t mask_lo = 0x000F000Fu, mask_hi = 0x00F000F0u;      // kept in SGPRs
+    asm("" : "+s"(mask_lo));
+    asm("" : "+s"(mask_hi));
+
+    // which linear of the list this workgroup belongs to (wave-uniform)
+    int pi = 0;
+    for (int i = 1; i < L.count; ++i)
+        if ((int)blockIdx.x >= L.p[i].wg_begin) pi = i;
+    const GemvProblem &P = L.p[pi];
+
+    const int M = L.M, mlog = L.mlog, Mpad = 1 << mlog;
+    const int K = P.K, N = P.N;
+    const int G = K >> 7, NRB = N >> 4, NBT = (G + 3) >> 2;
+    const int ksl = P.ks_log, KS = 1 << ksl;
+    const int W = 1 << L.logW, RW = W >> ksl;
+    const int iters = P.iters;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ks = wave & (KS - 1), ri = wave >> ksl;
+    const int b0 = (NBT * ks) >> ksl, b1 = (NBT * (ks + 1)) >> ksl;      // 1..16/Mpad batches (host)
+    const int unit = (int)blockIdx.x - P.wg_begin;
+    const int rb_wg = unit * iters * RW;                                 // first row block of the WG
+    const int r = lane & 15, c = lane >> 4;
+    const int zshift = (r & 1) * 4;
+
+    // LDS: [W][STAGES] ring slots, then the cross-wave reduction area (two buffers)
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
+    const uint32_t ring = lds0 + (uint32_t)wave * (STAGES * STAGE_BYTES);
+    float *red = reinterpret_cast<float *>(smem + (size_t)W * STAGES * STAGE_BYTES);
+    const int red_floats = W * Mpad * 16;           // [ri][ks][token][column]
+
+    const unsigned char *qbase = reinterpret_cast<const unsigned char *>(P.q);
+    const unsigned char *scbase = reinterpret_cast<const unsigned char *>(P.sc);
+    const unsigned char *zpbase = reinterpret_cast<const unsigned char *>(P.zp);
+    const uint32_t lane16 = (uint32_t)lane << 4;
+
+    // per-lane parts of the source addresses: tile bytes; step of (row lane/4, group lane%4);
+    // zero-point byte of (row pair lane/4, group lane%4)
+    const uint32_t sc_lane = (uint32_t)(lane & 3) * 32 + (uint32_t)(lane >> 2) * 2;
+    const uint32_t zp_lane = (uint32_t)(lane & 3) * 8 + (uint32_t)((lane >> 2) & 7);
+    const bool ragged = (G & 3) != 0;
+
+    // request one job: 4 tiles (all lanes, 16 B each), 64 steps (all lanes, 2 B each), 32
+    // zero-point bytes (lanes 0..31).  Groups beyond G-1 (ragged last batch) re-read group
+    // G-1; their activation fragments are zero, so they contribute nothing.
+    auto issue = [&](int it, int b, int slot) {
+        int rb = rb_wg + it * RW + ri;
+        rb = rb < NRB ? rb : NRB - 1;                       // surplus waves redo the last block
+        const size_t t0 = (size_t)rb * G + (size_t)b * 4;   // first tile of the batch
+        const uint32_t dst = ring + (uint32_t)slot * STAGE_BYTES;
+        const unsigned char *tq = qbase + (t0 << 10), *ts = scbase + t0 * 32, *tz = zpbase + t0 * 8;
+        if (!ragged || b * 4 + 4 <= G) {
+            dma16_to_lds<0>(tq + lane16, dst);
+            dma16_to_lds<1024>(tq + lane16, dst);
+            dma16_to_lds<2048>(tq + lane16, dst);
+            dma16_to_lds<3072>(tq + lane16, dst);
+            dma2_to_lds(ts + sc_lane, dst + STAGE_SC);
+            if (lane < 32) dma1_to_lds(tz + zp_lane, dst + STAGE_ZP);
+        } else {
+            const int last = G - 1 - b * 4;                 // last valid group of this batch (0..2)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                dma16_to_lds<0>(tq + ((size_t)min(u, last) << 10) + lane16, dst + u * 1024);
+            const int gl = min(lane & 3, last);
+            dma2_to_lds(ts + gl * 32 + (lane >> 2) * 2, dst + STAGE_SC);
+            if (lane < 32) dma1_to_lds(tz + gl * 8 + ((lane >> 2) & 7), dst + STAGE_ZP);
+        }
+    };
+
+    // the first weight requests go out before anything else, so that their latency and the
+    // latency of the activation loads overlap
+    const int nbw = b1 - b0;
+    const int J = iters * nbw;                               // jobs of this wave
+    int nit = 0, nb = b0, nslot = 0, nj = 0;                 // next job to request
+    auto issue_next = [&]() {
+        issue(nit, nb, nslot);
+        ++nj;
+        if (++nslot == STAGES) nslot = 0;
+        if (++nb == b1) { nb = b0; ++nit; }
+    };
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (nj < J) issue_next();
+
+    // activation fragments (see the header comment), loaded once; halves 2,3,6,7 of every
+    // fragment meet the 2^-20 codes and are scaled by 2^-4 to match the 2^-24 ones
+    uint4 xa[16];
+    {
+        const int slot = r >> mlog;
+        int m = r & (Mpad - 1);
+        m = m < M ? m : M - 1;
+        const int bl = b0 + slot;
+        const half_t *xrow = P.x + (size_t)m * K + 8 * c;
+        const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int g = 4 * bl + u;
+            const bool ok = bl < b1 && g < G;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint4 f = ok ? *reinterpret_cast<const uint4 *>(xrow + g * 128 + 32 * j)
+                             : make_uint4(0, 0, 0, 0);
+                f.y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, f.y) * sixteenth);
+                f.w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, f.w) * sixteenth);
+                xa[4 * u + j] = f;
+            }
+        }
+    }
+    // 2^-24 * sum of the activations of each tile, per output row: the fragments against the
+    // constant code 1 (halves 2^-24, 2^-24, 2^-20, 2^-20, ...)
+    floatx4 xsum[4];
+    {
+        const half8_t ones = __builtin_bit_cast(half8_t, make_uint4(0x00010001u, 0x00100010u, 0x00010001u, 0x00100010u));
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            floatx4 t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                t = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa[4 * u + j]), ones, t, 0, 0, 0);
+            xsum[u] = t;
+        }
+    }
+
+    // slot of output row 4c + v
+    int slotv[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) slotv[v] = (4 * c + v) >> mlog;
+
+    const uint32_t rd_tile = ring + lane16, rd_sc = ring + 16 * r, rd_zp = ring + 16 * (r >> 1);
+    floatx4 total = {0.f, 0.f, 0.f, 0.f};
+    int cit = 0, cb = b0, cslot = 0;                         // job being consumed
+
+    // fold the running sums over the slots: afterwards lanes with c < max(1, Mpad/4) hold
+    // token m = 4c + v (v < min(4, Mpad)) of column r
+    auto fold = [&]() {
+        if (mlog < 2) { total[0] += total[2]; total[1] += total[3]; }
+        if (mlog < 1) total[0] += total[1];
+        if (mlog < 4) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) total[v] += __shfl_xor(total[v], 32);
+        }
+        if (mlog < 3) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) total[v] += __shfl_xor(total[v], 16);
+        }
+    };
+    const int cmax = Mpad >= 4 ? Mpad >> 2 : 1;
+
+    auto finish_block = [&](int it) {
+        fold();
+        if (KS == 1) {
+            const int rbo = rb_wg + it * RW + ri;
+            if (rbo < NRB && c < cmax) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = 4 * c + v;
+                    if (v < Mpad && m < M) P.y[(size_t)m * N + rbo * 16 + r] = (half_t)total[v];
+                }
+            }
+            total = floatx4{0.f, 0.f, 0.f, 0.f};
+            return;
+        }
+        float *rbuf = red + (it & 1) * red_floats;
+        if (c < cmax) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (v < Mpad) rbuf[((ri * KS + ks) * Mpad + 4 * c + v) * 16 + r] = total[v];
+        }
+        total = floatx4{0.f, 0.f, 0.f, 0.f};
+        __syncthreads();
+        for (int t = tid; t < RW * M * 16; t += W * 64) {
+            const int tri = t / (M * 16), rem = t - tri * (M * 16);
+            const float *p = rbuf + tri * KS * Mpad * 16 + rem;
+            float sum = 0.f;
+            for (int k = 0; k < KS; ++k) sum += p[k * Mpad * 16];
+            const int rbo = rb_wg + it * RW + tri;
+            if (rbo < NRB) P.y[(size_t)(rem >> 4) * N + rbo * 16 + (rem & 15)] = (half_t)sum;
+        }
+    };
+
+    for (int j = 0; j < J; ++j) {
+        if (nj < J) issue_next();
+        // jobs requested after job j: min(STAGES-1, J-1-j); job j has landed once at most that
+        // many jobs' loads are outstanding
+        const int later = nj - j - 1;
+        if (later >= STAGES - 1) wait_loads<LOADS_PER_JOB *(STAGES - 1)>();
+        else if (STAGES > 2 && later == 2) wait_loads<LOADS_PER_JOB * 2>();
+        else if (later == 1) wait_loads<LOADS_PER_JOB>();
+        else wait_loads<0>();
+        Landed cur;
+        const uint32_t off = (uint32_t)cslot * STAGE_BYTES;
+        read_slot(cur, rd_tile + off, rd_sc + off, rd_zp + off);
+        if (++cslot == STAGES) cslot = 0;
+        const floatx4 bacc = consume_batch(cur, xa, xsum, mask_lo, mask_hi, zshift);
+        const int slot = cb - b0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) total[v] += slotv[v] == slot ? bacc[v] : 0.f;
+        if (++cb == b1) { finish_block(cit); cb = b0; ++cit; }
+    }
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return e ? atoi(e) : dflt;
+}
+
+int ceil_log2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
+
+}  // namespace
+
+// Plans and launches one grouped decode launch.  Returns AWQ_OK, an error, or
+// AWQ_GEMV_STREAM_UNFIT when some linear has more batches along K than the waves of a
+// workgroup can hold as register-resident activations (the caller then uses the batch
+// kernel).
+//
+// Plan.  The kernel is bound by how evenly the memory requests of all resident waves cover
+// the run time, so every wave should get the same number of jobs T = (all batches) / (wave
+// slots of the chip), with a floor of one job.  Per linear, K is split over KS waves and a
+// workgroup takes `iters` consecutive row-block steps so that iters * (batches per wave and
+// row block) comes as close to T as possible.
+int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream)
+{
+    static const int f_logw = env_int("AWQ_GEMV_LOGW", -1);
+    static const int f_iters = env_int("AWQ_GEMV_ITERS", -1);
+    static const int f_ksl = env_int("AWQ_GEMV_KSL", -1);
+    static const int f_stages = env_int("AWQ_GEMV_STAGES", 2);
+    static const int f_slots = env_int("AWQ_GEMV_SLOTS", 1536);
+    static const int f_jobs = env_int("AWQ_GEMV_JOBS", -1);
+    if (count < 1 || count > GEMV_MAX_PROBLEMS) return AWQ_ERR_BAD_ARGUMENT;
+
+    GemvLaunch L;
+    L.count = count;
+    L.M = M;
+    L.mlog = ceil_log2(M);
+    const int bpr = 16 >> L.mlog;                  // batches one wave can hold activations for
+    double total_batches = 0;
+    for (int i = 0; i < count; ++i)
+        total_batches += (double)(problems[i].N / 16) * ((problems[i].K / 128 + 3) / 4);
+    const double T = f_jobs > 0 ? f_jobs : std::max(1.0, total_batches / f_slots);
+
+    int ksl_of[GEMV_MAX_PROBLEMS], iters_of[GEMV_MAX_PROBLEMS];
+    int logW = 2;
+    for (int i = 0; i < count; ++i) {
+        const int NBT = (problems[i].K / 128 + 3) / 4;
+        const int ksl_min = ceil_log2((NBT + bpr - 1) / bpr);
+        if (ksl_min > 3) return AWQ_GEMV_STREAM_UNFIT;
+        // candidates: KS = 2^ksl waves along K (each gets ceil(NBT/KS) batches per row block)
+        int best_ksl = ksl_min, best_iters = 1;
+        double best_err = 1e30;
+        for (int ksl = ksl_min; ksl <= 3 && (1 << ksl) <= NBT; ++ksl) {
+            const int nbw = (NBT + (1 << ksl) - 1) >> ksl;
+            const int iters = std::max(1, (int)(T / nbw + 0.5));
+            // relative distance from T, with a small penalty on K-splitting (extra reduction)
+            const double err = std::abs(iters * nbw - T) / T + 0.02 * ksl;
+            if (err < best_err) { best_err = err; best_ksl = ksl; best_iters = iters; }
+        }
+        if ((1 << best_ksl) > NBT) return AWQ_GEMV_STREAM_UNFIT;
+        if (f_ksl >= 0) best_ksl = std::min(3, std::max(ksl_min, f_ksl));
+        while ((1 << best_ksl) > NBT && best_ksl > ksl_min) --best_ksl;
+        if (f_ksl >= 0) best_iters = std::max(1, (int)(T / ((NBT + (1 << best_ksl) - 1) >> best_ksl) + 0.5));
+        if (f_iters > 0) best_iters = f_iters;
+        ksl_of[i] = best_ksl;
+        iters_of[i] = best_iters;
+        logW = std::max(logW, best_ksl);
+    }
+    if (f_logw >= 0) logW = std::min(3, std::max(f_logw, logW));
+    L.logW = logW;
+    const int W = 1 << logW;
+    const int stages = f_stages == 3 ? 3 : (f_stages == 4 ? 4 : 2);
+    const size_t lds = (size_t)W * stages * STAGE_BYTES + 2 * (size_t)W * (16 << L.mlog) * 4;
+
+    int wg = 0;
+    for (int i = 0; i < count; ++i) {
+        GemvProblem p = problems[i];
+        const int NRB = p.N / 16;
+        const int RW = W >> ksl_of[i];
+        const int steps = (NRB + RW - 1) / RW;                // row-block steps of the whole linear
+        const int iters = std::min(iters_of[i], steps);
+        p.ks_log = ksl_of[i];
+        p.iters = iters;
+        p.wg_begin = wg;
+        wg += (steps + iters - 1) / iters;
+        L.p[i] = p;
+    }
+    static bool attr_set = false;
+    if (!attr_set) {
+        const int cap = 160 * 1024;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_stream_kernel<4>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_stream_kernel<3>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_stream_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
+            return AWQ_ERR_HIP;
+        attr_set = true;
+    }
+    if (stages == 4) gemv_stream_kernel<4><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
+    else if (stages == 3) gemv_stream_kernel<3><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
+    else gemv_stream_kernel<2><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
+    return awq_launch_status();
+}

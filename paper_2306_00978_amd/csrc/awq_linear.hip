@@ -2,6 +2,9 @@
 // prefill (M > 16) kernels.  AWQ Sec. 4.2: the same fused dequantization is used
 // by the matrix-vector and the matrix-matrix kernel.
 #include "awq_common.h"
+#include "awq_gemv_stream.h"
+
+#include <stdlib.h>
 
 int awq_gemv_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
                     void *y, int M, int N, int K, hipStream_t stream);
@@ -32,9 +35,63 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
         if (workspace_bytes < need) return AWQ_ERR_WORKSPACE_TOO_SMALL;
         if (!awq_aligned16(workspace)) return AWQ_ERR_MISALIGNED;
     }
-    if (M <= 16)
+    if (M <= 16) {
+        // a single linear is a short kernel dominated by one memory round trip: the batch
+        // kernel (everything requested at once) is the faster one; the streaming kernel is
+        // for grouped launches.  AWQ_GEMV_STREAM_SINGLE forces it for experiments.
+        static const bool stream_single = getenv("AWQ_GEMV_STREAM_SINGLE") != nullptr;
+        if (stream_single) {
+            GemvProblem p = {};
+            p.x = (const half_t *)x_f16;
+            p.q = (const uint4 *)qweight;
+            p.sc = (const uint16_t *)scales;
+            p.zp = (const uint8_t *)zeros;
+            p.y = (half_t *)y_f16;
+            p.N = (int)N;
+            p.K = (int)K;
+            st = awq_gemv_stream_launch(&p, 1, (int)M, (hipStream_t)stream);
+            if (st != AWQ_GEMV_STREAM_UNFIT) return st;
+        }
         return awq_gemv_launch(x_f16, qweight, scales, zeros, y_f16, (int)M, (int)N, (int)K,
                                (hipStream_t)stream);
+    }
     return awq_gemm_launch(x_f16, qweight, scales, zeros, y_f16, (int)M, (int)N, (int)K,
                            (hipStream_t)stream);
+}
+
+extern "C" int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (!descs) return AWQ_ERR_NULL_POINTER;
+    if (count < 1 || count > AWQ_MULTI_MAX) return AWQ_ERR_BAD_ARGUMENT;
+    if (M <= 0 || M > 16) return AWQ_ERR_BAD_SHAPE;
+    GemvProblem p[GEMV_MAX_PROBLEMS] = {};
+    for (int i = 0; i < count; ++i) {
+        const awq_linear_desc &d = descs[i];
+        if (!d.x_f16 || !d.qweight || !d.scales || !d.zeros || !d.y_f16) return AWQ_ERR_NULL_POINTER;
+        int st = awq_check_weight_shape(d.N, d.K, group);
+        if (st != AWQ_OK) return st;
+        if (!awq_aligned16(d.x_f16) || !awq_aligned16(d.qweight) || !awq_aligned16(d.scales) ||
+            !awq_aligned16(d.zeros) || !awq_aligned16(d.y_f16))
+            return AWQ_ERR_MISALIGNED;
+        p[i].x = (const half_t *)d.x_f16;
+        p[i].q = (const uint4 *)d.qweight;
+        p[i].sc = (const uint16_t *)d.scales;
+        p[i].zp = (const uint8_t *)d.zeros;
+        p[i].y = (half_t *)d.y_f16;
+        p[i].N = (int)d.N;
+        p[i].K = (int)d.K;
+    }
+    int st = count > 1 ? awq_gemv_stream_launch(p, count, (int)M, (hipStream_t)stream)
+                       : AWQ_GEMV_STREAM_UNFIT;
+    if (st != AWQ_GEMV_STREAM_UNFIT) return st;
+    // a single linear, or K too long for register-resident activations at this M: one
+    // launch of the batch kernel per linear
+    for (int i = 0; i < count; ++i) {
+        st = awq_gemv_launch(p[i].x, p[i].q, p[i].sc, p[i].zp, p[i].y, (int)M, p[i].N, p[i].K,
+                             (hipStream_t)stream);
+        if (st != AWQ_OK) return st;
+    }
+    return AWQ_OK;
 }

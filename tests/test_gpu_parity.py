@@ -135,7 +135,8 @@ def config_case(awq, N, K, sigma, cfg):
     """Quantize once per distinct shape (bit-exact check included) and reuse."""
     key = (N, K, cfg)
     if key not in _cache:
-        _cache.clear()                                   # keep host memory bounded
+        while len(_cache) >= 3:                          # keep host memory bounded
+            _cache.pop(next(iter(_cache)))
         proj = [c[:2] for c in CONFIG_SHAPES].index((N, K))
         case, s, xs16 = make_case(N, K, 16, sigma, cfg, proj=proj)
         ref, gpu = assert_quantize_bit_exact(awq, case.W, s)
@@ -238,6 +239,103 @@ def test_linear_is_deterministic_and_exact_on_integer_data(awq):
         y2 = host(awq.awq_w4a16_linear(dev(x), *gpu, N))
         assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
         assert np.array_equal(y1.astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
+
+
+# ------------------------------------------------------------------- grouped decode call
+
+def check_multi(awq, problems, M):
+    """problems: list of (xs[>=M,K], Wdq[N,K], gpu_packed, N).  One awq_w4a16_linear_multi
+    call; every output is compared with the oracle, canaries around every output buffer."""
+    import torch
+    import oracle
+    linears, checks, outs = [], [], []
+    for xs, Wdq, gpu_packed, N in problems:
+        y, cy = guarded(M * N * 2, torch.float16)
+        y = y.view(M, N)
+        linears.append((dev(xs[:M]), *gpu_packed, y, N))
+        checks.append(cy)
+        outs.append(y)
+    awq.awq_w4a16_linear_multi(linears)
+    worst = 0.0
+    for (xs, Wdq, gpu_packed, N), y, cy in zip(problems, outs, checks):
+        cy()
+        yh = host(y)
+        assert np.all(np.isfinite(yh.astype(np.float32)))
+        err = oracle.norm_error(yh, oracle.matmul(xs[:M], Wdq), xs[:M], Wdq)
+        assert err.max() <= TOL, f"max normalised error {err.max():.3e} (N={N}, M={M})"
+        worst = max(worst, float(err.max()))
+    return worst
+
+
+@pytest.fixture(scope="module")
+def small_group(awq):
+    """Four small linears of different shapes: ragged group count (K=1408: 11 groups), a K that
+    needs more than one wave along K at larger M, shared and separate inputs."""
+    import oracle
+    out = []
+    for i, (N, K) in enumerate([(176, 1408), (64, 1408), (48, 2048), (320, 512)]):
+        case, s, xs = make_case(N, K, 16, 0.02, cfg=0, proj=3 + i)
+        ref, gpu = assert_quantize_bit_exact(awq, case.W, s)
+        out.append((xs, oracle.dequant(*ref), gpu, N))
+    return out
+
+
+@pytest.mark.parametrize("M", list(range(1, 17)))
+def test_multi_every_m(awq, small_group, M):
+    check_multi(awq, small_group, M)
+
+
+def test_multi_single_entry_and_limits(awq, small_group):
+    import torch
+    check_multi(awq, small_group[:1], 3)
+    check_multi(awq, small_group * 4, 2)                     # 16 entries: the maximum
+    xs, Wdq, gpu, N = small_group[0]
+    y = torch.empty((17, N), dtype=torch.float16, device="cuda")
+    with pytest.raises(awq.AwqError) as e:                   # M > 16 is not a decode call
+        awq.awq_w4a16_linear_multi([(dev(np.repeat(xs, 2, axis=0)[:17]), *gpu, y, N)])
+    assert e.value.status == -2
+    with pytest.raises(ValueError):
+        awq.prepare_linear_multi(small_group * 5)
+
+
+def test_multi_exact_and_deterministic_on_integer_data(awq):
+    """Small integers: all products and sums are exact in fp32, so the grouped call must
+    reproduce the oracle bit for bit, twice in a row."""
+    import torch
+    import oracle
+    g = np.random.default_rng(12)
+    probs = []
+    for N, K in [(64, 512), (32, 1408), (96, 2048)]:
+        codes = g.integers(0, 16, size=(N, K), dtype=np.uint8)
+        scales = (2.0 ** g.integers(-3, 2, size=(N, K // 128))).astype(np.float16)
+        zeros = g.integers(0, 16, size=(N, K // 128), dtype=np.uint8)
+        q, sp, zp = oracle.pack(codes, scales, zeros)
+        probs.append((N, K, (dev(q), dev(sp.view(np.float16)), dev(zp)), oracle.dequant(codes, scales, zeros)))
+    for M in (1, 2, 5, 16):
+        linears, refs = [], []
+        for N, K, gpu, Wdq in probs:
+            x = g.integers(-4, 5, size=(M, K)).astype(np.float16)
+            y_ref = oracle.matmul(x, Wdq)
+            assert np.abs(y_ref).max() < 60000
+            linears.append((dev(x), *gpu, torch.empty((M, N), dtype=torch.float16, device="cuda"), N))
+            refs.append(y_ref)
+        first = [host(y).copy() for y in awq.awq_w4a16_linear_multi(linears)]
+        second = [host(y).copy() for y in awq.awq_w4a16_linear_multi(linears)]
+        for y1, y2, y_ref in zip(first, second, refs):
+            assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+            assert np.array_equal(y1.astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
+
+
+def test_multi_llama7b_layer_full_size(awq):
+    """The launch configuration bench.py times: the seven projections of one Llama-2-7B-shaped
+    layer in one grouped call (M = 1, 4, 16), every output against the oracle."""
+    probs = []
+    for N, K in [(4096, 4096), (11008, 4096), (4096, 11008)]:
+        case, s, xs16, ref, gpu, Wdq = config_case(awq, N, K, 0.02, 1)
+        probs.append((xs16, Wdq, gpu, N))
+    layer = [probs[0]] * 4 + [probs[1]] * 2 + [probs[2]]
+    for M in (1, 4, 16):
+        check_multi(awq, layer, M)
 
 
 # ----------------------------------------------------------------------------- a0 / a0'
