@@ -30,6 +30,8 @@
 // fp32 accumulation, one rounding to fp16 at the end.
 #include "awq_common.h"
 
+#include <type_traits>
+
 namespace {
 
 typedef __attribute__((address_space(3))) void lds_void_t;
@@ -102,26 +104,55 @@ __device__ __forceinline__ DqConsts dq_consts()
     return k;
 }
 
-// eight codes of one packed word -> (q - z) * scale in fp16, k order.
-// (w & mask) | magic is 1024+q or 64+q as a half pair; subtracting 1024+z / 64+z is exact.
-__device__ __forceinline__ half8_t dequant_word(uint32_t w, const DqConsts &k, half2_t zA,
-                                                half2_t zB, half2_t s2)
+// Dequantization of one packed word (eight codes) to fp16 (q - z) * scale, k order, cut into
+// 13 single-instruction steps so that the main loop can place them one by one in the issue
+// shadow of the MFMAs:  (w & mask) | magic is 1024+q or 64+q as a half pair; subtracting
+// 1024+z / 64+z is exact; one rounding in the multiplication by the step.
+struct DqWord {
+    uint32_t w, w8;
+    uint32_t t[4];
+};
+
+template <int OP>
+__device__ __forceinline__ void dq_step(DqWord &d, const DqConsts &k, half2_t zA, half2_t zB,
+                                        half2_t s2)
 {
-    const uint32_t w8 = w >> 8;
-    const uint32_t t0 = (w & k.mask_lo) | k.magA;
-    const uint32_t t1 = (w & k.mask_hi) | k.magB;
-    const uint32_t t2 = (w8 & k.mask_lo) | k.magA;
-    const uint32_t t3 = (w8 & k.mask_hi) | k.magB;
-    const half2_t d0 = (__builtin_bit_cast(half2_t, t0) - zA) * s2;
-    const half2_t d1 = (__builtin_bit_cast(half2_t, t1) - zB) * s2;
-    const half2_t d2 = (__builtin_bit_cast(half2_t, t2) - zA) * s2;
-    const half2_t d3 = (__builtin_bit_cast(half2_t, t3) - zB) * s2;
-    uint4 out;
-    out.x = __builtin_bit_cast(uint32_t, d0);
-    out.y = __builtin_bit_cast(uint32_t, d1);
-    out.z = __builtin_bit_cast(uint32_t, d2);
-    out.w = __builtin_bit_cast(uint32_t, d3);
-    return __builtin_bit_cast(half8_t, out);
+    if (OP == 0) d.w8 = d.w >> 8;
+    if (OP == 1) d.t[0] = (d.w & k.mask_lo) | k.magA;
+    if (OP == 2) d.t[1] = (d.w & k.mask_hi) | k.magB;
+    if (OP == 3) d.t[2] = (d.w8 & k.mask_lo) | k.magA;
+    if (OP == 4) d.t[3] = (d.w8 & k.mask_hi) | k.magB;
+    if (OP >= 5 && OP <= 8) {
+        const int i = OP - 5;
+        d.t[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, d.t[i]) - ((i & 1) ? zB : zA));
+    }
+    if (OP >= 9 && OP <= 12) {
+        const int i = OP - 9;
+        d.t[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, d.t[i]) * s2);
+    }
+}
+
+// steps [26 SLOT / 8, 26 (SLOT + 1) / 8) of the 26 that dequantize the two words of an MFMA step
+template <int SLOT>
+__device__ __forceinline__ void dq_slice(DqWord (&d)[2], const DqConsts &k, const half2_t (&zA)[2],
+                                         const half2_t (&zB)[2], const half2_t (&s2)[2])
+{
+#define AWQ_DQ_ONE(I)                                                                           \
+    if ((I) >= 26 * SLOT / 8 && (I) < 26 * (SLOT + 1) / 8) {                                    \
+        constexpr int b_ = (I) / 13, op_ = (I) % 13;                                            \
+        dq_step<op_>(d[b_], k, zA[b_], zB[b_], s2[b_]);                                         \
+    }
+    AWQ_DQ_ONE(0) AWQ_DQ_ONE(1) AWQ_DQ_ONE(2) AWQ_DQ_ONE(3) AWQ_DQ_ONE(4) AWQ_DQ_ONE(5) AWQ_DQ_ONE(6)
+    AWQ_DQ_ONE(7) AWQ_DQ_ONE(8) AWQ_DQ_ONE(9) AWQ_DQ_ONE(10) AWQ_DQ_ONE(11) AWQ_DQ_ONE(12)
+    AWQ_DQ_ONE(13) AWQ_DQ_ONE(14) AWQ_DQ_ONE(15) AWQ_DQ_ONE(16) AWQ_DQ_ONE(17) AWQ_DQ_ONE(18)
+    AWQ_DQ_ONE(19) AWQ_DQ_ONE(20) AWQ_DQ_ONE(21) AWQ_DQ_ONE(22) AWQ_DQ_ONE(23) AWQ_DQ_ONE(24)
+    AWQ_DQ_ONE(25)
+#undef AWQ_DQ_ONE
+}
+
+__device__ __forceinline__ half8_t dq_result(const DqWord &d)
+{
+    return __builtin_bit_cast(half8_t, make_uint4(d.t[0], d.t[1], d.t[2], d.t[3]));
 }
 
 __device__ __forceinline__ uint32_t word_of(const u32x4 &v, int j)
@@ -132,29 +163,39 @@ __device__ __forceinline__ uint32_t word_of(const u32x4 &v, int j)
 __global__ __launch_bounds__(256, 1) void gemm_kernel(
     const half_t *__restrict__ x, const unsigned char *__restrict__ qweight,
     const unsigned char *__restrict__ scales, const unsigned char *__restrict__ zeros,
-    half_t *__restrict__ y, int M, int N, int K, int G)
+    half_t *__restrict__ y, int M, int N, int K, int G, int tiles_n, int tiles_total)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    // Workgroups are handed to the eight XCDs round-robin by their linear id, and each XCD has
+    // its own L2.  The tile a workgroup computes is therefore chosen so that an XCD gets a
+    // contiguous range of tiles in token-block-major order: its workgroups then share a few x
+    // row blocks and sweep the same weight groups at about the same time, which keeps the
+    // operand traffic inside that L2.
+    const int per_xcd = (tiles_total + 7) >> 3;
+    const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (tile >= tiles_total) return;
+    const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
     const DqConsts kc = dq_consts();
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
-    const int m0 = blockIdx.y * BM;
+    const int m0 = tile_m * BM;
     const int NT = N >> 4;                                   // 16-row weight tiles in the matrix
-    const int nt0 = blockIdx.x * (BN / 16) + wave * 4;      // first of the wave's four tiles
+    const int nt0 = tile_n * (BN / 16) + wave * 4;          // first of the wave's four tiles
 
     // ---- sources of this lane's memory->LDS loads (group 0), advanced by constant strides
     // x: load instruction d of a group (d = 0..7) covers rows 8 (d%4) .. +8 of the wave's 32
     // rows and columns 64 (d/4) .. +64; lane l takes row 8 (d%4) + l/8 (rows >= M repeat row
-    // M-1) and chunk (l%8) ^ f, f = (l/16)%4 = ((row in block)/2)%4, and lands at chunk l%8
+    // M-1) and chunk (l%8) ^ f, f = ((row in block)/2)%8, and lands at chunk l%8: sixteen
+    // consecutive rows then hold any given chunk in sixteen different bank groups
     const unsigned char *xsrc[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         int xr = m0 + 32 * wave + 8 * q + (lane >> 3);
         xr = xr < M ? xr : M - 1;
-        const int chunk = (lane & 7) ^ ((lane >> 4) & 3);
+        const int chunk = (lane & 7) ^ (((8 * q + (lane >> 3)) >> 1) & 7);
         xsrc[q] = reinterpret_cast<const unsigned char *>(x) + ((size_t)xr * K + 8 * chunk) * 2;
     }
     // weights: block b (32 out-features = tiles nt0+2b, nt0+2b+1), half h
@@ -179,22 +220,34 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
     const uint32_t a_ring = lds0;
     const uint32_t b_ring = lds0 + NSTAGE * A_STAGE + (uint32_t)wave * (NSTAGE * B_STAGE);
 
-    auto issue_group = [&](int g, int stage) {
+    // One of the 14 loads of a group (PIECE 0..7: x, 8..11: weights, 12: steps, 13: zero points).
+    // They are issued one at a time from the issue shadow of the MFMAs.
+    auto issue_piece = [&](auto piece_tag, int g, int stage) {
+        constexpr int PIECE = decltype(piece_tag)::value;
         g = g < G ? g : G - 1;                               // past the end: a harmless repeat
-        // LDS: [row block 4][column half 2][32 rows x 128 B]
-        const uint32_t adst = a_ring + (uint32_t)stage * A_STAGE + (uint32_t)wave * 8192;
-#pragma unroll
-        for (int d = 0; d < 8; ++d)
+        if (PIECE < 8) {
+            // LDS: [row block 4][column half 2][32 rows x 128 B]
+            const uint32_t adst = a_ring + (uint32_t)stage * A_STAGE + (uint32_t)wave * 8192;
+            constexpr int d = PIECE & 7;
             dma16(xsrc[d & 3] + (size_t)g * 256 + (d >> 2) * 128, adst + (d >> 2) * 4096 + (d & 3) * 1024);
-        const uint32_t bdst = b_ring + (uint32_t)stage * B_STAGE;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const unsigned char *qs = qsrc[b] + (size_t)g * 1024;
-            dma16(qs, bdst + (2 * b) * 1024);
-            dma16(qs + 512, bdst + (2 * b + 1) * 1024);
+        } else {
+            const uint32_t bdst = b_ring + (uint32_t)stage * B_STAGE;
+            if (PIECE < 12) {
+                constexpr int b = ((PIECE - 8) >> 1) & 1, h = (PIECE - 8) & 1;
+                dma16(qsrc[b] + (size_t)g * 1024 + h * 512, bdst + (2 * b + h) * 1024);
+            } else if (PIECE == 12) {
+                dma2(ssrc + (size_t)g * 32, bdst + B_SC);
+            } else {
+                if (lane < 32) dma1(zsrc + (size_t)g * 8, bdst + B_ZP);
+            }
         }
-        dma2(ssrc + (size_t)g * 32, bdst + B_SC);
-        if (lane < 32) dma1(zsrc + (size_t)g * 8, bdst + B_ZP);
+    };
+#define AWQ_PIECE(P, G_, ST_) issue_piece(std::integral_constant<int, (P)>{}, (G_), (ST_))
+    auto issue_group = [&](int g, int stage) {
+        AWQ_PIECE(0, g, stage); AWQ_PIECE(1, g, stage); AWQ_PIECE(2, g, stage); AWQ_PIECE(3, g, stage);
+        AWQ_PIECE(4, g, stage); AWQ_PIECE(5, g, stage); AWQ_PIECE(6, g, stage); AWQ_PIECE(7, g, stage);
+        AWQ_PIECE(8, g, stage); AWQ_PIECE(9, g, stage); AWQ_PIECE(10, g, stage); AWQ_PIECE(11, g, stage);
+        AWQ_PIECE(12, g, stage); AWQ_PIECE(13, g, stage);
     };
 
     floatx16 acc[4][2];
@@ -212,86 +265,153 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
 
     const uint32_t lane16 = (uint32_t)lane << 4;
     // byte offset of this lane's A fragment inside a (row block, column half) area, for the
-    // four steps of the half: row l32, chunk (2 s' + hi) ^ ((l32/2)%4)
+    // four steps of the half: row l32, chunk (2 s' + hi) ^ ((l32/2)%8)
     uint32_t aoff[4];
 #pragma unroll
     for (int sp = 0; sp < 4; ++sp)
-        aoff[sp] = (uint32_t)l32 * 128 + (uint32_t)(((2 * sp + hi) ^ ((l32 >> 1) & 3)) * 16);
+        aoff[sp] = (uint32_t)l32 * 128 + (uint32_t)(((2 * sp + hi) ^ ((l32 >> 1) & 7)) * 16);
+
+    // ---- what a wave holds in registers for the group it is computing
+    u32x4 braw[2][2];            // packed words: [block][half], word j = MFMA step 2 j + half
+    half2_t s2[2], zA[2], zB[2]; // per block: step, 1024 + z, 64 + z (as half pairs)
+    u32x4 a[4];                  // A fragments of the current step
+    DqWord dq[2];                // dequantization in flight (current or next step)
+
+    // request the packed words, steps, zero points and the first A fragments of a stage
+    u32x4 nbraw[2][2], na[4];
+    uint32_t nsraw[2], nzraw[2];
+    auto read_group = [&](int st) {
+        const uint32_t bb = b_ring + (uint32_t)st * B_STAGE;
+        const uint32_t ab = a_ring + (uint32_t)st * A_STAGE + aoff[0];
+        nbraw[0][0] = lds_read16_off<0>(bb + lane16);
+        nbraw[0][1] = lds_read16_off<1024>(bb + lane16);
+        nbraw[1][0] = lds_read16_off<2048>(bb + lane16);
+        nbraw[1][1] = lds_read16_off<3072>(bb + lane16);
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            nsraw[b] = lds_read4(bb + B_SC + 4 * (32 * b + l32));
+            nzraw[b] = lds_read4(bb + B_ZP + 4 * (16 * b + (l32 >> 1)));
+        }
+        na[0] = lds_read16_off<0>(ab);
+        na[1] = lds_read16_off<8192>(ab);
+        na[2] = lds_read16_off<16384>(ab);
+        na[3] = lds_read16_off<24576>(ab);
+    };
+    auto wait_group = [&]() {
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(nbraw[0][0]), "+v"(nbraw[0][1]), "+v"(nbraw[1][0]), "+v"(nbraw[1][1]),
+                       "+v"(nsraw[0]), "+v"(nsraw[1]), "+v"(nzraw[0]), "+v"(nzraw[1]), "+v"(na[0]),
+                       "+v"(na[1]), "+v"(na[2]), "+v"(na[3]));
+    };
+    // the group's constants from what was read, and step 0 of its dequantization set up
+    half2_t ns2[2], nzA[2], nzB[2];
+    DqWord ndq[2];
+    auto group_consts = [&]() {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const half_t sh = __builtin_bit_cast(half_t, (uint16_t)nsraw[b]);
+            ns2[b] = half2_t{sh, sh};
+            const uint32_t z = (nzraw[b] >> ((l32 & 1) * 4)) & 0xFu;
+            nzA[b] = __builtin_bit_cast(half2_t, 0x64006400u | (z * 0x00010001u));
+            nzB[b] = __builtin_bit_cast(half2_t, 0x54005400u | (z * 0x00100010u));
+            ndq[b].w = nbraw[b][0][0];
+        }
+    };
+    auto adopt_group = [&]() {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            braw[b][0] = nbraw[b][0]; braw[b][1] = nbraw[b][1];
+            s2[b] = ns2[b]; zA[b] = nzA[b]; zB[b] = nzB[b];
+            dq[b] = ndq[b];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = na[i];
+    };
+
+    // group 0: nothing to overlap with yet
+    read_group(0);
+    wait_group();
+    group_consts();
+    dq_slice<0>(ndq, kc, nzA, nzB, ns2); dq_slice<1>(ndq, kc, nzA, nzB, ns2);
+    dq_slice<2>(ndq, kc, nzA, nzB, ns2); dq_slice<3>(ndq, kc, nzA, nzB, ns2);
+    dq_slice<4>(ndq, kc, nzA, nzB, ns2); dq_slice<5>(ndq, kc, nzA, nzB, ns2);
+    dq_slice<6>(ndq, kc, nzA, nzB, ns2); dq_slice<7>(ndq, kc, nzA, nzB, ns2);
+    adopt_group();
+
+    // One MFMA and, in its issue shadow, EXTRA.  The scheduling barrier pins the interleaving.
+#define AWQ_MFMA_SLOT(I, B, EXTRA)                                                                 \
+    acc[I][B] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a[I]),          \
+                                                       (B) ? bf1 : bf0, acc[I][B], 0, 0, 0);       \
+    EXTRA;                                                                                         \
+    __builtin_amdgcn_sched_barrier(0);
+
     int stage = 0;
     for (int g = 0; g < G; ++g) {
-        // two groups ahead; the stage it overwrites was last read in group g-1, which every
-        // wave left before the barrier at its end
-        int nstage = stage + 2;
-        nstage = nstage >= NSTAGE ? nstage - NSTAGE : nstage;
-        issue_group(g + 2, nstage);
-
+        int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;    // stage of group g+1
+        int fstage = nstage + 1 == NSTAGE ? 0 : nstage + 1;  // stage to fill with group g+2; it was
+                                                             // last read in group g-1, which every
+                                                             // wave left before the previous barrier
         const uint32_t abase = a_ring + (uint32_t)stage * A_STAGE;
-        const uint32_t bbase = b_ring + (uint32_t)stage * B_STAGE;
-        // this group's packed words, steps and zero points
-        u32x4 braw[2][2];
-        braw[0][0] = lds_read16(bbase + lane16);
-        braw[0][1] = lds_read16_off<1024>(bbase + lane16);
-        braw[1][0] = lds_read16_off<2048>(bbase + lane16);
-        braw[1][1] = lds_read16_off<3072>(bbase + lane16);
-        uint32_t sraw[2], zraw[2];
+        // steps 0..6: every MFMA is followed by a slice of the dequantization of the next step;
+        // the first four also by a fragment read of the next step, two more by a load of group g+2
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            sraw[b] = lds_read4(bbase + B_SC + 4 * (32 * b + l32));
-            zraw[b] = lds_read4(bbase + B_ZP + 4 * (16 * b + (l32 >> 1)));
-        }
-        u32x4 a[4];
-        a[0] = lds_read16_off<0>(abase + aoff[0]);
-        a[1] = lds_read16_off<8192>(abase + aoff[0]);
-        a[2] = lds_read16_off<16384>(abase + aoff[0]);
-        a[3] = lds_read16_off<24576>(abase + aoff[0]);
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(braw[0][0]), "+v"(braw[0][1]), "+v"(braw[1][0]), "+v"(braw[1][1]),
-                       "+v"(sraw[0]), "+v"(sraw[1]), "+v"(zraw[0]), "+v"(zraw[1]), "+v"(a[0]),
-                       "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
-        half2_t s2[2], zA[2], zB[2];
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const half_t sh = __builtin_bit_cast(half_t, (uint16_t)sraw[b]);
-            s2[b] = half2_t{sh, sh};
-            const uint32_t z = (zraw[b] >> ((l32 & 1) * 4)) & 0xFu;
-            zA[b] = __builtin_bit_cast(half2_t, 0x64006400u | (z * 0x00010001u));
-            zB[b] = __builtin_bit_cast(half2_t, 0x54005400u | (z * 0x00100010u));
-        }
-
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int j = s >> 1, h = s & 1;
-            // fragments of the next step are requested before this step's MFMAs
+        for (int s = 0; s < 7; ++s) {
+            const half8_t bf0 = dq_result(dq[0]), bf1 = dq_result(dq[1]);
             u32x4 an[4];
-            if (s < 7) {
-                const uint32_t ad = abase + aoff[(s + 1) & 3] + ((s + 1) >> 2) * 4096;
-                an[0] = lds_read16_off<0>(ad);
-                an[1] = lds_read16_off<8192>(ad);
-                an[2] = lds_read16_off<16384>(ad);
-                an[3] = lds_read16_off<24576>(ad);
+            const uint32_t ad = abase + aoff[(s + 1) & 3] + ((s + 1) >> 2) * 4096;
+            {
+                const int jn = (s + 1) >> 1, hn = (s + 1) & 1;
+#pragma unroll
+                for (int b = 0; b < 2; ++b) dq[b].w = word_of(braw[b][hn], jn);
             }
-            half8_t bf[2];
+            __builtin_amdgcn_sched_barrier(0);
+            AWQ_MFMA_SLOT(0, 0, an[0] = lds_read16_off<0>(ad); dq_slice<0>(dq, kc, zA, zB, s2))
+            AWQ_MFMA_SLOT(0, 1, an[1] = lds_read16_off<8192>(ad); dq_slice<1>(dq, kc, zA, zB, s2))
+            AWQ_MFMA_SLOT(1, 0, an[2] = lds_read16_off<16384>(ad); dq_slice<2>(dq, kc, zA, zB, s2))
+            AWQ_MFMA_SLOT(1, 1, an[3] = lds_read16_off<24576>(ad); dq_slice<3>(dq, kc, zA, zB, s2))
+            AWQ_MFMA_SLOT(2, 0, if (s == 0) AWQ_PIECE(0, g + 2, fstage); if (s == 1) AWQ_PIECE(2, g + 2, fstage);
+                                if (s == 2) AWQ_PIECE(4, g + 2, fstage); if (s == 3) AWQ_PIECE(6, g + 2, fstage);
+                                if (s == 4) AWQ_PIECE(8, g + 2, fstage); if (s == 5) AWQ_PIECE(10, g + 2, fstage);
+                                if (s == 6) AWQ_PIECE(12, g + 2, fstage);
+                                dq_slice<4>(dq, kc, zA, zB, s2))
+            AWQ_MFMA_SLOT(2, 1, if (s == 0) AWQ_PIECE(1, g + 2, fstage); if (s == 1) AWQ_PIECE(3, g + 2, fstage);
+                                if (s == 2) AWQ_PIECE(5, g + 2, fstage); if (s == 3) AWQ_PIECE(7, g + 2, fstage);
+                                if (s == 4) AWQ_PIECE(9, g + 2, fstage); if (s == 5) AWQ_PIECE(11, g + 2, fstage);
+                                if (s == 6) AWQ_PIECE(13, g + 2, fstage);
+                                dq_slice<5>(dq, kc, zA, zB, s2))
+            AWQ_MFMA_SLOT(3, 0, dq_slice<6>(dq, kc, zA, zB, s2))
+            AWQ_MFMA_SLOT(3, 1, dq_slice<7>(dq, kc, zA, zB, s2))
+            lds_wait(an[0], an[1], an[2], an[3]);
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
-                bf[b] = dequant_word(word_of(braw[b][h], j), kc, zA[b], zB[b], s2[b]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[i][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a[i]),
-                                                                       bf[b], acc[i][b], 0, 0, 0);
-            if (s < 7) {
-                lds_wait(an[0], an[1], an[2], an[3]);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) a[i] = an[i];
-            }
+            for (int i = 0; i < 4; ++i) a[i] = an[i];
         }
 
-        // group g+1 has landed once only the loads of group g+2 are outstanding
+        // group g+1 has landed once only the loads of group g+2 are outstanding; after the barrier
+        // every wave's part of it is visible.  Step 7 of this group has all its operands in
+        // registers already: its MFMAs cover the reads and the set-up of group g+1.
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_GROUP) : "memory");
         __builtin_amdgcn_s_barrier();
-        stage = stage + 1 == NSTAGE ? 0 : stage + 1;
+        {
+            const half8_t bf0 = dq_result(dq[0]), bf1 = dq_result(dq[1]);
+            read_group(nstage);
+            __builtin_amdgcn_sched_barrier(0);
+            AWQ_MFMA_SLOT(0, 0, (void)0)
+            AWQ_MFMA_SLOT(0, 1, (void)0)
+            AWQ_MFMA_SLOT(1, 0, (void)0)
+            AWQ_MFMA_SLOT(1, 1, (void)0)
+            wait_group();
+            group_consts();
+            __builtin_amdgcn_sched_barrier(0);
+            AWQ_MFMA_SLOT(2, 0, dq_slice<0>(ndq, kc, nzA, nzB, ns2); dq_slice<1>(ndq, kc, nzA, nzB, ns2))
+            AWQ_MFMA_SLOT(2, 1, dq_slice<2>(ndq, kc, nzA, nzB, ns2); dq_slice<3>(ndq, kc, nzA, nzB, ns2))
+            AWQ_MFMA_SLOT(3, 0, dq_slice<4>(ndq, kc, nzA, nzB, ns2); dq_slice<5>(ndq, kc, nzA, nzB, ns2))
+            AWQ_MFMA_SLOT(3, 1, dq_slice<6>(ndq, kc, nzA, nzB, ns2); dq_slice<7>(ndq, kc, nzA, nzB, ns2))
+            adopt_group();
+        }
+        stage = nstage;
     }
+#undef AWQ_MFMA_SLOT
+#undef AWQ_PIECE
     // drain the two harmless repeats before the LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
@@ -317,8 +437,10 @@ int awq_gemm_launch(const void *x, const void *qweight, const void *scales, cons
                     void *y, int M, int N, int K, hipStream_t stream)
 {
     const int G = K / AWQ_GROUP;
-    const dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM), block(256);
-    if (grid.y > 65535) return AWQ_ERR_BAD_SHAPE;
+    const int tiles_n = (N + BN - 1) / BN;
+    const int64_t tiles_total = (int64_t)tiles_n * ((M + BM - 1) / BM);
+    if (tiles_total > (1 << 30)) return AWQ_ERR_BAD_SHAPE;
+    const dim3 grid((unsigned)((tiles_total + 7) / 8 * 8)), block(256);
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel),
@@ -328,6 +450,6 @@ int awq_gemm_launch(const void *x, const void *qweight, const void *scales, cons
     }
     gemm_kernel<<<grid, block, LDS_BYTES, stream>>>(
         (const half_t *)x, (const unsigned char *)qweight, (const unsigned char *)scales,
-        (const unsigned char *)zeros, (half_t *)y, M, N, K, G);
+        (const unsigned char *)zeros, (half_t *)y, M, N, K, G, tiles_n, (int)tiles_total);
     return awq_launch_status();
 }
