@@ -3,14 +3,15 @@
 
 Headline workload (`config.workload`): the seven projections of one Llama-2-7B-shaped
 decoder layer (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), INT4 group-128
-weights, decode at M = 1.  One *step* is one pass over the seven linears of one layer; steps
-cycle through `--layers` distinct layers (> 800 MB of packed weights by default) so that
-every weight byte really comes from HBM and not from the 256 MB Infinity Cache.
-`value` is algorithmic bytes per step / time per step, in GB/s.
+weights, decode at M = 1.  One *step* is one pass over the seven linears of one layer, issued
+as ONE grouped launch (awq_w4a16_linear_multi); steps cycle through `--layers` distinct layers
+(> 800 MB of packed weights by default) so that every weight byte really comes from HBM and
+not from the 256 MB Infinity Cache.  `value` is algorithmic bytes per step / time per step.
 
-Also measured in the same run and reported as sub-objects of the same JSON line:
-decode at M = 4 and 16, the M = 2048 prefill GEMM (TFLOP/s), awq_quantize_pack (GB/s), and
-the CPU oracle on the host cores (`cpu_baseline`).
+Also measured in the same run and reported as sub-objects of the same JSON line: the same
+step as 4 launches (Q,K,V fused; gate,up fused) and as 7 single launches, grouped decode at
+M = 4 and 16, several layers per launch, the M = 2048 prefill GEMM (TFLOP/s),
+awq_quantize_pack (GB/s), and the CPU oracle on the host cores (`cpu_baseline`).
 
 Everything timed goes through the C ABI (paper_2306_00978_amd -> libawq_mi355x.so).
 Only the cpu_baseline leg imports the oracle.
@@ -37,10 +38,15 @@ def parse():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--layers", type=int, default=8, help="distinct layers cycled (cold cache)")
-    ap.add_argument("--no-graph", action="store_true", help="plain stream launches only")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the headline step from a hipGraph instead of launching it on the stream "
+                         "(slower for a single-kernel step; the multi-launch extras always use graphs)")
     ap.add_argument("--skip-extras", action="store_true",
                     help="only the headline decode measurement (used under rocprofv3)")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain elementwise copy of known size (256 MiB read, 256 MiB "
+                         "written, 5 times): the calibration kernel for rocprofv3 FETCH_SIZE / WRITE_SIZE")
     return ap.parse_args()
 
 
@@ -111,44 +117,70 @@ def main():
             del W
         layers.append(packed)
 
+    # ------------------------------------------------------------------ decode launch modes
+    # "grouped": ONE awq_w4a16_linear_multi per `span` layers (span = 1: the 7 projections of
+    #            a layer in one launch);
+    # "fused":   4 launches per layer as TinyChat runs it (Q,K,V in one kernel; gate,up in one);
+    # "single":  7 awq_w4a16_linear launches per layer.
+    ys_by_m = {}
     plans = {}
 
-    def run_layer(l, M, ys):
-        key = (l, M)
-        if key not in plans:       # arguments marshalled once; the call itself is one C call
-            plans[key] = [awq.prepare_linear(x_by_k[K][:M], *layers[l][p], ys[p], N)
-                          for p, (name, N, K) in enumerate(shapes)]
-        for call in plans[key]:
-            call()
+    def outputs(M):
+        return ys_by_m.setdefault(M, [torch.empty((M, N), dtype=torch.float16, device=dev)
+                                      for _, N, K in shapes])
 
-    ys_by_m = {}
+    def entries(l, M, ps):
+        ys = outputs(M)
+        return [(x_by_k[shapes[p][2]][:M], *layers[l][p], ys[p], shapes[p][1]) for p in ps]
+
+    def plan(mode, l, M, span=1):
+        key = (mode, l, M, span)
+        if key not in plans:       # arguments marshalled once; a call is then one C call
+            if mode == "grouped":
+                ent = []
+                for j in range(span):
+                    ent += entries((l + j) % L, M, range(7))
+                calls = [awq.prepare_linear_multi(ent)]
+            elif mode == "fused":
+                calls = [awq.prepare_linear_multi(entries(l, M, ps))
+                         for ps in ((0, 1, 2), (3,), (4, 5), (6,))]
+            else:
+                ys = outputs(M)
+                calls = [awq.prepare_linear(x_by_k[K][:M], *layers[l][p], ys[p], N)
+                         for p, (name, N, K) in enumerate(shapes)]
+            plans[key] = calls
+        return plans[key]
 
     def step_bytes(M):
         return sum(workloads.algorithmic_bytes(M, N, K) for _, N, K in shapes)
 
-    def time_decode(M, steps, warmup, use_graph):
-        ys = ys_by_m.setdefault(M, [torch.empty((M, N), dtype=torch.float16, device=dev)
-                                    for _, N, K in shapes])
+    def time_decode(mode, M, steps, warmup, use_graph, span=1):
+        """Returns (wall ms, event ms) per step of `span` layers.  Steps cycle through the L
+        distinct layers so that the weights of a step were last touched L/span steps ago."""
+        starts = list(range(0, L - span + 1, span)) or [0]
         graphs = None
         if use_graph:
             graphs = []
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(side):
-                run_layer(0, M, ys)
+                for call in plan(mode, 0, M, span):
+                    call()
             torch.cuda.current_stream().wait_stream(side)
             torch.cuda.synchronize()
-            for l in range(L):
+            for l in starts:
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g):
-                    run_layer(l, M, ys)
+                    for call in plan(mode, l, M, span):
+                        call()
                 graphs.append(g)
 
         def one(i):
             if graphs is not None:
-                graphs[i % L].replay()
+                graphs[i % len(starts)].replay()
             else:
-                run_layer(i % L, M, ys)
+                for call in plan(mode, starts[i % len(starts)], M, span):
+                    call()
 
         for i in range(warmup):
             one(i)
@@ -164,21 +196,27 @@ def main():
         ev_ms = e0.elapsed_time(e1)
         return wall_ms / steps, ev_ms / steps
 
-    use_graph = not args.no_graph
-    wall_ms, ev_ms = time_decode(1, args.steps, args.warmup, use_graph)
+    use_graph = args.graph
+    wall_ms, ev_ms = time_decode("grouped", 1, args.steps, args.warmup, use_graph)
     bytes_m1 = step_bytes(1)
     value = bytes_m1 / (wall_ms * 1e-3) / 1e9
-    launches = len(shapes)
+    launches = 1
     kernel_us = ev_ms * 1e3 / launches                     # average per launch, HIP events
     achieved = bytes_m1 / launches / (kernel_us * 1e-6) / 1e9
 
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "traffic.txt")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("decode_gemv_7b_m1_bytes_per_launch")
-        except Exception:
-            traffic = None
+        for line in open(tpath):
+            if line.startswith("decode_grouped_7b_layer_m1_bytes_per_launch"):
+                try:
+                    traffic = int(line.split("=")[1])
+                except ValueError:
+                    traffic = None
+
+    def gbs(b, ms):
+        return round(b / (ms * 1e-3) / 1e9, 1)
 
     result = {
         "metric": "W4A16 decode GEMV HBM GB/s (Llama-2-7B layer shapes, M=1)",
@@ -196,12 +234,13 @@ def main():
         "config": {
             "workload": "configs[1]: 7 projections of one Llama-2-7B-shaped layer, M=1, "
                         f"group 128, {L} distinct layers cycled (cold cache)",
-            "launch": "hipGraph replay of 7 launches per step" if use_graph else "plain stream",
+            "launch": "one grouped launch (awq_w4a16_linear_multi) of the 7 projections per step"
+                      + (", replayed from a hipGraph" if use_graph else ", launched on the stream"),
             "bytes_per_step": bytes_m1,
             "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         },
         "roofline": {
-            "kernel": "gemv_kernel (decode, M=1)",
+            "kernel": "gemv_stream_kernel (grouped decode, 7 linears, M=1)",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
@@ -215,16 +254,31 @@ def main():
 
     if not args.skip_extras:
         extras = {}
-        if use_graph:
-            w2, e2 = time_decode(1, args.steps, args.warmup, False)
-            extras["decode_m1_plain_stream"] = {"ms_per_step": round(w2, 5),
-                                                "GB/s": round(bytes_m1 / (w2 * 1e-3) / 1e9, 1)}
+        w2, e2 = time_decode("grouped", 1, args.steps, args.warmup, not use_graph)
+        extras["decode_m1_grouped_plain_stream" if use_graph else "decode_m1_grouped_graph_replay"] = {
+            "ms_per_step": round(w2, 5), "GB/s": gbs(bytes_m1, w2)}
+        w, e = time_decode("fused", 1, args.steps, args.warmup, True)
+        extras["decode_m1_fused_qkv_gateup_4_launches"] = {
+            "ms_per_step": round(w, 5), "GB/s": gbs(bytes_m1, w),
+            "pct_of_hbm_peak": round(100 * gbs(bytes_m1, w) / HBM_PEAK_GBS, 2)}
+        w, e = time_decode("single", 1, args.steps, args.warmup, True)
+        extras["decode_m1_7_single_launches"] = {
+            "ms_per_step": round(w, 5), "GB/s": gbs(bytes_m1, w),
+            "pct_of_hbm_peak": round(100 * gbs(bytes_m1, w) / HBM_PEAK_GBS, 2)}
+        span = min(8, L)
+        if span > 1:
+            w, e = time_decode("grouped", 1, max(20, args.steps // span), max(4, args.warmup // span),
+                               use_graph, span=span)
+            extras[f"decode_m1_grouped_{span}_layers_per_launch"] = {
+                "note": "launch amortisation only: the benchmark models no data dependence between "
+                        "linears, a real decoder has one between layers",
+                "ms_per_launch": round(w, 5), "GB/s": gbs(bytes_m1 * span, w),
+                "pct_of_hbm_peak": round(100 * gbs(bytes_m1 * span, w) / HBM_PEAK_GBS, 2)}
         for M in (4, 16):
-            w, e = time_decode(M, args.steps, args.warmup, use_graph)
+            w, e = time_decode("grouped", M, args.steps, args.warmup, use_graph)
             b = step_bytes(M)
-            extras[f"decode_m{M}"] = {"ms_per_step": round(w, 5),
-                                      "GB/s": round(b / (w * 1e-3) / 1e9, 1),
-                                      "pct_of_hbm_peak": round(100 * b / (w * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+            extras[f"decode_m{M}_grouped"] = {"ms_per_step": round(w, 5), "GB/s": gbs(b, w),
+                                              "pct_of_hbm_peak": round(100 * gbs(b, w) / HBM_PEAK_GBS, 2)}
         # prefill GEMM, M = 2048, the three distinct shapes
         M = workloads.PREFILL_M
         pre = {}
@@ -259,6 +313,15 @@ def main():
                                    "GB/s": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
                                    "pct_of_hbm_peak": round(100 * quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
         result["extras"] = extras
+
+    if args.copy_probe:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        result["copy_probe"] = {"kernel": "torch elementwise add (vectorized_elementwise_kernel)",
+                                "bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4, "launches": 5}
 
     if not args.skip_cpu:
         result["cpu_baseline"] = cpu_baseline(W0, calib_by_k, x_by_k, shapes)

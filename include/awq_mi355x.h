@@ -116,7 +116,7 @@ typedef struct awq_linear_desc {
     int64_t N, K;
 } awq_linear_desc;
 
-#define AWQ_MULTI_MAX 16
+#define AWQ_MULTI_MAX 56
 
 /* Sec. 4.2 (kernel fusion: several projections in one kernel, because a decode
  * kernel is about as short as a launch): the same computation as `count` calls of

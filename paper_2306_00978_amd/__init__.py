@@ -26,7 +26,7 @@ EXPORTS = [
     "awq_apply_inv_scale", "awq_quantize_pack", "awq_unpack", "awq_linear_workspace_bytes",
     "awq_w4a16_linear", "awq_w4a16_linear_multi",
 ]
-MULTI_MAX = 16
+MULTI_MAX = 56
 
 
 class LinearDesc(ctypes.Structure):

@@ -3,7 +3,7 @@
 
 #include "awq_common.h"
 
-constexpr int GEMV_MAX_PROBLEMS = 16;
+constexpr int GEMV_MAX_PROBLEMS = 56;     // 56 x 64 B of kernel arguments (limit: 4 KB)
 constexpr int AWQ_GEMV_STREAM_UNFIT = 1;    // internal: shape not covered, use the batch kernel
 
 // One linear of a grouped decode launch.  The caller fills the pointers and N, K; the
@@ -27,5 +27,7 @@ struct GemvLaunch {
     int logW;                 // log2 of the waves per workgroup
     int mlog;                 // log2 of M rounded up to a power of two
 };
+
+static_assert(sizeof(GemvLaunch) <= 4096, "kernel arguments are limited to 4 KB");
 
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream);

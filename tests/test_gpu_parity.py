@@ -288,14 +288,14 @@ def test_multi_every_m(awq, small_group, M):
 def test_multi_single_entry_and_limits(awq, small_group):
     import torch
     check_multi(awq, small_group[:1], 3)
-    check_multi(awq, small_group * 4, 2)                     # 16 entries: the maximum
+    check_multi(awq, small_group * 14, 2)                    # 56 entries: the maximum
     xs, Wdq, gpu, N = small_group[0]
     y = torch.empty((17, N), dtype=torch.float16, device="cuda")
     with pytest.raises(awq.AwqError) as e:                   # M > 16 is not a decode call
         awq.awq_w4a16_linear_multi([(dev(np.repeat(xs, 2, axis=0)[:17]), *gpu, y, N)])
     assert e.value.status == -2
     with pytest.raises(ValueError):
-        awq.prepare_linear_multi(small_group * 5)
+        awq.prepare_linear_multi(small_group * 15)
 
 
 def test_multi_exact_and_deterministic_on_integer_data(awq):
