@@ -374,17 +374,17 @@ int ceil_log2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 // kernel).
 //
 // Plan.  The kernel is bound by how evenly the memory requests of all resident waves cover
-// the run time, so every wave should get the same number of jobs T = (all batches) / (wave
-// slots of the chip), with a floor of one job.  Per linear, K is split over KS waves and a
-// workgroup takes `iters` consecutive row-block steps so that iters * (batches per wave and
-// row block) comes as close to T as possible.
+// the run time, so every wave should get about the same number of jobs T = (all batches) /
+// (waves wanted on the chip), with a floor of one job.  Per linear, K is split over the fewest
+// waves the register slots allow, and a workgroup takes `iters` consecutive row-block steps
+// so that iters * (batches per wave and row block) comes as close to T as possible.
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream)
 {
     static const int f_logw = env_int("AWQ_GEMV_LOGW", -1);
     static const int f_iters = env_int("AWQ_GEMV_ITERS", -1);
     static const int f_ksl = env_int("AWQ_GEMV_KSL", -1);
     static const int f_stages = env_int("AWQ_GEMV_STAGES", 2);
-    static const int f_slots = env_int("AWQ_GEMV_SLOTS", 1536);
+    static const int f_slots = env_int("AWQ_GEMV_SLOTS", 1792);
     static const int f_jobs = env_int("AWQ_GEMV_JOBS", -1);
     if (count < 1 || count > GEMV_MAX_PROBLEMS) return AWQ_ERR_BAD_ARGUMENT;
 
@@ -404,20 +404,15 @@ int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStr
         const int NBT = (problems[i].K / 128 + 3) / 4;
         const int ksl_min = ceil_log2((NBT + bpr - 1) / bpr);
         if (ksl_min > 3) return AWQ_GEMV_STREAM_UNFIT;
-        // candidates: KS = 2^ksl waves along K (each gets ceil(NBT/KS) batches per row block)
-        int best_ksl = ksl_min, best_iters = 1;
-        double best_err = 1e30;
-        for (int ksl = ksl_min; ksl <= 3 && (1 << ksl) <= NBT; ++ksl) {
-            const int nbw = (NBT + (1 << ksl) - 1) >> ksl;
-            const int iters = std::max(1, (int)(T / nbw + 0.5));
-            // relative distance from T, with a small penalty on K-splitting (extra reduction)
-            const double err = std::abs(iters * nbw - T) / T + 0.02 * ksl;
-            if (err < best_err) { best_err = err; best_ksl = ksl; best_iters = iters; }
-        }
-        if ((1 << best_ksl) > NBT) return AWQ_GEMV_STREAM_UNFIT;
-        if (f_ksl >= 0) best_ksl = std::min(3, std::max(ksl_min, f_ksl));
+        // K is split over as few waves as the register slots allow (splitting costs a pass
+        // through LDS and a barrier per row block); the row-block steps per workgroup bring the
+        // jobs of a wave as close to T as they get
+        int best_ksl = ksl_min;
+        if (f_ksl > ksl_min) best_ksl = std::min(3, f_ksl);
         while ((1 << best_ksl) > NBT && best_ksl > ksl_min) --best_ksl;
-        if (f_ksl >= 0) best_iters = std::max(1, (int)(T / ((NBT + (1 << best_ksl) - 1) >> best_ksl) + 0.5));
+        if ((1 << best_ksl) > NBT) return AWQ_GEMV_STREAM_UNFIT;
+        const int nbw = (NBT + (1 << best_ksl) - 1) >> best_ksl;
+        int best_iters = std::max(1, (int)(T / nbw + 0.5));
         if (f_iters > 0) best_iters = f_iters;
         ksl_of[i] = best_ksl;
         iters_of[i] = best_iters;
