@@ -338,6 +338,21 @@ def test_multi_llama7b_layer_full_size(awq):
         check_multi(awq, layer, M)
 
 
+def test_multi_llama70b_shapes_full_size(awq):
+    """Llama-2-70B-shaped linears (config 3) through the grouped call at M = 1 and 8, two shapes at
+    a time to bound host memory.  K = 28672 needs four waves along K at M = 1 and does not fit
+    the register slots at M = 8 (the call then runs one launch per linear): both paths are
+    checked against the oracle."""
+    pairs = [((8192, 8192), (1024, 8192)), ((28672, 8192), (1024, 8192)), ((8192, 28672), (1024, 8192))]
+    for a, b in pairs:
+        probs = []
+        for N, K in (a, b):
+            case, s, xs16, ref, gpu, Wdq = config_case(awq, N, K, 0.015, 3)
+            probs.append((xs16, Wdq, gpu, N))
+        for M in (1, 8):
+            check_multi(awq, probs + probs[1:], M)
+
+
 # ----------------------------------------------------------------------------- a0 / a0'
 
 @pytest.mark.parametrize("T,K", [(64, 4096), (5, 136), (1000, 11008)])
