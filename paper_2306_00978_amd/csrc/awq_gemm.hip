@@ -412,21 +412,36 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
     }
 #undef AWQ_MFMA_SLOT
 #undef AWQ_PIECE
-    // drain the two harmless repeats before the LDS is released
+    // drain the two harmless repeats; after the barrier nobody reads the rings any more
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
 
-    // epilogue: accumulator v of tile (i, b) is y[m0 + 32 i + 8 (v/4) + 4 hi + v%4][16 nt0 + 32 b + l32]
+    // Epilogue.  Accumulator v of tile (i, b) is y[m0 + 32 i + 8 (v/4) + 4 hi + v%4][16 nt0 + 32 b
+    // + l32]: a lane holds single columns, which would leave as 2-byte stores.  Each wave turns
+    // its 128 x 64 sub-tile around through its own 18 KB of the now idle LDS (rows of 128 + 16
+    // bytes: the padding spreads the banks) and stores 16 bytes per lane, 8 rows x 128 contiguous
+    // bytes per instruction.
+    {
+        constexpr int ROWB = 144;
+        unsigned char *mine = smem + (size_t)wave * (128 * ROWB);
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int n = (nt0 + 2 * b) * 16 + l32;
-        if (n >= N) continue;
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + 32 * i + 8 * (v >> 2) + 4 * hi + (v & 3);
-                if (m < M) y[(size_t)m * N + n] = (half_t)acc[i][b][v];
-            }
+                for (int v = 0; v < 16; ++v) {
+                    const int row = 32 * i + 8 * (v >> 2) + 4 * hi + (v & 3);
+                    *reinterpret_cast<half_t *>(mine + row * ROWB + (32 * b + l32) * 2) = (half_t)acc[i][b][v];
+                }
+        // wave-private area: the compiler orders these LDS reads after the writes above
+        const int n = nt0 * 16 + (lane & 7) * 8;
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int row = it * 8 + (lane >> 3);
+            const uint4 v = *reinterpret_cast<const uint4 *>(mine + row * ROWB + (lane & 7) * 16);
+            const int m = m0 + row;
+            if (m < M && n < N) *reinterpret_cast<uint4 *>(y + (size_t)m * N + n) = v;
+        }
     }
 }
 
