@@ -4,8 +4,8 @@
 // 16-level min/max form; Sec. 4.2: the codes are written directly in the packed
 // order the linear kernels consume.
 //
-// One wavefront owns one tile (16 rows x 128 columns = one quantization group for
-// 16 rows).  Lane l works on row l%16 and on the four 8-column runs
+// A wavefront works on one tile at a time (16 rows x 128 columns = one quantization group
+// for 16 rows).  Lane l works on row l%16 and on the four 8-column runs
 // 32*j + 8*(l/16) + 0..7, which is exactly the 16-byte slot it will write, so the
 // packed tile leaves the wave as a single coalesced 1 KB store.  The four lanes
 // l, l^16, l^32, l^48 share a row; its min/max are combined with two xor-shuffles.
@@ -27,81 +27,140 @@ __device__ __forceinline__ float clampf(float v, float lo, float hi)
 // nibble position of element e inside a packed word: {0,4,1,5,2,6,3,7}
 __device__ __forceinline__ int nib_shift(int e) { return 4 * ((e >> 1) + 4 * (e & 1)); }
 
+// Correctly rounded n / d for a divisor shared by many numerators: the refinement of the
+// reciprocal (which depends on d only) is done once, the numerator-dependent tail is the
+// same Newton-residual sequence the compiler emits for an IEEE division, without the
+// range-scaling steps.  Valid when neither operand nor the quotient comes near the ends of the
+// fp32 range, which the caller checks per group (otherwise it divides with `/`).
+struct Reciprocal {
+    float d, r;
+};
+__device__ __forceinline__ Reciprocal make_reciprocal(float d)
+{
+    const float r0 = __builtin_amdgcn_rcpf(d);
+    const float e0 = __builtin_fmaf(-d, r0, 1.0f);
+    return {d, __builtin_fmaf(e0, r0, r0)};
+}
+__device__ __forceinline__ float divide(float n, const Reciprocal &k)
+{
+    const float q0 = n * k.r;
+    const float e1 = __builtin_fmaf(-k.d, q0, n);
+    const float q1 = __builtin_fmaf(e1, k.r, q0);
+    const float e2 = __builtin_fmaf(-k.d, q1, n);
+    return __builtin_fmaf(e2, k.r, q1);
+}
+
+// One wave owns group g of a range of consecutive row blocks: the 128 scale factors s of the
+// group stay in registers, and the loads of the next tile are in flight while the current one
+// is quantized.
 __global__ __launch_bounds__(256) void quantize_pack_kernel(
     const uint4 *__restrict__ W,   // [N, K/8] runs of eight fp16
     const float4 *__restrict__ s,  // [K/4] or nullptr
     uint4 *__restrict__ qweight, uint16_t *__restrict__ scales, uint8_t *__restrict__ zeros,
-    int G, int num_tiles)
+    int G, int NRB, int rb_per_wave, int num_units)
 {
     const int lane = threadIdx.x & 63;
-    const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= num_tiles) return;                 // whole wave leaves together
-    const int rb = tile / G, g = tile - rb * G;
+    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (unit >= num_units) return;                 // whole wave leaves together
+    const int g = unit % G, part = unit / G;
+    const int rb0 = part * rb_per_wave;
+    const int rb1 = min(NRB, rb0 + rb_per_wave);
     const int r = lane & 15, c = lane >> 4;
-    const int64_t n = (int64_t)rb * 16 + r;
     const int64_t K8 = (int64_t)G * 16;            // row length in 8-element runs
 
-    float wp[4][8];
+    // s for this lane's four runs (columns 32 j + 8 c + 0..7 of the group)
+    float sv[4][8];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int run = g * 16 + 4 * j + c;        // 8-column run inside the row
-        uint4 raw = W[n * K8 + run];
-        const half_t *h = reinterpret_cast<const half_t *>(&raw);
-        float sv[8];
+        const int run = g * 16 + 4 * j + c;
         if (s) {
-            float4 a = s[2 * run], b = s[2 * run + 1];
-            sv[0] = a.x; sv[1] = a.y; sv[2] = a.z; sv[3] = a.w;
-            sv[4] = b.x; sv[5] = b.y; sv[6] = b.z; sv[7] = b.w;
+            const float4 a = s[2 * run], b = s[2 * run + 1];
+            sv[j][0] = a.x; sv[j][1] = a.y; sv[j][2] = a.z; sv[j][3] = a.w;
+            sv[j][4] = b.x; sv[j][5] = b.y; sv[j][6] = b.z; sv[j][7] = b.w;
         } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sv[e] = 1.0f;
+            for (int e = 0; e < 8; ++e) sv[j][e] = 1.0f;
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) wp[j][e] = (float)h[e] * sv[e];
     }
 
-    float mx = wp[0][0], mn = wp[0][0];
+    auto load_tile = [&](uint4 (&raw)[4], int rb) {
+        const int64_t n = (int64_t)rb * 16 + r;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j) raw[j] = W[n * K8 + g * 16 + 4 * j + c];
+    };
+
+    uint4 cur[4], nxt[4];
+    if (rb0 < rb1) load_tile(cur, rb0);
+    for (int rb = rb0; rb < rb1; ++rb) {
+        if (rb + 1 < rb1) load_tile(nxt, rb + 1);
+
+        float wp[4][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            mx = fmaxf(mx, wp[j][e]);
-            mn = fminf(mn, wp[j][e]);
+        for (int j = 0; j < 4; ++j) {
+            const half_t *h = reinterpret_cast<const half_t *>(&cur[j]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wp[j][e] = (float)h[e] * sv[j][e];
         }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mn = fminf(mn, __shfl_xor(mn, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    mn = fminf(mn, __shfl_xor(mn, 32));
 
-    const float range = mx - mn;
-    float sc32 = range / 15.0f;
-    sc32 = clampf(sc32, 6.103515625e-05f, 65504.0f);
-    const half_t sc_h = (half_t)sc32;              // v_cvt_f16_f32, round-half-even
-    const float scale = (float)sc_h;
-    const float nmn = -mn;
-    const float zr = nmn / scale;
-    const float zero = clampf(__builtin_rintf(zr), 0.0f, 15.0f);
+        float mx = wp[0][0], mn = wp[0][0];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                mx = fmaxf(mx, wp[j][e]);
+                mn = fminf(mn, wp[j][e]);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mn = fminf(mn, __shfl_xor(mn, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mn = fminf(mn, __shfl_xor(mn, 32));
 
-    uint32_t words[4];
+        const float range = mx - mn;
+        float sc32 = range / 15.0f;
+        sc32 = clampf(sc32, 6.103515625e-05f, 65504.0f);
+        const half_t sc_h = (half_t)sc32;              // v_cvt_f16_f32, round-half-even
+        const float scale = (float)sc_h;
+        const float nmn = -mn;
+        const float zr = nmn / scale;
+        const float zero = clampf(__builtin_rintf(zr), 0.0f, 15.0f);
+
+        // scale is in [2^-14, 65504]; with |w'| below 1e18 the shared-reciprocal division is exact
+        // IEEE division.  Otherwise (never with real weights) the whole wave divides with `/`.
+        const bool tame = __all(fmaxf(fabsf(mx), fabsf(mn)) < 1.0e18f);
+        const Reciprocal rc = make_reciprocal(scale);
+
+        // a word is assembled as two exact fp32 integers of 16 bits (four nibbles each)
+        uint32_t words[4];
+        auto assemble = [&](auto quotient) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        uint32_t w = 0;
+            for (int j = 0; j < 4; ++j) {
+                float lo = 0.0f, hi = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float q = __builtin_rintf(wp[j][e] / scale);
-            q = q + zero;
-            q = clampf(q, 0.0f, 15.0f);
-            w |= (uint32_t)q << nib_shift(e);
+                for (int e = 0; e < 8; ++e) {
+                    float q = __builtin_rintf(quotient(wp[j][e]));
+                    q = q + zero;
+                    q = clampf(q, 0.0f, 15.0f);
+                    const int sh = nib_shift(e);            // 0,16,4,20,8,24,12,28
+                    const float weight = (float)(1u << (sh & 15));
+                    if (sh < 16) lo = __builtin_fmaf(q, weight, lo);
+                    else hi = __builtin_fmaf(q, weight, hi);
+                }
+                words[j] = (uint32_t)lo | ((uint32_t)hi << 16);
+            }
+        };
+        if (tame) assemble([&](float n) { return divide(n, rc); });
+        else assemble([&](float n) { return n / scale; });
+        const int64_t tile = (int64_t)rb * G + g;
+        qweight[tile * 64 + lane] = make_uint4(words[0], words[1], words[2], words[3]);
+
+        const uint32_t z = (uint32_t)zero;
+        const uint32_t z_hi = __shfl_xor(z, 1);        // the odd row of the pair
+        if (c == 0) {
+            scales[tile * 16 + r] = __builtin_bit_cast(uint16_t, sc_h);
+            if ((r & 1) == 0) zeros[tile * 8 + (r >> 1)] = (uint8_t)(z | (z_hi << 4));
         }
-        words[j] = w;
-    }
-    qweight[(int64_t)tile * 64 + lane] = make_uint4(words[0], words[1], words[2], words[3]);
-
-    const uint32_t z = (uint32_t)zero;
-    const uint32_t z_hi = __shfl_xor(z, 1);        // the odd row of the pair
-    if (c == 0) {
-        scales[(int64_t)tile * 16 + r] = __builtin_bit_cast(uint16_t, sc_h);
-        if ((r & 1) == 0) zeros[(int64_t)tile * 8 + (r >> 1)] = (uint8_t)(z | (z_hi << 4));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cur[j] = nxt[j];
     }
 }
 
@@ -153,11 +212,17 @@ extern "C" int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, i
         !awq_aligned16(zeros) || (s && !awq_aligned16(s)))
         return AWQ_ERR_MISALIGNED;
     const int G = (int)(K / AWQ_GROUP);
-    const int num_tiles = (int)(N / 16) * G;
-    const int blocks = (num_tiles + 3) / 4;
+    const int NRB = (int)(N / 16);
+    // about 16 waves per CU in flight; a wave keeps its group and walks down the row blocks
+    int parts = (4096 + G - 1) / G;
+    parts = parts < 1 ? 1 : (parts > NRB ? NRB : parts);
+    const int rb_per_wave = (NRB + parts - 1) / parts;
+    parts = (NRB + rb_per_wave - 1) / rb_per_wave;
+    const int num_units = parts * G;
+    const int blocks = (num_units + 3) / 4;
     quantize_pack_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
         (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
-        (uint8_t *)zeros, G, num_tiles);
+        (uint8_t *)zeros, G, NRB, rb_per_wave, num_units);
     return awq_launch_status();
 }
 
