@@ -122,6 +122,29 @@ def test_quantize_pack_edge_groups(awq):
     assert_quantize_bit_exact(awq, W, s2)
 
 
+def test_quantize_near_ties_and_wide_ranges(awq):
+    """Groups built so that w/step lands on or next to half-integers, over the whole range of
+    step magnitudes (2^-14 .. 6e4) and with s spread over six decades: the kernel's division by
+    the group's step must reproduce the IEEE quotient the oracle uses, bit for bit."""
+    g = np.random.default_rng(99)
+    N, K = 512, 1024
+    W = np.zeros((N, K), dtype=np.float32)
+    for n in range(N):
+        for grp in range(K // 128):
+            step = 2.0 ** g.uniform(-13, 11)
+            k = g.integers(0, 16, size=128).astype(np.float64)
+            frac = g.choice([0.0, 0.5, 0.5 - 2e-4, 0.5 + 2e-4, 0.25, 0.4999, 0.5001], size=128)
+            v = (k + frac) * step - g.integers(0, 9) * step
+            v[0], v[1] = v.min() - 0.0, v.max() + 0.0
+            W[n, grp * 128:(grp + 1) * 128] = v
+    W = np.clip(W, -60000, 60000).astype(np.float16)
+    assert_quantize_bit_exact(awq, W, None)
+    s = (10.0 ** g.uniform(-3, 3, size=K)).astype(np.float32)
+    assert_quantize_bit_exact(awq, W, s)
+    s_huge = np.full(K, 1e25, dtype=np.float32)            # |w s| beyond the shared-reciprocal range
+    assert_quantize_bit_exact(awq, W, s_huge)
+
+
 CONFIG_SHAPES = [
     # (N, K, sigma, cfg)
     (4096, 4096, 0.02, 1), (11008, 4096, 0.02, 1), (4096, 11008, 0.02, 1),
