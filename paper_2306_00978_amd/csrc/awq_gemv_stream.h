@@ -15,12 +15,15 @@ struct GemvProblem {
     const uint8_t *zp;        // zero points
     half_t *y;                // [M,N]
     int N, K;
-    int wg_begin;             // first workgroup of this linear in the grid
     int ks_log;               // log2 of the waves that split K for one row block
     int iters;                // row-block iterations per workgroup
 };
 
 struct GemvLaunch {
+    // first workgroup of each linear in the grid; kept together (and first) so that finding the
+    // linear of a workgroup touches one or two cache lines of the kernel arguments, not one per
+    // linear
+    int wg_begin[GEMV_MAX_PROBLEMS];
     GemvProblem p[GEMV_MAX_PROBLEMS];
     int count;
     int M;

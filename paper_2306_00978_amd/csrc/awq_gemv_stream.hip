@@ -164,7 +164,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
     // which linear of the list this workgroup belongs to (wave-uniform)
     int pi = 0;
     for (int i = 1; i < L.count; ++i)
-        if ((int)blockIdx.x >= L.p[i].wg_begin) pi = i;
+        if ((int)blockIdx.x >= L.wg_begin[i]) pi = i;
     const GemvProblem &P = L.p[pi];
 
     const int M = L.M, mlog = L.mlog, Mpad = 1 << mlog;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ks = wave & (KS - 1), ri = wave >> ksl;
     const int b0 = (NBT * ks) >> ksl, b1 = (NBT * (ks + 1)) >> ksl;      // 1..16/Mpad batches (host)
-    const int unit = (int)blockIdx.x - P.wg_begin;
+    const int unit = (int)blockIdx.x - L.wg_begin[pi];
     const int rb_wg = unit * iters * RW;                                 // first row block of the WG
     const int r = lane & 15, c = lane >> 4;
     const int zshift = (r & 1) * 4;
@@ -226,8 +226,28 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
         }
     };
 
-    // the first weight requests go out before anything else, so that their latency and the
-    // latency of the activation loads overlap
+    // activation fragments (see the header comment), loaded once.  Their loads go out first:
+    // they are tiny, and behind the first weight requests of the whole grid they would wait
+    // for megabytes that are of no use before the fragments are there.
+    uint4 xa[16];
+    {
+        const int slot = r >> mlog;
+        int m = r & (Mpad - 1);
+        m = m < M ? m : M - 1;
+        const int bl = b0 + slot;
+        const half_t *xrow = P.x + (size_t)m * K + 8 * c;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int g = 4 * bl + u;
+            const bool ok = bl < b1 && g < G;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xa[4 * u + j] = ok ? *reinterpret_cast<const uint4 *>(xrow + g * 128 + 32 * j)
+                                   : make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    // the first weight requests
     const int nbw = b1 - b0;
     const int J = iters * nbw;                               // jobs of this wave
     int nit = 0, nb = b0, nslot = 0, nj = 0;                 // next job to request
@@ -241,28 +261,14 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
     for (int s = 0; s < STAGES - 1; ++s)
         if (nj < J) issue_next();
 
-    // activation fragments (see the header comment), loaded once; halves 2,3,6,7 of every
-    // fragment meet the 2^-20 codes and are scaled by 2^-4 to match the 2^-24 ones
-    uint4 xa[16];
+    // halves 2,3,6,7 of every fragment meet the 2^-20 codes and are scaled by 2^-4 to match the
+    // 2^-24 ones
     {
-        const int slot = r >> mlog;
-        int m = r & (Mpad - 1);
-        m = m < M ? m : M - 1;
-        const int bl = b0 + slot;
-        const half_t *xrow = P.x + (size_t)m * K + 8 * c;
         const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int g = 4 * bl + u;
-            const bool ok = bl < b1 && g < G;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint4 f = ok ? *reinterpret_cast<const uint4 *>(xrow + g * 128 + 32 * j)
-                             : make_uint4(0, 0, 0, 0);
-                f.y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, f.y) * sixteenth);
-                f.w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, f.w) * sixteenth);
-                xa[4 * u + j] = f;
-            }
+        for (int i = 0; i < 16; ++i) {
+            xa[i].y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, xa[i].y) * sixteenth);
+            xa[i].w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, xa[i].w) * sixteenth);
         }
     }
     // 2^-24 * sum of the activations of each tile, per output row: the fragments against the
@@ -433,7 +439,7 @@ int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStr
         const int iters = std::min(iters_of[i], steps);
         p.ks_log = ksl_of[i];
         p.iters = iters;
-        p.wg_begin = wg;
+        L.wg_begin[i] = wg;
         wg += (steps + iters - 1) / iters;
         L.p[i] = p;
     }
