@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--layers", type=int, default=8, help="distinct layers cycled (cold cache)")
+    ap.add_argument("--layers", type=int, default=32,
+                    help="distinct layers cycled (cold cache); 32 = the whole Llama-2-7B-shaped stack")
     ap.add_argument("--graph", action="store_true",
                     help="replay the headline step from a hipGraph instead of launching it on the stream "
                          "(slower for a single-kernel step; the multi-launch extras always use graphs)")
@@ -274,6 +275,15 @@ def main():
                         "linears, a real decoder has one between layers",
                 "ms_per_launch": round(w, 5), "GB/s": gbs(bytes_m1 * span, w),
                 "pct_of_hbm_peak": round(100 * gbs(bytes_m1 * span, w) / HBM_PEAK_GBS, 2)}
+            # configs[4]: the whole stack token by token (all L layers once per token step)
+            extras[f"decode_m1_full_stack_{L}_layers"] = {
+                "bytes_per_token_step": bytes_m1 * L,
+                "one_launch_per_layer": {"launches_per_token_step": L,
+                                         "ms_per_token_step": round(wall_ms * L, 4),
+                                         "GB/s": gbs(bytes_m1, wall_ms)},
+                f"one_launch_per_{span}_layers": {"launches_per_token_step": L // span,
+                                                  "ms_per_token_step": round(w * (L // span), 4),
+                                                  "GB/s": gbs(bytes_m1 * span, w)}}
         for M in (4, 16):
             w, e = time_decode("grouped", M, args.steps, args.warmup, use_graph)
             b = step_bytes(M)

@@ -376,6 +376,125 @@ def test_multi_llama70b_shapes_full_size(awq):
             check_multi(awq, probs + probs[1:], M)
 
 
+# ------------------------------------------------------------------- the full stack (config 4)
+
+def test_config4_full_stack(awq):
+    """The 32-layer Llama-2-7B-shaped stack: one awq_quantize_pack pass over all 224 matrices
+    (every packed byte, step and zero point against the oracle), then 128 decode steps at M = 1
+    over the 224 linears, issued as grouped launches (even steps: 32 launches of one layer's 7
+    projections; odd steps: 4 launches of 8 layers = 56 linears).  Step 0 and three further
+    seeded steps are compared with the oracle, every output element.
+
+    s of layer 0's four distinct inputs comes from the full calibration set (128 sequences of
+    512 rows), which also checks awq_act_scale at T = 65 536; the other layers use one sequence
+    (512 rows) to bound the host time spent drawing random numbers."""
+    import os
+    import torch
+    import oracle
+    import workloads
+    from concurrent.futures import ThreadPoolExecutor
+
+    threads = max(1, min(16, len(os.sched_getaffinity(0))))
+    shapes = workloads.LLAMA2_7B_LAYER
+    L, STEPS = workloads.STACK_LAYERS, workloads.STACK_STEPS
+    widths = (4096, 11008)
+    check_steps = [0] + sorted(int(v) for v in
+                               np.random.default_rng(4).choice(np.arange(1, STEPS), size=3, replace=False))
+    if all(st % 2 == 0 for st in check_steps[1:]):
+        check_steps[-1] |= 1                                   # both launch groupings get checked
+
+    # ---- s per (layer, distinct input); layer 0 from the full calibration set, also on the GPU
+    s_of = {}
+    for l in range(L):
+        for inp in range(4):
+            K = 11008 if inp == 3 else 4096
+            out = workloads.outlier_channels(K, 4, l, inp)
+            n_seq = workloads.CALIB_SEQUENCES if l == 0 else 1
+            X = workloads.calibration_sequences(n_seq, K, 4, l, inp, out, threads=threads)
+            s64 = oracle.act_scale(X, 0.5)
+            s_of[(l, inp)] = s64.astype(np.float32)
+            if l == 0:
+                T = X.shape[0]
+                s_gpu = host(awq.awq_act_scale(dev(X), 0.5)).astype(np.float64)
+                # fp32 running sums of T/128 non-negative terms per partial, then a 7-level tree:
+                # relative error of the mean <= (T/128 + 7) * 2^-24; the square root halves it
+                assert np.abs(s_gpu / s64 - 1.0).max() <= 0.5 * (T / 128 + 7) * 2.0 ** -24 + 1e-7
+            del X
+
+    # ---- x' per step and width: fresh seeded rows, divided by layer 0's s of that width
+    xs_all = {}
+    for ki, K in enumerate(widths):
+        out = workloads.outlier_channels(K, 4, 0, 0 if K == 4096 else 3)
+        rows = np.concatenate([workloads.activations(1, K, 4, STEPS + st, ki, workloads.ROLE_X, out)
+                               for st in range(STEPS)])
+        xs_all[K] = oracle.apply_inv_scale(rows, s_of[(0, 0 if K == 4096 else 3)])
+    x_chk = {K: np.ascontiguousarray(xs_all[K][check_steps]) for K in widths}
+
+    # ---- quantize pass: layer by layer, bit-exact against the oracle; keep the packed arrays on
+    # the GPU, and of the oracle only y_ref of the checked steps and max|Wdq| per matrix
+    packed, y_ref, wmax, canaries = [], [], [], []
+    for l in range(L):
+        with ThreadPoolExecutor(min(threads, 7)) as ex:
+            Ws = list(ex.map(lambda p: workloads.weights(shapes[p][1], shapes[p][2], workloads.SIGMA_7B,
+                                                         4, l, p), range(7)))
+        lp, ly, lw = [], [], []
+        for p, (name, N, K) in enumerate(shapes):
+            s = s_of[(l, workloads.LAYER_INPUT_OF_PROJ[p])]
+            qb, sb, zb = awq.awq_packed_sizes(N, K)
+            q_gpu, cq = guarded(qb, torch.uint8)
+            s_gpu, cs = guarded(sb, torch.float16)
+            z_gpu, cz = guarded(zb, torch.uint8)
+            awq.awq_quantize_pack(dev(Ws[p]), dev(s), out=(q_gpu, s_gpu, z_gpu))
+            codes, scales, zeros = oracle.quantize(Ws[p], s)
+            q_ref, s_ref, z_ref = oracle.pack(codes, scales, zeros)
+            cq(); cs(); cz()
+            canaries += [cq, cs, cz]
+            assert np.array_equal(host(s_gpu).view(np.uint16), s_ref), f"steps differ (layer {l}, {name})"
+            assert np.array_equal(host(z_gpu), z_ref), f"zero points differ (layer {l}, {name})"
+            assert np.array_equal(host(q_gpu), q_ref), f"packed codes differ (layer {l}, {name})"
+            Wdq = oracle.dequant(codes, scales, zeros)
+            ly.append(oracle.matmul(x_chk[K], Wdq))
+            lw.append(float(np.abs(Wdq).max()))
+            lp.append((q_gpu, s_gpu, z_gpu))
+            del Wdq, codes
+        packed.append(lp); y_ref.append(ly); wmax.append(lw)
+        del Ws
+
+    # ---- decode: 128 steps over the 224 linears
+    x_dev = {K: dev(xs_all[K]) for K in widths}
+    x_cur = {K: torch.empty((1, K), dtype=torch.float16, device="cuda") for K in widths}
+    ys = [[torch.empty((1, N), dtype=torch.float16, device="cuda") for _, N, K in shapes] for l in range(L)]
+
+    def entries(l):
+        return [(x_cur[K], *packed[l][p], ys[l][p], N) for p, (_, N, K) in enumerate(shapes)]
+
+    per_layer = [awq.prepare_linear_multi(entries(l)) for l in range(L)]
+    per_eight = [awq.prepare_linear_multi(sum((entries(l) for l in range(l0, l0 + 8)), []))
+                 for l0 in range(0, L, 8)]
+    worst = 0.0
+    for st in range(STEPS):
+        for K in widths:
+            x_cur[K].copy_(x_dev[K][st:st + 1])
+        for call in (per_layer if st % 2 == 0 else per_eight):
+            call()
+        if st in check_steps:
+            j = check_steps.index(st)
+            for l in range(L):
+                for p, (name, N, K) in enumerate(shapes):
+                    y = host(ys[l][p]).astype(np.float64)[0]
+                    assert np.all(np.isfinite(y))
+                    xn = np.linalg.norm(x_chk[K][j].astype(np.float64))
+                    err = np.abs(y - y_ref[l][p][j]) / (xn * wmax[l][p] + 1e-6)
+                    assert err.max() <= TOL, f"step {st}, layer {l}, {name}: error {err.max():.3e}"
+                    worst = max(worst, float(err.max()))
+            for l in range(L):                                  # stale outputs cannot pass later
+                for y in ys[l]:
+                    y.zero_()
+    for check in canaries:                                      # the decode steps wrote nothing there
+        check()
+    print(f"config 4: worst normalised error over steps {check_steps}: {worst:.3e}")
+
+
 # ----------------------------------------------------------------------------- a0 / a0'
 
 @pytest.mark.parametrize("T,K", [(64, 4096), (5, 136), (1000, 11008)])

@@ -39,10 +39,20 @@ OUTLIER_GAIN = 20.0
 CALIB_TOKENS = 64
 PREFILL_M = 2048
 
+# the full stack: 32 decoder layers, 128 decode steps, calibration set of 128 sequences of 512
+# tokens (the size the paper calibrates on, Sec. 5 "Settings")
+STACK_LAYERS = 32
+STACK_STEPS = 128
+CALIB_SEQUENCES = 128
+CALIB_SEQ_LEN = 512
+# distinct inputs of a decoder layer and the input each of the seven projections reads:
+# 0 = attention input (q,k,v), 1 = attention output (o), 2 = MLP input (gate, up), 3 = down's input
+LAYER_INPUT_OF_PROJ = (0, 0, 0, 1, 2, 2, 3)
 
-def rng(cfg: int, layer: int, proj: int, role: int) -> np.random.Generator:
+
+def rng(cfg: int, layer: int, proj: int, role: int, *more: int) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64(np.random.SeedSequence(
-        [BASE_SEED, int(cfg), int(layer), int(proj), int(role)])))
+        [BASE_SEED, int(cfg), int(layer), int(proj), int(role)] + [int(v) for v in more])))
 
 
 def weights(N: int, K: int, sigma: float, cfg: int, layer: int, proj: int) -> np.ndarray:
@@ -71,6 +81,29 @@ def activations(T: int, K: int, cfg: int, layer: int, proj: int, role: int,
     X = g.standard_normal((T, K), dtype=np.float32)
     X[:, outliers] *= np.float32(OUTLIER_GAIN)
     return X.astype(np.float16)
+
+
+def calibration_sequences(n_seq: int, K: int, cfg: int, layer: int, inp: int,
+                          outliers: np.ndarray, threads: int = 1) -> np.ndarray:
+    """X[n_seq * 512, K] fp16: calibration sequences of 512 rows each, every sequence from a
+    generator of its own (so they can be drawn in parallel and the result does not depend on
+    the number of threads)."""
+    X = np.empty((n_seq * CALIB_SEQ_LEN, K), dtype=np.float16)
+
+    def one(i):
+        g = rng(cfg, layer, inp, ROLE_CALIB, i)
+        blk = g.standard_normal((CALIB_SEQ_LEN, K), dtype=np.float32)
+        blk[:, outliers] *= np.float32(OUTLIER_GAIN)
+        X[i * CALIB_SEQ_LEN:(i + 1) * CALIB_SEQ_LEN] = blk.astype(np.float16)
+
+    if threads > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(one, range(n_seq)))
+    else:
+        for i in range(n_seq):
+            one(i)
+    return X
 
 
 @dataclass
