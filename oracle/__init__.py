@@ -201,3 +201,29 @@ def norm_error(y_gpu, y_ref, x, Wdq) -> np.ndarray:
 def linear(x, codes, scales, zeros, group: int = GROUP) -> np.ndarray:
     """The whole layer as the paper states it: dequantize, then matmul (fp64 acc)."""
     return matmul(x, dequant(codes, scales, zeros, group))
+
+
+def scale_search_loss(W, X, s) -> float:
+    """Sec. 3.2, Eq. 4: L(s) = || Q(W diag(s)) (diag(s)^-1 X) - W X ||^2 for one linear layer,
+    the norm taken over all entries (Frobenius) and returned squared.  Q is `quantize`, the
+    diag(s)^-1 X factor is the fp16 array the layer is really fed (`apply_inv_scale`), both
+    products are accumulated in fp64.  W [N,K] fp16, X [T,K] fp16 (rows = tokens), s [K]."""
+    W = np.ascontiguousarray(W)
+    if W.dtype != np.float16:
+        raise TypeError("W must be float16")
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    codes, scales, zeros = quantize(W, s)
+    yq = matmul(apply_inv_scale(X, s), dequant(codes, scales, zeros))
+    y = matmul(X, W.astype(np.float32))
+    d = yq - y
+    return float(np.sum(d * d))
+
+
+def search_scale(W, X, alphas):
+    """Sec. 3.2, Eq. 5: s = s_X^alpha with s_X the per-channel mean |X|; alpha* minimises the
+    loss of Eq. 4 over the given grid (first minimum on ties).
+    Returns (index of alpha*, losses[len(alphas)] fp64, s* [K] fp32)."""
+    losses = np.array([scale_search_loss(W, X, act_scale(X, float(a)).astype(np.float32))
+                       for a in alphas], dtype=np.float64)
+    best = int(np.argmin(losses))
+    return best, losses, act_scale(X, float(alphas[best])).astype(np.float32)
