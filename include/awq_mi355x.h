@@ -130,6 +130,30 @@ typedef struct awq_linear_desc {
 int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+#define AWQ_SEARCH_MAX_ALPHAS 64
+
+/* Bytes of scratch awq_search_scale needs (0 for an invalid shape): the packed candidate,
+ * x / s, the fp16 layer output and the candidate's output ([T,N] fp16 each) and the partial
+ * sums. */
+size_t awq_search_scale_workspace_bytes(int64_t T, int64_t N, int64_t K, int n_alpha, int group);
+
+/* Sec. 3.2 "Searching to scale", Eq. 4-5: for every alpha of the grid, s = s_X^alpha with
+ * s_X[k] = max(mean_t |X[t,k]|, 1e-4), and
+ *   loss(alpha) = sum_{t,n} ( y_q[t,n] - y[t,n] )^2,
+ *   y_q = awq_w4a16_linear(awq_apply_inv_scale(X, s), awq_quantize_pack(W, s)),  y = fp16(X W^T)
+ * (the squared Frobenius norm of Eq. 4, both outputs as the fp16 arrays the layers produce,
+ * squares summed in fp64 in a fixed order).  best = first index of the smallest loss;
+ * s_best = s_X^alphas[best], bit-identical to awq_act_scale(X, alphas[best]).
+ *   W_f16 [N,K], X_f16 [T,K] fp16 row-major (device, read); alphas: HOST array of n_alpha
+ *   values in [0,1], 1 <= n_alpha <= AWQ_SEARCH_MAX_ALPHAS, read before the call returns;
+ *   workspace: device, 256-byte aligned, awq_search_scale_workspace_bytes() bytes, contents
+ *   undefined afterwards; losses [n_alpha] fp64, best [1] int32, s_best [K] fp32: device,
+ *   written.  Like every other call it only enqueues work on `stream`. */
+int awq_search_scale(const void *W_f16, const void *X_f16, int64_t T, int64_t N, int64_t K,
+                     const float *alphas, int n_alpha, int group, void *workspace,
+                     size_t workspace_bytes, double *losses, int32_t *best, float *s_best,
+                     void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,6 +9,7 @@ Function names and argument order mirror the C ABI:
     awq_act_scale, awq_apply_inv_scale            (AWQ Sec. 3.2, Eq. 4-5)
     awq_quantize_pack, awq_unpack                 (Sec. 3.2, Eq. 1-2; Sec. 4.2 packing)
     awq_w4a16_linear, awq_w4a16_linear_multi      (Sec. 4.2 fused dequantization, kernel fusion)
+    awq_search_scale                              (Sec. 3.2 searching to scale, Eq. 4-5)
 """
 from __future__ import annotations
 
@@ -25,6 +26,7 @@ EXPORTS = [
     "awq_version", "awq_status_string", "awq_packed_sizes", "awq_act_scale",
     "awq_apply_inv_scale", "awq_quantize_pack", "awq_unpack", "awq_linear_workspace_bytes",
     "awq_w4a16_linear", "awq_w4a16_linear_multi",
+    "awq_search_scale_workspace_bytes", "awq_search_scale",
 ]
 MULTI_MAX = 56
 
@@ -76,6 +78,11 @@ def load() -> ctypes.CDLL:
     lib.awq_w4a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
     lib.awq_w4a16_linear_multi.restype = i32
     lib.awq_w4a16_linear_multi.argtypes = [ctypes.POINTER(LinearDesc), i32, i64, i32, vp, sz, vp]
+    lib.awq_search_scale_workspace_bytes.restype = sz
+    lib.awq_search_scale_workspace_bytes.argtypes = [i64, i64, i64, i32, i32]
+    lib.awq_search_scale.restype = i32
+    lib.awq_search_scale.argtypes = [vp, vp, i64, i64, i64, ctypes.POINTER(ctypes.c_float), i32, i32,
+                                     vp, sz, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -276,3 +283,28 @@ def awq_w4a16_linear_multi(linears, group: int = GROUP):
     """The linears of `linears` = [(x, qweight, scales, zeros, y, N), ...] in one kernel launch."""
     prepare_linear_multi(linears, group)()
     return [l[4] for l in linears]
+
+
+def awq_search_scale(W: torch.Tensor, X: torch.Tensor, alphas, group: int = GROUP,
+                     workspace: torch.Tensor | None = None):
+    """Grid search of Eq. 5 for one linear: W [N,K] fp16, X [T,K] fp16 calibration rows,
+    `alphas` a sequence of values in [0,1].  Returns device tensors
+    (best [1] int32, losses [len(alphas)] fp64, s_best [K] fp32); nothing is synchronised."""
+    _dev(W, torch.float16, "W")
+    _dev(X, torch.float16, "X")
+    N, K = W.shape
+    T, K2 = X.shape
+    if K2 != K:
+        raise ValueError("W and X disagree on K")
+    n = len(alphas)
+    arr = (ctypes.c_float * max(n, 1))(*[float(a) for a in alphas])
+    need = load().awq_search_scale_workspace_bytes(T, N, K, n, group)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W.device)
+    losses = torch.empty(max(n, 1), dtype=torch.float64, device=W.device)
+    best = torch.empty(1, dtype=torch.int32, device=W.device)
+    s_best = torch.empty(K, dtype=torch.float32, device=W.device)
+    _check(load().awq_search_scale(W.data_ptr(), X.data_ptr(), T, N, K, arr, n, group,
+                                   workspace.data_ptr(), workspace.numel(), losses.data_ptr(),
+                                   best.data_ptr(), s_best.data_ptr(), _stream()), "awq_search_scale")
+    return best, losses[:n], s_best

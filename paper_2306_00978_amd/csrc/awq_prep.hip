@@ -14,6 +14,8 @@ constexpr int ACT_PHASES = 128;  // row phases per workgroup (1024 threads)
 // Each workgroup owns 64 columns and walks all T rows; thread (phase, oct) sums |x|
 // of rows phase, phase+128, ... for its eight columns.  The 128 partial sums per
 // column are then added in a fixed tree order, so the result is deterministic.
+// RAW: store the (floored) mean itself instead of its power.
+template <bool RAW>
 __global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict__ X,
                                                          int64_t T, int64_t K, float alpha,
                                                          float *__restrict__ s)
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict
         if (col < K) {
             float mean = red[0][threadIdx.x] / (float)T;
             mean = fmaxf(mean, 1e-4f);
-            s[col] = powf(mean, alpha);
+            s[col] = RAW ? mean : powf(mean, alpha);
         }
     }
 }
@@ -82,8 +84,17 @@ extern "C" int awq_act_scale(const void *X_f16, int64_t T, int64_t K, float alph
     if (!(alpha >= 0.0f && alpha <= 1.0f)) return AWQ_ERR_BAD_ARGUMENT;
     if (!awq_aligned16(X_f16) || !awq_aligned16(s)) return AWQ_ERR_MISALIGNED;
     const int blocks = (int)((K + ACT_COLS - 1) / ACT_COLS);
-    act_scale_kernel<<<dim3(blocks), dim3(1024), 0, (hipStream_t)stream>>>(
+    act_scale_kernel<false><<<dim3(blocks), dim3(1024), 0, (hipStream_t)stream>>>(
         (const uint4 *)X_f16, T, K, alpha, s);
+    return awq_launch_status();
+}
+
+// s_X itself: max(mean_t |X[t,k]|, 1e-4), the base of Eq. 5 (used by the scale search, which
+// raises it to every alpha of its grid).  Arguments validated by the caller.
+int awq_act_mean_launch(const void *X_f16, int64_t T, int64_t K, float *mean, hipStream_t stream)
+{
+    const int blocks = (int)((K + ACT_COLS - 1) / ACT_COLS);
+    act_scale_kernel<true><<<dim3(blocks), dim3(1024), 0, stream>>>((const uint4 *)X_f16, T, K, 1.0f, mean);
     return awq_launch_status();
 }
 

@@ -514,6 +514,83 @@ def test_act_scale_and_inverse_scale(awq, T, K):
     assert np.array_equal(xs_gpu.view(np.uint16), xs_ref.view(np.uint16))
 
 
+# ------------------------------------------------------------------- scale search (Eq. 4-5)
+
+def loss_rtol(count):
+    """Tolerance of a loss that sums `count` squared output differences d.  The GPU's d carries
+    the fp16 rounding of both outputs and of the dequantized weights: uncorrelated noise e with
+    rms(e) / rms(d) = r ~ 1e-2 (2^-11 of the outputs against a quantization error of about a
+    tenth of a step per weight).  sum (d + e)^2 - sum d^2 = sum e^2 + 2 sum d e: the first term
+    is r^2 ~ 1e-4 of the loss, the second has standard deviation 2 r / sqrt(count) of it;
+    three standard deviations: 0.06 / sqrt(count)."""
+    return 2e-4 + 0.06 / np.sqrt(count)
+
+
+ALPHAS = [i / 20 for i in range(20)]
+
+
+def check_search(awq, W, X, alphas=ALPHAS):
+    import oracle
+    N, K = W.shape
+    best_g, losses_g, s_g = awq.awq_search_scale(dev(W), dev(X), alphas)
+    best_g, losses_g, s_g = int(host(best_g)[0]), host(losses_g), host(s_g)
+    best_o, losses_o, s_o = oracle.search_scale(W, X, alphas)
+    assert losses_g.shape == losses_o.shape
+    assert np.all(np.isfinite(losses_g))
+    LOSS_RTOL = loss_rtol(N * X.shape[0])
+    assert np.abs(losses_g / losses_o - 1.0).max() <= LOSS_RTOL, (losses_g / losses_o)
+    # the decision is taken on the GPU's own sums: it is the first minimum of those, and by the
+    # oracle's sums it is the minimum or within the tolerance of it
+    assert best_g == int(np.argmin(losses_g))
+    assert losses_o[best_g] <= losses_o[best_o] * (1.0 + 2 * LOSS_RTOL)
+    if len(alphas) > 1 and np.sort(losses_o)[1] > losses_o[best_o] * (1.0 + 2 * LOSS_RTOL):
+        assert best_g == best_o
+    print(f"search N={N} K={K} T={X.shape[0]}: alpha*={alphas[best_g]}, "
+          f"max |loss_gpu/loss_oracle - 1| = {np.abs(losses_g / losses_o - 1.0).max():.2e}")
+    # s* is what awq_act_scale gives for alpha*, and what the oracle gives
+    s_again = host(awq.awq_act_scale(dev(X), alphas[best_g]))
+    assert np.array_equal(s_g.view(np.uint32), s_again.view(np.uint32))
+    s_ref = oracle.act_scale(X, alphas[best_g])
+    assert np.abs(s_g.astype(np.float64) / s_ref - 1.0).max() <= 2e-6
+    # and quantizing with it is bit-exact against the oracle given the same s
+    assert_quantize_bit_exact(awq, W, s_g)
+    return best_g, losses_g
+
+
+@pytest.mark.parametrize("N,K,T", [(176, 1408, 300), (48, 256, 5), (272, 512, 129)])
+def test_search_scale_small(awq, N, K, T):
+    """Ragged token counts and row-block counts; T = 5 evaluates through the decode kernel."""
+    import workloads
+    out = workloads.outlier_channels(K, 0, 0, 5)
+    W = workloads.weights(N, K, 0.02, 0, 0, 5)
+    X = workloads.activations(T, K, 0, 0, 5, workloads.ROLE_CALIB, out)
+    best, losses = check_search(awq, W, X)
+    assert best > 0                                   # outlier channels: scaling beats plain RTN
+    check_search(awq, W, X, alphas=[0.5])             # a grid of one
+    check_search(awq, W, X, alphas=[1.0, 0.0, 0.5, 0.5])   # unordered, with a tie: first wins
+
+
+def test_search_scale_config0_full_size(awq):
+    """The 4096 x 4096 linear of config 0 with its 64 calibration rows, grid of 20."""
+    import workloads
+    case = workloads.linear_case("cfg0", 4096, 4096, 1, workloads.SIGMA_7B, 0)
+    check_search(awq, case.W, case.calib)
+
+
+def test_search_scale_rejects_bad_arguments(awq):
+    import torch
+    W = torch.zeros((16, 128), dtype=torch.float16, device="cuda")
+    X = torch.zeros((4, 128), dtype=torch.float16, device="cuda")
+    for alphas, status in (([], -7), ([0.5] * 65, -7), ([1.5], -7), ([float("nan")], -7)):
+        with pytest.raises(awq.AwqError) as e:
+            awq.awq_search_scale(W, X, alphas)
+        assert e.value.status == status
+    with pytest.raises(awq.AwqError) as e:
+        awq.awq_search_scale(W, X, [0.5], workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -5
+    assert awq.load().awq_search_scale_workspace_bytes(4, 16, 100, 1, 128) == 0
+
+
 def test_errors_surface_as_exceptions(awq):
     import torch
     W = torch.zeros((16, 100), dtype=torch.float16, device="cuda")
