@@ -322,6 +322,30 @@ def main():
         extras["quantize_pack"] = {"matrices": L * len(shapes), "ms_total": round(quant_ms, 3),
                                    "GB/s": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
                                    "pct_of_hbm_peak": round(100 * quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+        # scale search (Eq. 4-5): 20 grid points on one 4096 x 4096 linear with 2048 cached rows
+        name, N, K = shapes[0]
+        out = workloads.outlier_channels(K, 1, 0, 0)
+        Xs = torch.from_numpy(workloads.activations(M, K, 1, 1, 0, workloads.ROLE_CALIB, out)).to(dev)
+        Ws = torch.from_numpy(W0[0]).to(dev)
+        alphas = [i / 20 for i in range(20)]
+        need = awq.load().awq_search_scale_workspace_bytes(M, N, K, len(alphas), 128)
+        wsp = torch.empty(need, dtype=torch.uint8, device=dev)
+        awq.awq_search_scale(Ws, Xs, alphas, workspace=wsp)
+        torch.cuda.synchronize()
+        reps = 5
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            best, losses, s_best = awq.awq_search_scale(Ws, Xs, alphas, workspace=wsp)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        fl = (len(alphas) + 1) * workloads.flops(M, N, K)
+        extras["search_scale"] = {"shape": f"{N}x{K}, T={M}, {len(alphas)} grid points", "ms": round(ms, 3),
+                                  "alpha_best": alphas[int(best.item())],
+                                  "loss_best_over_rtn": round(float(losses[int(best.item())] / losses[0]), 4),
+                                  "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
+                                  "pct_of_mfma_peak": round(100 * fl / (ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 2)}
         result["extras"] = extras
 
     if args.copy_probe:
