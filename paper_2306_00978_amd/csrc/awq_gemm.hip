@@ -5,11 +5,15 @@
 // epilogue as with W8A8), and dequantized weights are never written to memory.
 //
 // Mapping.  A workgroup computes a 128 (tokens) x 256 (out-features) tile of y with
-// four waves side by side along N; a wave owns 128 x 64 = 4 x 2 tiles of
-// v_mfma_f32_32x32x16_f16 (128 fp32 accumulators per lane) and loops over K one
-// quantization group (128 columns = 8 MFMA steps) at a time.  The 32x32x16 shape is
-// chosen for its issue budget: one MFMA keeps the matrix pipe busy for 32 cycles, and in
-// that shadow the wave has to issue everything else (operand reads, dequantization).
+// eight waves: four side by side along N (128 x 64 = 4 x 2 tiles of
+// v_mfma_f32_32x32x16_f16, 128 fp32 accumulators per lane), each of them twice, the two
+// copies sharing a SIMD and splitting K between them: of the eight MFMA steps of a
+// quantization group (128 columns) one wave takes the even ones, the other the odd ones, and
+// the two partial tiles are added through LDS at the end.  A single wave per SIMD cannot keep
+// the matrix pipe busy (loop overhead, waits, the change of group all stall it); with two,
+// one computes while the other does that work, and no weight is dequantized twice.  The
+// 32x32x16 shape is chosen for its issue budget: one MFMA occupies the matrix pipe for 32
+// cycles, and in that shadow the wave issues everything else (operand reads, dequantization).
 //
 // Operands.  Nothing is staged through registers on the way in: both operands are
 // fetched with global_load_lds (memory -> LDS, 16 bytes per lane landing in lane order),
@@ -18,12 +22,12 @@
 //     lands as 8 LDS rows of 128 bytes.  Which 16-byte chunk of the row a lane fetches is
 //     XOR-swizzled with the row index, so that the A fragment of any MFMA step (lane l: row
 //     l%32, 16 bytes at columns 16 s + 8 (l/32)) is read back with one conflict-free
-//     ds_read_b128.  The four waves share the x tile (each loads its own 32 rows, all read
-//     all four row blocks); one barrier per group.
+//     ds_read_b128.  All waves share the x tile (wave (n-quarter q, k-half h) loads row block
+//     q, column half h of every group); one barrier per group.
 //   * weights: the packed layout is already the B-operand layout.  For a block of 32
 //     out-features (two 16-row tiles), lane l takes slot (l%16) + 16 (2h + l/32) of tile
-//     (l%32)/16: its word j is the fragment of MFMA step k = 32 j + 16 h.  A wave's
-//     weights are private to it (4 KB + steps + zero points per group).
+//     (l%32)/16: its word j is the fragment of MFMA step 2 j + h, i.e. half h of a tile holds
+//     exactly the steps of k-half h.  A wave loads and reads only its own half.
 //   Each fragment word is expanded in registers to fp16 (q - z) * scale and feeds four
 //   MFMAs (the four token blocks), so dequantization costs about three vector
 //   instructions per MFMA.
@@ -45,7 +49,7 @@ constexpr int A_STAGE = 32 * 1024;               // 4 row blocks x 2 column halv
 constexpr int B_STAGE = 4096 + 256 + 128;        // 2 blocks x 2 halves x 1 KB, 64 steps, 32 zero bytes
 constexpr int B_SC = 4096, B_ZP = 4352;
 constexpr int LDS_BYTES = NSTAGE * A_STAGE + 4 * NSTAGE * B_STAGE;
-constexpr int LOADS_PER_GROUP = 8 + 4 + 2;       // per wave
+constexpr int LOADS_PER_GROUP = 4 + 2 + 1;       // per wave
 
 __device__ __forceinline__ void dma16(const void *g, uint32_t lds_addr)
 {
@@ -160,7 +164,7 @@ __device__ __forceinline__ uint32_t word_of(const u32x4 &v, int j)
     return v[j];
 }
 
-__global__ __launch_bounds__(256, 1) void gemm_kernel(
+__global__ __launch_bounds__(512, 1) void gemm_kernel(
     const half_t *__restrict__ x, const unsigned char *__restrict__ qweight,
     const unsigned char *__restrict__ scales, const unsigned char *__restrict__ zeros,
     half_t *__restrict__ y, int M, int N, int K, int G, int tiles_n, int tiles_total)
@@ -180,74 +184,76 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // waves w and w+4 run on the same SIMD: they form a pair on the same 128 x 64 sub-tile
+    const int nq = wave & 3;                                 // which 64 out-features
+    const int kh = wave >> 2;                                // which MFMA steps: 2 t + kh
     const int l32 = lane & 31, hi = lane >> 5;
     const int m0 = tile_m * BM;
     const int NT = N >> 4;                                   // 16-row weight tiles in the matrix
-    const int nt0 = tile_n * (BN / 16) + wave * 4;          // first of the wave's four tiles
+    const int nt0 = tile_n * (BN / 16) + nq * 4;            // first of the pair's four tiles
 
     // ---- sources of this lane's memory->LDS loads (group 0), advanced by constant strides
-    // x: load instruction d of a group (d = 0..7) covers rows 8 (d%4) .. +8 of the wave's 32
-    // rows and columns 64 (d/4) .. +64; lane l takes row 8 (d%4) + l/8 (rows >= M repeat row
-    // M-1) and chunk (l%8) ^ f, f = ((row in block)/2)%8, and lands at chunk l%8: sixteen
-    // consecutive rows then hold any given chunk in sixteen different bank groups
+    // x: the wave fetches rows 32 nq .. +32, columns 64 kh .. +64 of the group; load q (0..3)
+    // covers rows 8 q .. +8 of them; lane l takes row 8 q + l/8 (rows >= M repeat row M-1) and
+    // chunk (l%8) ^ f, f = ((row in block)/2)%8, and lands at chunk l%8: sixteen consecutive
+    // rows then hold any given chunk in sixteen different bank groups
     const unsigned char *xsrc[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        int xr = m0 + 32 * wave + 8 * q + (lane >> 3);
+        int xr = m0 + 32 * nq + 8 * q + (lane >> 3);
         xr = xr < M ? xr : M - 1;
         const int chunk = (lane & 7) ^ (((8 * q + (lane >> 3)) >> 1) & 7);
-        xsrc[q] = reinterpret_cast<const unsigned char *>(x) + ((size_t)xr * K + 8 * chunk) * 2;
+        xsrc[q] = reinterpret_cast<const unsigned char *>(x) + ((size_t)xr * K + 8 * chunk) * 2 + kh * 128;
     }
-    // weights: block b (32 out-features = tiles nt0+2b, nt0+2b+1), half h
+    // weights: block b (32 out-features = tiles nt0+2b, nt0+2b+1), half kh
     const unsigned char *qsrc[2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         int t = nt0 + 2 * b + (l32 >> 4);
         t = t < NT ? t : NT - 1;                             // ragged N: repeat the last tile
-        qsrc[b] = qweight + ((size_t)t * G * 64 + (l32 & 15) + 16 * hi) * 16;
+        qsrc[b] = qweight + ((size_t)t * G * 64 + (l32 & 15) + 16 * hi) * 16 + kh * 512;
     }
-    // steps: lane -> block lane/32, row l32; zero points: lane < 32 -> block lane/16, byte lane%16
-    const unsigned char *ssrc, *zsrc;
-    {
+    // steps (fetched by the kh = 0 wave): lane -> block lane/32, row l32;
+    // zero points (kh = 1 wave): lane < 32 -> block lane/16, byte lane%16
+    const unsigned char *msrc;
+    if (kh == 0) {
         int t = nt0 + 2 * hi + (l32 >> 4);
         t = t < NT ? t : NT - 1;
-        ssrc = scales + ((size_t)t * G * 16 + (l32 & 15)) * 2;
+        msrc = scales + ((size_t)t * G * 16 + (l32 & 15)) * 2;
+    } else {
         int tz = nt0 + 2 * ((lane >> 4) & 1) + ((lane >> 3) & 1);
         tz = tz < NT ? tz : NT - 1;
-        zsrc = zeros + (size_t)tz * G * 8 + (lane & 7);
+        msrc = zeros + (size_t)tz * G * 8 + (lane & 7);
     }
 
     const uint32_t a_ring = lds0;
-    const uint32_t b_ring = lds0 + NSTAGE * A_STAGE + (uint32_t)wave * (NSTAGE * B_STAGE);
+    const uint32_t b_ring = lds0 + NSTAGE * A_STAGE + (uint32_t)nq * (NSTAGE * B_STAGE);
 
-    // One of the 14 loads of a group (PIECE 0..7: x, 8..11: weights, 12: steps, 13: zero points).
+    // One of the 7 loads of a group (PIECE 0..3: x, 4..5: weights, 6: steps or zero points).
     // They are issued one at a time from the issue shadow of the MFMAs.
     auto issue_piece = [&](auto piece_tag, int g, int stage) {
         constexpr int PIECE = decltype(piece_tag)::value;
         g = g < G ? g : G - 1;                               // past the end: a harmless repeat
-        if (PIECE < 8) {
+        if constexpr (PIECE < 4) {
             // LDS: [row block 4][column half 2][32 rows x 128 B]
-            const uint32_t adst = a_ring + (uint32_t)stage * A_STAGE + (uint32_t)wave * 8192;
-            constexpr int d = PIECE & 7;
-            dma16(xsrc[d & 3] + (size_t)g * 256 + (d >> 2) * 128, adst + (d >> 2) * 4096 + (d & 3) * 1024);
+            const uint32_t adst = a_ring + (uint32_t)stage * A_STAGE + (uint32_t)nq * 8192 + (uint32_t)kh * 4096;
+            dma16(xsrc[PIECE] + (size_t)g * 256, adst + PIECE * 1024);
         } else {
             const uint32_t bdst = b_ring + (uint32_t)stage * B_STAGE;
-            if (PIECE < 12) {
-                constexpr int b = ((PIECE - 8) >> 1) & 1, h = (PIECE - 8) & 1;
-                dma16(qsrc[b] + (size_t)g * 1024 + h * 512, bdst + (2 * b + h) * 1024);
-            } else if (PIECE == 12) {
-                dma2(ssrc + (size_t)g * 32, bdst + B_SC);
+            if constexpr (PIECE < 6) {
+                constexpr int b = PIECE - 4;
+                dma16(qsrc[b] + (size_t)g * 1024, bdst + (2 * b) * 1024 + (uint32_t)kh * 1024);
+            } else if (kh == 0) {
+                dma2(msrc + (size_t)g * 32, bdst + B_SC);
             } else {
-                if (lane < 32) dma1(zsrc + (size_t)g * 8, bdst + B_ZP);
+                if (lane < 32) dma1(msrc + (size_t)g * 8, bdst + B_ZP);
             }
         }
     };
 #define AWQ_PIECE(P, G_, ST_) issue_piece(std::integral_constant<int, (P)>{}, (G_), (ST_))
     auto issue_group = [&](int g, int stage) {
         AWQ_PIECE(0, g, stage); AWQ_PIECE(1, g, stage); AWQ_PIECE(2, g, stage); AWQ_PIECE(3, g, stage);
-        AWQ_PIECE(4, g, stage); AWQ_PIECE(5, g, stage); AWQ_PIECE(6, g, stage); AWQ_PIECE(7, g, stage);
-        AWQ_PIECE(8, g, stage); AWQ_PIECE(9, g, stage); AWQ_PIECE(10, g, stage); AWQ_PIECE(11, g, stage);
-        AWQ_PIECE(12, g, stage); AWQ_PIECE(13, g, stage);
+        AWQ_PIECE(4, g, stage); AWQ_PIECE(5, g, stage); AWQ_PIECE(6, g, stage);
     };
 
     floatx16 acc[4][2];
@@ -264,29 +270,29 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
     __builtin_amdgcn_s_barrier();
 
     const uint32_t lane16 = (uint32_t)lane << 4;
-    // byte offset of this lane's A fragment inside a (row block, column half) area, for the
-    // four steps of the half: row l32, chunk (2 s' + hi) ^ ((l32/2)%8)
+    // byte offset of this lane's A fragment inside a row block for the wave's four steps
+    // S = 2 t + kh of a group: column half S/4, row l32, chunk (2 (S%4) + hi) ^ ((l32/2)%8)
     uint32_t aoff[4];
 #pragma unroll
-    for (int sp = 0; sp < 4; ++sp)
-        aoff[sp] = (uint32_t)l32 * 128 + (uint32_t)(((2 * sp + hi) ^ ((l32 >> 1) & 7)) * 16);
+    for (int t = 0; t < 4; ++t)
+        aoff[t] = (uint32_t)(t >> 1) * 4096 + (uint32_t)l32 * 128 +
+                  (uint32_t)(((4 * (t & 1) + 2 * kh + hi) ^ ((l32 >> 1) & 7)) * 16);
 
     // ---- what a wave holds in registers for the group it is computing
-    u32x4 braw[2][2];            // packed words: [block][half], word j = MFMA step 2 j + half
+    u32x4 braw[2];               // packed words of its k-half: [block], word t = its step t
     half2_t s2[2], zA[2], zB[2]; // per block: step, 1024 + z, 64 + z (as half pairs)
     u32x4 a[4];                  // A fragments of the current step
     DqWord dq[2];                // dequantization in flight (current or next step)
 
     // request the packed words, steps, zero points and the first A fragments of a stage
-    u32x4 nbraw[2][2], na[4];
+    u32x4 nbraw[2], na[4];
     uint32_t nsraw[2], nzraw[2];
     auto read_group = [&](int st) {
         const uint32_t bb = b_ring + (uint32_t)st * B_STAGE;
+        const uint32_t bk = bb + (uint32_t)kh * 1024 + lane16;
         const uint32_t ab = a_ring + (uint32_t)st * A_STAGE + aoff[0];
-        nbraw[0][0] = lds_read16_off<0>(bb + lane16);
-        nbraw[0][1] = lds_read16_off<1024>(bb + lane16);
-        nbraw[1][0] = lds_read16_off<2048>(bb + lane16);
-        nbraw[1][1] = lds_read16_off<3072>(bb + lane16);
+        nbraw[0] = lds_read16_off<0>(bk);
+        nbraw[1] = lds_read16_off<2048>(bk);
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
             nsraw[b] = lds_read4(bb + B_SC + 4 * (32 * b + l32));
@@ -299,9 +305,8 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
     };
     auto wait_group = [&]() {
         asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(nbraw[0][0]), "+v"(nbraw[0][1]), "+v"(nbraw[1][0]), "+v"(nbraw[1][1]),
-                       "+v"(nsraw[0]), "+v"(nsraw[1]), "+v"(nzraw[0]), "+v"(nzraw[1]), "+v"(na[0]),
-                       "+v"(na[1]), "+v"(na[2]), "+v"(na[3]));
+                     : "+v"(nbraw[0]), "+v"(nbraw[1]), "+v"(nsraw[0]), "+v"(nsraw[1]), "+v"(nzraw[0]),
+                       "+v"(nzraw[1]), "+v"(na[0]), "+v"(na[1]), "+v"(na[2]), "+v"(na[3]));
     };
     // the group's constants from what was read, and step 0 of its dequantization set up
     half2_t ns2[2], nzA[2], nzB[2];
@@ -314,13 +319,13 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
             const uint32_t z = (nzraw[b] >> ((l32 & 1) * 4)) & 0xFu;
             nzA[b] = __builtin_bit_cast(half2_t, 0x64006400u | (z * 0x00010001u));
             nzB[b] = __builtin_bit_cast(half2_t, 0x54005400u | (z * 0x00100010u));
-            ndq[b].w = nbraw[b][0][0];
+            ndq[b].w = nbraw[b][0];
         }
     };
     auto adopt_group = [&]() {
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            braw[b][0] = nbraw[b][0]; braw[b][1] = nbraw[b][1];
+            braw[b] = nbraw[b];
             s2[b] = ns2[b]; zA[b] = nzA[b]; zB[b] = nzB[b];
             dq[b] = ndq[b];
         }
@@ -352,34 +357,28 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
                                                              // last read in group g-1, which every
                                                              // wave left before the previous barrier
         const uint32_t abase = a_ring + (uint32_t)stage * A_STAGE;
-        // steps 0..6: every MFMA is followed by a slice of the dequantization of the next step;
-        // the first four also by a fragment read of the next step, two more by a load of group g+2
+        // the wave's steps 0..2: every MFMA is followed by a slice of the dequantization of its
+        // next step; the first four also by a fragment read of that step, later ones by a load
+        // of group g+2
 #pragma unroll
-        for (int s = 0; s < 7; ++s) {
+        for (int t = 0; t < 3; ++t) {
             const half8_t bf0 = dq_result(dq[0]), bf1 = dq_result(dq[1]);
             u32x4 an[4];
-            const uint32_t ad = abase + aoff[(s + 1) & 3] + ((s + 1) >> 2) * 4096;
-            {
-                const int jn = (s + 1) >> 1, hn = (s + 1) & 1;
+            const uint32_t ad = abase + aoff[t + 1];
 #pragma unroll
-                for (int b = 0; b < 2; ++b) dq[b].w = word_of(braw[b][hn], jn);
-            }
+            for (int b = 0; b < 2; ++b) dq[b].w = word_of(braw[b], t + 1);
             __builtin_amdgcn_sched_barrier(0);
             AWQ_MFMA_SLOT(0, 0, an[0] = lds_read16_off<0>(ad); dq_slice<0>(dq, kc, zA, zB, s2))
             AWQ_MFMA_SLOT(0, 1, an[1] = lds_read16_off<8192>(ad); dq_slice<1>(dq, kc, zA, zB, s2))
             AWQ_MFMA_SLOT(1, 0, an[2] = lds_read16_off<16384>(ad); dq_slice<2>(dq, kc, zA, zB, s2))
             AWQ_MFMA_SLOT(1, 1, an[3] = lds_read16_off<24576>(ad); dq_slice<3>(dq, kc, zA, zB, s2))
-            AWQ_MFMA_SLOT(2, 0, if (s == 0) AWQ_PIECE(0, g + 2, fstage); if (s == 1) AWQ_PIECE(2, g + 2, fstage);
-                                if (s == 2) AWQ_PIECE(4, g + 2, fstage); if (s == 3) AWQ_PIECE(6, g + 2, fstage);
-                                if (s == 4) AWQ_PIECE(8, g + 2, fstage); if (s == 5) AWQ_PIECE(10, g + 2, fstage);
-                                if (s == 6) AWQ_PIECE(12, g + 2, fstage);
+            AWQ_MFMA_SLOT(2, 0, if (t == 0) AWQ_PIECE(0, g + 2, fstage); if (t == 1) AWQ_PIECE(2, g + 2, fstage);
+                                if (t == 2) AWQ_PIECE(4, g + 2, fstage);
                                 dq_slice<4>(dq, kc, zA, zB, s2))
-            AWQ_MFMA_SLOT(2, 1, if (s == 0) AWQ_PIECE(1, g + 2, fstage); if (s == 1) AWQ_PIECE(3, g + 2, fstage);
-                                if (s == 2) AWQ_PIECE(5, g + 2, fstage); if (s == 3) AWQ_PIECE(7, g + 2, fstage);
-                                if (s == 4) AWQ_PIECE(9, g + 2, fstage); if (s == 5) AWQ_PIECE(11, g + 2, fstage);
-                                if (s == 6) AWQ_PIECE(13, g + 2, fstage);
+            AWQ_MFMA_SLOT(2, 1, if (t == 0) AWQ_PIECE(1, g + 2, fstage); if (t == 1) AWQ_PIECE(3, g + 2, fstage);
+                                if (t == 2) AWQ_PIECE(5, g + 2, fstage);
                                 dq_slice<5>(dq, kc, zA, zB, s2))
-            AWQ_MFMA_SLOT(3, 0, dq_slice<6>(dq, kc, zA, zB, s2))
+            AWQ_MFMA_SLOT(3, 0, if (t == 2) AWQ_PIECE(6, g + 2, fstage); dq_slice<6>(dq, kc, zA, zB, s2))
             AWQ_MFMA_SLOT(3, 1, dq_slice<7>(dq, kc, zA, zB, s2))
             lds_wait(an[0], an[1], an[2], an[3]);
 #pragma unroll
@@ -387,8 +386,8 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
         }
 
         // group g+1 has landed once only the loads of group g+2 are outstanding; after the barrier
-        // every wave's part of it is visible.  Step 7 of this group has all its operands in
-        // registers already: its MFMAs cover the reads and the set-up of group g+1.
+        // every wave's part of it is visible.  The wave's last step of this group has all its
+        // operands in registers already: its MFMAs cover the reads and the set-up of group g+1.
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_GROUP) : "memory");
         __builtin_amdgcn_s_barrier();
         {
@@ -416,30 +415,63 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
 
+    // The two waves of a pair hold partial sums of the same 128 x 64 sub-tile.  Wave kh keeps
+    // token blocks 2 kh, 2 kh + 1 and hands the other two to its partner through the now idle
+    // LDS: 64 accumulators per lane, stored as [wave][accumulator][lane] (consecutive lanes in
+    // consecutive words).
+    {
+        float *xch = reinterpret_cast<float *>(smem);
+        float *mine = xch + (size_t)wave * (64 * 64);
+        const float *theirs = xch + (size_t)(wave ^ 4) * (64 * 64);
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    // the block this wave gives away: kh = 0 gives 2, 3; kh = 1 gives 0, 1
+                    const float give = kh ? acc[ii][b][v] : acc[2 + ii][b][v];
+                    mine[((ii * 2 + b) * 16 + v) * 64 + lane] = give;
+                }
+        __syncthreads();
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float got = theirs[((ii * 2 + b) * 16 + v) * 64 + lane];
+                    if (kh) acc[2 + ii][b][v] += got;
+                    else acc[ii][b][v] += got;
+                }
+        __syncthreads();
+    }
+
     // Epilogue.  Accumulator v of tile (i, b) is y[m0 + 32 i + 8 (v/4) + 4 hi + v%4][16 nt0 + 32 b
     // + l32]: a lane holds single columns, which would leave as 2-byte stores.  Each wave turns
-    // its 128 x 64 sub-tile around through its own 18 KB of the now idle LDS (rows of 128 + 16
-    // bytes: the padding spreads the banks) and stores 16 bytes per lane, 8 rows x 128 contiguous
-    // bytes per instruction.
+    // its 64 x 64 part around through its own 9 KB of LDS (rows of 128 + 16 bytes: the padding
+    // spreads the banks) and stores 16 bytes per lane, 8 rows x 128 contiguous bytes per
+    // instruction.
     {
         constexpr int ROWB = 144;
-        unsigned char *mine = smem + (size_t)wave * (128 * ROWB);
+        unsigned char *mine = smem + (size_t)wave * (64 * ROWB);
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = 32 * i + 8 * (v >> 2) + 4 * hi + (v & 3);
-                    *reinterpret_cast<half_t *>(mine + row * ROWB + (32 * b + l32) * 2) = (half_t)acc[i][b][v];
+                    const int row = 32 * ii + 8 * (v >> 2) + 4 * hi + (v & 3);
+                    const float val = kh ? acc[2 + ii][b][v] : acc[ii][b][v];
+                    *reinterpret_cast<half_t *>(mine + row * ROWB + (32 * b + l32) * 2) = (half_t)val;
                 }
         // wave-private area: the compiler orders these LDS reads after the writes above
         const int n = nt0 * 16 + (lane & 7) * 8;
 #pragma unroll
-        for (int it = 0; it < 16; ++it) {
+        for (int it = 0; it < 8; ++it) {
             const int row = it * 8 + (lane >> 3);
             const uint4 v = *reinterpret_cast<const uint4 *>(mine + row * ROWB + (lane & 7) * 16);
-            const int m = m0 + row;
+            const int m = m0 + 64 * kh + row;
             if (m < M && n < N) *reinterpret_cast<uint4 *>(y + (size_t)m * N + n) = v;
         }
     }
@@ -455,7 +487,7 @@ int awq_gemm_launch(const void *x, const void *qweight, const void *scales, cons
     const int tiles_n = (N + BN - 1) / BN;
     const int64_t tiles_total = (int64_t)tiles_n * ((M + BM - 1) / BM);
     if (tiles_total > (1 << 30)) return AWQ_ERR_BAD_SHAPE;
-    const dim3 grid((unsigned)((tiles_total + 7) / 8 * 8)), block(256);
+    const dim3 grid((unsigned)((tiles_total + 7) / 8 * 8)), block(512);
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel),
