@@ -92,6 +92,55 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert lib.awq_linear_workspace_bytes(-1, 0, 7, 3) == 0
 
 
+def test_grouped_and_search_calls_validate_before_any_launch(lib):
+    import paper_2306_00978_amd as awq
+    ok, odd = 0x1000, 0x1008
+    def descs(n, **kw):
+        arr = (awq.LinearDesc * max(n, 1))()
+        for i in range(n):
+            d = dict(x_f16=ok, qweight=ok, scales=ok, zeros=ok, y_f16=ok, N=16, K=128)
+            d.update(kw)
+            arr[i] = awq.LinearDesc(**d)
+        return arr
+    f = lib.awq_w4a16_linear_multi
+    assert f(None, 1, 1, 128, None, 0, None) == -1
+    assert f(descs(1), 0, 1, 128, None, 0, None) == -7
+    assert f(descs(1), awq.MULTI_MAX + 1, 1, 128, None, 0, None) == -7
+    assert f(descs(2), 2, 17, 128, None, 0, None) == -2          # not a decode call
+    assert f(descs(2), 2, 0, 128, None, 0, None) == -2
+    assert f(descs(2, y_f16=None), 2, 1, 128, None, 0, None) == -1
+    assert f(descs(2, K=100), 2, 1, 128, None, 0, None) == -2
+    assert f(descs(2, N=8), 2, 1, 128, None, 0, None) == -2
+    assert f(descs(2), 2, 1, 64, None, 0, None) == -3
+    assert f(descs(2, x_f16=odd), 2, 1, 128, None, 0, None) == -4
+
+    g = lib.awq_search_scale
+    wsb = lib.awq_search_scale_workspace_bytes
+    al = (ctypes.c_float * 3)(0.0, 0.5, 1.0)
+    need = wsb(64, 4096, 4096, 3, 128)
+    # packed candidate + x/s + two [T,N] outputs + means, s and partial sums
+    assert need >= 4096 * 4096 // 2 + 64 * 4096 * 2 * 3 + 3 * 1024 * 8
+    assert wsb(64, 4096, 4000, 3, 128) == 0 and wsb(0, 4096, 4096, 3, 128) == 0
+    assert wsb(64, 4096, 4096, 65, 128) == 0 and wsb(64, 4096, 4096, 3, 64) == 0
+    P = ctypes.c_void_p
+    args = lambda **kw: [kw.get("W", P(ok)), kw.get("X", P(ok)), kw.get("T", 64), 4096, kw.get("K", 4096),
+                         kw.get("al", al), kw.get("n", 3), kw.get("group", 128), kw.get("ws", P(ok)),
+                         kw.get("wsb", need), kw.get("losses", P(ok)), kw.get("best", P(ok)),
+                         kw.get("s", P(ok)), None]
+    assert g(*args(W=None)) == -1
+    assert g(*args(al=None)) == -1
+    assert g(*args(ws=None)) == -1
+    assert g(*args(K=4000)) == -2
+    assert g(*args(T=0)) == -2
+    assert g(*args(group=32)) == -3
+    assert g(*args(n=0)) == -7
+    assert g(*args(n=65)) == -7
+    assert g(*args(al=(ctypes.c_float * 3)(0.0, 1.5, 1.0))) == -7
+    assert g(*args(X=P(odd))) == -4
+    assert g(*args(ws=P(0x1010))) == -4                           # workspace wants 256-byte alignment
+    assert g(*args(wsb=need - 1)) == -5
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     import paper_2306_00978_amd as awq
