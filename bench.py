@@ -289,6 +289,41 @@ def main():
             b = step_bytes(M)
             extras[f"decode_m{M}_grouped"] = {"ms_per_step": round(w, 5), "GB/s": gbs(b, w),
                                               "pct_of_hbm_peak": round(100 * gbs(b, w) / HBM_PEAK_GBS, 2)}
+        # configs[3]: the seven projections of a Llama-2-70B-shaped layer (444.5 MB per launch), M = 1
+        # and 8, one grouped launch per step, two distinct layers cycled
+        shapes70 = workloads.LLAMA2_70B_LAYER
+        lay70 = []
+        for l in range(2):
+            packed = []
+            for name, N, K in shapes70:
+                W = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
+                     * workloads.SIGMA_70B).to(torch.float16)
+                packed.append(awq.awq_quantize_pack(W))
+                del W
+            lay70.append(packed)
+        x70 = {K: (torch.randn((8, K), generator=gen, device=dev, dtype=torch.float32)).to(torch.float16)
+               for K in (8192, 28672)}
+        for M70 in (1, 8):
+            ys70 = [torch.empty((M70, N), dtype=torch.float16, device=dev) for _, N, K in shapes70]
+            calls70 = [awq.prepare_linear_multi([(x70[K][:M70], *lay70[l][p], ys70[p], N)
+                                                 for p, (_, N, K) in enumerate(shapes70)]) for l in range(2)]
+            for i in range(6):
+                calls70[i % 2]()
+            torch.cuda.synchronize()
+            reps = 40
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(reps):
+                calls70[i % 2]()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            b70 = sum(workloads.algorithmic_bytes(M70, N, K) for _, N, K in shapes70)
+            extras[f"decode_m{M70}_llama70b_layer_grouped"] = {
+                "bytes_per_launch": b70, "ms_per_launch": round(ms, 5), "GB/s": gbs(b70, ms),
+                "pct_of_hbm_peak": round(100 * gbs(b70, ms) / HBM_PEAK_GBS, 2)}
+        del lay70
+
         # prefill GEMM, M = 2048, the three distinct shapes
         M = workloads.PREFILL_M
         pre = {}
