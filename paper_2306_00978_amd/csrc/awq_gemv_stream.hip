@@ -333,13 +333,14 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
         }
         total = floatx4{0.f, 0.f, 0.f, 0.f};
         __syncthreads();
-        for (int t = tid; t < RW * M * 16; t += W * 64) {
-            const int tri = t / (M * 16), rem = t - tri * (M * 16);
-            const float *p = rbuf + tri * KS * Mpad * 16 + rem;
+        // one output per thread and pass: (row block tri, token m, column n) = bits of t
+        for (int t = tid; t < (RW << (mlog + 4)); t += W * 64) {
+            const int tri = t >> (mlog + 4), rem = t & ((16 << mlog) - 1), m = rem >> 4;
+            const float *p = rbuf + ((tri * KS) << (mlog + 4)) + rem;
             float sum = 0.f;
-            for (int k = 0; k < KS; ++k) sum += p[k * Mpad * 16];
+            for (int k = 0; k < KS; ++k) sum += p[k << (mlog + 4)];
             const int rbo = rb_wg + it * RW + tri;
-            if (rbo < NRB) P.y[(size_t)(rem >> 4) * N + rbo * 16 + (rem & 15)] = (half_t)sum;
+            if (rbo < NRB && m < M) P.y[(size_t)m * N + rbo * 16 + (rem & 15)] = (half_t)sum;
         }
     };
 
@@ -384,6 +385,15 @@ int ceil_log2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 // (waves wanted on the chip), with a floor of one job.  Per linear, K is split over the fewest
 // waves the register slots allow, and a workgroup takes `iters` consecutive row-block steps
 // so that iters * (batches per wave and row block) comes as close to T as possible.
+bool awq_gemv_stream_fits(int N, int K, int M)
+{
+    (void)N;
+    const int bpr = 16 >> ceil_log2(M);
+    const int NBT = (K / 128 + 3) / 4;
+    const int ksl_min = ceil_log2((NBT + bpr - 1) / bpr);
+    return ksl_min <= 3 && (1 << ksl_min) <= NBT;
+}
+
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream)
 {
     static const int f_logw = env_int("AWQ_GEMV_LOGW", -1);
@@ -402,7 +412,7 @@ int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStr
     double total_batches = 0;
     for (int i = 0; i < count; ++i)
         total_batches += (double)(problems[i].N / 16) * ((problems[i].K / 128 + 3) / 4);
-    const double T = f_jobs > 0 ? f_jobs : std::max(1.0, total_batches / f_slots);
+    double T = f_jobs > 0 ? f_jobs : std::max(1.0, total_batches / f_slots);
 
     int ksl_of[GEMV_MAX_PROBLEMS], iters_of[GEMV_MAX_PROBLEMS];
     int logW = 2;
@@ -411,17 +421,12 @@ int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStr
         const int ksl_min = ceil_log2((NBT + bpr - 1) / bpr);
         if (ksl_min > 3) return AWQ_GEMV_STREAM_UNFIT;
         // K is split over as few waves as the register slots allow (splitting costs a pass
-        // through LDS and a barrier per row block); the row-block steps per workgroup bring the
-        // jobs of a wave as close to T as they get
+        // through LDS and a barrier per row block)
         int best_ksl = ksl_min;
         if (f_ksl > ksl_min) best_ksl = std::min(3, f_ksl);
         while ((1 << best_ksl) > NBT && best_ksl > ksl_min) --best_ksl;
         if ((1 << best_ksl) > NBT) return AWQ_GEMV_STREAM_UNFIT;
-        const int nbw = (NBT + (1 << best_ksl) - 1) >> best_ksl;
-        int best_iters = std::max(1, (int)(T / nbw + 0.5));
-        if (f_iters > 0) best_iters = f_iters;
         ksl_of[i] = best_ksl;
-        iters_of[i] = best_iters;
         logW = std::max(logW, best_ksl);
     }
     if (f_logw >= 0) logW = std::min(3, std::max(f_logw, logW));
@@ -430,18 +435,33 @@ int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStr
     const int stages = f_stages == 3 ? 3 : (f_stages == 4 ? 4 : 2);
     const size_t lds = (size_t)W * stages * STAGE_BYTES + 2 * (size_t)W * (16 << L.mlog) * 4;
 
+    // The row-block steps per workgroup bring the jobs of a wave as close to T as they get.
+    // Workgroups of eight waves take more than half of a CU's LDS, so only one is resident per
+    // CU: their number must not exceed the CUs (a second round would run nearly alone), and T
+    // is raised until it does not.
+    const int wg_cap = lds * 2 > 160 * 1024 ? 256 : (1 << 30);
     int wg = 0;
-    for (int i = 0; i < count; ++i) {
-        GemvProblem p = problems[i];
-        const int NRB = p.N / 16;
-        const int RW = W >> ksl_of[i];
-        const int steps = (NRB + RW - 1) / RW;                // row-block steps of the whole linear
-        const int iters = std::min(iters_of[i], steps);
-        p.ks_log = ksl_of[i];
-        p.iters = iters;
-        L.wg_begin[i] = wg;
-        wg += (steps + iters - 1) / iters;
-        L.p[i] = p;
+    for (int attempt = 0; attempt < 64; ++attempt) {
+        wg = 0;
+        for (int i = 0; i < count; ++i) {
+            GemvProblem p = problems[i];
+            const int NBT = (p.K / 128 + 3) / 4;
+            const int nbw = (NBT + (1 << ksl_of[i]) - 1) >> ksl_of[i];
+            int it = std::max(1, (int)(T / nbw + 0.5));
+            if (f_iters > 0) it = f_iters;
+            const int NRB = p.N / 16;
+            const int RW = W >> ksl_of[i];
+            const int steps = (NRB + RW - 1) / RW;            // row-block steps of the whole linear
+            const int iters = std::min(it, steps);
+            iters_of[i] = iters;
+            p.ks_log = ksl_of[i];
+            p.iters = iters;
+            L.wg_begin[i] = wg;
+            wg += (steps + iters - 1) / iters;
+            L.p[i] = p;
+        }
+        if (wg <= wg_cap || f_iters > 0 || f_jobs > 0) break;
+        T *= 1.04;
     }
     static bool attr_set = false;
     if (!attr_set) {
@@ -455,6 +475,7 @@ int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStr
             return AWQ_ERR_HIP;
         attr_set = true;
     }
+    if (lds > (size_t)160 * 1024) return AWQ_GEMV_STREAM_UNFIT;
     if (stages == 4) gemv_stream_kernel<4><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
     else if (stages == 3) gemv_stream_kernel<3><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
     else gemv_stream_kernel<2><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);

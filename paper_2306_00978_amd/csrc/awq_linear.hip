@@ -83,14 +83,35 @@ extern "C" int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, i
         p[i].N = (int)d.N;
         p[i].K = (int)d.K;
     }
-    int st = count > 1 ? awq_gemv_stream_launch(p, count, (int)M, (hipStream_t)stream)
-                       : AWQ_GEMV_STREAM_UNFIT;
-    if (st != AWQ_GEMV_STREAM_UNFIT) return st;
-    // a single linear, or K too long for register-resident activations at this M: one
-    // launch of the batch kernel per linear
+    // The linears whose K fits the register-resident activations of the streaming kernel at
+    // this M go out in one launch; the others (and a lone linear) take one launch of the batch
+    // kernel each.
+    GemvProblem fit[GEMV_MAX_PROBLEMS];
+    int nfit = 0;
+    bool grouped[GEMV_MAX_PROBLEMS] = {};
+    if (count > 1) {
+        for (int i = 0; i < count; ++i)
+            if (awq_gemv_stream_fits(p[i].N, p[i].K, (int)M)) {
+                fit[nfit++] = p[i];
+                grouped[i] = true;
+            }
+        if (nfit < 2) {
+            nfit = 0;
+            for (int i = 0; i < count; ++i) grouped[i] = false;
+        }
+    }
+    if (nfit > 0) {
+        int st = awq_gemv_stream_launch(fit, nfit, (int)M, (hipStream_t)stream);
+        if (st == AWQ_GEMV_STREAM_UNFIT) {
+            for (int i = 0; i < count; ++i) grouped[i] = false;
+        } else if (st != AWQ_OK) {
+            return st;
+        }
+    }
     for (int i = 0; i < count; ++i) {
-        st = awq_gemv_launch(p[i].x, p[i].q, p[i].sc, p[i].zp, p[i].y, (int)M, p[i].N, p[i].K,
-                             (hipStream_t)stream);
+        if (grouped[i]) continue;
+        int st = awq_gemv_launch(p[i].x, p[i].q, p[i].sc, p[i].zp, p[i].y, (int)M, p[i].N, p[i].K,
+                                 (hipStream_t)stream);
         if (st != AWQ_OK) return st;
     }
     return AWQ_OK;
