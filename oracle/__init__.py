@@ -119,6 +119,32 @@ def quantize(W, s=None, group: int = GROUP):
     return codes, scales.view(np.float16), zeros
 
 
+def quantize_clip(W, s, ratios, group: int = GROUP):
+    """Sec. 3.2, weight clipping (one sentence in the paper; the reading is stated in the C
+    file): per group the range of w*s is shrunk by each ratio of the grid and the ratio with
+    the smallest squared quantization error wins.  Returns codes, scales, zeros as `quantize`
+    and choice[N,G] u8, the index of the winning ratio."""
+    Wb = _as_f16_bits(W)
+    N, K = Wb.shape
+    if K % group:
+        raise ValueError("K must be a multiple of the group size")
+    G = K // group
+    sp = None
+    if s is not None:
+        s = np.ascontiguousarray(s, dtype=np.float32)
+        assert s.shape == (K,)
+        sp = _p(s)
+    ratios = np.ascontiguousarray(ratios, dtype=np.float32)
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, G), dtype=np.uint16)
+    zeros = np.empty((N, G), dtype=np.uint8)
+    choice = np.empty((N, G), dtype=np.uint8)
+    _chk(_load().awq_oracle_quantize_clip(_p(Wb), sp, _i64(N), _i64(K), ctypes.c_int(group),
+                                          _p(ratios), ctypes.c_int(ratios.size), _p(codes),
+                                          _p(scales), _p(zeros), _p(choice)), "quantize_clip")
+    return codes, scales.view(np.float16), zeros, choice
+
+
 def packed_sizes(N: int, K: int, group: int = GROUP):
     G = K // group
     return N * K // 2, N * G * 2, N * G // 2

@@ -186,6 +186,96 @@ int awq_oracle_quantize(const uint16_t *W, const float *s, int64_t N, int64_t K,
     return 0;
 }
 
+/* ---------- weight clipping (Sec. 3.2: "we further apply weight clipping to minimize the
+ * MSE error of quantization").  The paper gives no more than that sentence; the reading
+ * taken here: per quantization group, the range [min, max] of w*s is shrunk to
+ * [r*min, r*max] for every r of a given grid, the group is quantized with that range (values
+ * outside it saturate at code 0 or 15), and the r with the smallest sum of squared
+ * differences between the dequantized and the scaled weights wins (first one on ties).
+ * Quantization arithmetic as in awq_oracle_quantize (binary32, one rounding per operation);
+ * an error is e = (q - zero) * scale - w*s in binary32, the sum of e*e is taken in binary64.
+ * choice[n*G+g] (optional) receives the index of the winning r.                        */
+static void quantize_group_range(const float *wp, int group, float mx, float mn, uint16_t *sc_h_out,
+                                 float *zero_out, uint8_t *codes /* may be NULL */, double *err)
+{
+    float range = mx - mn;
+    float sc32 = range / 15.0f;
+    sc32 = clampf(sc32, 6.103515625e-05f, 65504.0f);
+    uint16_t sc_h = awq_oracle_f32_to_f16(sc32);
+    float scale = awq_oracle_f16_to_f32(sc_h);
+    float nmn = -mn;
+    float zr = nmn / scale;
+    float zero = clampf(rintf(zr), 0.0f, 15.0f);
+    double acc = 0.0;
+    for (int j = 0; j < group; ++j) {
+        float r = wp[j] / scale;
+        float q = rintf(r);
+        q = q + zero;
+        q = clampf(q, 0.0f, 15.0f);
+        if (codes) codes[j] = (uint8_t)q;
+        float lv = q - zero;
+        float dq = lv * scale;
+        float e = dq - wp[j];
+        acc += (double)e * (double)e;
+    }
+    *sc_h_out = sc_h;
+    *zero_out = zero;
+    *err = acc;
+}
+
+int awq_oracle_quantize_clip(const uint16_t *W, const float *s, int64_t N, int64_t K, int group,
+                             const float *ratios, int n_ratios, uint8_t *codes, uint16_t *scales,
+                             uint8_t *zeros, uint8_t *choice)
+{
+    if (!W || !codes || !scales || !zeros || !ratios) return -1;
+    if (group != ORACLE_GROUP || N <= 0 || K <= 0 || K % group) return -2;
+    if (n_ratios < 1 || n_ratios > 255) return -3;
+    const int64_t G = K / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float wp[ORACLE_GROUP];
+        for (int64_t g = 0; g < G; ++g) {
+            const int64_t k0 = g * group;
+            for (int j = 0; j < group; ++j) {
+                float w = awq_oracle_f16_to_f32(W[n * K + k0 + j]);
+                float sk = s ? s[k0 + j] : 1.0f;
+                wp[j] = w * sk;
+            }
+            float mx = wp[0], mn = wp[0];
+            for (int j = 1; j < group; ++j) {
+                if (wp[j] > mx) mx = wp[j];
+                if (wp[j] < mn) mn = wp[j];
+            }
+            int best = 0;
+            double best_err = 0.0;
+            for (int i = 0; i < n_ratios; ++i) {
+                float mxr = mx * ratios[i];
+                float mnr = mn * ratios[i];
+                uint16_t sc_h;
+                float zero;
+                double err;
+                quantize_group_range(wp, group, mxr, mnr, &sc_h, &zero, NULL, &err);
+                if (i == 0 || err < best_err) {
+                    best = i;
+                    best_err = err;
+                }
+            }
+            {
+                float mxr = mx * ratios[best];
+                float mnr = mn * ratios[best];
+                uint16_t sc_h;
+                float zero;
+                double err;
+                quantize_group_range(wp, group, mxr, mnr, &sc_h, &zero, codes + n * K + k0, &err);
+                scales[n * G + g] = sc_h;
+                zeros[n * G + g] = (uint8_t)zero;
+                if (choice) choice[n * G + g] = (uint8_t)best;
+            }
+        }
+    }
+    return 0;
+}
+
 /* ---------- a5: packed layout (written from the layout text) ----------
  * qweight: tiles of 16 rows x 128 columns, 1024 bytes each, tile index
  *          (n/16)*G + (k/128).  Inside a tile, 64 slots of 16 bytes; slot
