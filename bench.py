@@ -357,6 +357,27 @@ def main():
         extras["quantize_pack"] = {"matrices": L * len(shapes), "ms_total": round(quant_ms, 3),
                                    "GB/s": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
                                    "pct_of_hbm_peak": round(100 * quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+        # quantize with the clipping search (11 range ratios) on the three distinct shapes
+        ratios = [1.0 - 0.05 * i for i in range(11)]
+        cms, cbytes = 0.0, 0
+        for p in (0, 4, 6):
+            name, N, K = shapes[p]
+            Wd = torch.from_numpy(W0[p]).to(dev)
+            outc = awq.awq_quantize_pack_clip(Wd, s_by_k[K], ratios)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                awq.awq_quantize_pack_clip(Wd, s_by_k[K], ratios, out=outc)
+            e1.record()
+            torch.cuda.synchronize()
+            cms += e0.elapsed_time(e1) / 5
+            cbytes += 2 * N * K + sum(awq.awq_packed_sizes(N, K)) + 4 * K
+            del Wd
+        extras["quantize_pack_clip"] = {"ratios": len(ratios), "matrices": 3, "ms_total": round(cms, 3),
+                                        "GB/s": round(cbytes / (cms * 1e-3) / 1e9, 1),
+                                        "note": "arithmetic-bound: 11 trial quantizations per group"}
+
         # scale search (Eq. 4-5): 20 grid points on one 4096 x 4096 linear with 2048 cached rows
         name, N, K = shapes[0]
         out = workloads.outlier_channels(K, 1, 0, 0)

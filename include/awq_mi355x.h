@@ -84,6 +84,22 @@ int awq_apply_inv_scale(const void *x_f16, const float *s, int64_t M, int64_t K,
 int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K, int group,
                       void *qweight, void *scales, void *zeros, void *stream);
 
+#define AWQ_CLIP_MAX_RATIOS 32
+
+/* Sec. 3.2, weight clipping ("we further apply weight clipping to minimize the MSE error of
+ * quantization"; the paper says no more, this is the reading taken): awq_quantize_pack with a
+ * search per quantization group.  The group's range [min, max] of w' = W*s is shrunk to
+ * [r*min, r*max] for every r of `ratios`, the group is quantized with that range by the
+ * formulas of awq_quantize_pack (values outside it saturate at code 0 or 15), and the r with
+ * the smallest sum over the group of ((q - zero)*scale - w')^2 is used (differences in
+ * binary32, one rounding per operation; squares summed in binary64; the first r wins a tie).
+ *   ratios: HOST array of 1..AWQ_CLIP_MAX_RATIOS values in (0, 1], read before the call
+ *   returns; choice: device [N, K/128] bytes, row-major, receives the index of the winning
+ *   ratio of every group, or NULL.  Everything else as awq_quantize_pack. */
+int awq_quantize_pack_clip(const void *W_f16, const float *s, int64_t N, int64_t K, int group,
+                           const float *ratios, int n_ratios, void *qweight, void *scales,
+                           void *zeros, uint8_t *choice, void *stream);
+
 /* Inverse of the packing (export / test path): codes [N,K] one code per byte,
  * scales_f16 [N,K/128] fp16, zeros_u8 [N,K/128] one zero point per byte, all
  * device, row-major, written.  Any of the three outputs may be NULL (skipped). */

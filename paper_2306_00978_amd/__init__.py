@@ -10,6 +10,7 @@ Function names and argument order mirror the C ABI:
     awq_quantize_pack, awq_unpack                 (Sec. 3.2, Eq. 1-2; Sec. 4.2 packing)
     awq_w4a16_linear, awq_w4a16_linear_multi      (Sec. 4.2 fused dequantization, kernel fusion)
     awq_search_scale                              (Sec. 3.2 searching to scale, Eq. 4-5)
+    awq_quantize_pack_clip                        (Sec. 3.2 weight clipping)
 """
 from __future__ import annotations
 
@@ -26,7 +27,7 @@ EXPORTS = [
     "awq_version", "awq_status_string", "awq_packed_sizes", "awq_act_scale",
     "awq_apply_inv_scale", "awq_quantize_pack", "awq_unpack", "awq_linear_workspace_bytes",
     "awq_w4a16_linear", "awq_w4a16_linear_multi",
-    "awq_search_scale_workspace_bytes", "awq_search_scale",
+    "awq_search_scale_workspace_bytes", "awq_search_scale", "awq_quantize_pack_clip",
 ]
 MULTI_MAX = 56
 
@@ -78,6 +79,9 @@ def load() -> ctypes.CDLL:
     lib.awq_w4a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
     lib.awq_w4a16_linear_multi.restype = i32
     lib.awq_w4a16_linear_multi.argtypes = [ctypes.POINTER(LinearDesc), i32, i64, i32, vp, sz, vp]
+    lib.awq_quantize_pack_clip.restype = i32
+    lib.awq_quantize_pack_clip.argtypes = [vp, vp, i64, i64, i32, ctypes.POINTER(ctypes.c_float), i32,
+                                           vp, vp, vp, vp, vp]
     lib.awq_search_scale_workspace_bytes.restype = sz
     lib.awq_search_scale_workspace_bytes.argtypes = [i64, i64, i64, i32, i32]
     lib.awq_search_scale.restype = i32
@@ -308,3 +312,31 @@ def awq_search_scale(W: torch.Tensor, X: torch.Tensor, alphas, group: int = GROU
                                    workspace.data_ptr(), workspace.numel(), losses.data_ptr(),
                                    best.data_ptr(), s_best.data_ptr(), _stream()), "awq_search_scale")
     return best, losses[:n], s_best
+
+
+def awq_quantize_pack_clip(W: torch.Tensor, s: torch.Tensor | None, ratios, group: int = GROUP,
+                           out=None, want_choice: bool = False):
+    """awq_quantize_pack with the per-group clipping search over `ratios` (values in (0, 1]).
+    Returns (qweight, scales, zeros) and, if asked for, choice [N, K/128] u8."""
+    _dev(W, torch.float16, "W")
+    N, K = W.shape
+    if s is not None:
+        _dev(s, torch.float32, "s")
+        if s.numel() != K:
+            raise ValueError("s must have K elements")
+    qb, sb, zb = awq_packed_sizes(N, K, group)
+    if out is None:
+        out = (torch.empty(qb, dtype=torch.uint8, device=W.device),
+               torch.empty(sb // 2, dtype=torch.float16, device=W.device),
+               torch.empty(zb, dtype=torch.uint8, device=W.device))
+    qweight, scales, zeros = out
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * 2 < sb \
+            or zeros.numel() * zeros.element_size() < zb:
+        raise ValueError("output buffers are too small")
+    n = len(ratios)
+    arr = (ctypes.c_float * max(n, 1))(*[float(r) for r in ratios])
+    choice = torch.empty((N, K // group), dtype=torch.uint8, device=W.device) if want_choice else None
+    _check(load().awq_quantize_pack_clip(_ptr(W), _ptr(s), N, K, group, arr, n, _ptr(qweight),
+                                         _ptr(scales), _ptr(zeros), _ptr(choice), _stream()),
+           "awq_quantize_pack_clip")
+    return (qweight, scales, zeros, choice) if want_choice else (qweight, scales, zeros)

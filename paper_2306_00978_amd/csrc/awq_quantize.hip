@@ -50,14 +50,26 @@ __device__ __forceinline__ float divide(float n, const Reciprocal &k)
     return __builtin_fmaf(e2, k.r, q1);
 }
 
+// Range ratios of the clipping search (Sec. 3.2, "weight clipping to minimize the MSE error of
+// quantization").
+struct ClipRatios {
+    float v[AWQ_CLIP_MAX_RATIOS];
+    int n;
+};
+
 // One wave owns group g of a range of consecutive row blocks: the 128 scale factors s of the
 // group stay in registers, and the loads of the next tile are in flight while the current one
 // is quantized.
+// CLIP: before a group is quantized, its range [min, max] is tried shrunk by every ratio of
+// the grid; the ratio with the smallest sum of squared differences between dequantized and
+// scaled weights (differences in fp32, one rounding per operation; their squares summed in
+// fp64) is used, the first one on ties.  choice[n*G+g] (optional) receives its index.
+template <bool CLIP>
 __global__ __launch_bounds__(256) void quantize_pack_kernel(
     const uint4 *__restrict__ W,   // [N, K/8] runs of eight fp16
     const float4 *__restrict__ s,  // [K/4] or nullptr
     uint4 *__restrict__ qweight, uint16_t *__restrict__ scales, uint8_t *__restrict__ zeros,
-    int G, int NRB, int rb_per_wave, int num_units)
+    int G, int NRB, int rb_per_wave, int num_units, ClipRatios ratios, uint8_t *__restrict__ choice)
 {
     const int lane = threadIdx.x & 63;
     const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -115,6 +127,49 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         mn = fminf(mn, __shfl_xor(mn, 32));
 
+        // scale is in [2^-14, 65504]; with |w'| below 1e18 the shared-reciprocal division is exact
+        // IEEE division.  Otherwise (never with real weights) the whole wave divides with `/`.
+        const bool tame = __all(fmaxf(fabsf(mx), fabsf(mn)) < 1.0e18f);
+
+        int best = 0;
+        if (CLIP) {
+            double best_err = 0.0;
+            for (int i = 0; i < ratios.n; ++i) {
+                const float mxr = mx * ratios.v[i], mnr = mn * ratios.v[i];
+                float t32 = (mxr - mnr) / 15.0f;
+                t32 = clampf(t32, 6.103515625e-05f, 65504.0f);
+                const float tscale = (float)(half_t)t32;
+                const float tzero = clampf(__builtin_rintf((-mnr) / tscale), 0.0f, 15.0f);
+                const Reciprocal trc = make_reciprocal(tscale);
+                double err = 0.0;
+                auto accumulate = [&](auto quotient) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            float q = __builtin_rintf(quotient(wp[j][e]));
+                            q = q + tzero;
+                            q = clampf(q, 0.0f, 15.0f);
+                            const float lv = q - tzero;
+                            const float dq = lv * tscale;
+                            const float d = dq - wp[j][e];
+                            err += (double)d * (double)d;
+                        }
+                };
+                if (tame) accumulate([&](float n) { return divide(n, trc); });
+                else accumulate([&](float n) { return n / tscale; });
+                // the four lanes of a row: every one of them ends up with the same bits
+                err += __shfl_xor(err, 16);
+                err += __shfl_xor(err, 32);
+                if (i == 0 || err < best_err) {
+                    best = i;
+                    best_err = err;
+                }
+            }
+            mx = mx * ratios.v[best];
+            mn = mn * ratios.v[best];
+        }
+
         const float range = mx - mn;
         float sc32 = range / 15.0f;
         sc32 = clampf(sc32, 6.103515625e-05f, 65504.0f);
@@ -123,10 +178,6 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
         const float nmn = -mn;
         const float zr = nmn / scale;
         const float zero = clampf(__builtin_rintf(zr), 0.0f, 15.0f);
-
-        // scale is in [2^-14, 65504]; with |w'| below 1e18 the shared-reciprocal division is exact
-        // IEEE division.  Otherwise (never with real weights) the whole wave divides with `/`.
-        const bool tame = __all(fmaxf(fabsf(mx), fabsf(mn)) < 1.0e18f);
         const Reciprocal rc = make_reciprocal(scale);
 
         // a word is assembled as two exact fp32 integers of 16 bits (four nibbles each)
@@ -158,6 +209,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
         if (c == 0) {
             scales[tile * 16 + r] = __builtin_bit_cast(uint16_t, sc_h);
             if ((r & 1) == 0) zeros[tile * 8 + (r >> 1)] = (uint8_t)(z | (z_hi << 4));
+            if (CLIP && choice) choice[((int64_t)rb * 16 + r) * G + g] = (uint8_t)best;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) cur[j] = nxt[j];
@@ -201,9 +253,10 @@ __global__ __launch_bounds__(256) void unpack_kernel(
 
 }  // namespace
 
-extern "C" int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K,
-                                 int group, void *qweight, void *scales, void *zeros,
-                                 void *stream)
+namespace {
+
+int quantize_launch(const void *W_f16, const float *s, int64_t N, int64_t K, int group, void *qweight,
+                    void *scales, void *zeros, const ClipRatios *ratios, uint8_t *choice, void *stream)
 {
     if (!W_f16 || !qweight || !scales || !zeros) return AWQ_ERR_NULL_POINTER;
     int st = awq_check_weight_shape(N, K, group);
@@ -220,10 +273,39 @@ extern "C" int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, i
     parts = (NRB + rb_per_wave - 1) / rb_per_wave;
     const int num_units = parts * G;
     const int blocks = (num_units + 3) / 4;
-    quantize_pack_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
-        (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
-        (uint8_t *)zeros, G, NRB, rb_per_wave, num_units);
+    if (ratios)
+        quantize_pack_kernel<true><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
+            (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
+            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, *ratios, choice);
+    else
+        quantize_pack_kernel<false><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
+            (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
+            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, ClipRatios{}, nullptr);
     return awq_launch_status();
+}
+
+}  // namespace
+
+extern "C" int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K,
+                                 int group, void *qweight, void *scales, void *zeros,
+                                 void *stream)
+{
+    return quantize_launch(W_f16, s, N, K, group, qweight, scales, zeros, nullptr, nullptr, stream);
+}
+
+extern "C" int awq_quantize_pack_clip(const void *W_f16, const float *s, int64_t N, int64_t K,
+                                      int group, const float *ratios, int n_ratios, void *qweight,
+                                      void *scales, void *zeros, uint8_t *choice, void *stream)
+{
+    if (!ratios) return AWQ_ERR_NULL_POINTER;
+    if (n_ratios < 1 || n_ratios > AWQ_CLIP_MAX_RATIOS) return AWQ_ERR_BAD_ARGUMENT;
+    ClipRatios r = {};
+    r.n = n_ratios;
+    for (int i = 0; i < n_ratios; ++i) {
+        if (!(ratios[i] > 0.0f && ratios[i] <= 1.0f)) return AWQ_ERR_BAD_ARGUMENT;
+        r.v[i] = ratios[i];
+    }
+    return quantize_launch(W_f16, s, N, K, group, qweight, scales, zeros, &r, choice, stream);
 }
 
 extern "C" int awq_unpack(const void *qweight, const void *scales, const void *zeros,

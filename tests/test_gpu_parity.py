@@ -514,6 +514,74 @@ def test_act_scale_and_inverse_scale(awq, T, K):
     assert np.array_equal(xs_gpu.view(np.uint16), xs_ref.view(np.uint16))
 
 
+# ------------------------------------------------------------------- weight clipping
+
+CLIP_RATIOS = [1.0 - 0.05 * i for i in range(11)]
+
+
+def assert_clip_bit_exact(awq, W, s, ratios=CLIP_RATIOS):
+    import torch
+    import oracle
+    N, K = W.shape
+    codes, scales, zeros, choice = oracle.quantize_clip(W, s, ratios)
+    q_ref, s_ref, z_ref = oracle.pack(codes, scales, zeros)
+    qb, sb, zb = awq.awq_packed_sizes(N, K)
+    q_gpu, cq = guarded(qb, torch.uint8)
+    s_gpu, cs = guarded(sb, torch.float16)
+    z_gpu, cz = guarded(zb, torch.uint8)
+    _, _, _, ch_gpu = awq.awq_quantize_pack_clip(dev(W), None if s is None else dev(s), ratios,
+                                                 out=(q_gpu, s_gpu, z_gpu), want_choice=True)
+    cq(); cs(); cz()
+    ch = host(ch_gpu)
+    assert np.array_equal(ch, choice), f"{(ch != choice).sum()} of {choice.size} groups chose another ratio"
+    assert np.array_equal(host(s_gpu).view(np.uint16), s_ref), "steps differ"
+    assert np.array_equal(host(z_gpu), z_ref), "zero points differ"
+    assert np.array_equal(host(q_gpu), q_ref), "packed codes differ"
+    # without the optional output
+    q2, s2, z2 = awq.awq_quantize_pack_clip(dev(W), None if s is None else dev(s), ratios)
+    assert np.array_equal(host(q2), q_ref) and np.array_equal(host(z2), z_ref)
+    return choice
+
+
+@pytest.mark.parametrize("N,K", [(16, 128), (48, 640), (80, 1408), (272, 256)])
+def test_quantize_pack_clip_small_shapes(awq, N, K):
+    case, s, xs = make_case(N, K, 1, 0.02, cfg=0, proj=7)
+    choice = assert_clip_bit_exact(awq, case.W, s)
+    assert choice.max() > 0                                # the search does something
+    assert_clip_bit_exact(awq, case.W, None, ratios=[0.8, 1.0, 0.8, 0.9])
+    # a grid of one ratio 1.0 is awq_quantize_pack
+    q1, s1, z1 = awq.awq_quantize_pack_clip(dev(case.W), dev(s), [1.0])
+    q0, s0, z0 = awq.awq_quantize_pack(dev(case.W), dev(s))
+    assert np.array_equal(host(q1), host(q0)) and np.array_equal(host(z1), host(z0))
+    assert np.array_equal(host(s1).view(np.uint16), host(s0).view(np.uint16))
+
+
+def test_quantize_pack_clip_edge_groups_and_full_size(awq):
+    g = np.random.default_rng(31)
+    N, K = 64, 512
+    W = (g.standard_normal((N, K)) * 0.02).astype(np.float16)
+    W[0, :128] = 0                          # constant group
+    W[1, :128] = np.float16(0.37)
+    W[2, 128:256] = np.abs(W[2, 128:256])   # one-sided groups
+    W[3, 128:256] = -np.abs(W[3, 128:256])
+    W[4, 256:384] *= 1000                   # large magnitudes
+    W[5, 300] = np.float16(3.0)             # a lone outlier: clipping it costs more than it gains
+    assert_clip_bit_exact(awq, W, None)
+    s = (10.0 ** g.uniform(-2, 2, size=K)).astype(np.float32)
+    assert_clip_bit_exact(awq, W, s, ratios=[0.5, 0.75, 1.0])
+    case, s, xs = make_case(4096, 4096, 1, 0.02, cfg=0)
+    assert_clip_bit_exact(awq, case.W, s)
+
+
+def test_quantize_pack_clip_rejects_bad_ratios(awq):
+    import torch
+    W = torch.zeros((16, 128), dtype=torch.float16, device="cuda")
+    for ratios in ([], [1.0] * 33, [0.0], [1.5], [float("nan")], [-0.5]):
+        with pytest.raises(awq.AwqError) as e:
+            awq.awq_quantize_pack_clip(W, None, ratios)
+        assert e.value.status == -7
+
+
 # ------------------------------------------------------------------- scale search (Eq. 4-5)
 
 def loss_rtol(count):
