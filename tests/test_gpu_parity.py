@@ -659,6 +659,50 @@ def test_search_scale_rejects_bad_arguments(awq):
     assert awq.load().awq_search_scale_workspace_bytes(4, 16, 100, 1, 128) == 0
 
 
+# ------------------------------------------------------------------- the pieces together
+
+def test_awq_for_one_linear_end_to_end(awq):
+    """Search the scale, quantize, run the layer: every stage against the oracle on the same
+    inputs, and the result is closer to the fp16 layer than plain round-to-nearest.  The
+    clipping search (weight-space error) is checked on top of both: bit-exact, and it lowers the
+    output error of plain RTN; after activation-aware scaling it does not (the scaled-up salient
+    weights sit at the ends of the range), which is recorded here as a measured fact."""
+    import oracle
+    import workloads
+    N, K, T, M = 1024, 4096, 64, 16
+    case = workloads.linear_case("e2e", N, K, M, workloads.SIGMA_7B, 0, proj=9, calib_tokens=T)
+    W, X, x = case.W, case.calib, case.x
+    best, losses, s_gpu = awq.awq_search_scale(dev(W), dev(X), ALPHAS)
+    best = int(host(best)[0])
+    s = host(s_gpu)
+    assert 0 < best < len(ALPHAS) - 1                       # an interior alpha wins on outlier data
+    # quantize with that s: bit-exact with the oracle given the same s, with and without clipping
+    assert_clip_bit_exact(awq, W, s)
+    (codes, scales, zeros), (q, sc, zp) = assert_quantize_bit_exact(awq, W, s)
+    Wdq = oracle.dequant(codes, scales, zeros)
+    xs = oracle.apply_inv_scale(x, s)
+    xs_gpu = awq.awq_apply_inv_scale(dev(x), dev(s))
+    assert np.array_equal(host(xs_gpu).view(np.uint16), xs.view(np.uint16))
+    for m in (1, M):
+        y = host(awq.awq_w4a16_linear(xs_gpu[:m].contiguous(), q, sc, zp, N))
+        err = oracle.norm_error(y, oracle.matmul(xs[:m], Wdq), xs[:m], Wdq)
+        assert err.max() <= TOL
+    # against the unquantized layer, on fresh tokens: the searched scale beats RTN clearly
+    y_fp = oracle.matmul(x, W.astype(np.float32))
+
+    def out_err(xx, triple):
+        return float(np.sum((oracle.matmul(xx, oracle.dequant(*triple)) - y_fp) ** 2))
+
+    e_awq = out_err(xs, (codes, scales, zeros))
+    e_rtn = out_err(x, oracle.quantize(W, None))
+    assert e_awq < 0.6 * e_rtn, (e_awq, e_rtn)
+    e_rtn_clip = out_err(x, oracle.quantize_clip(W, None, CLIP_RATIOS)[:3])
+    e_awq_clip = out_err(xs, oracle.quantize_clip(W, s, CLIP_RATIOS)[:3])
+    assert e_rtn_clip < e_rtn
+    print(f"output error vs fp16 layer: RTN {e_rtn:.0f}, RTN+clip {e_rtn_clip:.0f}, "
+          f"searched scale {e_awq:.0f}, searched scale+clip {e_awq_clip:.0f}")
+
+
 def test_errors_surface_as_exceptions(awq):
     import torch
     W = torch.zeros((16, 100), dtype=torch.float16, device="cuda")
