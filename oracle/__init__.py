@@ -119,11 +119,13 @@ def quantize(W, s=None, group: int = GROUP):
     return codes, scales.view(np.float16), zeros
 
 
-def quantize_clip(W, s, ratios, group: int = GROUP):
+def quantize_clip(W, s, ratios, xs=None, group: int = GROUP):
     """Sec. 3.2, weight clipping (one sentence in the paper; the reading is stated in the C
     file): per group the range of w*s is shrunk by each ratio of the grid and the ratio with
-    the smallest squared quantization error wins.  Returns codes, scales, zeros as `quantize`
-    and choice[N,G] u8, the index of the winning ratio."""
+    the smallest squared quantization error wins -- the error of the weights themselves, or,
+    with rows xs = x/s [T,K] given, of the group's contribution to the layer output on those
+    rows.  Returns codes, scales, zeros as `quantize` and choice[N,G] u8, the index of the
+    winning ratio."""
     Wb = _as_f16_bits(W)
     N, K = Wb.shape
     if K % group:
@@ -139,9 +141,16 @@ def quantize_clip(W, s, ratios, group: int = GROUP):
     scales = np.empty((N, G), dtype=np.uint16)
     zeros = np.empty((N, G), dtype=np.uint8)
     choice = np.empty((N, G), dtype=np.uint8)
+    xp, T = None, 0
+    if xs is not None:
+        xb = _as_f16_bits(xs)
+        T = xb.shape[0]
+        assert xb.shape == (T, K)
+        xp = _p(xb)
     _chk(_load().awq_oracle_quantize_clip(_p(Wb), sp, _i64(N), _i64(K), ctypes.c_int(group),
-                                          _p(ratios), ctypes.c_int(ratios.size), _p(codes),
-                                          _p(scales), _p(zeros), _p(choice)), "quantize_clip")
+                                          _p(ratios), ctypes.c_int(ratios.size), xp, _i64(T),
+                                          _p(codes), _p(scales), _p(zeros), _p(choice)),
+         "quantize_clip")
     return codes, scales.view(np.float16), zeros, choice
 
 

@@ -194,10 +194,16 @@ int awq_oracle_quantize(const uint16_t *W, const float *s, int64_t N, int64_t K,
  * differences between the dequantized and the scaled weights wins (first one on ties).
  * Quantization arithmetic as in awq_oracle_quantize (binary32, one rounding per operation);
  * an error is e = (q - zero) * scale - w*s in binary32, the sum of e*e is taken in binary64.
- * choice[n*G+g] (optional) receives the index of the winning r.                        */
+ * With activation rows xs = x/s [T,K] (optional) the error of a group is instead its
+ * contribution to the layer output on those rows, sum_t (sum_k e[k] xs[t,k])^2 in binary64:
+ * the counterpart of Eq. 4 for one group, weighting every weight error by the activation
+ * it meets.  choice[n*G+g] (optional) receives the index of the winning r.              */
 static void quantize_group_range(const float *wp, int group, float mx, float mn, uint16_t *sc_h_out,
-                                 float *zero_out, uint8_t *codes /* may be NULL */, double *err)
+                                 float *zero_out, uint8_t *codes /* may be NULL */, double *err,
+                                 const uint16_t *xs /* may be NULL: rows of x/s, this group's columns */,
+                                 int64_t T, int64_t row_stride)
 {
+    float diff[ORACLE_GROUP];
     float range = mx - mn;
     float sc32 = range / 15.0f;
     sc32 = clampf(sc32, 6.103515625e-05f, 65504.0f);
@@ -216,7 +222,19 @@ static void quantize_group_range(const float *wp, int group, float mx, float mn,
         float lv = q - zero;
         float dq = lv * scale;
         float e = dq - wp[j];
+        diff[j] = e;
         acc += (double)e * (double)e;
+    }
+    if (xs) {
+        /* the group's contribution to the layer output on the given rows:
+         * sum_t ( sum_k e[k] * x'[t,k] )^2, in binary64 */
+        acc = 0.0;
+        for (int64_t t = 0; t < T; ++t) {
+            double dot = 0.0;
+            for (int j = 0; j < group; ++j)
+                dot += (double)diff[j] * (double)awq_oracle_f16_to_f32(xs[t * row_stride + j]);
+            acc += dot * dot;
+        }
     }
     *sc_h_out = sc_h;
     *zero_out = zero;
@@ -224,9 +242,10 @@ static void quantize_group_range(const float *wp, int group, float mx, float mn,
 }
 
 int awq_oracle_quantize_clip(const uint16_t *W, const float *s, int64_t N, int64_t K, int group,
-                             const float *ratios, int n_ratios, uint8_t *codes, uint16_t *scales,
-                             uint8_t *zeros, uint8_t *choice)
+                             const float *ratios, int n_ratios, const uint16_t *xs, int64_t T,
+                             uint8_t *codes, uint16_t *scales, uint8_t *zeros, uint8_t *choice)
 {
+    if (xs && T <= 0) return -4;
     if (!W || !codes || !scales || !zeros || !ratios) return -1;
     if (group != ORACLE_GROUP || N <= 0 || K <= 0 || K % group) return -2;
     if (n_ratios < 1 || n_ratios > 255) return -3;
@@ -254,7 +273,8 @@ int awq_oracle_quantize_clip(const uint16_t *W, const float *s, int64_t N, int64
                 uint16_t sc_h;
                 float zero;
                 double err;
-                quantize_group_range(wp, group, mxr, mnr, &sc_h, &zero, NULL, &err);
+                quantize_group_range(wp, group, mxr, mnr, &sc_h, &zero, NULL, &err,
+                                     xs ? xs + k0 : NULL, T, K);
                 if (i == 0 || err < best_err) {
                     best = i;
                     best_err = err;
@@ -266,7 +286,8 @@ int awq_oracle_quantize_clip(const uint16_t *W, const float *s, int64_t N, int64
                 uint16_t sc_h;
                 float zero;
                 double err;
-                quantize_group_range(wp, group, mxr, mnr, &sc_h, &zero, codes + n * K + k0, &err);
+                quantize_group_range(wp, group, mxr, mnr, &sc_h, &zero, codes + n * K + k0, &err,
+                                     NULL, 0, 0);
                 scales[n * G + g] = sc_h;
                 zeros[n * G + g] = (uint8_t)zero;
                 if (choice) choice[n * G + g] = (uint8_t)best;

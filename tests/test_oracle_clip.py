@@ -81,3 +81,54 @@ def test_a_lossless_grid_keeps_the_full_range_wherever_it_is_listed():
         codes, scales, zeros, choice = oracle.quantize_clip(W, None, ratios)
         assert np.all(choice == ratios.index(1.0))   # zero error; the first of equal ratios
         assert np.array_equal(codes, lv.astype(np.uint8))
+
+
+def test_activation_weighted_choice_against_independent_evaluation_and_its_special_cases():
+    W, g = gauss(54, 48, 512)
+    K, T = 512, 40
+    X = g.standard_normal((T, K)).astype(np.float32)
+    X[:, g.choice(K, size=5, replace=False)] *= 20
+    X = X.astype(np.float16)
+    s = oracle.act_scale(X, 0.4).astype(np.float32)
+    xs = oracle.apply_inv_scale(X, s)
+    codes, scales, zeros, choice = oracle.quantize_clip(W, s, RATIOS, xs=xs)
+    # independent route: one full quantization per ratio, the group's output error in numpy
+    wp = (W.astype(np.float32) * s[None, :]).astype(np.float64)
+    xg = xs.astype(np.float64).reshape(T, K // 128, 128)
+    errs, deq = [], []
+    for r in RATIOS:
+        c, sc, z, _ = oracle.quantize_clip(W, s, [r])
+        D = oracle.dequant(c, sc, z).astype(np.float64)
+        deq.append(D)
+        proj = np.einsum("ngk,tgk->ngt", (D - wp).reshape(48, K // 128, 128), xg)
+        errs.append((proj ** 2).sum(axis=2))
+    errs = np.stack(errs)
+    want = errs.argmin(axis=0)
+    diff = choice != want
+    if diff.any():
+        e_sorted = np.sort(errs, axis=0)
+        assert np.all((e_sorted[1] - e_sorted[0])[diff] <= 1e-9 * e_sorted[0][diff])
+    assert diff.mean() < 1e-2
+    got = oracle.dequant(codes, scales, zeros).astype(np.float64)
+    for i in range(len(RATIOS)):
+        m = np.repeat(choice == i, 128, axis=1)
+        assert np.array_equal(got[m], deq[i][m])
+    # it differs from the weight-space choice, and lowers the output error on those rows
+    _, _, _, choice_w = oracle.quantize_clip(W, s, RATIOS)
+    assert (choice != choice_w).mean() > 0.2
+    y = xs.astype(np.float64) @ wp.T
+    out_err = lambda D: np.sum((xs.astype(np.float64) @ D.T - y) ** 2)
+    assert out_err(got) < out_err(deq[0])
+    # rows that are zero outside one group leave every other group indifferent: first ratio
+    xz = np.zeros_like(xs)
+    xz[:, 128:256] = xs[:, 128:256]
+    _, _, _, cz = oracle.quantize_clip(W, s, RATIOS[::-1], xs=xz)
+    assert np.all(cz[:, [0, 2, 3]] == 0) and np.array_equal(cz[:, 1], len(RATIOS) - 1 - choice[:, 1])
+    # one-hot rows on every column make it the weight-space error
+    eye = np.zeros((128, 512), np.float16)
+    eye[np.arange(128), 128 + np.arange(128)] = 1
+    _, _, _, ce = oracle.quantize_clip(W, s, RATIOS, xs=eye)
+    assert np.array_equal(ce[:, 1], choice_w[:, 1])
+    # a power-of-two factor on the rows changes no choice
+    _, _, _, c4 = oracle.quantize_clip(W, s, RATIOS, xs=(xs.astype(np.float32) * 4).astype(np.float16))
+    assert np.array_equal(c4, choice)
