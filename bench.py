@@ -377,6 +377,23 @@ def main():
         extras["quantize_pack_clip"] = {"ratios": len(ratios), "matrices": 3, "ms_total": round(cms, 3),
                                         "GB/s": round(cbytes / (cms * 1e-3) / 1e9, 1),
                                         "note": "arithmetic-bound: 11 trial quantizations per group"}
+        # the same with the error measured on 64 calibration rows (matrix cores)
+        ams = 0.0
+        for p in (0, 4, 6):
+            name, N, K = shapes[p]
+            Wd = torch.from_numpy(W0[p]).to(dev)
+            xs64 = awq.awq_apply_inv_scale(torch.from_numpy(calib_by_k[K]).to(dev), s_by_k[K])
+            outc = awq.awq_quantize_pack_clip(Wd, s_by_k[K], ratios, xs=xs64)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                awq.awq_quantize_pack_clip(Wd, s_by_k[K], ratios, out=outc, xs=xs64)
+            e1.record()
+            torch.cuda.synchronize()
+            ams += e0.elapsed_time(e1) / 5
+            del Wd
+        extras["quantize_pack_clip_on_64_rows"] = {"ratios": len(ratios), "matrices": 3, "ms_total": round(ams, 3)}
 
         # scale search (Eq. 4-5): 20 grid points on one 4096 x 4096 linear with 2048 cached rows
         name, N, K = shapes[0]

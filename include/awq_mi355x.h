@@ -85,6 +85,7 @@ int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K, i
                       void *qweight, void *scales, void *zeros, void *stream);
 
 #define AWQ_CLIP_MAX_RATIOS 32
+#define AWQ_CLIP_MAX_ROWS 64
 
 /* Sec. 3.2, weight clipping ("we further apply weight clipping to minimize the MSE error of
  * quantization"; the paper says no more, this is the reading taken): awq_quantize_pack with a
@@ -93,12 +94,19 @@ int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K, i
  * formulas of awq_quantize_pack (values outside it saturate at code 0 or 15), and the r with
  * the smallest sum over the group of ((q - zero)*scale - w')^2 is used (differences in
  * binary32, one rounding per operation; squares summed in binary64; the first r wins a tie).
+ * With xs_f16 != NULL the error of a trial is instead the group's contribution to the layer
+ * output on the rows xs = x/s [T,K] fp16 (device, 1 <= T <= AWQ_CLIP_MAX_ROWS; take a sample
+ * of a larger calibration set): sum_t (sum_k ((q - zero)*scale - w')[k] * xs[t,k])^2, the
+ * counterpart of Eq. 4 for one group.  Here the inner sums run on the matrix cores from
+ * errors rounded to fp16 (relative 2^-11), so among trials whose errors agree to about 1e-3
+ * the choice is not unique; the codes are always exactly those of the chosen ratio.
  *   ratios: HOST array of 1..AWQ_CLIP_MAX_RATIOS values in (0, 1], read before the call
  *   returns; choice: device [N, K/128] bytes, row-major, receives the index of the winning
  *   ratio of every group, or NULL.  Everything else as awq_quantize_pack. */
 int awq_quantize_pack_clip(const void *W_f16, const float *s, int64_t N, int64_t K, int group,
-                           const float *ratios, int n_ratios, void *qweight, void *scales,
-                           void *zeros, uint8_t *choice, void *stream);
+                           const float *ratios, int n_ratios, const void *xs_f16, int64_t T,
+                           void *qweight, void *scales, void *zeros, uint8_t *choice,
+                           void *stream);
 
 /* Inverse of the packing (export / test path): codes [N,K] one code per byte,
  * scales_f16 [N,K/128] fp16, zeros_u8 [N,K/128] one zero point per byte, all

@@ -81,7 +81,7 @@ def load() -> ctypes.CDLL:
     lib.awq_w4a16_linear_multi.argtypes = [ctypes.POINTER(LinearDesc), i32, i64, i32, vp, sz, vp]
     lib.awq_quantize_pack_clip.restype = i32
     lib.awq_quantize_pack_clip.argtypes = [vp, vp, i64, i64, i32, ctypes.POINTER(ctypes.c_float), i32,
-                                           vp, vp, vp, vp, vp]
+                                           vp, i64, vp, vp, vp, vp, vp]
     lib.awq_search_scale_workspace_bytes.restype = sz
     lib.awq_search_scale_workspace_bytes.argtypes = [i64, i64, i64, i32, i32]
     lib.awq_search_scale.restype = i32
@@ -315,8 +315,9 @@ def awq_search_scale(W: torch.Tensor, X: torch.Tensor, alphas, group: int = GROU
 
 
 def awq_quantize_pack_clip(W: torch.Tensor, s: torch.Tensor | None, ratios, group: int = GROUP,
-                           out=None, want_choice: bool = False):
-    """awq_quantize_pack with the per-group clipping search over `ratios` (values in (0, 1]).
+                           out=None, want_choice: bool = False, xs: torch.Tensor | None = None):
+    """awq_quantize_pack with the per-group clipping search over `ratios` (values in (0, 1]);
+    with `xs` ([T,K] fp16 rows of x/s, T <= 64) the error is measured on the layer output.
     Returns (qweight, scales, zeros) and, if asked for, choice [N, K/128] u8."""
     _dev(W, torch.float16, "W")
     N, K = W.shape
@@ -336,7 +337,14 @@ def awq_quantize_pack_clip(W: torch.Tensor, s: torch.Tensor | None, ratios, grou
     n = len(ratios)
     arr = (ctypes.c_float * max(n, 1))(*[float(r) for r in ratios])
     choice = torch.empty((N, K // group), dtype=torch.uint8, device=W.device) if want_choice else None
-    _check(load().awq_quantize_pack_clip(_ptr(W), _ptr(s), N, K, group, arr, n, _ptr(qweight),
-                                         _ptr(scales), _ptr(zeros), _ptr(choice), _stream()),
+    T = 0
+    if xs is not None:
+        _dev(xs, torch.float16, "xs")
+        T, K2 = xs.shape
+        if K2 != K:
+            raise ValueError("xs and W disagree on K")
+    _check(load().awq_quantize_pack_clip(_ptr(W), _ptr(s), N, K, group, arr, n, _ptr(xs), T,
+                                         _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(choice),
+                                         _stream()),
            "awq_quantize_pack_clip")
     return (qweight, scales, zeros, choice) if want_choice else (qweight, scales, zeros)

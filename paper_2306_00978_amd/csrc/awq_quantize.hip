@@ -64,12 +64,21 @@ struct ClipRatios {
 // the grid; the ratio with the smallest sum of squared differences between dequantized and
 // scaled weights (differences in fp32, one rounding per operation; their squares summed in
 // fp64) is used, the first one on ties.  choice[n*G+g] (optional) receives its index.
-template <bool CLIP>
+// ACT (with CLIP): the error of a trial is not that of the weights but the group's contribution
+// to the layer output on up to 64 rows xs = x/s: sum_t (sum_k e[k] xs[t,k])^2.  That is a
+// 16 x 128 by 128 x T product per tile and trial, and the lane layout of this kernel is the
+// B-operand layout of v_mfma_f32_16x16x32_f16 (row l%16, columns 32 j + 8 (l/16) + 0..7 in
+// step j): the errors go to the matrix core as they are, scaled by a power of two into fp16
+// range, against the rows of xs held in registers as A operands for the wave's whole life (its
+// group never changes).  Lane l receives the sums of its own row for tokens 4 (l/16) + 0..3 of
+// every block of 16 rows; squares are added in fp64 and combined over the four lanes of the row.
+template <bool CLIP, bool ACT>
 __global__ __launch_bounds__(256) void quantize_pack_kernel(
     const uint4 *__restrict__ W,   // [N, K/8] runs of eight fp16
     const float4 *__restrict__ s,  // [K/4] or nullptr
     uint4 *__restrict__ qweight, uint16_t *__restrict__ scales, uint8_t *__restrict__ zeros,
-    int G, int NRB, int rb_per_wave, int num_units, ClipRatios ratios, uint8_t *__restrict__ choice)
+    int G, int NRB, int rb_per_wave, int num_units, ClipRatios ratios, uint8_t *__restrict__ choice,
+    const uint4 *__restrict__ xs, int T)
 {
     const int lane = threadIdx.x & 63;
     const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -92,6 +101,19 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) sv[j][e] = 1.0f;
+        }
+    }
+
+    // A operands of the activation rows: token 16 tb + l%16, columns 32 j + 8 (l/16) + 0..7
+    uint4 xa[ACT ? 4 : 1][4];
+    const int tblocks = ACT ? (T + 15) >> 4 : 0;
+    if (ACT) {
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {
+            const int t = 16 * tb + r;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xa[tb][j] = t < T ? xs[(int64_t)t * K8 + g * 16 + 4 * j + c] : make_uint4(0, 0, 0, 0);
         }
     }
 
@@ -142,6 +164,10 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
                 const float tzero = clampf(__builtin_rintf((-mnr) / tscale), 0.0f, 15.0f);
                 const Reciprocal trc = make_reciprocal(tscale);
                 double err = 0.0;
+                // ACT: errors times 2^-e, e the exponent of the step, fit fp16 (|e[k]| <= 16 steps)
+                const uint32_t sbits = __builtin_bit_cast(uint32_t, tscale);
+                const float down = __builtin_bit_cast(float, (254u - ((sbits >> 23) & 255u)) << 23);
+                half_t eh[4][8];
                 auto accumulate = [&](auto quotient) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
@@ -153,11 +179,30 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
                             const float lv = q - tzero;
                             const float dq = lv * tscale;
                             const float d = dq - wp[j][e];
-                            err += (double)d * (double)d;
+                            if (ACT) eh[j][e] = (half_t)(d * down);
+                            else err += (double)d * (double)d;
                         }
                 };
                 if (tame) accumulate([&](float n) { return divide(n, trc); });
                 else accumulate([&](float n) { return n / tscale; });
+                if (ACT) {
+                    for (int tb = 0; tb < tblocks; ++tb) {
+                        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            half8_t b;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) b[e] = eh[j][e];
+                            // tb is wave-uniform; the four A operands of a block are picked by it
+                            const uint4 a = tb == 0 ? xa[0][j] : tb == 1 ? xa[1][j] : tb == 2 ? xa[2][j] : xa[3][j];
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), b, acc, 0, 0, 0);
+                        }
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) err += (double)acc[v] * (double)acc[v];
+                    }
+                    const double up = 1.0 / (double)down;          // a power of two
+                    err = err * up * up;
+                }
                 // the four lanes of a row: every one of them ends up with the same bits
                 err += __shfl_xor(err, 16);
                 err += __shfl_xor(err, 32);
@@ -256,7 +301,8 @@ __global__ __launch_bounds__(256) void unpack_kernel(
 namespace {
 
 int quantize_launch(const void *W_f16, const float *s, int64_t N, int64_t K, int group, void *qweight,
-                    void *scales, void *zeros, const ClipRatios *ratios, uint8_t *choice, void *stream)
+                    void *scales, void *zeros, const ClipRatios *ratios, uint8_t *choice,
+                    const void *xs_f16, int64_t T, void *stream)
 {
     if (!W_f16 || !qweight || !scales || !zeros) return AWQ_ERR_NULL_POINTER;
     int st = awq_check_weight_shape(N, K, group);
@@ -273,14 +319,18 @@ int quantize_launch(const void *W_f16, const float *s, int64_t N, int64_t K, int
     parts = (NRB + rb_per_wave - 1) / rb_per_wave;
     const int num_units = parts * G;
     const int blocks = (num_units + 3) / 4;
-    if (ratios)
-        quantize_pack_kernel<true><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
+    if (ratios && xs_f16)
+        quantize_pack_kernel<true, true><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
             (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
-            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, *ratios, choice);
+            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, *ratios, choice, (const uint4 *)xs_f16, (int)T);
+    else if (ratios)
+        quantize_pack_kernel<true, false><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
+            (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
+            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, *ratios, choice, nullptr, 0);
     else
-        quantize_pack_kernel<false><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
+        quantize_pack_kernel<false, false><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
             (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
-            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, ClipRatios{}, nullptr);
+            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, ClipRatios{}, nullptr, nullptr, 0);
     return awq_launch_status();
 }
 
@@ -290,14 +340,18 @@ extern "C" int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, i
                                  int group, void *qweight, void *scales, void *zeros,
                                  void *stream)
 {
-    return quantize_launch(W_f16, s, N, K, group, qweight, scales, zeros, nullptr, nullptr, stream);
+    return quantize_launch(W_f16, s, N, K, group, qweight, scales, zeros, nullptr, nullptr, nullptr, 0,
+                           stream);
 }
 
 extern "C" int awq_quantize_pack_clip(const void *W_f16, const float *s, int64_t N, int64_t K,
-                                      int group, const float *ratios, int n_ratios, void *qweight,
-                                      void *scales, void *zeros, uint8_t *choice, void *stream)
+                                      int group, const float *ratios, int n_ratios,
+                                      const void *xs_f16, int64_t T, void *qweight, void *scales,
+                                      void *zeros, uint8_t *choice, void *stream)
 {
     if (!ratios) return AWQ_ERR_NULL_POINTER;
+    if (xs_f16 && (T < 1 || T > AWQ_CLIP_MAX_ROWS)) return AWQ_ERR_BAD_SHAPE;
+    if (xs_f16 && !awq_aligned16(xs_f16)) return AWQ_ERR_MISALIGNED;
     if (n_ratios < 1 || n_ratios > AWQ_CLIP_MAX_RATIOS) return AWQ_ERR_BAD_ARGUMENT;
     ClipRatios r = {};
     r.n = n_ratios;
@@ -305,7 +359,7 @@ extern "C" int awq_quantize_pack_clip(const void *W_f16, const float *s, int64_t
         if (!(ratios[i] > 0.0f && ratios[i] <= 1.0f)) return AWQ_ERR_BAD_ARGUMENT;
         r.v[i] = ratios[i];
     }
-    return quantize_launch(W_f16, s, N, K, group, qweight, scales, zeros, &r, choice, stream);
+    return quantize_launch(W_f16, s, N, K, group, qweight, scales, zeros, &r, choice, xs_f16, T, stream);
 }
 
 extern "C" int awq_unpack(const void *qweight, const void *scales, const void *zeros,

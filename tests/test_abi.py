@@ -117,13 +117,16 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     c = lib.awq_quantize_pack_clip
     rat = (ctypes.c_float * 3)(1.0, 0.9, 0.8)
     Pq = ctypes.c_void_p
-    assert c(Pq(ok), None, 16, 128, 128, None, 3, Pq(ok), Pq(ok), Pq(ok), None, None) == -1
-    assert c(None, None, 16, 128, 128, rat, 3, Pq(ok), Pq(ok), Pq(ok), None, None) == -1
-    assert c(Pq(ok), None, 16, 128, 128, rat, 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -7
-    assert c(Pq(ok), None, 16, 128, 128, rat, 33, Pq(ok), Pq(ok), Pq(ok), None, None) == -7
-    assert c(Pq(ok), None, 16, 128, 128, (ctypes.c_float * 1)(0.0), 1, Pq(ok), Pq(ok), Pq(ok), None, None) == -7
-    assert c(Pq(ok), None, 16, 100, 128, rat, 3, Pq(ok), Pq(ok), Pq(ok), None, None) == -2
-    assert c(Pq(odd), None, 16, 128, 128, rat, 3, Pq(ok), Pq(ok), Pq(ok), None, None) == -4
+    assert c(Pq(ok), None, 16, 128, 128, None, 3, None, 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -1
+    assert c(None, None, 16, 128, 128, rat, 3, None, 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -1
+    assert c(Pq(ok), None, 16, 128, 128, rat, 0, None, 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -7
+    assert c(Pq(ok), None, 16, 128, 128, rat, 33, None, 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -7
+    assert c(Pq(ok), None, 16, 128, 128, (ctypes.c_float * 1)(0.0), 1, None, 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -7
+    assert c(Pq(ok), None, 16, 100, 128, rat, 3, None, 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -2
+    assert c(Pq(odd), None, 16, 128, 128, rat, 3, None, 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -4
+    assert c(Pq(ok), None, 16, 128, 128, rat, 3, Pq(ok), 0, Pq(ok), Pq(ok), Pq(ok), None, None) == -2
+    assert c(Pq(ok), None, 16, 128, 128, rat, 3, Pq(ok), 65, Pq(ok), Pq(ok), Pq(ok), None, None) == -2
+    assert c(Pq(ok), None, 16, 128, 128, rat, 3, Pq(odd), 8, Pq(ok), Pq(ok), Pq(ok), None, None) == -4
 
     g = lib.awq_search_scale
     wsb = lib.awq_search_scale_workspace_bytes

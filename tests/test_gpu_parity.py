@@ -573,6 +573,65 @@ def test_quantize_pack_clip_edge_groups_and_full_size(awq):
     assert_clip_bit_exact(awq, case.W, s)
 
 
+def check_clip_on_activations(awq, W, s, xs, ratios=CLIP_RATIOS):
+    """Error of a trial = the group's contribution to the layer output on the rows xs.  The
+    kernel forms it on the matrix cores from errors rounded to fp16, so near-equal trials may be
+    ordered differently than in the fp64 oracle: the choice of every group must be the oracle's
+    or a trial whose oracle error is within 5e-3 of the smallest (rounding of 2^-11 per error,
+    twice through the square, with margin), and the packed result must be exactly the
+    quantization by the chosen ratio."""
+    import torch
+    import oracle
+    N, K = W.shape
+    G = K // 128
+    T = xs.shape[0]
+    q_gpu, s_gpu, z_gpu, ch_gpu = awq.awq_quantize_pack_clip(dev(W), None if s is None else dev(s), ratios,
+                                                             want_choice=True, xs=dev(xs))
+    ch = host(ch_gpu)
+    _, _, _, ch_ref = oracle.quantize_clip(W, s, ratios, xs=xs)
+    # the oracle's errors of all trials, from one full quantization per ratio
+    wp = (W.astype(np.float32) * (np.ones(K, np.float32) if s is None else s)[None, :]).astype(np.float64)
+    xg = xs.astype(np.float64).reshape(T, G, 128)
+    per_ratio, errs = [], []
+    for r in ratios:
+        c, sc, z, _ = oracle.quantize_clip(W, s, [r])
+        per_ratio.append((c, sc, z))
+        d = (oracle.dequant(c, sc, z).astype(np.float64) - wp).reshape(N, G, 128)
+        errs.append((np.einsum("ngk,tgk->ngt", d, xg) ** 2).sum(axis=2))
+    errs = np.stack(errs)
+    e_min = errs.min(axis=0)
+    e_got = np.take_along_axis(errs, ch[None].astype(np.int64), 0)[0]
+    assert np.all(e_got <= e_min * (1 + 5e-3) + 1e-30), "a group chose a clearly worse ratio"
+    agree = float((ch == ch_ref).mean())
+    assert agree > 0.97, agree
+    # assemble the oracle's quantization for the GPU's choices and compare bit for bit
+    codes = np.empty((N, K), np.uint8)
+    scales = np.empty((N, G), np.float16)
+    zeros = np.empty((N, G), np.uint8)
+    for i, (c, sc, z) in enumerate(per_ratio):
+        m = ch == i
+        scales[m], zeros[m] = sc[m], z[m]
+        mk = np.repeat(m, 128, axis=1)
+        codes[mk] = c[mk]
+    q_ref, s_ref, z_ref = oracle.pack(codes, scales, zeros)
+    assert np.array_equal(host(s_gpu).view(np.uint16), s_ref)
+    assert np.array_equal(host(z_gpu), z_ref)
+    assert np.array_equal(host(q_gpu), q_ref)
+    return agree
+
+
+@pytest.mark.parametrize("N,K,T", [(48, 640, 64), (80, 1408, 5), (272, 256, 33), (1024, 4096, 64)])
+def test_quantize_pack_clip_on_activation_rows(awq, N, K, T):
+    import oracle
+    import workloads
+    case = workloads.linear_case("clipx", N, K, 1, 0.02, 0, proj=11, calib_tokens=T)
+    s = oracle.act_scale(case.calib, 0.35).astype(np.float32)
+    xs = oracle.apply_inv_scale(case.calib, s)
+    agree = check_clip_on_activations(awq, case.W, s, xs)
+    print(f"clip on {T} rows, {N}x{K}: {100 * agree:.2f} % of the groups choose as the fp64 oracle")
+    check_clip_on_activations(awq, case.W, None, case.calib, ratios=[0.7, 1.0, 0.85])
+
+
 def test_quantize_pack_clip_rejects_bad_ratios(awq):
     import torch
     W = torch.zeros((16, 128), dtype=torch.float16, device="cuda")
@@ -663,10 +722,11 @@ def test_search_scale_rejects_bad_arguments(awq):
 
 def test_awq_for_one_linear_end_to_end(awq):
     """Search the scale, quantize, run the layer: every stage against the oracle on the same
-    inputs, and the result is closer to the fp16 layer than plain round-to-nearest.  The
-    clipping search (weight-space error) is checked on top of both: bit-exact, and it lowers the
-    output error of plain RTN; after activation-aware scaling it does not (the scaled-up salient
-    weights sit at the ends of the range), which is recorded here as a measured fact."""
+    inputs, and the result is closer to the fp16 layer than plain round-to-nearest.  Both
+    clipping searches are checked on top: the one on the weights' own error lowers the output
+    error of plain RTN but not that of the scaled layer (the scaled-up salient weights sit at
+    the ends of the range); the one that measures the error on the calibration rows lowers it
+    further."""
     import oracle
     import workloads
     N, K, T, M = 1024, 4096, 64, 16
@@ -699,8 +759,15 @@ def test_awq_for_one_linear_end_to_end(awq):
     e_rtn_clip = out_err(x, oracle.quantize_clip(W, None, CLIP_RATIOS)[:3])
     e_awq_clip = out_err(xs, oracle.quantize_clip(W, s, CLIP_RATIOS)[:3])
     assert e_rtn_clip < e_rtn
+    Xs = oracle.apply_inv_scale(X, s)
+    check_clip_on_activations(awq, W, s, Xs)
+    qa, sa, za = awq.awq_quantize_pack_clip(dev(W), dev(s), CLIP_RATIOS, xs=dev(Xs))
+    ca, sca, zca = (host(t) for t in awq.awq_unpack(qa, sa, za, N, K))
+    e_awq_act = out_err(xs, (ca, sca, zca))
+    assert e_awq_act < 0.95 * e_awq
     print(f"output error vs fp16 layer: RTN {e_rtn:.0f}, RTN+clip {e_rtn_clip:.0f}, "
-          f"searched scale {e_awq:.0f}, searched scale+clip {e_awq_clip:.0f}")
+          f"searched scale {e_awq:.0f}, +clip on weights {e_awq_clip:.0f}, "
+          f"+clip on calibration rows {e_awq_act:.0f}")
 
 
 def test_errors_surface_as_exceptions(awq):
