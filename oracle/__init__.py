@@ -262,3 +262,65 @@ def search_scale(W, X, alphas):
                        for a in alphas], dtype=np.float64)
     best = int(np.argmin(losses))
     return best, losses, act_scale(X, float(alphas[best])).astype(np.float32)
+
+
+# ---------------------------------------------------------------- INT3-g128 variant
+
+def quantize_w3(W, s=None, group: int = GROUP):
+    """Sec. 5 (INT3-g128): the 8-level form of `quantize`.  Returns codes[N,K] u8 in 0..7,
+    scales[N,G] f16, zeros[N,G] u8 in 0..7."""
+    Wb = _as_f16_bits(W)
+    N, K = Wb.shape
+    if K % group:
+        raise ValueError("K must be a multiple of the group size")
+    G = K // group
+    sp = None
+    if s is not None:
+        s = np.ascontiguousarray(s, dtype=np.float32)
+        assert s.shape == (K,)
+        sp = _p(s)
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, G), dtype=np.uint16)
+    zeros = np.empty((N, G), dtype=np.uint8)
+    _chk(_load().awq_oracle_quantize_w3(_p(Wb), sp, _i64(N), _i64(K), ctypes.c_int(group),
+                                        _p(codes), _p(scales), _p(zeros)), "quantize_w3")
+    return codes, scales.view(np.float16), zeros
+
+
+def packed_sizes_w3(N: int, K: int, group: int = GROUP):
+    G = K // group
+    return N * K * 3 // 8, N * G * 2, N * G // 2
+
+
+def pack_w3(codes, scales, zeros, group: int = GROUP):
+    """The 3-bit packed layout of this library (see the C file)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, K = codes.shape
+    G = K // group
+    sb = _as_f16_bits(scales)
+    zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+    assert sb.shape == (N, G) and zeros.shape == (N, G)
+    qb, sbytes, zb = packed_sizes_w3(N, K, group)
+    qweight = np.empty(qb, dtype=np.uint8)
+    scales_p = np.empty(sbytes // 2, dtype=np.uint16)
+    zeros_p = np.empty(zb, dtype=np.uint8)
+    _chk(_load().awq_oracle_pack_w3(_p(codes), _p(sb), _p(zeros), _i64(N), _i64(K),
+                                    ctypes.c_int(group), _p(qweight), _p(scales_p), _p(zeros_p)),
+         "pack_w3")
+    return qweight, scales_p, zeros_p
+
+
+def unpack_w3(qweight, scales_p, zeros_p, N: int, K: int, group: int = GROUP):
+    qweight = np.ascontiguousarray(qweight, dtype=np.uint8)
+    scales_p = _as_f16_bits(scales_p).reshape(-1)
+    zeros_p = np.ascontiguousarray(zeros_p, dtype=np.uint8)
+    G = K // group
+    qb, sbytes, zb = packed_sizes_w3(N, K, group)
+    assert qweight.size == qb and scales_p.size * 2 == sbytes and zeros_p.size == zb
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, G), dtype=np.uint16)
+    zeros = np.empty((N, G), dtype=np.uint8)
+    _chk(_load().awq_oracle_unpack_w3(_p(qweight), _p(scales_p), _p(zeros_p), _i64(N), _i64(K),
+                                      ctypes.c_int(group), _p(codes), _p(scales), _p(zeros)),
+         "unpack_w3")
+    return codes, scales.view(np.float16), zeros

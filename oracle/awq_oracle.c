@@ -390,6 +390,140 @@ int awq_oracle_dequant(const uint8_t *codes, const uint16_t *scales, const uint8
     return 0;
 }
 
+/* ---------- INT3-g128 variant (Sec. 5: "We focus on INT4/INT3 quantization"; Tab. 2 uses
+ * INT3-g128).  The same asymmetric min/max quantizer with 8 levels:
+ *   scale = fp16(clamp((max-min)/7, 2^-14, 65504)); zero = clamp(rint(-min/scale), 0, 7);
+ *   q = clamp(rint(w'/scale) + zero, 0, 7).                                              */
+int awq_oracle_quantize_w3(const uint16_t *W, const float *s, int64_t N, int64_t K,
+                           int group, uint8_t *codes, uint16_t *scales, uint8_t *zeros)
+{
+    if (!W || !codes || !scales || !zeros) return -1;
+    if (group != ORACLE_GROUP || N <= 0 || K <= 0 || K % group) return -2;
+    const int64_t G = K / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float wp[ORACLE_GROUP];
+        for (int64_t g = 0; g < G; ++g) {
+            const int64_t k0 = g * group;
+            for (int j = 0; j < group; ++j) {
+                float w = awq_oracle_f16_to_f32(W[n * K + k0 + j]);
+                float sk = s ? s[k0 + j] : 1.0f;
+                wp[j] = w * sk;
+            }
+            float mx = wp[0], mn = wp[0];
+            for (int j = 1; j < group; ++j) {
+                if (wp[j] > mx) mx = wp[j];
+                if (wp[j] < mn) mn = wp[j];
+            }
+            float range = mx - mn;
+            float sc32 = range / 7.0f;
+            sc32 = clampf(sc32, 6.103515625e-05f, 65504.0f);
+            uint16_t sc_h = awq_oracle_f32_to_f16(sc32);
+            float scale = awq_oracle_f16_to_f32(sc_h);
+            float nmn = -mn;
+            float zr = nmn / scale;
+            float zero = clampf(rintf(zr), 0.0f, 7.0f);
+            scales[n * G + g] = sc_h;
+            zeros[n * G + g] = (uint8_t)zero;
+            for (int j = 0; j < group; ++j) {
+                float r = wp[j] / scale;
+                float q = rintf(r);
+                q = q + zero;
+                q = clampf(q, 0.0f, 7.0f);
+                codes[n * K + k0 + j] = (uint8_t)q;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Packed layout of the 3-bit codes (written from the layout text):
+ * qweight: tiles of 16 rows x 128 columns, 768 bytes each, tile index (n/16)*G + k/128.
+ *          Inside a tile, 64 slots of 12 bytes = three little-endian 32-bit words; slot
+ *          l = (n%16) + 16*c owns row n%16 and the 32 codes of columns 32*j + 8*c + e
+ *          (j = 0..3, e = 0..7).  Code i = 8*j + e belongs to pair p = i/2, member h = i%2
+ *          (h = 0: low 16-bit half of a word, h = 1: high half).  Pairs 0..14 sit in word p/5
+ *          at bits [3f, 3f+3) of their half, f = p%5.  Pair 15 is spread over the spare top
+ *          bit of the halves: bit b of its code is bit 15 (h = 0) or bit 31 (h = 1) of word b.
+ * scales, zeros: as in the 4-bit layout (zero points 0..7 in nibbles).                  */
+static void w3_position(int i, int bit, int *word, int *pos)
+{
+    int p = i / 2, h = i % 2;
+    if (p < 15) {
+        *word = p / 5;
+        *pos = 16 * h + 3 * (p % 5) + bit;
+    } else {
+        *word = bit;
+        *pos = 16 * h + 15;
+    }
+}
+
+int awq_oracle_pack_w3(const uint8_t *codes, const uint16_t *scales, const uint8_t *zeros,
+                       int64_t N, int64_t K, int group, uint8_t *qweight,
+                       uint16_t *scales_p, uint8_t *zeros_p)
+{
+    if (!codes || !scales || !zeros || !qweight || !scales_p || !zeros_p) return -1;
+    if (group != ORACLE_GROUP || N <= 0 || K <= 0 || K % group || N % 16) return -2;
+    const int64_t G = K / group;
+    memset(qweight, 0, (size_t)(N * K * 3 / 8));
+    memset(zeros_p, 0, (size_t)(N * G / 2));
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t tile = (n / 16) * G + (k / 128);
+            int kk = (int)(k % 128);
+            int j = kk / 32, c = (kk % 32) / 8, e = kk % 8;
+            int slot = (int)(n % 16) + 16 * c;
+            uint8_t code = codes[n * K + k] & 0x7;
+            for (int bit = 0; bit < 3; ++bit) {
+                int word, pos;
+                w3_position(8 * j + e, bit, &word, &pos);
+                if ((code >> bit) & 1)
+                    qweight[tile * 768 + slot * 12 + word * 4 + pos / 8] |= (uint8_t)(1u << (pos % 8));
+            }
+        }
+        for (int64_t g = 0; g < G; ++g) {
+            int64_t rb = n / 16;
+            int r = (int)(n % 16);
+            scales_p[(rb * G + g) * 16 + r] = scales[n * G + g];
+            zeros_p[(rb * G + g) * 8 + r / 2] |= (uint8_t)((zeros[n * G + g] & 0xf) << (4 * (r % 2)));
+        }
+    }
+    return 0;
+}
+
+int awq_oracle_unpack_w3(const uint8_t *qweight, const uint16_t *scales_p,
+                         const uint8_t *zeros_p, int64_t N, int64_t K, int group,
+                         uint8_t *codes, uint16_t *scales, uint8_t *zeros)
+{
+    if (!codes || !scales || !zeros || !qweight || !scales_p || !zeros_p) return -1;
+    if (group != ORACLE_GROUP || N <= 0 || K <= 0 || K % group || N % 16) return -2;
+    const int64_t G = K / group;
+    for (int64_t tile = 0; tile < (N / 16) * G; ++tile) {
+        int64_t rb = tile / G, g = tile % G;
+        for (int slot = 0; slot < 64; ++slot) {
+            int r = slot % 16, c = slot / 16;
+            const uint8_t *sb = qweight + tile * 768 + slot * 12;
+            for (int i = 0; i < 32; ++i) {
+                uint8_t code = 0;
+                for (int bit = 0; bit < 3; ++bit) {
+                    int word, pos;
+                    w3_position(i, bit, &word, &pos);
+                    if ((sb[word * 4 + pos / 8] >> (pos % 8)) & 1) code |= (uint8_t)(1u << bit);
+                }
+                int64_t n = rb * 16 + r;
+                int64_t k = g * 128 + 32 * (i / 8) + 8 * c + (i % 8);
+                codes[n * K + k] = code;
+            }
+        }
+        for (int r = 0; r < 16; ++r) {
+            int64_t n = rb * 16 + r;
+            scales[n * G + g] = scales_p[tile * 16 + r];
+            zeros[n * G + g] = (uint8_t)((zeros_p[tile * 8 + r / 2] >> (4 * (r % 2))) & 0xf);
+        }
+    }
+    return 0;
+}
+
 /* ---------- a6/a7: y[m,n] = sum_k x[m,k] * Wdq[n,k] ----------
  * x [M,K] binary16; Wdq [N,K] binary32; y [M,N] binary64.
  * acc32 != 0 switches to sequential binary32 accumulation (reported variant). */
