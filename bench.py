@@ -183,6 +183,8 @@ def main():
                 for call in plan(mode, starts[i % len(starts)], M, span):
                     call()
 
+        for i in range(len(starts)):       # set-up: every layer's weights touched once (page tables)
+            one(i)
         for i in range(warmup):
             one(i)
         torch.cuda.synchronize()
@@ -289,6 +291,51 @@ def main():
             b = step_bytes(M)
             extras[f"decode_m{M}_grouped"] = {"ms_per_step": round(w, 5), "GB/s": gbs(b, w),
                                               "pct_of_hbm_peak": round(100 * gbs(b, w) / HBM_PEAK_GBS, 2)}
+        # INT3-g128 variant: the seven projections of a layer as seven launches of its decode
+        # kernel, M = 1 (0.39453125 B per weight), L distinct layers cycled
+        lay3 = []
+        for l in range(min(L, 8)):
+            packed = []
+            for name, N, K in shapes:
+                W = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
+                     * workloads.SIGMA_7B).to(torch.float16)
+                packed.append(awq.awq_quantize_pack_w3(W, s_by_k[K]))
+                del W
+            lay3.append(packed)
+        ys3 = [torch.empty((1, N), dtype=torch.float16, device=dev) for _, N, K in shapes]
+        def step3(l):
+            for p, (name, N, K) in enumerate(shapes):
+                awq.awq_w3a16_linear(x_by_k[K][:1], *lay3[l][p], N, out=ys3[p])
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step3(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graphs3 = []
+        for l in range(len(lay3)):                      # replayed from graphs like the INT4 single launches
+            g3 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g3):
+                step3(l)
+            graphs3.append(g3)
+        for i in range(8):
+            graphs3[i % len(graphs3)].replay()
+        torch.cuda.synchronize()
+        reps = 100
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            graphs3[i % len(graphs3)].replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        b3 = sum(sum(awq.awq_packed_sizes_w3(N, K)) + 2 * K + 2 * N for _, N, K in shapes)
+        extras["decode_m1_int3_7_single_launches"] = {
+            "bytes_per_step": b3, "ms_per_step": round(ms, 5), "GB/s": gbs(b3, ms),
+            "pct_of_hbm_peak": round(100 * gbs(b3, ms) / HBM_PEAK_GBS, 2),
+            "note": "compare decode_m1_7_single_launches (INT4): same launches, 0.76 of the bytes"}
+        del graphs3, lay3
+
         # configs[3]: the seven projections of a Llama-2-70B-shaped layer (444.5 MB per launch), M = 1
         # and 8, one grouped launch per step, two distinct layers cycled
         shapes70 = workloads.LLAMA2_70B_LAYER

@@ -154,6 +154,30 @@ typedef struct awq_linear_desc {
 int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- INT3-g128 variant (Sec. 5: INT4/INT3 with group size 128) ----------------------------
+ * The 8-level form of the quantizer (15 -> 7 in the formulas of awq_quantize_pack) and its own
+ * packed layout, version 1:
+ *   qweight : N*K*3/8 bytes; tiles of 16 rows x 128 columns (768 B), tile index as above.  A
+ *             tile is 64 slots of 12 B = three little-endian 32-bit words; slot (n%16) + 16*c
+ *             holds the 32 codes of columns 32*j + 8*c + e (j = 0..3, e = 0..7).  Code
+ *             i = 8*j + e is member h = i%2 of pair p = i/2; pairs 0..14 sit in word p/5 at bits
+ *             [3f, 3f+3), f = p%5, of the low (h = 0) or high (h = 1) 16-bit half; bit b of a
+ *             code of pair 15 is bit 15 (h = 0) or bit 31 (h = 1) of word b.
+ *   scales, zeros : as in the 4-bit layout (zero points 0..7 in nibbles).
+ * Arguments, ownership and errors as for the 4-bit calls of the same name. */
+int awq_packed_sizes_w3(int64_t N, int64_t K, int group, size_t *qweight_bytes,
+                        size_t *scales_bytes, size_t *zeros_bytes);
+int awq_quantize_pack_w3(const void *W_f16, const float *s, int64_t N, int64_t K, int group,
+                         void *qweight, void *scales, void *zeros, void *stream);
+int awq_unpack_w3(const void *qweight, const void *scales, const void *zeros, int64_t N,
+                  int64_t K, int group, uint8_t *codes, void *scales_f16, uint8_t *zeros_u8,
+                  void *stream);
+/* Sec. 4.2 decode kernel for the 3-bit layout: y = x' * dequant(q)^T, fp32 accumulation,
+ * 1 <= M <= 16 (AWQ_ERR_BAD_SHAPE otherwise: there is no 3-bit prefill kernel). */
+int awq_w3a16_linear(const void *x_f16, const void *qweight, const void *scales,
+                     const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K, int group,
+                     void *stream);
+
 #define AWQ_SEARCH_MAX_ALPHAS 64
 
 /* Bytes of scratch awq_search_scale needs (0 for an invalid shape): the packed candidate,

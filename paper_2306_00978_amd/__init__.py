@@ -11,6 +11,7 @@ Function names and argument order mirror the C ABI:
     awq_w4a16_linear, awq_w4a16_linear_multi      (Sec. 4.2 fused dequantization, kernel fusion)
     awq_search_scale                              (Sec. 3.2 searching to scale, Eq. 4-5)
     awq_quantize_pack_clip                        (Sec. 3.2 weight clipping)
+    awq_*_w3                                      (Sec. 5, INT3-g128 variant: quantize, unpack, decode)
 """
 from __future__ import annotations
 
@@ -28,6 +29,7 @@ EXPORTS = [
     "awq_apply_inv_scale", "awq_quantize_pack", "awq_unpack", "awq_linear_workspace_bytes",
     "awq_w4a16_linear", "awq_w4a16_linear_multi",
     "awq_search_scale_workspace_bytes", "awq_search_scale", "awq_quantize_pack_clip",
+    "awq_packed_sizes_w3", "awq_quantize_pack_w3", "awq_unpack_w3", "awq_w3a16_linear",
 ]
 MULTI_MAX = 56
 
@@ -82,6 +84,14 @@ def load() -> ctypes.CDLL:
     lib.awq_quantize_pack_clip.restype = i32
     lib.awq_quantize_pack_clip.argtypes = [vp, vp, i64, i64, i32, ctypes.POINTER(ctypes.c_float), i32,
                                            vp, i64, vp, vp, vp, vp, vp]
+    lib.awq_packed_sizes_w3.restype = i32
+    lib.awq_packed_sizes_w3.argtypes = [i64, i64, i32, szp, szp, szp]
+    lib.awq_quantize_pack_w3.restype = i32
+    lib.awq_quantize_pack_w3.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.awq_unpack_w3.restype = i32
+    lib.awq_unpack_w3.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.awq_w3a16_linear.restype = i32
+    lib.awq_w3a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
     lib.awq_search_scale_workspace_bytes.restype = sz
     lib.awq_search_scale_workspace_bytes.argtypes = [i64, i64, i64, i32, i32]
     lib.awq_search_scale.restype = i32
@@ -348,3 +358,57 @@ def awq_quantize_pack_clip(W: torch.Tensor, s: torch.Tensor | None, ratios, grou
                                          _stream()),
            "awq_quantize_pack_clip")
     return (qweight, scales, zeros, choice) if want_choice else (qweight, scales, zeros)
+
+
+# ---------------------------------------------------------------- INT3-g128 variant
+
+def awq_packed_sizes_w3(N: int, K: int, group: int = GROUP):
+    q, s, z = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load().awq_packed_sizes_w3(N, K, group, ctypes.byref(q), ctypes.byref(s), ctypes.byref(z)),
+           "awq_packed_sizes_w3")
+    return q.value, s.value, z.value
+
+
+def awq_quantize_pack_w3(W: torch.Tensor, s: torch.Tensor | None = None, group: int = GROUP, out=None):
+    """W [N,K] fp16, s [K] fp32 or None -> (qweight u8[N*K*3/8], scales f16, zeros u8), 3-bit layout."""
+    _dev(W, torch.float16, "W")
+    N, K = W.shape
+    if s is not None:
+        _dev(s, torch.float32, "s")
+        if s.numel() != K:
+            raise ValueError("s must have K elements")
+    qb, sb, zb = awq_packed_sizes_w3(N, K, group)
+    if out is None:
+        out = (torch.empty(qb, dtype=torch.uint8, device=W.device),
+               torch.empty(sb // 2, dtype=torch.float16, device=W.device),
+               torch.empty(zb, dtype=torch.uint8, device=W.device))
+    qweight, scales, zeros = out
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * 2 < sb \
+            or zeros.numel() * zeros.element_size() < zb:
+        raise ValueError("output buffers are too small")
+    _check(load().awq_quantize_pack_w3(_ptr(W), _ptr(s), N, K, group, _ptr(qweight), _ptr(scales),
+                                       _ptr(zeros), _stream()), "awq_quantize_pack_w3")
+    return qweight, scales, zeros
+
+
+def awq_unpack_w3(qweight, scales, zeros, N: int, K: int, group: int = GROUP):
+    """Canonical arrays of the 3-bit layout: codes u8[N,K], scales f16[N,K/128], zeros u8[N,K/128]."""
+    dev = qweight.device
+    codes = torch.empty((N, K), dtype=torch.uint8, device=dev)
+    sc = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+    zp = torch.empty((N, K // group), dtype=torch.uint8, device=dev)
+    _check(load().awq_unpack_w3(_ptr(qweight), _ptr(scales), _ptr(zeros), N, K, group, _ptr(codes),
+                                _ptr(sc), _ptr(zp), _stream()), "awq_unpack_w3")
+    return codes, sc, zp
+
+
+def awq_w3a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int = GROUP, out=None):
+    """y [M,N] fp16 = x [M,K] fp16 (already divided by s) times the 3-bit packed weight; M <= 16."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _dev(out, torch.float16, "y")
+    _check(load().awq_w3a16_linear(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(out), M, N, K,
+                                   group, _stream()), "awq_w3a16_linear")
+    return out

@@ -69,23 +69,47 @@ __device__ __forceinline__ half8_t biased_halves(uint32_t w, const ExpandConsts 
 // whole batch: lane (r, c) fetches those of row r of group base + min(c, U-1), turns them
 // into the three per-tile constants, and tile u later takes them from lane r + 16u with
 // cross-lane permutes.
-template <int U>
+// BITS = 4: a tile is 64 slots of 16 bytes; BITS = 3 (the INT3-g128 variant of Sec. 5): 64 slots
+// of 12 bytes, three words per lane.
+template <int BITS, int U>
 struct TileBatch {
-    uint4 q[U];
+    uint32_t q[U][BITS];
     uint32_t s_raw, z_raw;
 };
 
-template <int U>
-__device__ __forceinline__ void load_batch(TileBatch<U> &b, const uint4 *qt, const uint16_t *sc,
+template <int BITS, int U>
+__device__ __forceinline__ void load_batch(TileBatch<BITS, U> &b, const uint32_t *qt, const uint16_t *sc,
                                            const uint8_t *zp, int base)
 {
     // the two small loads go first: loads return in order, and the first tile can only be
     // consumed once its step and zero point are there
     b.s_raw = sc[base * 16];
     b.z_raw = zp[base * 8];
-    const uint4 *p = qt + base * 64;
+    const uint32_t *p = qt + base * (64 * BITS);          // qt already points at this lane's slot
 #pragma unroll
-    for (int u = 0; u < U; ++u) b.q[u] = p[u * 64];
+    for (int u = 0; u < U; ++u) {
+        if (BITS == 4) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(p + u * 256);
+            b.q[u][0] = v.x; b.q[u][1] = v.y; b.q[u][2] = v.z; b.q[u][BITS - 1] = v.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < BITS; ++i) b.q[u][i] = p[u * 192 + i];
+        }
+    }
+}
+
+// INT3 slot: pair p = 0..14 of the 16 code pairs sits in word p/5 at bits [3f, 3f+3), f = p%5,
+// of both halves; pair 15 in the top bits of the six halves.  (word >> 3f) & 0x00070007 is the
+// pair as two fp16 subnormals q * 2^-24, which the matrix core takes at full precision.
+__device__ __forceinline__ half8_t w3_halves(const uint32_t (&w)[3], uint32_t last_pair, int j)
+{
+    uint32_t t[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int p = 4 * j + i;
+        t[i] = p < 15 ? ((w[p / 5] >> (3 * (p % 5))) & 0x00070007u) : last_pair;
+    }
+    return __builtin_bit_cast(half8_t, make_uint4(t[0], t[1], t[2], t[3]));
 }
 
 constexpr int GEMV_STAGE_MAX_M = 4;   // activations of up to this many rows go through LDS
@@ -105,9 +129,9 @@ constexpr int GEMV_STAGE_MAX_M = 4;   // activations of up to this many rows go 
 // The workgroup has W = 2^logW waves; wave w owns batches [NB*w/W, NB*(w+1)/W), NB = G/U.
 // Dynamic LDS: [W][MS rows x (U*256 + 16) bytes], then 16*M outputs x 16 wave slots of
 // fp32 for the cross-wave reduction.
-template <int U, int MS, bool PIPE>
+template <int BITS, int U, int MS, bool PIPE>
 __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void gemv_kernel(
-    const half_t *__restrict__ x, const uint4 *__restrict__ qweight,
+    const half_t *__restrict__ x, const uint32_t *__restrict__ qweight,
     const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
     half_t *__restrict__ y, int M, int N, int K, int G, int logW)
 {
@@ -126,7 +150,7 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
 
     const int NB = G / U;
     const int g0 = ((NB * wave) >> logW) * U, g1 = ((NB * (wave + 1)) >> logW) * U;
-    const uint4 *qt = qweight + (int64_t)rb * G * 64 + lane;
+    const uint32_t *qt = qweight + ((int64_t)rb * G * 64 + lane) * BITS;
     const uint16_t *sc = scales + (int64_t)rb * G * 16 + cu * 16 + r;
     const uint8_t *zp = zeros + (int64_t)rb * G * 8 + cu * 8 + (r >> 1);
     const int zshift = (r & 1) * 4;
@@ -145,7 +169,7 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
     for (int m = 0; m < NS; ++m)
         xsrc[m] = reinterpret_cast<const uint4 *>(x + (int64_t)(m < M ? m : M - 1) * K) + lane;
 
-    TileBatch<U> cur;
+    TileBatch<BITS, U> cur;
     uint4 xs[NS];
 #pragma unroll
     for (int m = 0; m < NS; ++m) xs[m] = make_uint4(0, 0, 0, 0);
@@ -154,7 +178,7 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
 #pragma unroll
             for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][g0 * 16];
         }
-        load_batch<U>(cur, qt, sc, zp, g0);
+        load_batch<BITS, U>(cur, qt, sc, zp, g0);
     }
 
     floatx4 total = {0.f, 0.f, 0.f, 0.f};
@@ -164,14 +188,14 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
             for (int m = 0; m < NS; ++m) reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[lane] = xs[m];
         }
         // PIPE: the next batch is requested before this one is consumed
-        TileBatch<U> nxt;
+        TileBatch<BITS, U> nxt;
         const bool more = base + U < g1;
         if (PIPE && more) {
             if (stager) {
 #pragma unroll
                 for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][(base + U) * 16];
             }
-            load_batch<U>(nxt, qt, sc, zp, base + U);
+            load_batch<BITS, U>(nxt, qt, sc, zp, base + U);
         }
         // constants of (group base + cu, row r), computed once per batch by their owner lane
         const uint32_t z = (cur.z_raw >> zshift) & 0xFu;
@@ -190,18 +214,37 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
             const uint32_t nzA = __shfl(own_nzA, src);
             const uint32_t nzB = __shfl(own_nzB, src);
             const float sv = __shfl(own_sv, src);
-            const half8_t nb = __builtin_bit_cast(half8_t, make_uint4(nzA, nzB, nzA, nzB));
-            const uint32_t words[4] = {cur.q[u].x, cur.q[u].y, cur.q[u].z, cur.q[u].w};
-            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+            if (BITS == 4) {
+                const half8_t nb = __builtin_bit_cast(half8_t, make_uint4(nzA, nzB, nzA, nzB));
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const half8_t a = __builtin_bit_cast(half8_t, xa[j]);
-                const half8_t b = biased_halves(words[j], kc);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, nb, acc, 0, 0, 0);
+                for (int j = 0; j < 4; ++j) {
+                    const half8_t a = __builtin_bit_cast(half8_t, xa[j]);
+                    const half8_t b = biased_halves(cur.q[u][j & (BITS - 1)], kc);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, nb, acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) total[v] += sv * acc[v];
+            } else {
+                // codes as subnormals q * 2^-24; the zero point leaves in fp32 through
+                // S = 2^-24 * sum_k x_k (a second chain against the constant code 1)
+                const uint32_t w3[3] = {cur.q[u][0], cur.q[u][1], cur.q[u][2]};
+                const uint32_t last = ((w3[0] >> 15) & 0x00010001u) | ((w3[1] >> 14) & 0x00020002u) |
+                                      ((w3[2] >> 13) & 0x00040004u);
+                const half8_t ones = __builtin_bit_cast(half8_t, make_uint4(0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u));
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f}, xsum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const half8_t a = __builtin_bit_cast(half8_t, xa[j]);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, w3_halves(w3, last, j), acc, 0, 0, 0);
+                    xsum = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ones, xsum, 0, 0, 0);
+                }
+                const float zf = __shfl((float)z, src);
+                const float s24 = sv * 16777216.f;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) total[v] += s24 * (acc[v] - zf * xsum[v]);
             }
-#pragma unroll
-            for (int v = 0; v < 4; ++v) total[v] += sv * acc[v];
         }
         if (PIPE) {
             if (more) cur = nxt;
@@ -210,7 +253,7 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
 #pragma unroll
                 for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][(base + U) * 16];
             }
-            load_batch<U>(cur, qt, sc, zp, base + U);
+            load_batch<BITS, U>(cur, qt, sc, zp, base + U);
         }
     }
 
@@ -261,9 +304,11 @@ int pick_unroll(int G)
 
 }  // namespace
 
-// Host side of the decode path; arguments were validated by awq_w4a16_linear.
-int awq_gemv_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
-                    void *y, int M, int N, int K, hipStream_t stream)
+namespace {
+
+template <int BITS>
+int gemv_launch_bits(const void *x, const void *qweight, const void *scales, const void *zeros,
+                     void *y, int M, int N, int K, hipStream_t stream)
 {
     const int G = K / AWQ_GROUP;
     const int logW = pick_log_waves(G);
@@ -273,10 +318,11 @@ int awq_gemv_launch(const void *x, const void *qweight, const void *scales, cons
     const bool pipe = (G / U + W - 1) / W > 1;      // some wave has more than one batch
     const int MS = M > GEMV_STAGE_MAX_M ? 0 : (M == 1 ? 1 : (M == 2 ? 2 : 4));
     // reduction area: 16*M outputs x 16 wave slots x 4 bytes, after the staging areas
-    const size_t lds = (size_t)M * 1024 + (size_t)W * MS * (U * 256 + 16);
-#define AWQ_GEMV_ARGS (const half_t *)x, (const uint4 *)qweight, (const uint16_t *)scales, \
+    // (a lane parks four token rows at once: the area covers M rounded up to a multiple of 4)
+    const size_t lds = (size_t)((M + 3) / 4 * 4) * 1024 + (size_t)W * MS * (U * 256 + 16);
+#define AWQ_GEMV_ARGS (const half_t *)x, (const uint32_t *)qweight, (const uint16_t *)scales, \
                       (const uint8_t *)zeros, (half_t *)y, M, N, K, G, logW
-#define AWQ_GEMV_LAUNCH(UU, MM, PP) gemv_kernel<UU, MM, PP><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS)
+#define AWQ_GEMV_LAUNCH(UU, MM, PP) gemv_kernel<BITS, UU, MM, PP><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS)
 #define AWQ_GEMV_CASE(UU)                                                                   \
     case UU:                                                                                \
         if (pipe) {                                                                         \
@@ -301,4 +347,19 @@ int awq_gemv_launch(const void *x, const void *qweight, const void *scales, cons
 #undef AWQ_GEMV_LAUNCH
 #undef AWQ_GEMV_ARGS
     return awq_launch_status();
+}
+
+}  // namespace
+
+// Host side of the decode path; arguments were validated by awq_w4a16_linear / awq_w3a16_linear.
+int awq_gemv_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
+                    void *y, int M, int N, int K, hipStream_t stream)
+{
+    return gemv_launch_bits<4>(x, qweight, scales, zeros, y, M, N, K, stream);
+}
+
+int awq_gemv_launch_w3(const void *x, const void *qweight, const void *scales, const void *zeros,
+                       void *y, int M, int N, int K, hipStream_t stream)
+{
+    return gemv_launch_bits<3>(x, qweight, scales, zeros, y, M, N, K, stream);
 }

@@ -128,6 +128,21 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert c(Pq(ok), None, 16, 128, 128, rat, 3, Pq(ok), 65, Pq(ok), Pq(ok), Pq(ok), None, None) == -2
     assert c(Pq(ok), None, 16, 128, 128, rat, 3, Pq(odd), 8, Pq(ok), Pq(ok), Pq(ok), None, None) == -4
 
+    # INT3-g128 variant
+    q3, s3, z3 = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.awq_packed_sizes_w3(4096, 4096, 128, ctypes.byref(q3), ctypes.byref(s3), ctypes.byref(z3)) == 0
+    assert (q3.value, s3.value, z3.value) == (4096 * 4096 * 3 // 8, 4096 * 32 * 2, 4096 * 32 // 2)
+    assert (q3.value + s3.value + z3.value) * 256 == 4096 * 4096 * 101          # 0.39453125 B per weight
+    assert lib.awq_packed_sizes_w3(4096, 4000, 128, None, None, None) == -2
+    assert lib.awq_quantize_pack_w3(None, None, 16, 128, 128, Pq(ok), Pq(ok), Pq(ok), None) == -1
+    assert lib.awq_quantize_pack_w3(Pq(ok), None, 16, 128, 64, Pq(ok), Pq(ok), Pq(ok), None) == -3
+    assert lib.awq_quantize_pack_w3(Pq(odd), None, 16, 128, 128, Pq(ok), Pq(ok), Pq(ok), None) == -4
+    assert lib.awq_unpack_w3(Pq(ok), None, Pq(ok), 16, 128, 128, Pq(ok), Pq(ok), Pq(ok), None) == -1
+    assert lib.awq_w3a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), None, 1, 16, 128, 128, None) == -1
+    assert lib.awq_w3a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 17, 16, 128, 128, None) == -2
+    assert lib.awq_w3a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 0, 16, 128, 128, None) == -2
+    assert lib.awq_w3a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(odd), 1, 16, 128, 128, None) == -4
+
     g = lib.awq_search_scale
     wsb = lib.awq_search_scale_workspace_bytes
     al = (ctypes.c_float * 3)(0.0, 0.5, 1.0)

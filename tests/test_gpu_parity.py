@@ -718,6 +718,98 @@ def test_search_scale_rejects_bad_arguments(awq):
     assert awq.load().awq_search_scale_workspace_bytes(4, 16, 100, 1, 128) == 0
 
 
+# ------------------------------------------------------------------- INT3-g128 variant
+
+def quantize_w3_bit_exact(awq, W, s):
+    import torch
+    import oracle
+    N, K = W.shape
+    codes, scales, zeros = oracle.quantize_w3(W, s)
+    q_ref, s_ref, z_ref = oracle.pack_w3(codes, scales, zeros)
+    qb, sb, zb = awq.awq_packed_sizes_w3(N, K)
+    assert (qb, sb, zb) == oracle.packed_sizes_w3(N, K)
+    q_gpu, cq = guarded(qb, torch.uint8)
+    s_gpu, cs = guarded(sb, torch.float16)
+    z_gpu, cz = guarded(zb, torch.uint8)
+    awq.awq_quantize_pack_w3(dev(W), None if s is None else dev(s), out=(q_gpu, s_gpu, z_gpu))
+    cq(); cs(); cz()
+    assert np.array_equal(host(s_gpu).view(np.uint16), s_ref), "steps differ"
+    assert np.array_equal(host(z_gpu), z_ref), "zero points differ"
+    assert np.array_equal(host(q_gpu), q_ref), "packed codes differ"
+    c_u, s_u, z_u = awq.awq_unpack_w3(q_gpu, s_gpu, z_gpu, N, K)
+    assert np.array_equal(host(c_u), codes)
+    assert np.array_equal(host(s_u).view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(host(z_u), zeros)
+    return (codes, scales, zeros), (q_gpu, s_gpu, z_gpu)
+
+
+def check_linear_w3(awq, xs, Wdq, gpu_packed, N):
+    import torch
+    import oracle
+    M, K = xs.shape
+    y_gpu, cy = guarded(M * N * 2, torch.float16)
+    y_gpu = y_gpu.view(M, N)
+    awq.awq_w3a16_linear(dev(xs), *gpu_packed, N, out=y_gpu)
+    cy()
+    yh = host(y_gpu)
+    assert np.all(np.isfinite(yh.astype(np.float32)))
+    err = oracle.norm_error(yh, oracle.matmul(xs, Wdq), xs, Wdq)
+    assert err.max() <= TOL, f"max normalised error {err.max():.3e}"
+
+
+@pytest.mark.parametrize("N,K", [(16, 128), (48, 640), (176, 1408), (272, 256)])
+def test_w3_small_shapes_every_m(awq, N, K):
+    import oracle
+    case, s, xs = make_case(N, K, 16, 0.02, cfg=0, proj=13)
+    ref, gpu = quantize_w3_bit_exact(awq, case.W, s)
+    quantize_w3_bit_exact(awq, case.W, None)
+    Wdq = oracle.dequant(*ref)
+    for M in range(1, 17):
+        check_linear_w3(awq, xs[:M], Wdq, gpu, N)
+
+
+def test_w3_edge_groups_and_exactness_on_integer_data(awq):
+    import oracle
+    g = np.random.default_rng(71)
+    N, K = 64, 512
+    W = (g.standard_normal((N, K)) * 0.02).astype(np.float16)
+    W[0, :128] = 0
+    W[1, :128] = np.float16(0.37)
+    W[2, 128:256] = np.abs(W[2, 128:256])
+    W[3, 128:256] = -np.abs(W[3, 128:256])
+    W[4, 256:384] *= 1000
+    quantize_w3_bit_exact(awq, W, None)
+    quantize_w3_bit_exact(awq, W, (10.0 ** g.uniform(-3, 3, size=K)).astype(np.float32))
+    # small integers: every product and sum is exact, the kernel must reproduce the oracle
+    codes = g.integers(0, 8, size=(N, K), dtype=np.uint8)
+    scales = (2.0 ** g.integers(-3, 2, size=(N, K // 128))).astype(np.float16)
+    zeros = g.integers(0, 8, size=(N, K // 128), dtype=np.uint8)
+    q, sp, zp = oracle.pack_w3(codes, scales, zeros)
+    gpu = (dev(q), dev(sp.view(np.float16)), dev(zp))
+    Wdq = oracle.dequant(codes, scales, zeros)
+    for M in (1, 5, 16):
+        x = g.integers(-4, 5, size=(M, K)).astype(np.float16)
+        y_ref = oracle.matmul(x, Wdq)
+        y1 = host(awq.awq_w3a16_linear(dev(x), *gpu, N))
+        y2 = host(awq.awq_w3a16_linear(dev(x), *gpu, N))
+        assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+        assert np.array_equal(y1.astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
+
+
+@pytest.mark.parametrize("N,K", [(4096, 4096), (4096, 11008)])
+def test_w3_llama7b_shapes_full_size(awq, N, K):
+    import oracle
+    import torch
+    case, s, xs = make_case(N, K, 16, 0.02, cfg=1, proj=14)
+    ref, gpu = quantize_w3_bit_exact(awq, case.W, s)
+    Wdq = oracle.dequant(*ref)
+    for M in (1, 4, 16):
+        check_linear_w3(awq, xs[:M], Wdq, gpu, N)
+    with pytest.raises(awq.AwqError) as e:                   # no 3-bit prefill kernel
+        awq.awq_w3a16_linear(torch.zeros((17, K), dtype=torch.float16, device="cuda"), *gpu, N)
+    assert e.value.status == -2
+
+
 # ------------------------------------------------------------------- the pieces together
 
 def test_awq_for_one_linear_end_to_end(awq):
