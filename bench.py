@@ -330,6 +330,24 @@ def main():
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
         b3 = sum(sum(awq.awq_packed_sizes_w3(N, K)) + 2 * K + 2 * N for _, N, K in shapes)
+        calls3 = [awq.prepare_linear_multi_w3([(x_by_k[K][:1], *lay3[l][p], ys3[p], N)
+                                               for p, (_, N, K) in enumerate(shapes)]) for l in range(len(lay3))]
+        for i in range(2 * len(calls3)):
+            calls3[i % len(calls3)]()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            calls3[i % len(calls3)]()
+        e1.record()
+        torch.cuda.synchronize()
+        msg = e0.elapsed_time(e1) / args.steps
+        b3g = sum(sum(awq.awq_packed_sizes_w3(N, K)) + 2 * K + 2 * N for _, N, K in shapes)
+        extras["decode_m1_int3_grouped"] = {
+            "bytes_per_step": b3g, "ms_per_step": round(msg, 5), "GB/s": gbs(b3g, msg),
+            "pct_of_hbm_peak": round(100 * gbs(b3g, msg) / HBM_PEAK_GBS, 2),
+            "time_vs_int4_grouped": round(msg / ev_ms, 3),
+            "note": "one grouped launch of the 7 projections in the 3-bit layout (0.76 of the INT4 bytes)"}
         extras["decode_m1_int3_7_single_launches"] = {
             "bytes_per_step": b3, "ms_per_step": round(ms, 5), "GB/s": gbs(b3, ms),
             "pct_of_hbm_peak": round(100 * gbs(b3, ms) / HBM_PEAK_GBS, 2),

@@ -177,6 +177,9 @@ int awq_unpack_w3(const void *qweight, const void *scales, const void *zeros, in
 int awq_w3a16_linear(const void *x_f16, const void *qweight, const void *scales,
                      const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K, int group,
                      void *stream);
+/* As awq_w4a16_linear_multi for linears in the 3-bit layout (no workspace). */
+int awq_w3a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
+                           void *stream);
 
 #define AWQ_SEARCH_MAX_ALPHAS 64
 

@@ -30,6 +30,7 @@ EXPORTS = [
     "awq_w4a16_linear", "awq_w4a16_linear_multi",
     "awq_search_scale_workspace_bytes", "awq_search_scale", "awq_quantize_pack_clip",
     "awq_packed_sizes_w3", "awq_quantize_pack_w3", "awq_unpack_w3", "awq_w3a16_linear",
+    "awq_w3a16_linear_multi",
 ]
 MULTI_MAX = 56
 
@@ -92,6 +93,8 @@ def load() -> ctypes.CDLL:
     lib.awq_unpack_w3.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.awq_w3a16_linear.restype = i32
     lib.awq_w3a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
+    lib.awq_w3a16_linear_multi.restype = i32
+    lib.awq_w3a16_linear_multi.argtypes = [ctypes.POINTER(LinearDesc), i32, i64, i32, vp]
     lib.awq_search_scale_workspace_bytes.restype = sz
     lib.awq_search_scale_workspace_bytes.argtypes = [i64, i64, i64, i32, i32]
     lib.awq_search_scale.restype = i32
@@ -412,3 +415,39 @@ def awq_w3a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int
     _check(load().awq_w3a16_linear(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(out), M, N, K,
                                    group, _stream()), "awq_w3a16_linear")
     return out
+
+
+def prepare_linear_multi_w3(linears, group: int = GROUP):
+    """As prepare_linear_multi for linears in the 3-bit layout."""
+    if not 1 <= len(linears) <= MULTI_MAX:
+        raise ValueError(f"1..{MULTI_MAX} linears per grouped call")
+    descs = (LinearDesc * len(linears))()
+    M = None
+    for i, (x, qweight, scales, zeros, y, N) in enumerate(linears):
+        _dev(x, torch.float16, "x")
+        _dev(y, torch.float16, "y")
+        m, K = x.shape
+        if M is None:
+            M = m
+        if m != M:
+            raise ValueError("all linears of a grouped call share M")
+        qb, sb, zb = awq_packed_sizes_w3(N, K, group)
+        if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+                or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
+            raise ValueError("buffer sizes do not match the shape")
+        descs[i] = LinearDesc(x.data_ptr(), qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
+                              y.data_ptr(), N, K)
+    fn = load().awq_w3a16_linear_multi
+    count = len(linears)
+    keep = list(linears)
+
+    def call(_keep=keep):
+        st = fn(descs, count, M, group, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_w3a16_linear_multi")
+    return call
+
+
+def awq_w3a16_linear_multi(linears, group: int = GROUP):
+    prepare_linear_multi_w3(linears, group)()
+    return [l[4] for l in linears]

@@ -34,5 +34,7 @@ struct GemvLaunch {
 static_assert(sizeof(GemvLaunch) <= 4096, "kernel arguments are limited to 4 KB");
 
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream);
+// the same for linears in the 3-bit packed layout (q then points at 12-byte slots)
+int awq_gemv_stream_launch_w3(const GemvProblem *problems, int count, int M, hipStream_t stream);
 // whether a linear of this shape can be part of a grouped launch at this M
 bool awq_gemv_stream_fits(int N, int K, int M);

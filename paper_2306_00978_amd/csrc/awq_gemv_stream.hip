@@ -58,9 +58,14 @@ namespace {
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef const __attribute__((address_space(1))) void gbl_void_t;
 
-constexpr int STAGE_BYTES = 4480;        // 4 tiles, 256 B steps, 128 B zero points
-constexpr int STAGE_SC = 4096, STAGE_ZP = 4352;
-constexpr int LOADS_PER_JOB = 6;
+// Ring slot of one job: 4 tiles, 256 B of steps, 128 B of zero points.  BITS = 4: tiles of 1 KB;
+// BITS = 3 (INT3-g128 variant, Sec. 5): tiles of 768 B, the four of a batch are 3 KB contiguous
+// and arrive with three full-wave 16-byte loads.
+template <int BITS> struct Slot {
+    static constexpr int TILE = BITS == 4 ? 1024 : 768;
+    static constexpr int SC = 4 * TILE, ZP = SC + 256, BYTES = ZP + 128;
+    static constexpr int LOADS = (BITS == 4 ? 4 : 3) + 2;
+};
 
 // HBM -> LDS without a register in between.  Lane l's 16 bytes land at lds + OFF + 16 l (OFF is
 // added to the global address as well); 2- and 1-byte loads land zero-extended at lds + 4 l.
@@ -85,7 +90,7 @@ __device__ __forceinline__ void dma1_to_lds(const void *g, uint32_t lds_addr)
 // per lane and tile) and, for its row r, the four steps (fp16 bits) and the four zero-point
 // bytes (rows 2*(r/2) and 2*(r/2)+1 in the low and high nibble).
 struct Landed {
-    uint4 q[4];
+    uint4 q[4];          // BITS = 3: .x .y .z are the three words of the lane's slot
     uint4 s, z;
 };
 
@@ -93,6 +98,33 @@ template <int PENDING>
 __device__ __forceinline__ void wait_loads()
 {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
+}
+
+// BITS = 3: lane l's 12 bytes of tile u sit at 768 u + 12 l (4-byte aligned): three ds_read_b32
+__device__ __forceinline__ void read_slot_w3(Landed &d, uint32_t tile_addr, uint32_t sc_addr,
+                                             uint32_t zp_addr)
+{
+    asm volatile(
+        "ds_read_b128 %12, %15 offset:3072\n"
+        "ds_read_b128 %13, %16 offset:3328\n"
+        "ds_read_b32 %0, %14\n"
+        "ds_read_b32 %1, %14 offset:4\n"
+        "ds_read_b32 %2, %14 offset:8\n"
+        "ds_read_b32 %3, %14 offset:768\n"
+        "ds_read_b32 %4, %14 offset:772\n"
+        "ds_read_b32 %5, %14 offset:776\n"
+        "ds_read_b32 %6, %14 offset:1536\n"
+        "ds_read_b32 %7, %14 offset:1540\n"
+        "ds_read_b32 %8, %14 offset:1544\n"
+        "ds_read_b32 %9, %14 offset:2304\n"
+        "ds_read_b32 %10, %14 offset:2308\n"
+        "ds_read_b32 %11, %14 offset:2312\n"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(d.q[0].x), "=&v"(d.q[0].y), "=&v"(d.q[0].z), "=&v"(d.q[1].x), "=&v"(d.q[1].y), "=&v"(d.q[1].z),
+          "=&v"(d.q[2].x), "=&v"(d.q[2].y), "=&v"(d.q[2].z), "=&v"(d.q[3].x), "=&v"(d.q[3].y), "=&v"(d.q[3].z),
+          "=&v"(d.s), "=&v"(d.z)
+        : "v"(tile_addr), "v"(sc_addr), "v"(zp_addr)
+        : "memory");
 }
 
 __device__ __forceinline__ void read_slot(Landed &d, uint32_t tile_addr, uint32_t sc_addr,
@@ -153,9 +185,64 @@ __device__ __forceinline__ floatx4 consume_batch(const Landed &b, const uint4 (&
     return bacc;
 }
 
-template <int STAGES>
+// INT3: pair p = 4 j + i of a slot (MFMA step j, halves 2i, 2i+1) sits in word p/5 at field
+// f = p%5 (bits [3f, 3f+3) of both halves); pair 15 in the top bits of the six halves.  Fields 0..2
+// are taken where they are, fields 3, 4 after one shift by 9: the pair then reads as the fp16
+// subnormals q * 2^(3 cls - 24), cls = w3_cls(p), and the activation it meets carries 2^(-3 cls).
+__host__ __device__ constexpr int w3_cls(int p) { return p == 15 ? 0 : ((p % 5) % 3); }
+
+__device__ __forceinline__ half8_t w3_subnormal_halves(const uint32_t (&w)[3], const uint32_t (&w9)[3],
+                                                       uint32_t last_pair, int j)
+{
+    uint32_t t[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int p = 4 * j + i, f = p % 5;
+        const uint32_t mask = 0x00070007u << (3 * (f % 3));
+        t[i] = p == 15 ? last_pair : ((f < 3 ? w[p / 5] : w9[p / 5]) & mask);
+    }
+    return __builtin_bit_cast(half8_t, make_uint4(t[0], t[1], t[2], t[3]));
+}
+
+__device__ __forceinline__ floatx4 consume_batch_w3(const Landed &b, const uint4 (&xa)[16],
+                                                    const floatx4 (&xsum)[4], int zshift)
+{
+    floatx4 bacc = {0.f, 0.f, 0.f, 0.f};
+    const uint32_t sraw[4] = {b.s.x, b.s.y, b.s.z, b.s.w};
+    const uint32_t zraw[4] = {b.z.x, b.z.y, b.z.z, b.z.w};
+#pragma unroll
+    for (int u = 0; u < 4; u += 2) {
+        const uint32_t wa[3] = {b.q[u].x, b.q[u].y, b.q[u].z};
+        const uint32_t wb[3] = {b.q[u + 1].x, b.q[u + 1].y, b.q[u + 1].z};
+        const uint32_t wa9[3] = {wa[0] >> 9, wa[1] >> 9, wa[2] >> 9};
+        const uint32_t wb9[3] = {wb[0] >> 9, wb[1] >> 9, wb[2] >> 9};
+        const uint32_t la = ((wa[0] >> 15) & 0x00010001u) | ((wa[1] >> 14) & 0x00020002u) | ((wa[2] >> 13) & 0x00040004u);
+        const uint32_t lb = ((wb[0] >> 15) & 0x00010001u) | ((wb[1] >> 14) & 0x00020002u) | ((wb[2] >> 13) & 0x00040004u);
+        floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa[4 * u + j]),
+                                                          w3_subnormal_halves(wa, wa9, la, j), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa[4 * u + 4 + j]),
+                                                          w3_subnormal_halves(wb, wb9, lb, j), acc1, 0, 0, 0);
+        }
+        const float z0 = (float)((zraw[u] >> zshift) & 0xFu), z1 = (float)((zraw[u + 1] >> zshift) & 0xFu);
+        const float s0 = (float)__builtin_bit_cast(half_t, (uint16_t)sraw[u]) * 16777216.f;
+        const float s1 = (float)__builtin_bit_cast(half_t, (uint16_t)sraw[u + 1]) * 16777216.f;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            bacc[v] += s0 * (acc0[v] - z0 * xsum[u][v]);
+            bacc[v] += s1 * (acc1[v] - z1 * xsum[u + 1][v]);
+        }
+    }
+    return bacc;
+}
+
+template <int STAGES, int BITS>
 __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
 {
+    constexpr int STAGE_BYTES = Slot<BITS>::BYTES, STAGE_SC = Slot<BITS>::SC, STAGE_ZP = Slot<BITS>::ZP;
+    constexpr int TILE_BYTES = Slot<BITS>::TILE, LOADS_PER_JOB = Slot<BITS>::LOADS;
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t mask_lo = 0x000F000Fu, mask_hi = 0x00F000F0u;      // kept in SGPRs
     asm("" : "+s"(mask_lo));
@@ -207,19 +294,29 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
         rb = rb < NRB ? rb : NRB - 1;                       // surplus waves redo the last block
         const size_t t0 = (size_t)rb * G + (size_t)b * 4;   // first tile of the batch
         const uint32_t dst = ring + (uint32_t)slot * STAGE_BYTES;
-        const unsigned char *tq = qbase + (t0 << 10), *ts = scbase + t0 * 32, *tz = zpbase + t0 * 8;
+        const unsigned char *tq = qbase + t0 * TILE_BYTES, *ts = scbase + t0 * 32, *tz = zpbase + t0 * 8;
         if (!ragged || b * 4 + 4 <= G) {
             dma16_to_lds<0>(tq + lane16, dst);
             dma16_to_lds<1024>(tq + lane16, dst);
             dma16_to_lds<2048>(tq + lane16, dst);
-            dma16_to_lds<3072>(tq + lane16, dst);
+            if (BITS == 4) dma16_to_lds<3072>(tq + lane16, dst);
             dma2_to_lds(ts + sc_lane, dst + STAGE_SC);
             if (lane < 32) dma1_to_lds(tz + zp_lane, dst + STAGE_ZP);
         } else {
             const int last = G - 1 - b * 4;                 // last valid group of this batch (0..2)
+            if (BITS == 4) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                dma16_to_lds<0>(tq + ((size_t)min(u, last) << 10) + lane16, dst + u * 1024);
+                for (int u = 0; u < 4; ++u)
+                    dma16_to_lds<0>(tq + ((size_t)min(u, last) << 10) + lane16, dst + u * 1024);
+            } else {
+                // the same three loads; a 16-byte chunk that belongs to a tile beyond the last
+                // valid one re-reads that last tile instead (never past the end of the array)
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    const int ch = lane + 64 * i, tl = ch / 48, off = 16 * (ch - 48 * tl);
+                    dma16_to_lds<0>(tq + min(tl, last) * 768 + off, dst + i * 1024);
+                }
+            }
             const int gl = min(lane & 3, last);
             dma2_to_lds(ts + gl * 32 + (lane >> 2) * 2, dst + STAGE_SC);
             if (lane < 32) dma1_to_lds(tz + gl * 8 + ((lane >> 2) & 7), dst + STAGE_ZP);
@@ -263,13 +360,29 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
 
     // halves 2,3,6,7 of every fragment meet the 2^-20 codes and are scaled by 2^-4 to match the
     // 2^-24 ones
-    {
+    if (BITS == 4) {
         const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             xa[i].y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, xa[i].y) * sixteenth);
             xa[i].w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, xa[i].w) * sixteenth);
         }
+    } else {
+        // INT3: halves 2i, 2i+1 of step j meet the codes of pair 4j + i, which read as
+        // q * 2^(3 cls - 24): the activations carry 2^(-3 cls)
+        const half2_t down[3] = {{(half_t)1.0f, (half_t)1.0f}, {(half_t)0.125f, (half_t)0.125f},
+                                 {(half_t)0.015625f, (half_t)0.015625f}};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t *h = reinterpret_cast<uint32_t *>(&xa[4 * u + j]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int cls = w3_cls(4 * j + i);
+                    if (cls) h[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, h[i]) * down[cls]);
+                }
+            }
     }
     // 2^-24 * sum of the activations of each tile, per output row: the fragments against the
     // constant code 1 (halves 2^-24, 2^-24, 2^-20, 2^-20, ...)
@@ -280,8 +393,15 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
         for (int u = 0; u < 4; ++u) {
             floatx4 t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                t = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa[4 * u + j]), ones, t, 0, 0, 0);
+            for (int j = 0; j < 4; ++j) {
+                half8_t one_j = ones;
+                if (BITS == 3)   // the code 1 at the position of every pair of step j
+                    one_j = __builtin_bit_cast(half8_t, make_uint4(0x00010001u << (3 * w3_cls(4 * j)),
+                                                                   0x00010001u << (3 * w3_cls(4 * j + 1)),
+                                                                   0x00010001u << (3 * w3_cls(4 * j + 2)),
+                                                                   0x00010001u << (3 * w3_cls(4 * j + 3))));
+                t = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa[4 * u + j]), one_j, t, 0, 0, 0);
+            }
             xsum[u] = t;
         }
     }
@@ -291,7 +411,8 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
 #pragma unroll
     for (int v = 0; v < 4; ++v) slotv[v] = (4 * c + v) >> mlog;
 
-    const uint32_t rd_tile = ring + lane16, rd_sc = ring + 16 * r, rd_zp = ring + 16 * (r >> 1);
+    const uint32_t rd_tile = ring + (BITS == 4 ? lane16 : (uint32_t)lane * 12), rd_sc = ring + 16 * r,
+                   rd_zp = ring + 16 * (r >> 1);
     floatx4 total = {0.f, 0.f, 0.f, 0.f};
     int cit = 0, cb = b0, cslot = 0;                         // job being consumed
 
@@ -355,9 +476,11 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
         else wait_loads<0>();
         Landed cur;
         const uint32_t off = (uint32_t)cslot * STAGE_BYTES;
-        read_slot(cur, rd_tile + off, rd_sc + off, rd_zp + off);
+        if (BITS == 4) read_slot(cur, rd_tile + off, rd_sc + off, rd_zp + off);
+        else read_slot_w3(cur, rd_tile + off, rd_sc + off, rd_zp + off);
         if (++cslot == STAGES) cslot = 0;
-        const floatx4 bacc = consume_batch(cur, xa, xsum, mask_lo, mask_hi, zshift);
+        const floatx4 bacc = BITS == 4 ? consume_batch(cur, xa, xsum, mask_lo, mask_hi, zshift)
+                                       : consume_batch_w3(cur, xa, xsum, zshift);
         const int slot = cb - b0;
 #pragma unroll
         for (int v = 0; v < 4; ++v) total[v] += slotv[v] == slot ? bacc[v] : 0.f;
@@ -394,8 +517,12 @@ bool awq_gemv_stream_fits(int N, int K, int M)
     return ksl_min <= 3 && (1 << ksl_min) <= NBT;
 }
 
-int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream)
+namespace {
+
+template <int BITS>
+int stream_launch_bits(const GemvProblem *problems, int count, int M, hipStream_t stream)
 {
+    constexpr int STAGE_BYTES = Slot<BITS>::BYTES;
     static const int f_logw = env_int("AWQ_GEMV_LOGW", -1);
     static const int f_iters = env_int("AWQ_GEMV_ITERS", -1);
     static const int f_ksl = env_int("AWQ_GEMV_KSL", -1);
@@ -466,18 +593,29 @@ int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStr
     static bool attr_set = false;
     if (!attr_set) {
         const int cap = 160 * 1024;
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_stream_kernel<4>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_stream_kernel<3>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_stream_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
-            return AWQ_ERR_HIP;
+        const void *kernels[] = {reinterpret_cast<const void *>(gemv_stream_kernel<2, BITS>),
+                                 reinterpret_cast<const void *>(gemv_stream_kernel<3, BITS>),
+                                 reinterpret_cast<const void *>(gemv_stream_kernel<4, BITS>)};
+        for (const void *k : kernels)
+            if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
+                return AWQ_ERR_HIP;
         attr_set = true;
     }
     if (lds > (size_t)160 * 1024) return AWQ_GEMV_STREAM_UNFIT;
-    if (stages == 4) gemv_stream_kernel<4><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
-    else if (stages == 3) gemv_stream_kernel<3><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
-    else gemv_stream_kernel<2><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
+    if (stages == 4) gemv_stream_kernel<4, BITS><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
+    else if (stages == 3) gemv_stream_kernel<3, BITS><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
+    else gemv_stream_kernel<2, BITS><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
     return awq_launch_status();
+}
+
+}  // namespace
+
+int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream)
+{
+    return stream_launch_bits<4>(problems, count, M, stream);
+}
+
+int awq_gemv_stream_launch_w3(const GemvProblem *problems, int count, int M, hipStream_t stream)
+{
+    return stream_launch_bits<3>(problems, count, M, stream);
 }

@@ -19,6 +19,7 @@
 //
 // This file is compiled with -ffp-contract=off (integer decisions in the quantizer).
 #include "awq_common.h"
+#include "awq_gemv_stream.h"
 
 int awq_gemv_launch_w3(const void *x, const void *qweight, const void *scales, const void *zeros,
                        void *y, int M, int N, int K, hipStream_t stream);
@@ -228,4 +229,59 @@ extern "C" int awq_w3a16_linear(const void *x_f16, const void *qweight, const vo
         return AWQ_ERR_MISALIGNED;
     return awq_gemv_launch_w3(x_f16, qweight, scales, zeros, y_f16, (int)M, (int)N, (int)K,
                               (hipStream_t)stream);
+}
+
+// Sec. 4.2 kernel fusion for the 3-bit layout: as awq_w4a16_linear_multi.
+extern "C" int awq_w3a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
+                                      void *stream)
+{
+    if (!descs) return AWQ_ERR_NULL_POINTER;
+    if (count < 1 || count > AWQ_MULTI_MAX) return AWQ_ERR_BAD_ARGUMENT;
+    if (M <= 0 || M > 16) return AWQ_ERR_BAD_SHAPE;
+    GemvProblem p[GEMV_MAX_PROBLEMS] = {};
+    for (int i = 0; i < count; ++i) {
+        const awq_linear_desc &d = descs[i];
+        if (!d.x_f16 || !d.qweight || !d.scales || !d.zeros || !d.y_f16) return AWQ_ERR_NULL_POINTER;
+        int st = awq_check_weight_shape(d.N, d.K, group);
+        if (st != AWQ_OK) return st;
+        if (!awq_aligned16(d.x_f16) || !awq_aligned16(d.qweight) || !awq_aligned16(d.scales) ||
+            !awq_aligned16(d.zeros) || !awq_aligned16(d.y_f16))
+            return AWQ_ERR_MISALIGNED;
+        p[i].x = (const half_t *)d.x_f16;
+        p[i].q = (const uint4 *)d.qweight;
+        p[i].sc = (const uint16_t *)d.scales;
+        p[i].zp = (const uint8_t *)d.zeros;
+        p[i].y = (half_t *)d.y_f16;
+        p[i].N = (int)d.N;
+        p[i].K = (int)d.K;
+    }
+    GemvProblem fit[GEMV_MAX_PROBLEMS];
+    int nfit = 0;
+    bool grouped[GEMV_MAX_PROBLEMS] = {};
+    if (count > 1) {
+        for (int i = 0; i < count; ++i)
+            if (awq_gemv_stream_fits(p[i].N, p[i].K, (int)M)) {
+                fit[nfit++] = p[i];
+                grouped[i] = true;
+            }
+        if (nfit < 2) {
+            nfit = 0;
+            for (int i = 0; i < count; ++i) grouped[i] = false;
+        }
+    }
+    if (nfit > 0) {
+        int st = awq_gemv_stream_launch_w3(fit, nfit, (int)M, (hipStream_t)stream);
+        if (st == AWQ_GEMV_STREAM_UNFIT) {
+            for (int i = 0; i < count; ++i) grouped[i] = false;
+        } else if (st != AWQ_OK) {
+            return st;
+        }
+    }
+    for (int i = 0; i < count; ++i) {
+        if (grouped[i]) continue;
+        int st = awq_gemv_launch_w3(p[i].x, p[i].q, p[i].sc, p[i].zp, p[i].y, (int)M, p[i].N, p[i].K,
+                                    (hipStream_t)stream);
+        if (st != AWQ_OK) return st;
+    }
+    return AWQ_OK;
 }

@@ -810,6 +810,72 @@ def test_w3_llama7b_shapes_full_size(awq, N, K):
     assert e.value.status == -2
 
 
+def check_multi_w3(awq, problems, M):
+    import torch
+    import oracle
+    linears, checks, outs = [], [], []
+    for xs, Wdq, gpu_packed, N in problems:
+        y, cy = guarded(M * N * 2, torch.float16)
+        y = y.view(M, N)
+        linears.append((dev(xs[:M]), *gpu_packed, y, N))
+        checks.append(cy)
+        outs.append(y)
+    awq.awq_w3a16_linear_multi(linears)
+    for (xs, Wdq, gpu_packed, N), y, cy in zip(problems, outs, checks):
+        cy()
+        yh = host(y)
+        assert np.all(np.isfinite(yh.astype(np.float32)))
+        err = oracle.norm_error(yh, oracle.matmul(xs[:M], Wdq), xs[:M], Wdq)
+        assert err.max() <= TOL, f"max normalised error {err.max():.3e} (N={N}, M={M})"
+
+
+def test_w3_grouped_small_every_m_and_integer_exactness(awq):
+    """Ragged group counts (11 groups: the last batch of a row block has three tiles), K split
+    over several waves at larger M, a linear that does not fit and falls back."""
+    import torch
+    import oracle
+    probs = []
+    for i, (N, K) in enumerate([(176, 1408), (64, 1408), (48, 2048), (320, 512), (32, 128)]):
+        case, s, xs = make_case(N, K, 16, 0.02, cfg=0, proj=15 + i)
+        ref, gpu = quantize_w3_bit_exact(awq, case.W, s)
+        probs.append((xs, oracle.dequant(*ref), gpu, N))
+    for M in range(1, 17):
+        check_multi_w3(awq, probs, M)
+    check_multi_w3(awq, probs[:1], 3)
+    check_multi_w3(awq, (probs[:4] * 14), 2)                  # 56 entries
+    g = np.random.default_rng(72)
+    ints = []
+    for N, K in [(64, 512), (32, 1408), (96, 2048)]:
+        codes = g.integers(0, 8, size=(N, K), dtype=np.uint8)
+        scales = (2.0 ** g.integers(-3, 2, size=(N, K // 128))).astype(np.float16)
+        zeros = g.integers(0, 8, size=(N, K // 128), dtype=np.uint8)
+        q, sp, zp = oracle.pack_w3(codes, scales, zeros)
+        ints.append((N, K, (dev(q), dev(sp.view(np.float16)), dev(zp)), oracle.dequant(codes, scales, zeros)))
+    for M in (1, 2, 5, 16):
+        linears, refs = [], []
+        for N, K, gpu, Wdq in ints:
+            x = g.integers(-4, 5, size=(M, K)).astype(np.float16)
+            linears.append((dev(x), *gpu, torch.empty((M, N), dtype=torch.float16, device="cuda"), N))
+            refs.append(oracle.matmul(x, Wdq))
+        first = [host(y).copy() for y in awq.awq_w3a16_linear_multi(linears)]
+        second = [host(y).copy() for y in awq.awq_w3a16_linear_multi(linears)]
+        for y1, y2, y_ref in zip(first, second, refs):
+            assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+            assert np.array_equal(y1.astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
+
+
+def test_w3_grouped_llama7b_layer_full_size(awq):
+    import oracle
+    probs = []
+    for i, (N, K) in enumerate([(4096, 4096), (11008, 4096), (4096, 11008)]):
+        case, s, xs = make_case(N, K, 16, 0.02, cfg=1, proj=20 + i)
+        ref, gpu = quantize_w3_bit_exact(awq, case.W, s)
+        probs.append((xs, oracle.dequant(*ref), gpu, N))
+    layer = [probs[0]] * 4 + [probs[1]] * 2 + [probs[2]]
+    for M in (1, 4, 16):
+        check_multi_w3(awq, layer, M)
+
+
 # ------------------------------------------------------------------- the pieces together
 
 def test_awq_for_one_linear_end_to_end(awq):
