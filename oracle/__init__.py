@@ -98,6 +98,24 @@ def apply_inv_scale(x, s) -> np.ndarray:
     return out.view(np.float16)
 
 
+def rmsnorm_inv_scale(x, gamma, s=None, eps: float = 1e-5) -> np.ndarray:
+    """Sec. 4.2 kernel fusion + Sec. 3.2 Eq. 4: RMS normalisation with the 1/s factor folded in,
+    x' = fp16(x / sqrt(mean x^2 + eps) * gamma / s), fp64 inside."""
+    xb = _as_f16_bits(x)
+    M, K = xb.shape
+    gb = _as_f16_bits(gamma)
+    assert gb.shape == (K,)
+    sp = None
+    if s is not None:
+        s = np.ascontiguousarray(s, dtype=np.float32)
+        assert s.shape == (K,)
+        sp = _p(s)
+    out = np.empty((M, K), dtype=np.uint16)
+    _chk(_load().awq_oracle_rmsnorm_inv_scale(_p(xb), _p(gb), sp, _i64(M), _i64(K),
+                                              ctypes.c_double(eps), _p(out)), "rmsnorm_inv_scale")
+    return out.view(np.float16)
+
+
 def quantize(W, s=None, group: int = GROUP):
     """Sec. 3.2, Eq. 1-2: Q(w*s) per group of 128 input channels (asymmetric
     16-level min/max form).  Returns codes[N,K] u8, scales[N,G] f16, zeros[N,G] u8."""

@@ -132,6 +132,33 @@ int awq_oracle_apply_inv_scale(const uint16_t *x, const float *s, int64_t M,
  * codes  [N,K] one code per byte, 0..15
  * scales [N,G] binary16 bits, G = K/128
  * zeros  [N,G] one zero point per byte, 0..15                                   */
+/* ---------- normalisation fused with the inverse scale (Sec. 4.2 "Kernel fusion": all
+ * operators of the layer normalisation in one kernel; Sec. 3.2: the diag(s)^-1 factor of Eq. 4
+ * "can usually be fused into the previous operator").  RMS form, as the Llama-2-shaped layers
+ * of the workloads use it:
+ *   xs[m,k] = fp16( x[m,k] / sqrt(mean_k x[m,k]^2 + eps) * gamma[k] / s[k] ),  binary64 inside.
+ * gamma [K] binary16; s [K] binary32 or NULL (= ones).                                  */
+int awq_oracle_rmsnorm_inv_scale(const uint16_t *x, const uint16_t *gamma, const float *s,
+                                 int64_t M, int64_t K, double eps, uint16_t *xs)
+{
+    if (!x || !gamma || !xs || M <= 0 || K <= 0) return -1;
+    for (int64_t m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double v = (double)awq_oracle_f16_to_f32(x[m * K + k]);
+            ss += v * v;
+        }
+        double inv = 1.0 / sqrt(ss / (double)K + eps);
+        for (int64_t k = 0; k < K; ++k) {
+            double v = (double)awq_oracle_f16_to_f32(x[m * K + k]) * inv *
+                       (double)awq_oracle_f16_to_f32(gamma[k]);
+            if (s) v = v / (double)s[k];
+            xs[m * K + k] = awq_oracle_f32_to_f16((float)v);
+        }
+    }
+    return 0;
+}
+
 static float clampf(float v, float lo, float hi)
 {
     if (v < lo) return lo;
