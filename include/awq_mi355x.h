@@ -74,6 +74,14 @@ int awq_act_scale(const void *X_f16, int64_t T, int64_t K, float alpha, float *s
 int awq_apply_inv_scale(const void *x_f16, const float *s, int64_t M, int64_t K,
                         void *xs_f16, void *stream);
 
+/* Sec. 4.2 (kernel fusion: the operators of the normalisation in one kernel) with the 1/s factor
+ * of Eq. 4 folded in, as Sec. 3.2 suggests ("fused into the previous operator"): RMS form,
+ *   xs[m,k] = fp16( x[m,k] / sqrt(mean_k x[m,k]^2 + eps) * gamma[k] / s[k] ),  fp32 inside.
+ * x, xs [M,K] fp16 (device; xs may alias x), gamma [K] fp16 (device), s [K] fp32 (device) or
+ * NULL (= ones), eps >= 0.  K % 8 == 0.  The result feeds awq_w4a16_linear directly. */
+int awq_rmsnorm_inv_scale(const void *x_f16, const void *gamma_f16, const float *s, int64_t M,
+                          int64_t K, float eps, void *xs_f16, void *stream);
+
 /* Sec. 3.2, Eq. 1-2 and Sec. 4.2 (weight packing): quantize W*diag(s) per group of
  * 128 input channels and write the packed layout.
  *   w' = fp32(W)*s;  scale = fp16(clamp((max-min)/15, 2^-14, 65504));

@@ -7,6 +7,7 @@ library has not been built, importing a function from it raises.
 
 Function names and argument order mirror the C ABI:
     awq_act_scale, awq_apply_inv_scale            (AWQ Sec. 3.2, Eq. 4-5)
+    awq_rmsnorm_inv_scale                         (Sec. 4.2 fused normalisation with the 1/s of Eq. 4)
     awq_quantize_pack, awq_unpack                 (Sec. 3.2, Eq. 1-2; Sec. 4.2 packing)
     awq_w4a16_linear, awq_w4a16_linear_multi      (Sec. 4.2 fused dequantization, kernel fusion)
     awq_search_scale                              (Sec. 3.2 searching to scale, Eq. 4-5)
@@ -30,7 +31,7 @@ EXPORTS = [
     "awq_w4a16_linear", "awq_w4a16_linear_multi",
     "awq_search_scale_workspace_bytes", "awq_search_scale", "awq_quantize_pack_clip",
     "awq_packed_sizes_w3", "awq_quantize_pack_w3", "awq_unpack_w3", "awq_w3a16_linear",
-    "awq_w3a16_linear_multi",
+    "awq_w3a16_linear_multi", "awq_rmsnorm_inv_scale",
 ]
 MULTI_MAX = 56
 
@@ -93,6 +94,8 @@ def load() -> ctypes.CDLL:
     lib.awq_unpack_w3.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.awq_w3a16_linear.restype = i32
     lib.awq_w3a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
+    lib.awq_rmsnorm_inv_scale.restype = i32
+    lib.awq_rmsnorm_inv_scale.argtypes = [vp, vp, vp, i64, i64, ctypes.c_float, vp, vp]
     lib.awq_w3a16_linear_multi.restype = i32
     lib.awq_w3a16_linear_multi.argtypes = [ctypes.POINTER(LinearDesc), i32, i64, i32, vp]
     lib.awq_search_scale_workspace_bytes.restype = sz
@@ -451,3 +454,23 @@ def prepare_linear_multi_w3(linears, group: int = GROUP):
 def awq_w3a16_linear_multi(linears, group: int = GROUP):
     prepare_linear_multi_w3(linears, group)()
     return [l[4] for l in linears]
+
+
+def awq_rmsnorm_inv_scale(x: torch.Tensor, gamma: torch.Tensor, s: torch.Tensor | None = None,
+                          eps: float = 1e-5, out: torch.Tensor | None = None):
+    """x' = fp16(x / sqrt(mean x^2 + eps) * gamma / s); x [M,K] fp16, gamma [K] fp16, s [K] fp32 or None."""
+    _dev(x, torch.float16, "x")
+    _dev(gamma, torch.float16, "gamma")
+    M, K = x.shape
+    if gamma.numel() != K:
+        raise ValueError("gamma must have K elements")
+    if s is not None:
+        _dev(s, torch.float32, "s")
+        if s.numel() != K:
+            raise ValueError("s must have K elements")
+    if out is None:
+        out = torch.empty_like(x)
+    _dev(out, torch.float16, "out")
+    _check(load().awq_rmsnorm_inv_scale(_ptr(x), _ptr(gamma), _ptr(s), M, K, float(eps), _ptr(out),
+                                        _stream()), "awq_rmsnorm_inv_scale")
+    return out

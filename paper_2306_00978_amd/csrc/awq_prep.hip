@@ -74,7 +74,68 @@ __global__ __launch_bounds__(256) void apply_inv_scale_kernel(const uint4 *__res
     xs[i] = out;
 }
 
+// RMS normalisation with the 1/s factor of Eq. 4 folded in (Sec. 4.2: the operators of the
+// normalisation fused into a single kernel; Sec. 3.2: diag(s)^-1 X fused into the previous
+// operator).  One workgroup per row: sum of squares with 16-byte loads (the row is read a second
+// time from cache for the output), wave shuffles and one pass through LDS, then
+// x * rsqrt(mean + eps) * gamma / s in fp32, rounded once to fp16.
+__global__ __launch_bounds__(256) void rmsnorm_inv_scale_kernel(const uint4 *__restrict__ x,
+                                                                const uint4 *__restrict__ gamma,
+                                                                const float4 *__restrict__ s,
+                                                                int64_t K8, float inv_k, float eps,
+                                                                uint4 *__restrict__ xs)
+{
+    __shared__ float part[4];
+    const uint4 *row = x + (int64_t)blockIdx.x * K8;
+    float ss = 0.f;
+    for (int64_t i = threadIdx.x; i < K8; i += 256) {
+        const uint4 raw = row[i];
+        const half_t *h = reinterpret_cast<const half_t *>(&raw);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += (float)h[e] * (float)h[e];
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) ss += __shfl_xor(ss, d);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float total = (part[0] + part[1]) + (part[2] + part[3]);
+    const float inv = 1.0f / sqrtf(total * inv_k + eps);
+    uint4 *out = xs + (int64_t)blockIdx.x * K8;
+    for (int64_t i = threadIdx.x; i < K8; i += 256) {
+        const uint4 raw = row[i], graw = gamma[i];
+        const half_t *h = reinterpret_cast<const half_t *>(&raw);
+        const half_t *gm = reinterpret_cast<const half_t *>(&graw);
+        float sv[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+        if (s) {
+            const float4 a = s[2 * i], b = s[2 * i + 1];
+            sv[0] = a.x; sv[1] = a.y; sv[2] = a.z; sv[3] = a.w;
+            sv[4] = b.x; sv[5] = b.y; sv[6] = b.z; sv[7] = b.w;
+        }
+        uint4 o;
+        half_t *oh = reinterpret_cast<half_t *>(&o);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) oh[e] = (half_t)(((float)h[e] * inv) * (float)gm[e] / sv[e]);
+        out[i] = o;
+    }
+}
+
 }  // namespace
+
+extern "C" int awq_rmsnorm_inv_scale(const void *x_f16, const void *gamma_f16, const float *s,
+                                     int64_t M, int64_t K, float eps, void *xs_f16, void *stream)
+{
+    if (!x_f16 || !gamma_f16 || !xs_f16) return AWQ_ERR_NULL_POINTER;
+    if (M <= 0 || K <= 0 || (K % 8) != 0 || M > 0x7fffffff || K > (int64_t)1 << 30)
+        return AWQ_ERR_BAD_SHAPE;
+    if (!(eps >= 0.0f)) return AWQ_ERR_BAD_ARGUMENT;
+    if (!awq_aligned16(x_f16) || !awq_aligned16(gamma_f16) || !awq_aligned16(xs_f16) ||
+        (s && !awq_aligned16(s)))
+        return AWQ_ERR_MISALIGNED;
+    rmsnorm_inv_scale_kernel<<<dim3((unsigned)M), dim3(256), 0, (hipStream_t)stream>>>(
+        (const uint4 *)x_f16, (const uint4 *)gamma_f16, (const float4 *)s, K / 8, 1.0f / (float)K, eps,
+        (uint4 *)xs_f16);
+    return awq_launch_status();
+}
 
 extern "C" int awq_act_scale(const void *X_f16, int64_t T, int64_t K, float alpha, float *s,
                              void *stream)

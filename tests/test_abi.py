@@ -128,6 +128,16 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert c(Pq(ok), None, 16, 128, 128, rat, 3, Pq(ok), 65, Pq(ok), Pq(ok), Pq(ok), None, None) == -2
     assert c(Pq(ok), None, 16, 128, 128, rat, 3, Pq(odd), 8, Pq(ok), Pq(ok), Pq(ok), None, None) == -4
 
+    rn = lib.awq_rmsnorm_inv_scale
+    rn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                   ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
+    assert rn(None, ok, None, 1, 128, 1e-5, ok, None) == -1
+    assert rn(ok, ok, None, 0, 128, 1e-5, ok, None) == -2
+    assert rn(ok, ok, None, 1, 100, 1e-5, ok, None) == -2
+    assert rn(ok, ok, None, 1, 128, -1.0, ok, None) == -7
+    assert rn(ok, odd, None, 1, 128, 1e-5, ok, None) == -4
+    assert rn(ok, ok, odd, 1, 128, 1e-5, ok, None) == -4
+
     # INT3-g128 variant
     q3, s3, z3 = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
     assert lib.awq_packed_sizes_w3(4096, 4096, 128, ctypes.byref(q3), ctypes.byref(s3), ctypes.byref(z3)) == 0

@@ -928,6 +928,29 @@ def test_awq_for_one_linear_end_to_end(awq):
           f"+clip on calibration rows {e_awq_act:.0f}")
 
 
+@pytest.mark.parametrize("M,K", [(1, 4096), (16, 11008), (300, 1408), (3, 136), (2048, 4096)])
+def test_rmsnorm_with_folded_inverse_scale(awq, M, K):
+    """fp32 on the GPU against fp64 in the oracle, both rounded to fp16: at most one fp16 unit
+    apart (2^-10 relative), and the result is what the linear layer is fed."""
+    import oracle
+    import workloads
+    g = np.random.default_rng(90 + M)
+    out = workloads.outlier_channels(K, 0, 0, 6) if K >= 1000 else np.array([3])
+    x = workloads.activations(M, K, 0, 0, 6, workloads.ROLE_X, out)
+    gamma = g.uniform(0.5, 1.5, size=K).astype(np.float16)
+    s = g.uniform(0.5, 4.0, size=K).astype(np.float32)
+    for sv in (s, None):
+        ref = oracle.rmsnorm_inv_scale(x, gamma, sv, eps=1e-5).astype(np.float64)
+        got = host(awq.awq_rmsnorm_inv_scale(dev(x), dev(gamma), None if sv is None else dev(sv), 1e-5))
+        got = got.astype(np.float64)
+        assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -10 + 1e-7)
+        assert (got != ref).mean() < 0.02                      # roundings differ only rarely
+    xin = dev(x)                                               # in place
+    awq.awq_rmsnorm_inv_scale(xin, dev(gamma), dev(s), 1e-5, out=xin)
+    assert np.all(np.abs(host(xin).astype(np.float64) - oracle.rmsnorm_inv_scale(x, gamma, s).astype(np.float64))
+                  <= np.abs(oracle.rmsnorm_inv_scale(x, gamma, s).astype(np.float64)) * 2.0 ** -10 + 1e-7)
+
+
 def test_errors_surface_as_exceptions(awq):
     import torch
     W = torch.zeros((16, 100), dtype=torch.float16, device="cuda")
