@@ -91,8 +91,13 @@ def main():
     W0 = {}
     quant_bytes = 0
     quant_ms = 0.0
+    arena_bytes = sum((b + 255) // 256 * 256 for _, N, K in shapes for b in awq.awq_packed_sizes(N, K))
+    arenas = []
     for l in range(L):
         packed = []
+        arena = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)   # one buffer per layer
+        arenas.append(arena)
+        off = 0
         for p, (name, N, K) in enumerate(shapes):
             if l == 0:
                 Wh = workloads.weights(N, K, workloads.SIGMA_7B, 1, 0, p)
@@ -102,9 +107,11 @@ def main():
                 W = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
                      * workloads.SIGMA_7B).to(torch.float16)
             qb, sb, zb = awq.awq_packed_sizes(N, K)
-            out = (torch.empty(qb, dtype=torch.uint8, device=dev),
-                   torch.empty(sb // 2, dtype=torch.float16, device=dev),
-                   torch.empty(zb, dtype=torch.uint8, device=dev))
+            views = []
+            for nb_ in (qb, sb, zb):
+                views.append(arena[off:off + nb_])
+                off += (nb_ + 255) // 256 * 256
+            out = (views[0], views[1].view(torch.float16), views[2])
             if l == 0:
                 awq.awq_quantize_pack(W, s_by_k[K], out=out)       # warm-up of the kernel
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -155,6 +162,8 @@ def main():
     def step_bytes(M):
         return sum(workloads.algorithmic_bytes(M, N, K) for _, N, K in shapes)
 
+    last_spread = {}
+
     def time_decode(mode, M, steps, warmup, use_graph, span=1):
         """Returns (wall ms, event ms) per step of `span` layers.  Steps cycle through the L
         distinct layers so that the weights of a step were last touched L/span steps ago."""
@@ -188,21 +197,55 @@ def main():
         for i in range(warmup):
             one(i)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        # events around batches of steps as well: the spread of the per-step time
+        nbat = min(20, steps)
+        bounds = [steps * b // nbat for b in range(nbat + 1)]
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(nbat + 1)]
         t0 = time.perf_counter()
-        e0.record()
-        for i in range(steps):
-            one(warmup + i)
-        e1.record()
+        evs[0].record()
+        for b in range(nbat):
+            for i in range(bounds[b], bounds[b + 1]):
+                one(warmup + i)
+            evs[b + 1].record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
-        ev_ms = e0.elapsed_time(e1)
+        ev_ms = evs[0].elapsed_time(evs[-1])
+        per = sorted(evs[b].elapsed_time(evs[b + 1]) / (bounds[b + 1] - bounds[b]) for b in range(nbat))
+        last_spread.clear()
+        last_spread.update({"median": per[len(per) // 2], "p10": per[len(per) // 10],
+                            "p90": per[min(len(per) - 1, (9 * len(per)) // 10)]})
         return wall_ms / steps, ev_ms / steps
 
     use_graph = args.graph
     wall_ms, ev_ms = time_decode("grouped", 1, args.steps, args.warmup, use_graph)
+    spread = dict(last_spread)
     bytes_m1 = step_bytes(1)
     value = bytes_m1 / (wall_ms * 1e-3) / 1e9
+
+    # read-only reference on the same buffers: one streaming pass over a layer's packed arrays
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for i in range(L):
+        awq.awq_read_probe(arenas[i], sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps_probe = max(L, min(args.steps, 200))
+    e0.record()
+    for i in range(reps_probe):
+        awq.awq_read_probe(arenas[i % L], sink)
+    e1.record()
+    torch.cuda.synchronize()
+    probe_us = e0.elapsed_time(e1) / reps_probe * 1e3
+    probe_gbs = arena_bytes / (probe_us * 1e-6) / 1e9
+
+    def clocks():
+        import subprocess
+        try:
+            out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True,
+                                 timeout=20).stdout
+            card = next(iter(json.loads(out).values()))
+            return {k: v for k, v in card.items() if "sclk" in k.lower() or "mclk" in k.lower()}
+        except Exception as exc:          # the tool may be missing or not permitted: not an error
+            return {"unavailable": type(exc).__name__}
     launches = 1
     kernel_us = ev_ms * 1e3 / launches                     # average per launch, HIP events
     achieved = bytes_m1 / launches / (kernel_us * 1e-6) / 1e9
@@ -241,6 +284,12 @@ def main():
                       + (", replayed from a hipGraph" if use_graph else ", launched on the stream"),
             "bytes_per_step": bytes_m1,
             "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+            "ms_per_step_by_events": {k: round(v, 5) for k, v in spread.items()},
+            "read_only_reference": {"what": "awq_read_probe over one layer's packed arrays "
+                                            f"({arena_bytes} B), one launch per step, same cycling",
+                                    "us": round(probe_us, 3), "GB/s": round(probe_gbs, 1),
+                                    "value_over_reference": round(value / probe_gbs, 4)},
+            "clocks_after_run": clocks(),
         },
         "roofline": {
             "kernel": "gemv_stream_kernel (grouped decode, 7 linears, M=1)",

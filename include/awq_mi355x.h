@@ -57,6 +57,12 @@ int awq_version(void);
 /* Static, human-readable name of a status code (never NULL). */
 const char *awq_status_string(int status);
 
+/* Measurement aid, not part of the method: streams `bytes` (rounded down to a multiple of 16) of
+ * a device buffer with 128-bit loads and discards them -- the read bandwidth this machine
+ * reaches on a buffer of that size, against which the decode kernels are stated.  sink: device
+ * word, written only in a one-in-2^32 case. */
+int awq_read_probe(const void *buffer, size_t bytes, uint32_t *sink, void *stream);
+
 /* Bytes of the three packed arrays for an [N,K] weight.  Host pointers; any of
  * the three may be NULL. */
 int awq_packed_sizes(int64_t N, int64_t K, int group, size_t *qweight_bytes,

@@ -31,7 +31,7 @@ EXPORTS = [
     "awq_w4a16_linear", "awq_w4a16_linear_multi",
     "awq_search_scale_workspace_bytes", "awq_search_scale", "awq_quantize_pack_clip",
     "awq_packed_sizes_w3", "awq_quantize_pack_w3", "awq_unpack_w3", "awq_w3a16_linear",
-    "awq_w3a16_linear_multi", "awq_rmsnorm_inv_scale",
+    "awq_w3a16_linear_multi", "awq_rmsnorm_inv_scale", "awq_read_probe",
 ]
 MULTI_MAX = 56
 
@@ -94,6 +94,8 @@ def load() -> ctypes.CDLL:
     lib.awq_unpack_w3.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.awq_w3a16_linear.restype = i32
     lib.awq_w3a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
+    lib.awq_read_probe.restype = i32
+    lib.awq_read_probe.argtypes = [vp, sz, vp, vp]
     lib.awq_rmsnorm_inv_scale.restype = i32
     lib.awq_rmsnorm_inv_scale.argtypes = [vp, vp, vp, i64, i64, ctypes.c_float, vp, vp]
     lib.awq_w3a16_linear_multi.restype = i32
@@ -474,3 +476,9 @@ def awq_rmsnorm_inv_scale(x: torch.Tensor, gamma: torch.Tensor, s: torch.Tensor 
     _check(load().awq_rmsnorm_inv_scale(_ptr(x), _ptr(gamma), _ptr(s), M, K, float(eps), _ptr(out),
                                         _stream()), "awq_rmsnorm_inv_scale")
     return out
+
+
+def awq_read_probe(buffer: torch.Tensor, sink: torch.Tensor, nbytes: int | None = None):
+    """Read-only streaming pass over `buffer` (measurement aid of the benchmark)."""
+    n = buffer.numel() * buffer.element_size() if nbytes is None else nbytes
+    _check(load().awq_read_probe(_ptr(buffer), n, _ptr(sink), _stream()), "awq_read_probe")
