@@ -573,7 +573,29 @@ def cpu_baseline(W0, calib_by_k, x_by_k, shapes):
         t_total += time.perf_counter() - t0
         reps += 1
     omp = int(os.environ.get("OMP_NUM_THREADS", cores))
+    also = {}
+    try:
+        # quantize + pack of one 4096 x 4096 matrix (all cores), and one decode step on one thread
+        s0 = oracle.act_scale(calib_by_k[4096], 0.5).astype(np.float32)
+        t0 = time.perf_counter()
+        c, sc, z = oracle.quantize(W0[0], s0)
+        oracle.pack(c, sc, z)
+        tq = time.perf_counter() - t0
+        N0, K0 = shapes[0][1], shapes[0][2]
+        also["quantize_pack_4096x4096_GB/s"] = round((2 * N0 * K0 + N0 * K0 * 0.51953125) / tq / 1e9, 3)
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_set_num_threads(1)
+        t0 = time.perf_counter()
+        for p, (name, N, K) in enumerate(shapes):
+            c, sc, z = oracle.unpack(*packed[p], N, K)
+            oracle.matmul(xs[K], oracle.dequant(c, sc, z))
+        also["decode_step_one_thread_GB/s"] = round(bytes_step / (time.perf_counter() - t0) / 1e9, 3)
+        gomp.omp_set_num_threads(min(cores, omp))
+    except Exception as exc:
+        also["error"] = type(exc).__name__
     return {
+        "also": also,
         "value": round(bytes_step * reps / t_total / 1e9, 3),
         "unit": "GB/s",
         "cores": min(cores, omp),
