@@ -495,6 +495,26 @@ def test_config4_full_stack(awq):
     print(f"config 4: worst normalised error over steps {check_steps}: {worst:.3e}")
 
 
+@pytest.mark.parametrize("overrides", [
+    {"AWQ_GEMV_STAGES": "3"}, {"AWQ_GEMV_STAGES": "4"}, {"AWQ_GEMV_SLOTS": "200"},
+    {"AWQ_GEMV_SLOTS": "20000"}, {"AWQ_GEMV_KSL": "2"}, {"AWQ_GEMV_KSL": "3", "AWQ_GEMV_LOGW": "3"},
+    {"AWQ_GEMV_ITERS": "1"}, {"AWQ_GEMV_JOBS": "3", "AWQ_GEMV_STAGES": "3"},
+    {"AWQ_GEMV_WAVES": "2", "AWQ_GEMV_UNROLL": "1"}, {"AWQ_GEMV_WAVES": "16", "AWQ_GEMV_UNROLL": "2"},
+    {"AWQ_GEMV_STREAM_SINGLE": "1"},
+])
+def test_grouped_decode_under_planner_overrides(awq, overrides):
+    """The planner's constants can be overridden through the environment (read once per
+    process); every such plan must give the same results.  Runs the check in a child process."""
+    import os
+    import subprocess
+    import sys
+    env = dict(os.environ)
+    env.update(overrides)
+    child = os.path.join(os.path.dirname(os.path.abspath(__file__)), "child_grouped_decode.py")
+    res = subprocess.run([sys.executable, child], env=env, capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0 and res.stdout.strip().endswith("OK"), res.stdout[-2000:] + res.stderr[-2000:]
+
+
 # ----------------------------------------------------------------------------- a0 / a0'
 
 @pytest.mark.parametrize("T,K", [(64, 4096), (5, 136), (1000, 11008)])
