@@ -342,3 +342,48 @@ def unpack_w3(qweight, scales_p, zeros_p, N: int, K: int, group: int = GROUP):
                                       ctypes.c_int(group), _p(codes), _p(scales), _p(zeros)),
          "unpack_w3")
     return codes, scales.view(np.float16), zeros
+
+
+# ---------------------------------------------------------------- decode attention (Sec. 4.2 fusion)
+
+def rope_rotate(x, pos: int, theta: float = 10000.0) -> np.ndarray:
+    """Rotary position embedding of x [..., D] (fp64): the pairs (i, i + D/2) are rotated by the
+    angle pos * theta^(-2 i / D) (the half-split pairing of Llama-style models; the paper only
+    says the positional embedding is computed on the fly inside the attention kernel)."""
+    x = np.asarray(x, dtype=np.float64)
+    D = x.shape[-1]
+    i = np.arange(D // 2, dtype=np.float64)
+    ang = float(pos) * theta ** (-2.0 * i / D)
+    c, s_ = np.cos(ang), np.sin(ang)
+    a, b = x[..., : D // 2], x[..., D // 2:]
+    return np.concatenate([a * c - b * s_, b * c + a * s_], axis=-1)
+
+
+def decode_attention(q, k, v, k_cache, v_cache, pos: int, theta: float = 10000.0):
+    """Sec. 4.2 "Kernel fusion" (attention): one decode step of one sequence.  q [H,D], k, v
+    [Hkv,D] fp16 are the projections of the token at position pos; k_cache, v_cache
+    [Hkv,Lmax,D] fp16 hold the rotated keys and the values of positions < pos.  Rotates q and k,
+    stores fp16(k_rot) and v in row pos of the caches (returned as new arrays), and returns
+    out [H,D] fp16 = softmax(q_rot K^T / sqrt(D)) V over positions 0..pos, fp64 inside; query
+    head h reads kv head h // (H / Hkv).  The current token's key enters the scores unrounded
+    (it never left the chip), the cached ones as stored."""
+    q = np.asarray(q); k = np.asarray(k); v = np.asarray(v)
+    H, D = q.shape
+    Hkv = k.shape[0]
+    rep = H // Hkv
+    kc = np.array(k_cache, copy=True)
+    vc = np.array(v_cache, copy=True)
+    k_rot = rope_rotate(k.astype(np.float64), pos, theta)
+    q_rot = rope_rotate(q.astype(np.float64), pos, theta)
+    kc[:, pos, :] = k_rot.astype(np.float32).astype(np.float16)
+    vc[:, pos, :] = v
+    out = np.empty((H, D), dtype=np.float64)
+    for h in range(H):
+        g = h // rep
+        keys = kc[g, : pos + 1].astype(np.float64)
+        keys[pos] = k_rot[g]
+        vals = vc[g, : pos + 1].astype(np.float64)
+        sc = keys @ q_rot[h] / np.sqrt(D)
+        p = np.exp(sc - sc.max())
+        out[h] = (p / p.sum()) @ vals
+    return out.astype(np.float32).astype(np.float16), kc, vc
