@@ -514,6 +514,42 @@ def main():
             del Wd
         extras["quantize_pack_clip_on_64_rows"] = {"ratios": len(ratios), "matrices": 3, "ms_total": round(ams, 3)}
 
+        # decode attention with rotary embedding and cache update, Llama-2-7B heads, 2048 positions
+        Ha, Da, La = 32, 128, 2048
+        kcs = [torch.randn((Ha, La, Da), generator=gen, device=dev).to(torch.float16) for _ in range(8)]
+        vcs = [torch.randn((Ha, La, Da), generator=gen, device=dev).to(torch.float16) for _ in range(8)]
+        qa, ka, va = (torch.randn((Ha, Da), generator=gen, device=dev).to(torch.float16) for _ in range(3))
+        outa = torch.empty((Ha, Da), dtype=torch.float16, device=dev)
+        wsa = torch.empty(awq.load().awq_decode_attention_workspace_bytes(Ha, Da, La), dtype=torch.uint8, device=dev)
+        def att_pass():
+            for i in range(8):
+                awq.awq_decode_attention(qa, ka, va, kcs[i], vcs[i], La - 1, out=outa, workspace=wsa)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            att_pass()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        ga = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(ga):
+            att_pass()
+        ga.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(25):
+            ga.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        msa = e0.elapsed_time(e1) / 200
+        ba = 2 * Ha * La * Da * 2
+        extras["decode_attention_32_heads_2048_positions"] = {
+            "bytes_per_call": ba, "us": round(msa * 1e3, 2), "GB/s": gbs(ba, msa),
+            "pct_of_hbm_peak": round(100 * gbs(ba, msa) / HBM_PEAK_GBS, 2),
+            "note": "two launches (slices of the positions, merge) replayed from a graph; "
+                    "8 cache sets cycled (268 MB)"}
+        del ga, kcs, vcs
+
         # scale search (Eq. 4-5): 20 grid points on one 4096 x 4096 linear with 2048 cached rows
         name, N, K = shapes[0]
         out = workloads.outlier_channels(K, 1, 0, 0)

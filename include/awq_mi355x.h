@@ -195,6 +195,24 @@ int awq_w3a16_linear(const void *x_f16, const void *qweight, const void *scales,
 int awq_w3a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
                            void *stream);
 
+/* ---- decode attention (Sec. 4.2 "Kernel fusion": positional embedding computed on the fly,
+ * pre-allocated KV caches updated inside the attention kernel) --------------------------
+ * One decode step of one sequence.  q [H,D], k, v [Hkv,D] fp16: the projections of the token at
+ * position pos (0-based).  k_cache, v_cache [Hkv][Lmax][D] fp16, pre-allocated by the caller,
+ * rows < pos filled by earlier calls.  The call rotates q and k by the rotary embedding of pos
+ * (pairs (i, i + D/2), angle pos * rope_theta^(-2i/D)), writes fp16(k_rot) and v into row pos of
+ * the caches and out [H,D] fp16 = softmax(q_rot K^T / sqrt(D)) V over rows 0..pos; query head h
+ * reads kv head h / (H/Hkv).  fp32 arithmetic (fp64 for the angles).  D == 128, H % Hkv == 0,
+ * 0 <= pos < Lmax, rope_theta > 1.  workspace: device, 16-byte aligned,
+ * awq_decode_attention_workspace_bytes(H, D, pos + 1) bytes (partial results of the slices of
+ * the positions), contents undefined afterwards.  Calls for consecutive positions on one stream
+ * are ordered by the stream. */
+size_t awq_decode_attention_workspace_bytes(int64_t H, int64_t D, int64_t L);
+int awq_decode_attention(const void *q_f16, const void *k_f16, const void *v_f16, void *k_cache_f16,
+                         void *v_cache_f16, int64_t H, int64_t Hkv, int64_t D, int64_t Lmax,
+                         int64_t pos, float rope_theta, void *out_f16, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
 #define AWQ_SEARCH_MAX_ALPHAS 64
 
 /* Bytes of scratch awq_search_scale needs (0 for an invalid shape): the packed candidate,

@@ -12,6 +12,7 @@ Function names and argument order mirror the C ABI:
     awq_w4a16_linear, awq_w4a16_linear_multi      (Sec. 4.2 fused dequantization, kernel fusion)
     awq_search_scale                              (Sec. 3.2 searching to scale, Eq. 4-5)
     awq_quantize_pack_clip                        (Sec. 3.2 weight clipping)
+    awq_decode_attention                          (Sec. 4.2 fused attention: rotary embedding, cache update)
     awq_*_w3                                      (Sec. 5, INT3-g128 variant: quantize, unpack, decode)
 """
 from __future__ import annotations
@@ -32,6 +33,7 @@ EXPORTS = [
     "awq_search_scale_workspace_bytes", "awq_search_scale", "awq_quantize_pack_clip",
     "awq_packed_sizes_w3", "awq_quantize_pack_w3", "awq_unpack_w3", "awq_w3a16_linear",
     "awq_w3a16_linear_multi", "awq_rmsnorm_inv_scale", "awq_read_probe",
+    "awq_decode_attention_workspace_bytes", "awq_decode_attention",
 ]
 MULTI_MAX = 56
 
@@ -94,6 +96,11 @@ def load() -> ctypes.CDLL:
     lib.awq_unpack_w3.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.awq_w3a16_linear.restype = i32
     lib.awq_w3a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
+    lib.awq_decode_attention_workspace_bytes.restype = sz
+    lib.awq_decode_attention_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.awq_decode_attention.restype = i32
+    lib.awq_decode_attention.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ctypes.c_float,
+                                         vp, vp, sz, vp]
     lib.awq_read_probe.restype = i32
     lib.awq_read_probe.argtypes = [vp, sz, vp, vp]
     lib.awq_rmsnorm_inv_scale.restype = i32
@@ -482,3 +489,24 @@ def awq_read_probe(buffer: torch.Tensor, sink: torch.Tensor, nbytes: int | None 
     """Read-only streaming pass over `buffer` (measurement aid of the benchmark)."""
     n = buffer.numel() * buffer.element_size() if nbytes is None else nbytes
     _check(load().awq_read_probe(_ptr(buffer), n, _ptr(sink), _stream()), "awq_read_probe")
+
+
+def awq_decode_attention(q, k, v, k_cache, v_cache, pos: int, rope_theta: float = 10000.0,
+                         out=None, workspace=None):
+    """One decode step of the attention layer: q [H,D], k, v [Hkv,D] fp16 of the token at `pos`;
+    k_cache, v_cache [Hkv,Lmax,D] fp16 are updated in place; returns out [H,D] fp16."""
+    for t, name in ((q, "q"), (k, "k"), (v, "v"), (k_cache, "k_cache"), (v_cache, "v_cache")):
+        _dev(t, torch.float16, name)
+    H, D = q.shape
+    Hkv, Lmax, D2 = k_cache.shape
+    if k.shape != (Hkv, D) or v.shape != (Hkv, D) or v_cache.shape != k_cache.shape or D2 != D:
+        raise ValueError("shapes of q, k, v and the caches do not agree")
+    if out is None:
+        out = torch.empty((H, D), dtype=torch.float16, device=q.device)
+    need = load().awq_decode_attention_workspace_bytes(H, D, pos + 1)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(load().awq_decode_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(k_cache), _ptr(v_cache), H, Hkv, D,
+                                       Lmax, pos, float(rope_theta), _ptr(out), _ptr(workspace),
+                                       workspace.numel(), _stream()), "awq_decode_attention")
+    return out

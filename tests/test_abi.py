@@ -138,6 +138,22 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert rn(ok, odd, None, 1, 128, 1e-5, ok, None) == -4
     assert rn(ok, ok, odd, 1, 128, 1e-5, ok, None) == -4
 
+    at = lib.awq_decode_attention
+    wsa = lib.awq_decode_attention_workspace_bytes
+    assert wsa(32, 128, 2048) == 32 * 16 * 130 * 4 and wsa(32, 64, 10) == 0 and wsa(32, 128, 0) == 0
+    okp = ctypes.c_void_p(ok)
+    base = [okp, okp, okp, okp, okp, 32, 32, 128, 64, 5, 10000.0, okp, okp, 1 << 20, None]
+    def att(**kw):
+        a = list(base)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return at(*a)
+    assert att(_0=None) == -1 and att(_12=None) == -1
+    assert att(_7=64) == -2 and att(_6=5) == -2 and att(_9=64) == -2 and att(_9=-1) == -2
+    assert att(_10=1.0) == -7
+    assert att(_3=ctypes.c_void_p(odd)) == -4
+    assert att(_13=16) == -5
+
     # INT3-g128 variant
     q3, s3, z3 = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
     assert lib.awq_packed_sizes_w3(4096, 4096, 128, ctypes.byref(q3), ctypes.byref(s3), ctypes.byref(z3)) == 0

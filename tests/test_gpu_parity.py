@@ -971,6 +971,82 @@ def test_rmsnorm_with_folded_inverse_scale(awq, M, K):
                   <= np.abs(oracle.rmsnorm_inv_scale(x, gamma, s).astype(np.float64)) * 2.0 ** -10 + 1e-7)
 
 
+# ------------------------------------------------------------------- decode attention
+
+ATT_TOL = 2e-3      # of max|v|: fp16 rounding of the output (2^-11) and fp32 sums / exponentials
+
+
+@pytest.mark.parametrize("H,Hkv,pos,Lmax", [(32, 32, 0, 8), (32, 32, 5, 64), (8, 2, 63, 64), (32, 32, 256, 300),
+                                            (64, 8, 1000, 1024), (32, 32, 2047, 2048), (4, 1, 2048, 4096)])
+def test_decode_attention_against_the_oracle(awq, H, Hkv, pos, Lmax):
+    import torch
+    import oracle
+    g = np.random.default_rng(200 + pos)
+    D = 128
+    q = g.standard_normal((H, D)).astype(np.float16)
+    k = g.standard_normal((Hkv, D)).astype(np.float16)
+    v = g.standard_normal((Hkv, D)).astype(np.float16)
+    kc = np.zeros((Hkv, Lmax, D), np.float16)
+    vc = np.zeros((Hkv, Lmax, D), np.float16)
+    kc[:, :pos] = g.standard_normal((Hkv, pos, D)).astype(np.float16)
+    vc[:, :pos] = g.standard_normal((Hkv, pos, D)).astype(np.float16)
+    if pos > 10:
+        kc[:, 3] *= 3                                   # a few sharp scores as well
+    out_ref, kc_ref, vc_ref = oracle.decode_attention(q, k, v, kc, vc, pos)
+    kc_gpu, vc_gpu = dev(kc), dev(vc)
+    out_buf, check_out = guarded(H * D * 2, torch.float16)
+    out_gpu = awq.awq_decode_attention(dev(q), dev(k), dev(v), kc_gpu, vc_gpu, pos, out=out_buf.view(H, D))
+    check_out()
+    out = host(out_gpu).astype(np.float64)
+    assert np.all(np.isfinite(out))
+    scale = np.abs(vc_ref[:, : pos + 1].astype(np.float64)).max()
+    assert np.abs(out - out_ref.astype(np.float64)).max() <= ATT_TOL * scale
+    # the caches: the value row exactly, the rotated key within one fp16 unit, nothing else touched
+    kc_new, vc_new = host(kc_gpu), host(vc_gpu)
+    assert np.array_equal(vc_new, vc_ref)
+    assert np.array_equal(np.delete(kc_new, pos, axis=1), np.delete(kc_ref, pos, axis=1))
+    a, b = kc_new[:, pos].astype(np.float64), kc_ref[:, pos].astype(np.float64)
+    assert np.all(np.abs(a - b) <= np.abs(b) * 2.0 ** -10 + 1e-7)
+
+
+def test_decode_attention_step_by_step_fills_the_cache(awq):
+    """Twenty consecutive positions on one stream: every step sees the rows the earlier steps
+    wrote; the last output and the final caches match the oracle run the same way."""
+    import oracle
+    g = np.random.default_rng(300)
+    H, Hkv, D, Lmax = 16, 4, 128, 32
+    kc, vc = np.zeros((Hkv, Lmax, D), np.float16), np.zeros((Hkv, Lmax, D), np.float16)
+    kc_gpu, vc_gpu = dev(kc), dev(vc)
+    for pos in range(20):
+        q = g.standard_normal((H, D)).astype(np.float16)
+        k = g.standard_normal((Hkv, D)).astype(np.float16)
+        v = g.standard_normal((Hkv, D)).astype(np.float16)
+        out_ref, kc, vc = oracle.decode_attention(q, k, v, kc, vc, pos)
+        out = awq.awq_decode_attention(dev(q), dev(k), dev(v), kc_gpu, vc_gpu, pos)
+    assert np.abs(host(out).astype(np.float64) - out_ref.astype(np.float64)).max() <= ATT_TOL * 4
+    assert np.array_equal(host(vc_gpu), vc)
+    assert np.all(np.abs(host(kc_gpu).astype(np.float64) - kc.astype(np.float64))
+                  <= np.abs(kc.astype(np.float64)) * 2.0 ** -10 + 1e-7)
+
+
+def test_decode_attention_rejects_bad_arguments(awq):
+    import torch
+    z = lambda *s: torch.zeros(s, dtype=torch.float16, device="cuda")
+    with pytest.raises(awq.AwqError) as e:
+        awq.awq_decode_attention(z(8, 128), z(2, 128), z(2, 128), z(2, 16, 128), z(2, 16, 128), 16)
+    assert e.value.status == -2                               # pos >= Lmax
+    with pytest.raises(awq.AwqError) as e:
+        awq.awq_decode_attention(z(6, 128), z(4, 128), z(4, 128), z(4, 16, 128), z(4, 16, 128), 0)
+    assert e.value.status == -2                               # H % Hkv != 0
+    with pytest.raises(awq.AwqError) as e:
+        awq.awq_decode_attention(z(8, 64), z(2, 64), z(2, 64), z(2, 16, 64), z(2, 16, 64), 0)
+    assert e.value.status == -2                               # D != 128
+    with pytest.raises(awq.AwqError) as e:
+        awq.awq_decode_attention(z(8, 128), z(2, 128), z(2, 128), z(2, 16, 128), z(2, 16, 128), 3,
+                                 workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -5
+
+
 def test_errors_surface_as_exceptions(awq):
     import torch
     W = torch.zeros((16, 100), dtype=torch.float16, device="cuda")
