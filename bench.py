@@ -550,6 +550,71 @@ def main():
                     "8 cache sets cycled (268 MB)"}
         del ga, kcs, vcs
 
+        # one token through the whole stack of decoder layers (no embedding, no lm_head): per layer
+        # norm+1/s -> Q,K,V in one launch -> attention at position 2047 -> o -> residual ->
+        # norm+1/s -> gate,up in one launch -> silu*mul -> down -> residual
+        if L >= 2:
+            kcl = [torch.randn((Ha, La, Da), generator=gen, device=dev).to(torch.float16) for _ in range(L)]
+            vcl = [torch.randn((Ha, La, Da), generator=gen, device=dev).to(torch.float16) for _ in range(L)]
+            gam = torch.ones(4096, dtype=torch.float16, device=dev)
+            hid = torch.randn((1, 4096), generator=gen, device=dev).to(torch.float16)
+            xs1 = torch.empty_like(hid)
+            act = torch.empty((1, 11008), dtype=torch.float16, device=dev)
+            yq, yk, yv, yo, yg, yu, yd = (torch.empty((1, N), dtype=torch.float16, device=dev)
+                                          for _, N, K in shapes)
+            layer_calls = []
+            for l in range(L):
+                w = layers[l]
+                layer_calls.append((
+                    awq.prepare_linear_multi([(xs1, *w[0], yq, 4096), (xs1, *w[1], yk, 4096),
+                                              (xs1, *w[2], yv, 4096)]),
+                    awq.prepare_linear(outa.view(1, 4096), *w[3], yo, 4096),
+                    awq.prepare_linear_multi([(xs1, *w[4], yg, 11008), (xs1, *w[5], yu, 11008)]),
+                    awq.prepare_linear(act, *w[6], yd, 4096)))
+
+            def token_pass():
+                for l in range(L):
+                    qkv, o, gu, down = layer_calls[l]
+                    awq.awq_rmsnorm_inv_scale(hid, gam, s_by_k[4096], out=xs1)
+                    qkv()
+                    awq.awq_decode_attention(yq.view(Ha, Da), yk.view(Ha, Da), yv.view(Ha, Da),
+                                             kcl[l], vcl[l], La - 1, out=outa, workspace=wsa)
+                    o()
+                    hid.add_(yo)
+                    awq.awq_rmsnorm_inv_scale(hid, gam, s_by_k[4096], out=xs1)
+                    gu()
+                    awq.awq_silu_mul(yg, yu, out=act)
+                    down()
+                    hid.add_(yd)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                token_pass()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            gt = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gt):
+                token_pass()
+            gt.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(20):
+                hid.normal_(generator=gen)
+                gt.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            mst = e0.elapsed_time(e1) / 20
+            bt = L * (step_bytes(1) + ba)
+            extras[f"token_step_{L}_decoder_layers_context_2048"] = {
+                "ms_per_token": round(mst, 4), "us_per_layer": round(mst * 1e3 / L, 2),
+                "tokens_per_s": round(1e3 / mst, 1), "GB/s": gbs(bt, mst),
+                "finite": bool(torch.isfinite(hid.float()).all().item()),
+                "note": "11 launches per layer replayed from one graph; the two residual additions are "
+                        "torch element-wise kernels, every other step is this library's; embedding, "
+                        "final norm and lm_head are not included"}
+            del gt, kcl, vcl
+
         # scale search (Eq. 4-5): 20 grid points on one 4096 x 4096 linear with 2048 cached rows
         name, N, K = shapes[0]
         out = workloads.outlier_channels(K, 1, 0, 0)

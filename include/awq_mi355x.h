@@ -88,6 +88,11 @@ int awq_apply_inv_scale(const void *x_f16, const float *s, int64_t M, int64_t K,
 int awq_rmsnorm_inv_scale(const void *x_f16, const void *gamma_f16, const float *s, int64_t M,
                           int64_t K, float eps, void *xs_f16, void *stream);
 
+/* The gated activation between the gate/up and the down projection of a Llama-style MLP (one
+ * of the element-wise operators that Sec. 4.2 fuses): out[i] = fp16(silu(gate[i]) * up[i]),
+ * fp32 inside.  gate, up, out: n fp16 elements (device; out may alias either), n % 8 == 0. */
+int awq_silu_mul(const void *gate_f16, const void *up_f16, int64_t n, void *out_f16, void *stream);
+
 /* Sec. 3.2, Eq. 1-2 and Sec. 4.2 (weight packing): quantize W*diag(s) per group of
  * 128 input channels and write the packed layout.
  *   w' = fp32(W)*s;  scale = fp16(clamp((max-min)/15, 2^-14, 65504));

@@ -387,3 +387,11 @@ def decode_attention(q, k, v, k_cache, v_cache, pos: int, theta: float = 10000.0
         p = np.exp(sc - sc.max())
         out[h] = (p / p.sum()) @ vals
     return out.astype(np.float32).astype(np.float16), kc, vc
+
+
+def silu_mul(gate, up) -> np.ndarray:
+    """The gated activation between the gate/up and the down projection of a Llama-style MLP,
+    one of the element-wise operators Sec. 4.2 fuses: fp16(silu(gate) * up), fp64 inside."""
+    g = np.asarray(gate, dtype=np.float16).astype(np.float64)
+    u = np.asarray(up, dtype=np.float16).astype(np.float64)
+    return (g / (1.0 + np.exp(-g)) * u).astype(np.float32).astype(np.float16)

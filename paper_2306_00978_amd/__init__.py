@@ -33,7 +33,7 @@ EXPORTS = [
     "awq_search_scale_workspace_bytes", "awq_search_scale", "awq_quantize_pack_clip",
     "awq_packed_sizes_w3", "awq_quantize_pack_w3", "awq_unpack_w3", "awq_w3a16_linear",
     "awq_w3a16_linear_multi", "awq_rmsnorm_inv_scale", "awq_read_probe",
-    "awq_decode_attention_workspace_bytes", "awq_decode_attention",
+    "awq_decode_attention_workspace_bytes", "awq_decode_attention", "awq_silu_mul",
 ]
 MULTI_MAX = 56
 
@@ -101,6 +101,8 @@ def load() -> ctypes.CDLL:
     lib.awq_decode_attention.restype = i32
     lib.awq_decode_attention.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ctypes.c_float,
                                          vp, vp, sz, vp]
+    lib.awq_silu_mul.restype = i32
+    lib.awq_silu_mul.argtypes = [vp, vp, i64, vp, vp]
     lib.awq_read_probe.restype = i32
     lib.awq_read_probe.argtypes = [vp, sz, vp, vp]
     lib.awq_rmsnorm_inv_scale.restype = i32
@@ -509,4 +511,17 @@ def awq_decode_attention(q, k, v, k_cache, v_cache, pos: int, rope_theta: float 
     _check(load().awq_decode_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(k_cache), _ptr(v_cache), H, Hkv, D,
                                        Lmax, pos, float(rope_theta), _ptr(out), _ptr(workspace),
                                        workspace.numel(), _stream()), "awq_decode_attention")
+    return out
+
+
+def awq_silu_mul(gate: torch.Tensor, up: torch.Tensor, out: torch.Tensor | None = None):
+    """out = fp16(silu(gate) * up), element-wise; gate, up fp16 of the same shape."""
+    _dev(gate, torch.float16, "gate")
+    _dev(up, torch.float16, "up")
+    if gate.shape != up.shape:
+        raise ValueError("gate and up must have the same shape")
+    if out is None:
+        out = torch.empty_like(gate)
+    _dev(out, torch.float16, "out")
+    _check(load().awq_silu_mul(_ptr(gate), _ptr(up), gate.numel(), _ptr(out), _stream()), "awq_silu_mul")
     return out

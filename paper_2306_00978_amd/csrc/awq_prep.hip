@@ -119,7 +119,41 @@ __global__ __launch_bounds__(256) void rmsnorm_inv_scale_kernel(const uint4 *__r
     }
 }
 
+// silu(gate) * up, element-wise (the gated activation between gate/up and down): fp32, one rounding
+__global__ __launch_bounds__(256) void silu_mul_kernel(const uint4 *__restrict__ gate,
+                                                       const uint4 *__restrict__ up, int64_t n8,
+                                                       uint4 *__restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    const uint4 graw = gate[i], uraw = up[i];
+    const half_t *g = reinterpret_cast<const half_t *>(&graw);
+    const half_t *u = reinterpret_cast<const half_t *>(&uraw);
+    uint4 o;
+    half_t *oh = reinterpret_cast<half_t *>(&o);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float x = (float)g[e];
+        oh[e] = (half_t)(x / (1.0f + expf(-x)) * (float)u[e]);
+    }
+    out[i] = o;
+}
+
 }  // namespace
+
+extern "C" int awq_silu_mul(const void *gate_f16, const void *up_f16, int64_t n, void *out_f16,
+                            void *stream)
+{
+    if (!gate_f16 || !up_f16 || !out_f16) return AWQ_ERR_NULL_POINTER;
+    if (n <= 0 || (n % 8) != 0 || n > (int64_t)1 << 40) return AWQ_ERR_BAD_SHAPE;
+    if (!awq_aligned16(gate_f16) || !awq_aligned16(up_f16) || !awq_aligned16(out_f16))
+        return AWQ_ERR_MISALIGNED;
+    const int64_t n8 = n / 8, blocks = (n8 + 255) / 256;
+    if (blocks > 0x7fffffff) return AWQ_ERR_BAD_SHAPE;
+    silu_mul_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(
+        (const uint4 *)gate_f16, (const uint4 *)up_f16, n8, (uint4 *)out_f16);
+    return awq_launch_status();
+}
 
 extern "C" int awq_rmsnorm_inv_scale(const void *x_f16, const void *gamma_f16, const float *s,
                                      int64_t M, int64_t K, float eps, void *xs_f16, void *stream)

@@ -138,6 +138,12 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert rn(ok, odd, None, 1, 128, 1e-5, ok, None) == -4
     assert rn(ok, ok, odd, 1, 128, 1e-5, ok, None) == -4
 
+    sm = lib.awq_silu_mul
+    sm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+    assert sm(None, ok, 8, ok, None) == -1 and sm(ok, ok, 8, None, None) == -1
+    assert sm(ok, ok, 0, ok, None) == -2 and sm(ok, ok, 12, ok, None) == -2
+    assert sm(ok, odd, 8, ok, None) == -4
+
     at = lib.awq_decode_attention
     wsa = lib.awq_decode_attention_workspace_bytes
     assert wsa(32, 128, 2048) == 32 * 16 * 130 * 4 and wsa(32, 64, 10) == 0 and wsa(32, 128, 0) == 0

@@ -971,6 +971,17 @@ def test_rmsnorm_with_folded_inverse_scale(awq, M, K):
                   <= np.abs(oracle.rmsnorm_inv_scale(x, gamma, s).astype(np.float64)) * 2.0 ** -10 + 1e-7)
 
 
+def test_silu_mul(awq):
+    import oracle
+    g = np.random.default_rng(400)
+    for shape in ((1, 11008), (16, 11008), (300, 1408)):
+        gate = (g.standard_normal(shape) * 3).astype(np.float16)
+        up = g.standard_normal(shape).astype(np.float16)
+        ref = oracle.silu_mul(gate, up).astype(np.float64)
+        got = host(awq.awq_silu_mul(dev(gate), dev(up))).astype(np.float64)
+        assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -10 + 1e-7)
+
+
 # ------------------------------------------------------------------- decode attention
 
 ATT_TOL = 2e-3      # of max|v|: fp16 rounding of the output (2^-11) and fp32 sums / exponentials

@@ -40,3 +40,12 @@ def test_unit_rms_scale_invariance_and_per_channel_factors():
             * gamma.astype(np.float64) / s.astype(np.float64))
     got = oracle.rmsnorm_inv_scale(x, gamma, s, eps=1e-5).astype(np.float64)
     assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -11 + 1e-8)
+
+
+def test_silu_mul_special_values():
+    g = np.array([[0.0, 20.0, -20.0, 1.0, -1.0]], np.float16)
+    u = np.array([[3.0, 2.0, 2.0, 1.0, 1.0]], np.float16)
+    y = oracle.silu_mul(g, u).astype(np.float64)[0]
+    assert y[0] == 0.0 and abs(y[1] - 40.0) < 0.05 and abs(y[2]) < 1e-6
+    assert abs(y[3] - 0.7310585786) < 1e-3 and abs(y[4] + 0.2689414214) < 1e-3     # x * sigmoid(x)
+    assert abs(y[3] + y[4] - 0.4621171573) < 1e-3                                      # silu(x) + silu(-x) = x tanh(x/2)
