@@ -248,11 +248,53 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
     asm("" : "+s"(mask_lo));
     asm("" : "+s"(mask_hi));
 
-    // which linear of the list this workgroup belongs to (wave-uniform)
-    int pi = 0;
-    for (int i = 1; i < L.count; ++i)
-        if ((int)blockIdx.x >= L.wg_begin[i]) pi = i;
-    const GemvProblem &P = L.p[pi];
+    // Which linear of the list this workgroup belongs to, and that linear's entry.  Read through
+    // the scalar cache this is a chain of dependent misses (table, then entry) in front of the
+    // first weight request of every wave; instead lane l fetches wg_begin[l] and entry l of the
+    // kernel-argument block with vector loads, all in flight together, and the wave picks its
+    // entry with a ballot and readlanes: one memory round trip.  (Entries and table slots beyond
+    // `count` hold INT_MAX / unused bytes; they lie inside the argument block.)
+    typedef const __attribute__((address_space(1))) half_t gbl_half_t;
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(1))) u32x2_t gbl_u32x2_t;
+    typedef const __attribute__((address_space(1))) u32x4_t gbl_u32x4_t;
+    GemvProblem P;
+    gbl_half_t *px;                                     // activations and outputs of this linear,
+    __attribute__((address_space(1))) half_t *py;       // known to the compiler as global memory
+    int wg0;                                            // first workgroup of this linear
+    {
+        const unsigned char *ka = (const unsigned char *)__builtin_amdgcn_kernarg_segment_ptr();
+        const int l = threadIdx.x & 63, le = l < GEMV_MAX_PROBLEMS ? l : GEMV_MAX_PROBLEMS - 1;
+        typedef const __attribute__((address_space(1))) int gbl_int_t;
+        const int begin = *(gbl_int_t *)(uintptr_t)(ka + offsetof(GemvLaunch, wg_begin) + 4 * le);
+        gbl_u32x2_t *pe = (gbl_u32x2_t *)(uintptr_t)(ka + offsetof(GemvLaunch, p) + sizeof(GemvProblem) * le);
+        uint32_t f[14];
+#pragma unroll
+        for (int d = 0; d < 7; ++d) {
+            const u32x2_t t = pe[d];
+            f[2 * d] = t.x;
+            f[2 * d + 1] = t.y;
+        }
+        const uint64_t mine = __ballot(l < GEMV_MAX_PROBLEMS && (int)blockIdx.x >= begin);
+        const int pi = __builtin_amdgcn_readfirstlane(__popcll(mine) - 1);     // wg_begin is ascending from 0
+        uint32_t g[14];
+#pragma unroll
+        for (int d = 0; d < 14; ++d) g[d] = __builtin_amdgcn_readlane(f[d], pi);
+        static_assert(sizeof(GemvProblem) == 56 && offsetof(GemvProblem, N) == 40, "entry layout");
+        px = (gbl_half_t *)(uintptr_t)(((uint64_t)g[1] << 32) | g[0]);
+        py = (__attribute__((address_space(1))) half_t *)(uintptr_t)(((uint64_t)g[9] << 32) | g[8]);
+        P.x = nullptr;
+        P.y = nullptr;
+        P.q = reinterpret_cast<const uint4 *>(((uint64_t)g[3] << 32) | g[2]);
+        P.sc = reinterpret_cast<const uint16_t *>(((uint64_t)g[5] << 32) | g[4]);
+        P.zp = reinterpret_cast<const uint8_t *>(((uint64_t)g[7] << 32) | g[6]);
+        P.N = (int)g[10];
+        P.K = (int)g[11];
+        P.ks_log = (int)g[12];
+        P.iters = (int)g[13];
+        wg0 = __builtin_amdgcn_readlane(begin, pi);
+    }
 
     const int M = L.M, mlog = L.mlog, Mpad = 1 << mlog;
     const int K = P.K, N = P.N;
@@ -264,7 +306,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ks = wave & (KS - 1), ri = wave >> ksl;
     const int b0 = (NBT * ks) >> ksl, b1 = (NBT * (ks + 1)) >> ksl;      // 1..16/Mpad batches (host)
-    const int unit = (int)blockIdx.x - L.wg_begin[pi];
+    const int unit = (int)blockIdx.x - wg0;
     const int rb_wg = unit * iters * RW;                                 // first row block of the WG
     const int r = lane & 15, c = lane >> 4;
     const int zshift = (r & 1) * 4;
@@ -327,20 +369,21 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
     // they are tiny, and behind the first weight requests of the whole grid they would wait
     // for megabytes that are of no use before the fragments are there.
     uint4 xa[16];
+    bool okx[4];                 // whether tile u of the lane's slot exists (else its fragments are 0)
     {
         const int slot = r >> mlog;
         int m = r & (Mpad - 1);
         m = m < M ? m : M - 1;
         const int bl = b0 + slot;
-        const half_t *xrow = P.x + (size_t)m * K + 8 * c;
+        gbl_half_t *xrow = px + (size_t)m * K + 8 * c;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int g = 4 * bl + u;
-            const bool ok = bl < b1 && g < G;
+            okx[u] = bl < b1 && g < G;
+            const int gs = okx[u] ? g : 0;          // always a valid address: no branch, no wait
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                xa[4 * u + j] = ok ? *reinterpret_cast<const uint4 *>(xrow + g * 128 + 32 * j)
-                                   : make_uint4(0, 0, 0, 0);
+                xa[4 * u + j] = __builtin_bit_cast(uint4, *(gbl_u32x4_t *)(xrow + gs * 128 + 32 * j));
         }
     }
 
@@ -357,6 +400,10 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (nj < J) issue_next();
+
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        if (!okx[i >> 2]) xa[i] = make_uint4(0, 0, 0, 0);
 
     // halves 2,3,6,7 of every fragment meet the 2^-20 codes and are scaled by 2^-4 to match the
     // 2^-24 ones
@@ -440,7 +487,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int m = 4 * c + v;
-                    if (v < Mpad && m < M) P.y[(size_t)m * N + rbo * 16 + r] = (half_t)total[v];
+                    if (v < Mpad && m < M) py[(size_t)m * N + rbo * 16 + r] = (half_t)total[v];
                 }
             }
             total = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -461,7 +508,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
             float sum = 0.f;
             for (int k = 0; k < KS; ++k) sum += p[k << (mlog + 4)];
             const int rbo = rb_wg + it * RW + tri;
-            if (rbo < NRB && m < M) P.y[(size_t)m * N + rbo * 16 + (rem & 15)] = (half_t)sum;
+            if (rbo < NRB && m < M) py[(size_t)m * N + rbo * 16 + (rem & 15)] = (half_t)sum;
         }
     };
 
@@ -532,6 +579,7 @@ int stream_launch_bits(const GemvProblem *problems, int count, int M, hipStream_
     if (count < 1 || count > GEMV_MAX_PROBLEMS) return AWQ_ERR_BAD_ARGUMENT;
 
     GemvLaunch L;
+    for (int i = 0; i < GEMV_MAX_PROBLEMS; ++i) L.wg_begin[i] = 0x7fffffff;   // beyond the grid
     L.count = count;
     L.M = M;
     L.mlog = ceil_log2(M);
