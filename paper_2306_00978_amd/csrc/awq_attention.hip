@@ -31,15 +31,13 @@ struct RopeTable {
 
 // q (or k) of one head, rotated: pairs (i, i + 64), angle pos * theta^(-2 i / 128).  The angle (a
 // few thousand radians at long contexts) is formed and reduced to [-pi, pi] in fp64, sine and
-// cosine of the reduced angle in fp32.  Thread t < 64 produces elements t and t + 64.
-__device__ __forceinline__ void rope_pair(const half_t *src, int t, int pos, const RopeTable &tab,
-                                          float &lo, float &hi)
+// cosine of the reduced angle in fp32.  (a, b) are elements t and t + 64, inv_freq is entry t.
+__device__ __forceinline__ void rope_pair(float a, float b, double inv_freq, int pos, float &lo, float &hi)
 {
-    const double ang = (double)pos * tab.inv_freq[t];
+    const double ang = (double)pos * inv_freq;
     const double turns = __builtin_rint(ang * 0.15915494309189535);        // 1 / (2 pi)
     const float red = (float)(ang - turns * 6.283185307179586);
     const float sn = sinf(red), cs = cosf(red);
-    const float a = (float)src[t], b = (float)src[t + 64];
     lo = a * cs - b * sn;
     hi = b * cs + a * sn;
 }
@@ -79,33 +77,62 @@ __global__ __launch_bounds__(256) void attention_partial_kernel(
     __shared__ float qs[AD];                         // rotated query times 1/sqrt(D)
     __shared__ float ks[AD];                         // rotated key of the current token (fp32)
     __shared__ float wave_state[ATT_WAVES][AD + 2];
+    // all pointer arguments fetched in one round (the compiler would otherwise fetch each where
+    // it is first needed, one scalar-cache miss after the other)
+    asm volatile("" ::"s"(q), "s"(k), "s"(v), "s"(k_cache), "s"(v_cache), "s"(partial), "s"(H), "s"(Hkv),
+                 "s"(Lmax), "s"(pos), "s"(chunk));
     const int h = blockIdx.x, split = blockIdx.y;
     const int g_kv = h / (H / Hkv);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 64) {
+    const int grp = lane >> 4, u = lane & 15;
+    // what the rotary prologue needs (wave 0: the query, wave 1: the key; elements lane and
+    // lane + 64), requested before the cache rows so that it is not waited for behind them
+    const half_t *rsrc = wave == 1 ? k + (size_t)g_kv * AD : q + (size_t)h * AD;
+    const half_t ra_h = rsrc[lane], rb_h = rsrc[lane + 64];
+    const double rfreq = tab.inv_freq[lane];
+    const int L = pos + 1;
+    const int p0 = split * chunk, p1 = min(L, p0 + chunk);
+    const uint4 *kbase = reinterpret_cast<const uint4 *>(k_cache + (size_t)g_kv * Lmax * AD) + u;
+    const uint4 *vbase = reinterpret_cast<const uint4 *>(v_cache + (size_t)g_kv * Lmax * AD) + u;
+    // positions of this lane group: p, p + 16, ...; the loads of the next four are in flight while
+    // one is folded in.  The first ones go out before anything else: they do not depend on the
+    // query, and the rotary prologue below runs while they travel.
+    constexpr int AHEAD = 4;
+    uint4 kq[AHEAD + 1], vq[AHEAD + 1];
+    const int first = p0 + 4 * wave + grp;
+#pragma unroll
+    for (int a = 0; a < AHEAD; ++a) {
+        // unconditional (a row that is not needed reads row 0 and is ignored): a predicated
+        // load would be waited for on the spot
+        const int pa = first + 16 * a, pe = pa < p1 ? pa : 0;
+        kq[a] = kbase[(size_t)pe * (AD / 8)];
+        vq[a] = vbase[(size_t)pe * (AD / 8)];
+    }
+
+    {
+        // every wave rotates what it fetched (waves 2 and 3 discard the result): a rotation
+        // only some waves need would have its loads moved down behind the cache rows
         float lo, hi;
-        rope_pair(q + (size_t)h * AD, tid, pos, tab, lo, hi);
-        qs[tid] = lo * 0.08838834764831845f;         // 1 / sqrt(128)
-        qs[tid + 64] = hi * 0.08838834764831845f;
-    } else if (tid < 128) {
-        const int t = tid - 64;
-        float lo, hi;
-        rope_pair(k + (size_t)g_kv * AD, t, pos, tab, lo, hi);
-        ks[t] = lo;
-        ks[t + 64] = hi;
-        // the first query head of a kv group (first slice) files the token into the caches
-        if (split == 0 && h % (H / Hkv) == 0) {
-            half_t *kd = k_cache + ((size_t)g_kv * Lmax + pos) * AD;
-            half_t *vd = v_cache + ((size_t)g_kv * Lmax + pos) * AD;
-            kd[t] = (half_t)lo;
-            kd[t + 64] = (half_t)hi;
-            vd[t] = v[(size_t)g_kv * AD + t];
-            vd[t + 64] = v[(size_t)g_kv * AD + t + 64];
+        rope_pair((float)ra_h, (float)rb_h, rfreq, pos, lo, hi);
+        if (wave == 0) {
+            qs[lane] = lo * 0.08838834764831845f;    // 1 / sqrt(128)
+            qs[lane + 64] = hi * 0.08838834764831845f;
+        } else if (wave == 1) {
+            ks[lane] = lo;
+            ks[lane + 64] = hi;
+            // the first query head of a kv group (first slice) files the token into the caches
+            if (split == 0 && h % (H / Hkv) == 0) {
+                half_t *kd = k_cache + ((size_t)g_kv * Lmax + pos) * AD;
+                half_t *vd = v_cache + ((size_t)g_kv * Lmax + pos) * AD;
+                kd[lane] = (half_t)lo;
+                kd[lane + 64] = (half_t)hi;
+                vd[lane] = v[(size_t)g_kv * AD + lane];
+                vd[lane + 64] = v[(size_t)g_kv * AD + lane + 64];
+            }
         }
     }
     __syncthreads();
 
-    const int grp = lane >> 4, u = lane & 15;
     float qf[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) qf[e] = qs[8 * u + e];
@@ -115,32 +142,14 @@ __global__ __launch_bounds__(256) void attention_partial_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) r.acc[e] = 0.f;
 
-    const int L = pos + 1;
-    const int p0 = split * chunk, p1 = min(L, p0 + chunk);
-    const uint4 *kbase = reinterpret_cast<const uint4 *>(k_cache + (size_t)g_kv * Lmax * AD) + u;
-    const uint4 *vbase = reinterpret_cast<const uint4 *>(v_cache + (size_t)g_kv * Lmax * AD) + u;
-    // positions of this lane group: p, p + 16, ...; the loads of the next two are in flight while
-    // one is folded in
-    constexpr int AHEAD = 2;
-    uint4 kq[AHEAD + 1], vq[AHEAD + 1];
-    const int first = p0 + 4 * wave + grp;
-#pragma unroll
-    for (int a = 0; a < AHEAD; ++a) {
-        const int pa = first + 16 * a;
-        if (pa < p1 && pa != pos) {
-            kq[a] = kbase[(size_t)pa * (AD / 8)];
-            vq[a] = vbase[(size_t)pa * (AD / 8)];
-        }
-    }
     for (int p = first; p < p1; p += 16 * (AHEAD + 1)) {
 #pragma unroll
         for (int a = 0; a <= AHEAD; ++a) {
             const int pc = p + 16 * a;                       // position folded in now
             const int pn = pc + 16 * AHEAD;                  // position requested now
-            if (pn < p1 && pn != pos) {
-                kq[(a + AHEAD) % (AHEAD + 1)] = kbase[(size_t)pn * (AD / 8)];
-                vq[(a + AHEAD) % (AHEAD + 1)] = vbase[(size_t)pn * (AD / 8)];
-            }
+            const int pne = pn < p1 ? pn : 0;
+            kq[(a + AHEAD) % (AHEAD + 1)] = kbase[(size_t)pne * (AD / 8)];
+            vq[(a + AHEAD) % (AHEAD + 1)] = vbase[(size_t)pne * (AD / 8)];
             if (pc < p1) {
                 float kf[8], vf[8];
                 if (pc == pos) {                             // the token of this call: from the inputs
@@ -217,7 +226,21 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const float *__res
     __shared__ float ps[64 * (AD + 2)];
     const int h = blockIdx.x, t = threadIdx.x;
     const float *p = partial + (size_t)h * splits * (AD + 2);
-    for (int i = t; i < splits * (AD + 2); i += 256) ps[i] = p[i];
+    asm volatile("" ::"s"(partial), "s"(splits), "s"(out));       // arguments in one round
+    const int n = splits * (AD + 2);
+    for (int base = 0; base < n; base += 256 * 9) {               // nine loads in flight: 16 slices in one round
+        float tmp[9];
+#pragma unroll
+        for (int e = 0; e < 9; ++e) {
+            const int i = base + 256 * e + t;
+            tmp[e] = p[i < n ? i : n - 1];
+        }
+#pragma unroll
+        for (int e = 0; e < 9; ++e) {
+            const int i = base + 256 * e + t;
+            if (i < n) ps[i] = tmp[e];
+        }
+    }
     __syncthreads();
     if (t >= AD) return;
     float m = -__builtin_inff();
