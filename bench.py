@@ -613,7 +613,67 @@ def main():
                 "note": "11 launches per layer replayed from one graph; the two residual additions are "
                         "torch element-wise kernels, every other step is this library's; embedding, "
                         "final norm and lm_head are not included"}
-            del gt, kcl, vcl
+            # the same token step with the normalisations and residual additions inside the
+            # linears' launches (awq_w4a16_linear_fused_multi): 7 launches per layer
+            wnorm = (gam.float() / s_by_k[4096]).to(torch.float16)
+            fused_calls = []
+            for l in range(L):
+                w = layers[l]
+                def lin(x, p, y, N, **kw):
+                    return dict(x=x, qweight=w[p][0], scales=w[p][1], zeros=w[p][2], y=y, N=N, **kw)
+                fused_calls.append((
+                    awq.prepare_linear_fused_multi([lin(hid, 0, yq, 4096, norm=wnorm), lin(hid, 1, yk, 4096, norm=wnorm),
+                                                    lin(hid, 2, yv, 4096, norm=wnorm)]),
+                    awq.prepare_linear_fused_multi([lin(outa.view(1, 4096), 3, hid, 4096, residual=hid)]),
+                    awq.prepare_linear_fused_multi([lin(hid, 4, yg, 11008, norm=wnorm), lin(hid, 5, yu, 11008, norm=wnorm)]),
+                    awq.prepare_linear_fused_multi([lin(act, 6, hid, 4096, residual=hid)])))
+
+            def token_pass_fused():
+                for l in range(L):
+                    qkv, o, gu, down = fused_calls[l]
+                    qkv()
+                    awq.awq_decode_attention(yq.view(Ha, Da), yk.view(Ha, Da), yv.view(Ha, Da),
+                                             kcl[l], vcl[l], La - 1, out=outa, workspace=wsa)
+                    o()
+                    gu()
+                    awq.awq_silu_mul(yg, yu, out=act)
+                    down()
+            # both forms from the same hidden state: the results must agree to fp16 rounding
+            h0 = torch.randn((1, 4096), generator=gen, device=dev).to(torch.float16)
+            hid.copy_(h0)
+            token_pass()
+            h_plain = hid.float().clone()
+            hid.copy_(h0)
+            token_pass_fused()
+            h_fused = hid.float().clone()
+            torch.cuda.synchronize()
+            agree = float((h_plain - h_fused).abs().max() / h_plain.abs().max())
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                token_pass_fused()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            gf = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gf):
+                token_pass_fused()
+            gf.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(20):
+                hid.normal_(generator=gen)
+                gf.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            msf = e0.elapsed_time(e1) / 20
+            extras[f"token_step_{L}_decoder_layers_context_2048_fused_norm_residual"] = {
+                "ms_per_token": round(msf, 4), "us_per_layer": round(msf * 1e3 / L, 2),
+                "tokens_per_s": round(1e3 / msf, 1), "GB/s": gbs(bt, msf),
+                "max_difference_from_unfused_over_max": agree,
+                "note": "7 launches per layer: the RMS normalisations run in the prologue and the residual "
+                        "additions in the epilogue of the linears' launches"}
+            del gt, gf, kcl, vcl
 
         # scale search (Eq. 4-5): 20 grid points on one 4096 x 4096 linear with 2048 cached rows
         name, N, K = shapes[0]

@@ -173,6 +173,36 @@ typedef struct awq_linear_desc {
 int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* Sec. 4.2 (kernel fusion of the operators around a linear): a grouped decode call whose linears
+ * may carry a normalisation in front and a residual behind, so that a decoder layer needs no
+ * launch of its own for either:
+ *   pre_op == AWQ_PRE_RMSNORM: the linear runs on
+ *       x'[m,k] = fp16( x[m,k] * rsqrt(mean_k x[m,k]^2 + eps) * pre[k] ),
+ *     pre_f16 [K] fp16 (device, 16-byte aligned) = norm weight / AWQ scale s of Eq. 4 (the
+ *     composition awq_rmsnorm_inv_scale computes with gamma and s apart), fp32 inside;
+ *   residual_f16 != NULL: y[m,n] = fp16( residual[m,n] + sum ), [M,N] fp16 (device); it may be
+ *     y_f16 itself (in-place accumulation into the hidden state).
+ * A call with one linear and no normalisation runs at every decode shape.  Otherwise every
+ * linear must fit the streaming decode kernel at this M: its activations stay in the
+ * registers of the at most eight waves that share a row block, 8192 / M' columns per wave with
+ * M' = M rounded up to a power of two (so K <= 65536 / M', and K not so short that a wave would
+ * be left without columns).  awq_w4a16_linear_fused_fits() returns 1 for a shape that does, 0
+ * otherwise; the call returns AWQ_ERR_BAD_SHAPE for one that does not (use the separate calls).
+ * M <= 16, count <= AWQ_FUSED_MAX.  `descs` is a HOST array, read before the call returns. */
+#define AWQ_PRE_NONE 0
+#define AWQ_PRE_RMSNORM 1
+#define AWQ_FUSED_MAX 24
+typedef struct awq_fused_desc {
+    awq_linear_desc linear;
+    const void *pre_f16;        /* AWQ_PRE_RMSNORM: [K] fp16 factors; else ignored */
+    const void *residual_f16;   /* [M,N] fp16 or NULL */
+    float eps;
+    int pre_op;
+} awq_fused_desc;
+int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int count, int64_t M, int group,
+                                 void *stream);
+int awq_w4a16_linear_fused_fits(int64_t N, int64_t K, int64_t M, int group);
+
 /* ---- INT3-g128 variant (Sec. 5: INT4/INT3 with group size 128) ----------------------------
  * The 8-level form of the quantizer (15 -> 7 in the formulas of awq_quantize_pack) and its own
  * packed layout, version 1:

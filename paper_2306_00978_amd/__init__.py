@@ -34,6 +34,7 @@ EXPORTS = [
     "awq_packed_sizes_w3", "awq_quantize_pack_w3", "awq_unpack_w3", "awq_w3a16_linear",
     "awq_w3a16_linear_multi", "awq_rmsnorm_inv_scale", "awq_read_probe",
     "awq_decode_attention_workspace_bytes", "awq_decode_attention", "awq_silu_mul",
+    "awq_w4a16_linear_fused_multi", "awq_w4a16_linear_fused_fits",
 ]
 MULTI_MAX = 56
 
@@ -45,6 +46,14 @@ class LinearDesc(ctypes.Structure):
                 ("y_f16", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64)]
 
 _lib = None
+
+
+class FusedDesc(ctypes.Structure):
+    _fields_ = [("linear", LinearDesc), ("pre_f16", ctypes.c_void_p), ("residual_f16", ctypes.c_void_p),
+                ("eps", ctypes.c_float), ("pre_op", ctypes.c_int)]
+
+
+PRE_NONE, PRE_RMSNORM, FUSED_MAX = 0, 1, 24
 
 
 class AwqError(RuntimeError):
@@ -101,6 +110,10 @@ def load() -> ctypes.CDLL:
     lib.awq_decode_attention.restype = i32
     lib.awq_decode_attention.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ctypes.c_float,
                                          vp, vp, sz, vp]
+    lib.awq_w4a16_linear_fused_multi.restype = i32
+    lib.awq_w4a16_linear_fused_multi.argtypes = [ctypes.POINTER(FusedDesc), i32, i64, i32, vp]
+    lib.awq_w4a16_linear_fused_fits.restype = i32
+    lib.awq_w4a16_linear_fused_fits.argtypes = [i64, i64, i64, i32]
     lib.awq_silu_mul.restype = i32
     lib.awq_silu_mul.argtypes = [vp, vp, i64, vp, vp]
     lib.awq_read_probe.restype = i32
@@ -525,3 +538,62 @@ def awq_silu_mul(gate: torch.Tensor, up: torch.Tensor, out: torch.Tensor | None 
     _dev(out, torch.float16, "out")
     _check(load().awq_silu_mul(_ptr(gate), _ptr(up), gate.numel(), _ptr(out), _stream()), "awq_silu_mul")
     return out
+
+
+def prepare_linear_fused_multi(linears, group: int = GROUP):
+    """Marshal one fused grouped decode call.  `linears` is a list of dicts with the keys
+    x, qweight, scales, zeros, y, N and optionally norm (fp16 [K] factors: the linear then runs on
+    the RMS-normalised x times these), eps, residual (fp16 [M,N], added to the output; may be y).
+    Returns a zero-argument callable that enqueues ONE awq_w4a16_linear_fused_multi."""
+    if not 1 <= len(linears) <= FUSED_MAX:
+        raise ValueError(f"1..{FUSED_MAX} linears per fused call")
+    descs = (FusedDesc * len(linears))()
+    M = None
+    for i, l in enumerate(linears):
+        x, y, N = l["x"], l["y"], l["N"]
+        _dev(x, torch.float16, "x")
+        _dev(y, torch.float16, "y")
+        m, K = x.shape
+        if M is None:
+            M = m
+        if m != M:
+            raise ValueError("all linears of a grouped call share M")
+        qb, sb, zb = awq_packed_sizes(N, K, group)
+        qweight, scales, zeros = l["qweight"], l["scales"], l["zeros"]
+        if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+                or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
+            raise ValueError("buffer sizes do not match the shape")
+        norm, res = l.get("norm"), l.get("residual")
+        if norm is not None:
+            _dev(norm, torch.float16, "norm")
+            if norm.numel() != K:
+                raise ValueError("norm must have K elements")
+        if res is not None:
+            _dev(res, torch.float16, "residual")
+            if res.numel() != M * N:
+                raise ValueError("residual must be [M,N]")
+        descs[i] = FusedDesc(LinearDesc(x.data_ptr(), qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
+                                        y.data_ptr(), N, K),
+                             norm.data_ptr() if norm is not None else None,
+                             res.data_ptr() if res is not None else None,
+                             float(l.get("eps", 1e-5)), PRE_RMSNORM if norm is not None else PRE_NONE)
+    fn = load().awq_w4a16_linear_fused_multi
+    count = len(linears)
+    keep = list(linears)
+
+    def call(_keep=keep):
+        st = fn(descs, count, M, group, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_w4a16_linear_fused_multi")
+    return call
+
+
+def awq_w4a16_linear_fused_multi(linears, group: int = GROUP):
+    """The linears of `linears` (see prepare_linear_fused_multi) in one kernel launch."""
+    prepare_linear_fused_multi(linears, group)()
+    return [l["y"] for l in linears]
+
+
+def awq_w4a16_linear_fused_fits(N: int, K: int, M: int, group: int = GROUP) -> bool:
+    """Whether a linear of this shape can be part of a fused grouped call at this M."""
+    return bool(load().awq_w4a16_linear_fused_fits(N, K, M, group))

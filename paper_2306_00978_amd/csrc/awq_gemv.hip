@@ -133,14 +133,14 @@ template <int BITS, int U, int MS, bool PIPE>
 __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void gemv_kernel(
     const half_t *__restrict__ x, const uint32_t *__restrict__ qweight,
     const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
-    half_t *__restrict__ y, int M, int N, int K, int G, int logW)
+    half_t *y, int M, int N, int K, int G, int logW, const half_t *res)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     // all arguments are fetched in one round, before the first branch: left to itself the
     // compiler sinks the pointer loads below it, a second scalar-cache miss in front of the
     // first request of a kernel that lives for a few microseconds
     asm volatile("" ::"s"(x), "s"(qweight), "s"(scales), "s"(zeros), "s"(y), "s"(M), "s"(N), "s"(K), "s"(G),
-                 "s"(logW));
+                 "s"(logW), "s"(res));
     const ExpandConsts kc = expand_consts();
     constexpr bool STAGE = MS > 0;
     constexpr int NS = STAGE ? MS : 1;
@@ -278,7 +278,9 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
         float sum = 0.f;
 #pragma unroll
         for (int w = 0; w < 16; ++w) sum += (w < W) ? part[w] : 0.f;
-        y[(int64_t)(t >> 4) * N + rb * 16 + (t & 15)] = (half_t)sum;
+        // `res` (may be y itself): a residual added in fp32 before the one rounding
+        const int64_t at = (int64_t)(t >> 4) * N + rb * 16 + (t & 15);
+        y[at] = (half_t)(res ? sum + (float)res[at] : sum);
     }
 }
 
@@ -313,7 +315,7 @@ namespace {
 
 template <int BITS>
 int gemv_launch_bits(const void *x, const void *qweight, const void *scales, const void *zeros,
-                     void *y, int M, int N, int K, hipStream_t stream)
+                     void *y, int M, int N, int K, hipStream_t stream, const void *res = nullptr)
 {
     const int G = K / AWQ_GROUP;
     const int logW = pick_log_waves(G);
@@ -326,7 +328,7 @@ int gemv_launch_bits(const void *x, const void *qweight, const void *scales, con
     // (a lane parks four token rows at once: the area covers M rounded up to a multiple of 4)
     const size_t lds = (size_t)((M + 3) / 4 * 4) * 1024 + (size_t)W * MS * (U * 256 + 16);
 #define AWQ_GEMV_ARGS (const half_t *)x, (const uint32_t *)qweight, (const uint16_t *)scales, \
-                      (const uint8_t *)zeros, (half_t *)y, M, N, K, G, logW
+                      (const uint8_t *)zeros, (half_t *)y, M, N, K, G, logW, (const half_t *)res
 #define AWQ_GEMV_LAUNCH(UU, MM, PP) gemv_kernel<BITS, UU, MM, PP><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS)
 #define AWQ_GEMV_CASE(UU)                                                                   \
     case UU:                                                                                \
@@ -367,4 +369,11 @@ int awq_gemv_launch_w3(const void *x, const void *qweight, const void *scales, c
                        void *y, int M, int N, int K, hipStream_t stream)
 {
     return gemv_launch_bits<3>(x, qweight, scales, zeros, y, M, N, K, stream);
+}
+
+// the 4-bit decode launch with a residual [M,N] (may be y) added to the output
+int awq_gemv_launch_residual(const void *x, const void *qweight, const void *scales, const void *zeros,
+                             void *y, const void *res, int M, int N, int K, hipStream_t stream)
+{
+    return gemv_launch_bits<4>(x, qweight, scales, zeros, y, M, N, K, stream, res);
 }

@@ -33,8 +33,31 @@ struct GemvLaunch {
 
 static_assert(sizeof(GemvLaunch) <= 4096, "kernel arguments are limited to 4 KB");
 
+// Operators fused into a linear of a grouped launch (Sec. 4.2, kernel fusion).
+constexpr int GEMV_MAX_FUSED = 24;        // linears per fused launch (24 more bytes each)
+constexpr int GEMV_PRE_NONE = 0, GEMV_PRE_RMSNORM = 1;
+struct GemvFusedExtra {
+    const half_t *pre;        // RMSNORM: [K] fp16 factors (gamma / s); else unused
+    const half_t *res;        // [M,N] fp16 added to the output, or null
+    float eps;
+    int pre_op;
+};
+
+template <bool FUSED> struct GemvArgs {
+    GemvLaunch L;
+};
+template <> struct GemvArgs<true> {
+    GemvLaunch L;
+    GemvFusedExtra e[GEMV_MAX_FUSED];
+};
+static_assert(sizeof(GemvArgs<true>) <= 4096, "kernel arguments are limited to 4 KB");
+
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream);
 // the same for linears in the 3-bit packed layout (q then points at 12-byte slots)
 int awq_gemv_stream_launch_w3(const GemvProblem *problems, int count, int M, hipStream_t stream);
+// the 4-bit launch with a normalisation in front of and/or a residual behind each linear; every
+// linear must fit (awq_gemv_stream_fits), count <= GEMV_MAX_FUSED
+int awq_gemv_stream_launch_fused(const GemvProblem *problems, const GemvFusedExtra *extra, int count,
+                                 int M, hipStream_t stream);
 // whether a linear of this shape can be part of a grouped launch at this M
 bool awq_gemv_stream_fits(int N, int K, int M);

@@ -238,9 +238,35 @@ __device__ __forceinline__ floatx4 consume_batch_w3(const Landed &b, const uint4
     return bacc;
 }
 
-template <int STAGES, int BITS>
-__global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
+// Mixed-precision helpers of the fused normalisation (fp16 operands taken from a packed pair,
+// fp32 arithmetic, no separate conversions): acc + lo(h2)^2 + hi(h2)^2, and the pair
+// fp16(lo(x2) * f * lo(w2)), fp16(hi(x2) * f * hi(w2)).
+__device__ __forceinline__ float mix_sum_squares(uint32_t h2, float acc)
 {
+    asm("v_fma_mix_f32 %0, %1, %1, %0 op_sel_hi:[1,1,0]\n\t"
+        "v_fma_mix_f32 %0, %1, %1, %0 op_sel:[1,1,0] op_sel_hi:[1,1,0]"
+        : "+v"(acc)
+        : "v"(h2));
+    return acc;
+}
+
+__device__ __forceinline__ uint32_t mix_scale_pair(uint32_t x2, float f, uint32_t w2)
+{
+    float lo, hi;
+    uint32_t out;
+    asm("v_fma_mix_f32 %1, %3, %4, 0 op_sel_hi:[1,0,0]\n\t"
+        "v_fma_mix_f32 %2, %3, %4, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\t"
+        "v_fma_mixlo_f16 %0, %1, %5, 0 op_sel_hi:[0,1,0]\n\t"
+        "v_fma_mixhi_f16 %0, %2, %5, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]"
+        : "=&v"(out), "=&v"(lo), "=&v"(hi)
+        : "v"(x2), "v"(f), "v"(w2));
+    return out;
+}
+
+template <int STAGES, int BITS, bool FUSED>
+__global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSED> A)
+{
+    const GemvLaunch &L = A.L;
     constexpr int STAGE_BYTES = Slot<BITS>::BYTES, STAGE_SC = Slot<BITS>::SC, STAGE_ZP = Slot<BITS>::ZP;
     constexpr int TILE_BYTES = Slot<BITS>::TILE, LOADS_PER_JOB = Slot<BITS>::LOADS;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -263,6 +289,9 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
     gbl_half_t *px;                                     // activations and outputs of this linear,
     __attribute__((address_space(1))) half_t *py;       // known to the compiler as global memory
     int wg0;                                            // first workgroup of this linear
+    gbl_half_t *ppre = nullptr, *pres = nullptr;        // FUSED: normalisation factors, residual
+    float eps = 0.f;
+    int pre_op = GEMV_PRE_NONE;
     {
         const unsigned char *ka = (const unsigned char *)__builtin_amdgcn_kernarg_segment_ptr();
         const int l = threadIdx.x & 63, le = l < GEMV_MAX_PROBLEMS ? l : GEMV_MAX_PROBLEMS - 1;
@@ -275,6 +304,17 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
             const u32x2_t t = pe[d];
             f[2 * d] = t.x;
             f[2 * d + 1] = t.y;
+        }
+        uint32_t fe[6] = {};
+        if (FUSED) {
+            const int lf = l < GEMV_MAX_FUSED ? l : GEMV_MAX_FUSED - 1;
+            gbl_u32x2_t *ee = (gbl_u32x2_t *)(uintptr_t)(ka + sizeof(GemvLaunch) + sizeof(GemvFusedExtra) * lf);
+#pragma unroll
+            for (int d = 0; d < 3; ++d) {
+                const u32x2_t t = ee[d];
+                fe[2 * d] = t.x;
+                fe[2 * d + 1] = t.y;
+            }
         }
         const uint64_t mine = __ballot(l < GEMV_MAX_PROBLEMS && (int)blockIdx.x >= begin);
         const int pi = __builtin_amdgcn_readfirstlane(__popcll(mine) - 1);     // wg_begin is ascending from 0
@@ -294,6 +334,16 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
         P.ks_log = (int)g[12];
         P.iters = (int)g[13];
         wg0 = __builtin_amdgcn_readlane(begin, pi);
+        if (FUSED) {
+            static_assert(sizeof(GemvFusedExtra) == 24 && offsetof(GemvArgs<true>, e) == sizeof(GemvLaunch), "layout");
+            uint32_t ge[6];
+#pragma unroll
+            for (int d = 0; d < 6; ++d) ge[d] = __builtin_amdgcn_readlane(fe[d], pi);
+            ppre = (gbl_half_t *)(uintptr_t)(((uint64_t)ge[1] << 32) | ge[0]);
+            pres = (gbl_half_t *)(uintptr_t)(((uint64_t)ge[3] << 32) | ge[2]);
+            eps = __builtin_bit_cast(float, ge[4]);
+            pre_op = (int)ge[5];
+        }
     }
 
     const int M = L.M, mlog = L.mlog, Mpad = 1 << mlog;
@@ -369,6 +419,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
     // they are tiny, and behind the first weight requests of the whole grid they would wait
     // for megabytes that are of no use before the fragments are there.
     uint4 xa[16];
+    uint4 wn[16];                // FUSED: normalisation factors, alive until the fragments are final
     bool okx[4];                 // whether tile u of the lane's slot exists (else its fragments are 0)
     {
         const int slot = r >> mlog;
@@ -384,6 +435,15 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 xa[4 * u + j] = __builtin_bit_cast(uint4, *(gbl_u32x4_t *)(xrow + gs * 128 + 32 * j));
+        }
+        if (FUSED && pre_op == GEMV_PRE_RMSNORM) {   // the factors of the same columns
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int gs = okx[u] ? 4 * bl + u : 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    wn[4 * u + j] = __builtin_bit_cast(uint4, *(gbl_u32x4_t *)(ppre + 8 * c + gs * 128 + 32 * j));
+            }
         }
     }
 
@@ -404,6 +464,41 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
 #pragma unroll
     for (int i = 0; i < 16; ++i)
         if (!okx[i >> 2]) xa[i] = make_uint4(0, 0, 0, 0);
+
+    // FUSED, RMS normalisation in front of the linear: x' = fp16(x * rsqrt(mean_k x^2 + eps) * w_k).
+    // The fragments of a wave hold its K-slice of token r % Mpad once (lanes of the same token
+    // differ in c and in the slot bits of r); the waves that split K meet in LDS.
+    if (FUSED && pre_op == GEMV_PRE_RMSNORM) {
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            ss = mix_sum_squares(xa[i].x, ss);
+            ss = mix_sum_squares(xa[i].y, ss);
+            ss = mix_sum_squares(xa[i].z, ss);
+            ss = mix_sum_squares(xa[i].w, ss);
+        }
+        ss += __shfl_xor(ss, 16);
+        ss += __shfl_xor(ss, 32);
+        if (mlog < 4) ss += __shfl_xor(ss, 8);
+        if (mlog < 3) ss += __shfl_xor(ss, 4);
+        if (mlog < 2) ss += __shfl_xor(ss, 2);
+        if (mlog < 1) ss += __shfl_xor(ss, 1);
+        if (KS > 1) {
+            float *nred = red + 2 * red_floats;                 // [wave][16]
+            if (c == 0) nred[wave * 16 + r] = ss;
+            __syncthreads();
+            ss = 0.f;
+            for (int k = 0; k < KS; ++k) ss += nred[((ri << ksl) + k) * 16 + r];
+        }
+        const float rinv = rsqrtf(ss / (float)K + eps);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            xa[i].x = mix_scale_pair(xa[i].x, rinv, wn[i].x);
+            xa[i].y = mix_scale_pair(xa[i].y, rinv, wn[i].y);
+            xa[i].z = mix_scale_pair(xa[i].z, rinv, wn[i].z);
+            xa[i].w = mix_scale_pair(xa[i].w, rinv, wn[i].w);
+        }
+    }
 
     // halves 2,3,6,7 of every fragment meet the 2^-20 codes and are scaled by 2^-4 to match the
     // 2^-24 ones
@@ -487,7 +582,10 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int m = 4 * c + v;
-                    if (v < Mpad && m < M) py[(size_t)m * N + rbo * 16 + r] = (half_t)total[v];
+                    if (v < Mpad && m < M) {
+                        const size_t at = (size_t)m * N + rbo * 16 + r;
+                        py[at] = (half_t)(FUSED && pres ? total[v] + (float)pres[at] : total[v]);
+                    }
                 }
             }
             total = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -508,7 +606,10 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvLaunch L)
             float sum = 0.f;
             for (int k = 0; k < KS; ++k) sum += p[k << (mlog + 4)];
             const int rbo = rb_wg + it * RW + tri;
-            if (rbo < NRB && m < M) py[(size_t)m * N + rbo * 16 + (rem & 15)] = (half_t)sum;
+            if (rbo < NRB && m < M) {
+                const size_t at = (size_t)m * N + rbo * 16 + (rem & 15);
+                py[at] = (half_t)(FUSED && pres ? sum + (float)pres[at] : sum);
+            }
         }
     };
 
@@ -566,8 +667,9 @@ bool awq_gemv_stream_fits(int N, int K, int M)
 
 namespace {
 
-template <int BITS>
-int stream_launch_bits(const GemvProblem *problems, int count, int M, hipStream_t stream)
+template <int BITS, bool FUSED>
+int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra, int count, int M,
+                       hipStream_t stream)
 {
     constexpr int STAGE_BYTES = Slot<BITS>::BYTES;
     static const int f_logw = env_int("AWQ_GEMV_LOGW", -1);
@@ -576,9 +678,12 @@ int stream_launch_bits(const GemvProblem *problems, int count, int M, hipStream_
     static const int f_stages = env_int("AWQ_GEMV_STAGES", 2);
     static const int f_slots = env_int("AWQ_GEMV_SLOTS", 1792);
     static const int f_jobs = env_int("AWQ_GEMV_JOBS", -1);
-    if (count < 1 || count > GEMV_MAX_PROBLEMS) return AWQ_ERR_BAD_ARGUMENT;
+    if (count < 1 || count > (FUSED ? GEMV_MAX_FUSED : GEMV_MAX_PROBLEMS)) return AWQ_ERR_BAD_ARGUMENT;
 
-    GemvLaunch L;
+    GemvArgs<FUSED> A;
+    if constexpr (FUSED)
+        for (int i = 0; i < count; ++i) A.e[i] = extra[i];
+    GemvLaunch &L = A.L;
     for (int i = 0; i < GEMV_MAX_PROBLEMS; ++i) L.wg_begin[i] = 0x7fffffff;   // beyond the grid
     L.count = count;
     L.M = M;
@@ -598,6 +703,10 @@ int stream_launch_bits(const GemvProblem *problems, int count, int M, hipStream_
         // K is split over as few waves as the register slots allow (splitting costs a pass
         // through LDS and a barrier per row block)
         int best_ksl = ksl_min;
+        // ... unless the launch is so small that a wave would then have far more jobs than its
+        // share T (a single projection): more waves along K put the whole matrix in flight
+        while (best_ksl < 3 && (2 << best_ksl) <= NBT && ((NBT + (1 << best_ksl) - 1) >> best_ksl) > 1.5 * T)
+            ++best_ksl;
         if (f_ksl > ksl_min) best_ksl = std::min(3, f_ksl);
         while ((1 << best_ksl) > NBT && best_ksl > ksl_min) --best_ksl;
         if ((1 << best_ksl) > NBT) return AWQ_GEMV_STREAM_UNFIT;
@@ -608,7 +717,8 @@ int stream_launch_bits(const GemvProblem *problems, int count, int M, hipStream_
     L.logW = logW;
     const int W = 1 << logW;
     const int stages = f_stages == 3 ? 3 : (f_stages == 4 ? 4 : 2);
-    const size_t lds = (size_t)W * stages * STAGE_BYTES + 2 * (size_t)W * (16 << L.mlog) * 4;
+    const size_t lds = (size_t)W * stages * STAGE_BYTES + 2 * (size_t)W * (16 << L.mlog) * 4 +
+                       (FUSED ? (size_t)W * 16 * 4 : 0);
 
     // The row-block steps per workgroup bring the jobs of a wave as close to T as they get.
     // Workgroups of eight waves take more than half of a CU's LDS, so only one is resident per
@@ -641,18 +751,18 @@ int stream_launch_bits(const GemvProblem *problems, int count, int M, hipStream_
     static bool attr_set = false;
     if (!attr_set) {
         const int cap = 160 * 1024;
-        const void *kernels[] = {reinterpret_cast<const void *>(gemv_stream_kernel<2, BITS>),
-                                 reinterpret_cast<const void *>(gemv_stream_kernel<3, BITS>),
-                                 reinterpret_cast<const void *>(gemv_stream_kernel<4, BITS>)};
-        for (const void *k : kernels)
-            if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
+        const void *kernels[] = {reinterpret_cast<const void *>(gemv_stream_kernel<2, BITS, FUSED>),
+                                 reinterpret_cast<const void *>(gemv_stream_kernel<3, BITS, FUSED>),
+                                 reinterpret_cast<const void *>(gemv_stream_kernel<4, BITS, FUSED>)};
+        for (int k = 0; k < (FUSED ? 1 : 3); ++k)
+            if (hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
                 return AWQ_ERR_HIP;
         attr_set = true;
     }
     if (lds > (size_t)160 * 1024) return AWQ_GEMV_STREAM_UNFIT;
-    if (stages == 4) gemv_stream_kernel<4, BITS><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
-    else if (stages == 3) gemv_stream_kernel<3, BITS><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
-    else gemv_stream_kernel<2, BITS><<<dim3(wg), dim3(W * 64), lds, stream>>>(L);
+    if (stages == 4 && !FUSED) gemv_stream_kernel<4, BITS, FUSED><<<dim3(wg), dim3(W * 64), lds, stream>>>(A);
+    else if (stages == 3 && !FUSED) gemv_stream_kernel<3, BITS, FUSED><<<dim3(wg), dim3(W * 64), lds, stream>>>(A);
+    else gemv_stream_kernel<2, BITS, FUSED><<<dim3(wg), dim3(W * 64), lds, stream>>>(A);
     return awq_launch_status();
 }
 
@@ -660,10 +770,16 @@ int stream_launch_bits(const GemvProblem *problems, int count, int M, hipStream_
 
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream)
 {
-    return stream_launch_bits<4>(problems, count, M, stream);
+    return stream_launch_bits<4, false>(problems, nullptr, count, M, stream);
 }
 
 int awq_gemv_stream_launch_w3(const GemvProblem *problems, int count, int M, hipStream_t stream)
 {
-    return stream_launch_bits<3>(problems, count, M, stream);
+    return stream_launch_bits<3, false>(problems, nullptr, count, M, stream);
+}
+
+int awq_gemv_stream_launch_fused(const GemvProblem *problems, const GemvFusedExtra *extra, int count,
+                                 int M, hipStream_t stream)
+{
+    return stream_launch_bits<4, true>(problems, extra, count, M, stream);
 }

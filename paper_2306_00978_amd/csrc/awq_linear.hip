@@ -6,6 +6,8 @@
 
 #include <stdlib.h>
 
+int awq_gemv_launch_residual(const void *x, const void *qweight, const void *scales, const void *zeros,
+                             void *y, const void *res, int M, int N, int K, hipStream_t stream);
 int awq_gemv_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
                     void *y, int M, int N, int K, hipStream_t stream);
 int awq_gemm_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
@@ -115,4 +117,56 @@ extern "C" int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, i
         if (st != AWQ_OK) return st;
     }
     return AWQ_OK;
+}
+
+extern "C" int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int count, int64_t M, int group,
+                                            void *stream)
+{
+    if (!descs) return AWQ_ERR_NULL_POINTER;
+    if (count < 1 || count > AWQ_FUSED_MAX) return AWQ_ERR_BAD_ARGUMENT;
+    if (M <= 0 || M > 16) return AWQ_ERR_BAD_SHAPE;
+    GemvProblem p[GEMV_MAX_FUSED] = {};
+    GemvFusedExtra e[GEMV_MAX_FUSED] = {};
+    for (int i = 0; i < count; ++i) {
+        const awq_linear_desc &d = descs[i].linear;
+        if (!d.x_f16 || !d.qweight || !d.scales || !d.zeros || !d.y_f16) return AWQ_ERR_NULL_POINTER;
+        int st = awq_check_weight_shape(d.N, d.K, group);
+        if (st != AWQ_OK) return st;
+        if (!awq_aligned16(d.x_f16) || !awq_aligned16(d.qweight) || !awq_aligned16(d.scales) ||
+            !awq_aligned16(d.zeros) || !awq_aligned16(d.y_f16))
+            return AWQ_ERR_MISALIGNED;
+        if (descs[i].pre_op == AWQ_PRE_RMSNORM) {
+            if (!descs[i].pre_f16) return AWQ_ERR_NULL_POINTER;
+            if (!awq_aligned16(descs[i].pre_f16)) return AWQ_ERR_MISALIGNED;
+            if (!(descs[i].eps >= 0.0f)) return AWQ_ERR_BAD_ARGUMENT;
+        } else if (descs[i].pre_op != AWQ_PRE_NONE) {
+            return AWQ_ERR_BAD_ARGUMENT;
+        }
+        p[i].x = (const half_t *)d.x_f16;
+        p[i].q = (const uint4 *)d.qweight;
+        p[i].sc = (const uint16_t *)d.scales;
+        p[i].zp = (const uint8_t *)d.zeros;
+        p[i].y = (half_t *)d.y_f16;
+        p[i].N = (int)d.N;
+        p[i].K = (int)d.K;
+        e[i].pre = (const half_t *)descs[i].pre_f16;
+        e[i].res = (const half_t *)descs[i].residual_f16;
+        e[i].eps = descs[i].eps;
+        e[i].pre_op = descs[i].pre_op == AWQ_PRE_RMSNORM ? GEMV_PRE_RMSNORM : GEMV_PRE_NONE;
+    }
+    // a lone linear without a normalisation: the batch kernel (every shape, and the faster one
+    // for a single small matrix)
+    if (count == 1 && e[0].pre_op == GEMV_PRE_NONE)
+        return awq_gemv_launch_residual(p[0].x, p[0].q, p[0].sc, p[0].zp, p[0].y, e[0].res, (int)M, p[0].N,
+                                        p[0].K, (hipStream_t)stream);
+    for (int i = 0; i < count; ++i)
+        if (!awq_gemv_stream_fits(p[i].N, p[i].K, (int)M)) return AWQ_ERR_BAD_SHAPE;
+    int st = awq_gemv_stream_launch_fused(p, e, count, (int)M, (hipStream_t)stream);
+    return st == AWQ_GEMV_STREAM_UNFIT ? AWQ_ERR_BAD_SHAPE : st;
+}
+
+extern "C" int awq_w4a16_linear_fused_fits(int64_t N, int64_t K, int64_t M, int group)
+{
+    if (M <= 0 || M > 16 || awq_check_weight_shape(N, K, group) != AWQ_OK) return 0;
+    return awq_gemv_stream_fits((int)N, (int)K, (int)M) ? 1 : 0;
 }

@@ -138,6 +138,27 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert rn(ok, odd, None, 1, 128, 1e-5, ok, None) == -4
     assert rn(ok, ok, odd, 1, 128, 1e-5, ok, None) == -4
 
+    fm = lib.awq_w4a16_linear_fused_multi
+    ff = lib.awq_w4a16_linear_fused_fits
+    ff.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int]
+    assert ff(4096, 4096, 1, 128) == 1 and ff(4096, 11008, 4, 128) == 1 and ff(4096, 11008, 16, 128) == 0
+    assert ff(4096, 4096, 17, 128) == 0 and ff(4096, 4100, 1, 128) == 0 and ff(4096, 4096, 1, 64) == 0
+    fd = (awq.FusedDesc * 1)()
+    fd[0] = awq.FusedDesc(awq.LinearDesc(ok, ok, ok, ok, ok, 4096, 4096), None, None, 1e-5, 0)
+    fm.argtypes = [ctypes.POINTER(awq.FusedDesc), ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+    assert fm(None, 1, 1, 128, None) == -1 and fm(fd, 0, 1, 128, None) == -7 and fm(fd, 25, 1, 128, None) == -7
+    assert fm(fd, 1, 17, 128, None) == -2 and fm(fd, 1, 1, 64, None) != 0
+    fd[0].pre_op = 1                                       # normalisation without factors
+    assert fm(fd, 1, 1, 128, None) == -1
+    fd[0].pre_f16 = odd
+    assert fm(fd, 1, 1, 128, None) == -4
+    fd[0].pre_f16, fd[0].eps = ok, -1.0
+    assert fm(fd, 1, 1, 128, None) == -7
+    fd[0].eps, fd[0].pre_op = 1e-5, 5
+    assert fm(fd, 1, 1, 128, None) == -7
+    fd[0] = awq.FusedDesc(awq.LinearDesc(ok, ok, ok, ok, ok, 4096, 11008), ok, None, 1e-5, 1)
+    assert fm(fd, 1, 16, 128, None) == -2                  # with a normalisation: does not fit at M = 16
+
     sm = lib.awq_silu_mul
     sm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
     assert sm(None, ok, 8, ok, None) == -1 and sm(ok, ok, 8, None, None) == -1

@@ -982,6 +982,98 @@ def test_silu_mul(awq):
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -10 + 1e-7)
 
 
+def check_fused(awq, problems, M, norm=(), residual=(), in_place=()):
+    """One awq_w4a16_linear_fused_multi call over `problems` (as for check_multi).  Linears
+    whose index is in `norm` run on the RMS-normalised input times seeded factors, those in
+    `residual` add a seeded [M,N] tensor (those in `in_place` pass y itself as the residual).
+    Expected values: the oracle's normalisation, then its matmul, then the addition in fp64."""
+    import torch
+    import oracle
+    g = np.random.default_rng(500 + M)
+    linears, expect = [], []
+    for i, (xs, Wdq, gpu_packed, N) in enumerate(problems):
+        K = xs.shape[1]
+        h = xs[:M]
+        y, cy = guarded(M * N * 2, torch.float16)
+        y = y.view(M, N)
+        d = dict(x=dev(h), qweight=gpu_packed[0], scales=gpu_packed[1], zeros=gpu_packed[2], y=y, N=N)
+        x_eff = h
+        if i in norm:
+            w = g.uniform(0.25, 1.75, size=K).astype(np.float16)
+            d["norm"], d["eps"] = dev(w), 1e-5
+            x_eff = oracle.rmsnorm_inv_scale(h, w, None, 1e-5)
+        y_ref = oracle.matmul(x_eff, Wdq)
+        if i in residual or i in in_place:
+            res = (g.standard_normal((M, N)) * 2).astype(np.float16)
+            if i in in_place:
+                y.copy_(dev(res))
+                d["residual"] = y
+            else:
+                d["residual"] = dev(res)
+            y_ref = y_ref + res.astype(np.float64)
+        linears.append(d)
+        expect.append((x_eff, Wdq, y_ref, y, cy, N))
+    awq.awq_w4a16_linear_fused_multi(linears)
+    for x_eff, Wdq, y_ref, y, cy, N in expect:
+        cy()
+        yh = host(y)
+        assert np.all(np.isfinite(yh.astype(np.float32)))
+        err = oracle.norm_error(yh, y_ref, x_eff, Wdq)
+        den = np.linalg.norm(x_eff.astype(np.float64), axis=1)[:, None] * np.abs(Wdq).max() + 1e-6
+        # the output is rounded once to fp16 at the magnitude of residual + sum
+        allowed = TOL + 2.0 ** -11 * np.abs(y_ref) / den
+        assert np.all(err <= allowed), f"max normalised error {err.max():.3e} (N={N}, M={M})"
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 7, 8, 16])
+def test_fused_norm_and_residual_small(awq, small_group, M):
+    """K = 1408 (ragged groups), 2048 and 512: one wave or several along K depending on M."""
+    fits = [awq.awq_w4a16_linear_fused_fits(N, xs.shape[1], M) for xs, Wdq, gpu, N in small_group]
+    assert fits == ([True] * 4 if M < 16 else [False, False, True, True])   # 11 groups over 4 waves: no
+    group = [p for p, f in zip(small_group, fits) if f]
+    group = group if len(group) == 4 else group * 2
+    check_fused(awq, group, M, norm=(0, 2), residual=(1, 2), in_place=(3,))
+    check_fused(awq, group, M, norm=(0, 1, 2, 3))
+    check_fused(awq, group, M)                                         # nothing fused: plain grouped call
+    check_fused(awq, group[:1], M, norm=(0,), in_place=(0,))
+
+
+def test_fused_llama7b_layer_full_size(awq):
+    """The two launches of a decoder layer that carry fused operators: Q, K, V behind the
+    normalisation; gate, up behind the normalisation; o and down with the residual in place."""
+    probs = {}
+    for N, K in [(4096, 4096), (11008, 4096), (4096, 11008)]:
+        case, s, xs16, ref, gpu, Wdq = config_case(awq, N, K, 0.02, 1)
+        probs[(N, K)] = (xs16, Wdq, gpu, N)
+    for M in (1, 4):
+        check_fused(awq, [probs[(4096, 4096)]] * 3, M, norm=(0, 1, 2))
+        check_fused(awq, [probs[(11008, 4096)]] * 2, M, norm=(0, 1))
+        check_fused(awq, [probs[(4096, 4096)]], M, in_place=(0,))
+        check_fused(awq, [probs[(4096, 11008)]], M, in_place=(0,))
+    check_fused(awq, [probs[(4096, 4096)]] * 3, 16, norm=(0, 1, 2))
+
+
+def test_fused_rejects_what_it_cannot_run(awq, small_group):
+    import torch
+    xs, Wdq, gpu, N = small_group[0]
+    y = torch.empty((1, N), dtype=torch.float16, device="cuda")
+    base = dict(x=dev(xs[:1]), qweight=gpu[0], scales=gpu[1], zeros=gpu[2], y=y, N=N)
+    with pytest.raises(ValueError):
+        awq.prepare_linear_fused_multi([base] * 25)
+    with pytest.raises(ValueError):
+        awq.prepare_linear_fused_multi([dict(base, norm=dev(np.ones(7, np.float16)))])
+    # K = 11008 at M = 16 does not fit the register-resident activations of the streaming kernel
+    case, s, xs16, ref, gpu2, Wdq2 = config_case(awq, 4096, 11008, 0.02, 1)
+    y2 = torch.empty((16, 4096), dtype=torch.float16, device="cuda")
+    with pytest.raises(awq.AwqError) as e:
+        awq.awq_w4a16_linear_fused_multi([dict(x=dev(xs16), qweight=gpu2[0], scales=gpu2[1], zeros=gpu2[2],
+                                               y=y2, N=4096, norm=dev(np.ones(11008, np.float16)))])
+    assert e.value.status == -2
+    # ... but a lone linear with only a residual runs at every decode shape
+    check_fused(awq, [(xs16, Wdq2, gpu2, 4096)], 16, in_place=(0,))
+    check_fused(awq, [(xs16, Wdq2, gpu2, 4096)], 5, residual=(0,))
+
+
 # ------------------------------------------------------------------- decode attention
 
 ATT_TOL = 2e-3      # of max|v|: fp16 rounding of the output (2^-11) and fp32 sums / exponentials
