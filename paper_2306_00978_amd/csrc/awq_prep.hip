@@ -20,6 +20,8 @@ __global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict
                                                          int64_t T, int64_t K, float alpha,
                                                          float *__restrict__ s)
 {
+    // all arguments fetched in one round (otherwise one scalar-cache miss per first use)
+    asm volatile("" ::"s"(X), "s"(T), "s"(K), "s"(alpha), "s"(s));
     __shared__ float red[ACT_PHASES][ACT_COLS];
     const int oct = threadIdx.x & 7;
     const int phase = threadIdx.x >> 3;
@@ -60,6 +62,8 @@ __global__ __launch_bounds__(256) void apply_inv_scale_kernel(const uint4 *__res
                                                               int64_t runs_total, int64_t K8,
                                                               uint4 *__restrict__ xs)
 {
+    // all arguments fetched in one round (otherwise one scalar-cache miss per first use)
+    asm volatile("" ::"s"(x), "s"(s), "s"(runs_total), "s"(K8), "s"(xs));
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= runs_total) return;
     const int64_t run = i % K8;
@@ -85,12 +89,40 @@ __global__ __launch_bounds__(256) void rmsnorm_inv_scale_kernel(const uint4 *__r
                                                                 int64_t K8, float inv_k, float eps,
                                                                 uint4 *__restrict__ xs)
 {
+    // all arguments fetched in one round (otherwise one scalar-cache miss per first use)
+    asm volatile("" ::"s"(x), "s"(gamma), "s"(s), "s"(K8), "s"(inv_k), "s"(eps), "s"(xs));
     __shared__ float part[4];
     const uint4 *row = x + (int64_t)blockIdx.x * K8;
+    // The first KEEP x 256 runs of the row (K <= 8192: all of it) stay in registers, and their
+    // gamma and s are requested in the same round, before the reduction: a decode call is one
+    // short row, and every further round trip to memory would be a third of its time.
+    constexpr int KEEP = 4;
+    uint4 raw[KEEP], graw[KEEP];
+    float4 sa[KEEP], sb[KEEP];
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+        const int64_t i = threadIdx.x + 256 * j, ic = i < K8 ? i : K8 - 1;
+        raw[j] = row[ic];
+        graw[j] = gamma[ic];
+        if (s) {
+            sa[j] = s[2 * ic];
+            sb[j] = s[2 * ic + 1];
+        } else {
+            sa[j] = sb[j] = make_float4(1.f, 1.f, 1.f, 1.f);
+        }
+    }
     float ss = 0.f;
-    for (int64_t i = threadIdx.x; i < K8; i += 256) {
-        const uint4 raw = row[i];
-        const half_t *h = reinterpret_cast<const half_t *>(&raw);
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+        const half_t *h = reinterpret_cast<const half_t *>(&raw[j]);
+        float t = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t += (float)h[e] * (float)h[e];
+        ss += threadIdx.x + 256 * j < K8 ? t : 0.f;
+    }
+    for (int64_t i = threadIdx.x + 256 * KEEP; i < K8; i += 256) {
+        const uint4 r = row[i];
+        const half_t *h = reinterpret_cast<const half_t *>(&r);
 #pragma unroll
         for (int e = 0; e < 8; ++e) ss += (float)h[e] * (float)h[e];
     }
@@ -101,21 +133,24 @@ __global__ __launch_bounds__(256) void rmsnorm_inv_scale_kernel(const uint4 *__r
     const float total = (part[0] + part[1]) + (part[2] + part[3]);
     const float inv = 1.0f / sqrtf(total * inv_k + eps);
     uint4 *out = xs + (int64_t)blockIdx.x * K8;
-    for (int64_t i = threadIdx.x; i < K8; i += 256) {
-        const uint4 raw = row[i], graw = gamma[i];
-        const half_t *h = reinterpret_cast<const half_t *>(&raw);
-        const half_t *gm = reinterpret_cast<const half_t *>(&graw);
-        float sv[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
-        if (s) {
-            const float4 a = s[2 * i], b = s[2 * i + 1];
-            sv[0] = a.x; sv[1] = a.y; sv[2] = a.z; sv[3] = a.w;
-            sv[4] = b.x; sv[5] = b.y; sv[6] = b.z; sv[7] = b.w;
-        }
+    auto emit = [&](int64_t i, const uint4 &r, const uint4 &g, const float4 &a, const float4 &b) {
+        const half_t *h = reinterpret_cast<const half_t *>(&r);
+        const half_t *gm = reinterpret_cast<const half_t *>(&g);
+        const float sv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
         uint4 o;
         half_t *oh = reinterpret_cast<half_t *>(&o);
 #pragma unroll
         for (int e = 0; e < 8; ++e) oh[e] = (half_t)(((float)h[e] * inv) * (float)gm[e] / sv[e]);
         out[i] = o;
+    };
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+        const int64_t i = threadIdx.x + 256 * j;
+        if (i < K8) emit(i, raw[j], graw[j], sa[j], sb[j]);
+    }
+    for (int64_t i = threadIdx.x + 256 * KEEP; i < K8; i += 256) {
+        const float4 one = make_float4(1.f, 1.f, 1.f, 1.f);
+        emit(i, row[i], gamma[i], s ? s[2 * i] : one, s ? s[2 * i + 1] : one);
     }
 }
 
@@ -124,6 +159,8 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(const uint4 *__restrict__
                                                        const uint4 *__restrict__ up, int64_t n8,
                                                        uint4 *__restrict__ out)
 {
+    // all arguments fetched in one round (otherwise one scalar-cache miss per first use)
+    asm volatile("" ::"s"(gate), "s"(up), "s"(n8), "s"(out));
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n8) return;
     const uint4 graw = gate[i], uraw = up[i];

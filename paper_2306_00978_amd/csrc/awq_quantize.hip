@@ -80,6 +80,9 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
     int G, int NRB, int rb_per_wave, int num_units, ClipRatios ratios, uint8_t *__restrict__ choice,
     const uint4 *__restrict__ xs, int T)
 {
+    // every argument fetched in one round (otherwise: one scalar-cache miss per first use)
+    asm volatile("" ::"s"(W), "s"(s), "s"(qweight), "s"(scales), "s"(zeros), "s"(G), "s"(NRB), "s"(rb_per_wave),
+                 "s"(num_units), "s"(choice), "s"(xs), "s"(T));
     const int lane = threadIdx.x & 63;
     const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (unit >= num_units) return;                 // whole wave leaves together
