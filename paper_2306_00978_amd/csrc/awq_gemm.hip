@@ -170,6 +170,9 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(
     half_t *__restrict__ y, int M, int N, int K, int G, int tiles_n, int tiles_total)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    // all arguments fetched in one round (otherwise one scalar-cache miss per first use)
+    asm volatile("" ::"s"(x), "s"(qweight), "s"(scales), "s"(zeros), "s"(y), "s"(M), "s"(N), "s"(K), "s"(G),
+                 "s"(tiles_n), "s"(tiles_total));
     // Workgroups are handed to the eight XCDs round-robin by their linear id, and each XCD has
     // its own L2.  The tile a workgroup computes is therefore chosen so that an XCD gets a
     // contiguous range of tiles in token-block-major order: its workgroups then share a few x

@@ -28,6 +28,7 @@ struct AlphaList {
 __global__ __launch_bounds__(256) void pow_kernel(const float *__restrict__ mean, float alpha, int K,
                                                   float *__restrict__ s)
 {
+    asm volatile("" ::"s"(mean), "s"(alpha), "s"(K), "s"(s));           // arguments in one round
     const int k = blockIdx.x * 256 + threadIdx.x;
     if (k < K) s[k] = powf(mean[k], alpha);
 }
@@ -123,19 +124,32 @@ __global__ __launch_bounds__(256) void loss_kernel(const uint4 *__restrict__ Yq,
                                                    const uint4 *__restrict__ Y, int64_t chunks,
                                                    double *__restrict__ partial)
 {
+    asm volatile("" ::"s"(Yq), "s"(Y), "s"(chunks), "s"(partial));     // arguments in one round
     __shared__ double red[256];
     double acc = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (int64_t)LOSS_BLOCKS * 256) {
-        const uint4 a = Yq[i], b = Y[i];
-        const half_t *ha = reinterpret_cast<const half_t *>(&a);
-        const half_t *hb = reinterpret_cast<const half_t *>(&b);
-        float c = 0.f;
+    // four chunk pairs requested together (a chunk past the end re-reads the last one and is not
+    // counted); the order of the additions is the order of the chunks either way
+    const int64_t stride = (int64_t)LOSS_BLOCKS * 256;
+    for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < chunks; i0 += 4 * stride) {
+        uint4 a[4], b[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float d = (float)ha[e] - (float)hb[e];
-            c += d * d;
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = i0 + u * stride, ic = i < chunks ? i : chunks - 1;
+            a[u] = Yq[ic];
+            b[u] = Y[ic];
         }
-        acc += (double)c;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const half_t *ha = reinterpret_cast<const half_t *>(&a[u]);
+            const half_t *hb = reinterpret_cast<const half_t *>(&b[u]);
+            float c = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float d = (float)ha[e] - (float)hb[e];
+                c += d * d;
+            }
+            if (i0 + u * stride < chunks) acc += (double)c;
+        }
     }
     red[threadIdx.x] = acc;
     __syncthreads();
