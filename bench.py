@@ -413,7 +413,25 @@ def main():
             "bytes_per_step": b3, "ms_per_step": round(ms, 5), "GB/s": gbs(b3, ms),
             "pct_of_hbm_peak": round(100 * gbs(b3, ms) / HBM_PEAK_GBS, 2),
             "note": "compare decode_m1_7_single_launches (INT4): same launches, 0.76 of the bytes"}
-        del graphs3, lay3
+        # 3-bit prefill, M = 2048, 4096 x 4096: re-pack into the 4-bit layout + the 4-bit GEMM
+        Mp, (_, N3, K3) = workloads.PREFILL_M, shapes[0]
+        y3 = torch.empty((Mp, N3), dtype=torch.float16, device=dev)
+        ws3 = torch.empty(awq.load().awq_w3a16_prefill_workspace_bytes(N3, K3, 128), dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            awq.awq_w3a16_linear(x_by_k[K3], *lay3[0][0], N3, out=y3, workspace=ws3)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(20):
+            awq.awq_w3a16_linear(x_by_k[K3], *lay3[i % len(lay3)][0], N3, out=y3, workspace=ws3)
+        e1.record()
+        torch.cuda.synchronize()
+        ms3 = e0.elapsed_time(e1) / 20
+        extras["prefill_m2048_int3_4096x4096"] = {
+            "us": round(ms3 * 1e3, 2), "TFLOP/s": round(workloads.flops(Mp, N3, K3) / (ms3 * 1e-3) / 1e12, 1),
+            "note": "awq_w3a16_linear_prefill: codes re-packed into the 4-bit layout (one pass over the packed "
+                    "weights), then the 4-bit prefill kernel"}
+        del graphs3, lay3, y3, ws3
 
         # configs[3]: the seven projections of a Llama-2-70B-shaped layer (444.5 MB per launch), M = 1
         # and 8, one grouped launch per step, two distinct layers cycled

@@ -222,10 +222,26 @@ int awq_unpack_w3(const void *qweight, const void *scales, const void *zeros, in
                   int64_t K, int group, uint8_t *codes, void *scales_f16, uint8_t *zeros_u8,
                   void *stream);
 /* Sec. 4.2 decode kernel for the 3-bit layout: y = x' * dequant(q)^T, fp32 accumulation,
- * 1 <= M <= 16 (AWQ_ERR_BAD_SHAPE otherwise: there is no 3-bit prefill kernel). */
+ * 1 <= M <= 16 (AWQ_ERR_BAD_SHAPE otherwise: larger M goes through awq_w3a16_linear_prefill). */
 int awq_w3a16_linear(const void *x_f16, const void *qweight, const void *scales,
                      const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K, int group,
                      void *stream);
+/* Prefill (M > 16) for the 3-bit layout.  There is no 3-bit matrix-matrix kernel: the codes are
+ * re-packed into the 4-bit layout (the steps and zero points are stored identically in both, and
+ * a code 0..7 is a valid 4-bit code), then the prefill kernel of the 4-bit path runs on them --
+ * one extra pass over the packed weights, about a tenth of the GEMM's time at M = 2048.
+ *   awq_repack_w3_to_w4: qweight_w3 (N*K*3/8 bytes) -> qweight_w4 (N*K/2 bytes, written), both
+ *     device, 16-byte aligned; a caller with the memory can keep the result and use the 4-bit
+ *     calls with the 3-bit linear's scales and zeros.
+ *   awq_w3a16_linear_prefill: the two steps in one call; workspace (device, 16-byte aligned,
+ *     awq_w3a16_prefill_workspace_bytes() = N*K/2 bytes) holds the re-packed codes, contents
+ *     undefined afterwards.  M <= 16 returns AWQ_ERR_BAD_SHAPE (use awq_w3a16_linear). */
+int awq_repack_w3_to_w4(const void *qweight_w3, int64_t N, int64_t K, int group, void *qweight_w4,
+                        void *stream);
+size_t awq_w3a16_prefill_workspace_bytes(int64_t N, int64_t K, int group);
+int awq_w3a16_linear_prefill(const void *x_f16, const void *qweight, const void *scales,
+                             const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,
+                             int group, void *workspace, size_t workspace_bytes, void *stream);
 /* As awq_w4a16_linear_multi for linears in the 3-bit layout (no workspace). */
 int awq_w3a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
                            void *stream);

@@ -35,6 +35,7 @@ EXPORTS = [
     "awq_w3a16_linear_multi", "awq_rmsnorm_inv_scale", "awq_read_probe",
     "awq_decode_attention_workspace_bytes", "awq_decode_attention", "awq_silu_mul",
     "awq_w4a16_linear_fused_multi", "awq_w4a16_linear_fused_fits",
+    "awq_repack_w3_to_w4", "awq_w3a16_prefill_workspace_bytes", "awq_w3a16_linear_prefill",
 ]
 MULTI_MAX = 56
 
@@ -114,6 +115,12 @@ def load() -> ctypes.CDLL:
     lib.awq_w4a16_linear_fused_multi.argtypes = [ctypes.POINTER(FusedDesc), i32, i64, i32, vp]
     lib.awq_w4a16_linear_fused_fits.restype = i32
     lib.awq_w4a16_linear_fused_fits.argtypes = [i64, i64, i64, i32]
+    lib.awq_repack_w3_to_w4.restype = i32
+    lib.awq_repack_w3_to_w4.argtypes = [vp, i64, i64, i32, vp, vp]
+    lib.awq_w3a16_prefill_workspace_bytes.restype = ctypes.c_size_t
+    lib.awq_w3a16_prefill_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.awq_w3a16_linear_prefill.restype = i32
+    lib.awq_w3a16_linear_prefill.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
     lib.awq_silu_mul.restype = i32
     lib.awq_silu_mul.argtypes = [vp, vp, i64, vp, vp]
     lib.awq_read_probe.restype = i32
@@ -432,13 +439,34 @@ def awq_unpack_w3(qweight, scales, zeros, N: int, K: int, group: int = GROUP):
     return codes, sc, zp
 
 
-def awq_w3a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int = GROUP, out=None):
-    """y [M,N] fp16 = x [M,K] fp16 (already divided by s) times the 3-bit packed weight; M <= 16."""
+def awq_repack_w3_to_w4(qweight, N: int, K: int, group: int = GROUP, out=None):
+    """The codes of a 3-bit packed weight in the 4-bit layout (N*K/2 bytes); scales and zeros are
+    shared between the two layouts."""
+    if out is None:
+        out = torch.empty(N * K // 2, dtype=torch.uint8, device=qweight.device)
+    _check(load().awq_repack_w3_to_w4(_ptr(qweight), N, K, group, _ptr(out), _stream()), "awq_repack_w3_to_w4")
+    return out
+
+
+def awq_w3a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int = GROUP, out=None,
+                     workspace=None):
+    """y [M,N] fp16 = x [M,K] fp16 (already divided by s) times the 3-bit packed weight.  M <= 16:
+    the decode kernel; larger M: awq_w3a16_linear_prefill (workspace of N*K/2 bytes, allocated
+    here if not given)."""
     _dev(x, torch.float16, "x")
     M, K = x.shape
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=x.device)
     _dev(out, torch.float16, "y")
+    if M > 16:
+        need = int(load().awq_w3a16_prefill_workspace_bytes(N, K, group))
+        if workspace is None:
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+        _check(load().awq_w3a16_linear_prefill(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(out),
+                                               M, N, K, group, _ptr(workspace),
+                                               workspace.numel() * workspace.element_size(), _stream()),
+               "awq_w3a16_linear_prefill")
+        return out
     _check(load().awq_w3a16_linear(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(out), M, N, K,
                                    group, _stream()), "awq_w3a16_linear")
     return out

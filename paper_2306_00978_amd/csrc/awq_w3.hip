@@ -165,7 +165,66 @@ __global__ __launch_bounds__(256) void unpack_w3_kernel(
     }
 }
 
+// 3-bit slots -> 4-bit slots of the same tile: lane l owns the same 32 codes in both layouts, and
+// a pair read as (q, q') in the two halves goes to nibble i of both halves of word j
+__global__ __launch_bounds__(256) void repack_w3_to_w4_kernel(const uint32_t *__restrict__ q3,
+                                                              uint4 *__restrict__ q4, int num_tiles)
+{
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= num_tiles) return;
+    const uint32_t *src = q3 + (int64_t)tile * 192 + lane * 3;
+    const uint32_t w[3] = {src[0], src[1], src[2]};
+    const uint32_t last = w3_last_pair(w);
+    uint32_t out[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint4 f = w3_fragment(w, last, j);
+        out[j] = f.x | (f.y << 4) | (f.z << 8) | (f.w << 12);
+    }
+    q4[(int64_t)tile * 64 + lane] = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
 }  // namespace
+
+int awq_gemm_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
+                    void *y, int M, int N, int K, hipStream_t stream);
+
+extern "C" int awq_repack_w3_to_w4(const void *qweight_w3, int64_t N, int64_t K, int group,
+                                   void *qweight_w4, void *stream)
+{
+    if (!qweight_w3 || !qweight_w4) return AWQ_ERR_NULL_POINTER;
+    int st = awq_check_weight_shape(N, K, group);
+    if (st != AWQ_OK) return st;
+    if (!awq_aligned16(qweight_w3) || !awq_aligned16(qweight_w4)) return AWQ_ERR_MISALIGNED;
+    const int num_tiles = (int)(N / 16) * (int)(K / AWQ_GROUP);
+    repack_w3_to_w4_kernel<<<dim3((num_tiles + 3) / 4), dim3(256), 0, (hipStream_t)stream>>>(
+        (const uint32_t *)qweight_w3, (uint4 *)qweight_w4, num_tiles);
+    return awq_launch_status();
+}
+
+extern "C" size_t awq_w3a16_prefill_workspace_bytes(int64_t N, int64_t K, int group)
+{
+    if (awq_check_weight_shape(N, K, group) != AWQ_OK) return 0;
+    return (size_t)(N * K / 2);
+}
+
+extern "C" int awq_w3a16_linear_prefill(const void *x_f16, const void *qweight, const void *scales,
+                                        const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,
+                                        int group, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x_f16 || !qweight || !scales || !zeros || !y_f16 || !workspace) return AWQ_ERR_NULL_POINTER;
+    int st = awq_check_weight_shape(N, K, group);
+    if (st != AWQ_OK) return st;
+    if (M <= 16 || M > 0x7fffffff) return AWQ_ERR_BAD_SHAPE;   // M <= 16: awq_w3a16_linear
+    if (!awq_aligned16(x_f16) || !awq_aligned16(qweight) || !awq_aligned16(scales) ||
+        !awq_aligned16(zeros) || !awq_aligned16(y_f16) || !awq_aligned16(workspace))
+        return AWQ_ERR_MISALIGNED;
+    if (workspace_bytes < (size_t)(N * K / 2)) return AWQ_ERR_WORKSPACE_TOO_SMALL;
+    st = awq_repack_w3_to_w4(qweight, N, K, group, workspace, stream);
+    if (st != AWQ_OK) return st;
+    return awq_gemm_launch(x_f16, workspace, scales, zeros, y_f16, (int)M, (int)N, (int)K, (hipStream_t)stream);
+}
 
 extern "C" int awq_packed_sizes_w3(int64_t N, int64_t K, int group, size_t *qweight_bytes,
                                    size_t *scales_bytes, size_t *zeros_bytes)

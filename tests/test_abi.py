@@ -159,6 +159,22 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     fd[0] = awq.FusedDesc(awq.LinearDesc(ok, ok, ok, ok, ok, 4096, 11008), ok, None, 1e-5, 1)
     assert fm(fd, 1, 16, 128, None) == -2                  # with a normalisation: does not fit at M = 16
 
+    rp = lib.awq_repack_w3_to_w4
+    rp.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    assert rp(None, 16, 128, 128, ok, None) == -1 and rp(ok, 16, 100, 128, ok, None) == -2
+    assert rp(ok, 16, 128, 128, odd, None) == -4 and rp(ok, 16, 128, 64, ok, None) == -3
+    wb = lib.awq_w3a16_prefill_workspace_bytes
+    wb.restype = ctypes.c_size_t
+    wb.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+    assert wb(4096, 4096, 128) == 4096 * 4096 // 2 and wb(4096, 100, 128) == 0
+    pf = lib.awq_w3a16_linear_prefill
+    pf.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int64] * 3 + [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                                                 ctypes.c_void_p]
+    assert pf(ok, ok, ok, ok, ok, 64, 16, 128, 128, None, 1 << 20, None) == -1
+    assert pf(ok, ok, ok, ok, ok, 16, 16, 128, 128, ok, 1 << 20, None) == -2      # decode sizes: the other call
+    assert pf(ok, ok, ok, ok, ok, 64, 16, 128, 128, odd, 1 << 20, None) == -4
+    assert pf(ok, ok, ok, ok, ok, 64, 16, 128, 128, ok, 1023, None) == -5
+
     sm = lib.awq_silu_mul
     sm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
     assert sm(None, ok, 8, ok, None) == -1 and sm(ok, ok, 8, None, None) == -1

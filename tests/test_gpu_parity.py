@@ -816,6 +816,35 @@ def test_w3_edge_groups_and_exactness_on_integer_data(awq):
         assert np.array_equal(y1.astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
 
 
+@pytest.mark.parametrize("N,K", [(48, 640), (176, 1408), (272, 256)])
+def test_w3_repack_and_prefill(awq, N, K):
+    """The 3-bit codes re-packed into the 4-bit layout unpack to the same codes, and the prefill
+    call (re-pack + the 4-bit matrix-matrix kernel) matches the oracle at ragged M."""
+    import torch
+    import oracle
+    case, s, xs = make_case(N, K, 16, 0.02, cfg=0, proj=2)
+    (codes, scales, zeros), gpu = quantize_w3_bit_exact(awq, case.W, s)
+    q4 = awq.awq_repack_w3_to_w4(gpu[0], N, K)
+    c4, s4, z4 = awq.awq_unpack(q4, gpu[1], gpu[2], N, K)
+    assert np.array_equal(host(c4), codes)
+    assert np.array_equal(host(s4).view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(host(z4), zeros)
+    Wdq = oracle.dequant(codes, scales, zeros)
+    g = np.random.default_rng(77)
+    for M in (17, 64, 129, 300):
+        x = np.tile(xs, ((M + 15) // 16, 1))[:M] * g.uniform(0.5, 1.5, size=(M, 1)).astype(np.float16)
+        x = x.astype(np.float16)
+        y, cy = guarded(M * N * 2, torch.float16)
+        awq.awq_w3a16_linear(dev(x), *gpu, N, out=y.view(M, N))
+        cy()
+        yh = host(y.view(M, N))
+        err = oracle.norm_error(yh, oracle.matmul(x, Wdq), x, Wdq)
+        assert err.max() <= TOL, f"max normalised error {err.max():.3e} (M={M})"
+    with pytest.raises(awq.AwqError) as e:          # too small a workspace is refused
+        awq.awq_w3a16_linear(dev(np.tile(xs, (2, 1))), *gpu, N, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -5
+
+
 @pytest.mark.parametrize("N,K", [(4096, 4096), (4096, 11008)])
 def test_w3_llama7b_shapes_full_size(awq, N, K):
     import oracle
@@ -825,9 +854,7 @@ def test_w3_llama7b_shapes_full_size(awq, N, K):
     Wdq = oracle.dequant(*ref)
     for M in (1, 4, 16):
         check_linear_w3(awq, xs[:M], Wdq, gpu, N)
-    with pytest.raises(awq.AwqError) as e:                   # no 3-bit prefill kernel
-        awq.awq_w3a16_linear(torch.zeros((17, K), dtype=torch.float16, device="cuda"), *gpu, N)
-    assert e.value.status == -2
+    check_linear_w3(awq, np.tile(xs, (3, 1))[:40], Wdq, gpu, N)      # M = 40: re-pack + the 4-bit GEMM
 
 
 def check_multi_w3(awq, problems, M):
