@@ -180,9 +180,12 @@ int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, i
  *       x'[m,k] = fp16( x[m,k] * rsqrt(mean_k x[m,k]^2 + eps) * pre[k] ),
  *     pre_f16 [K] fp16 (device, 16-byte aligned) = norm weight / AWQ scale s of Eq. 4 (the
  *     composition awq_rmsnorm_inv_scale computes with gamma and s apart), fp32 inside;
+ *   pre_op == AWQ_PRE_SCALE: the division by s of Eq. 4 as a multiplication inside the launch,
+ *       x'[m,k] = fp16( x[m,k] * pre[k] ),  pre_f16 [K] fp16 = 1/s (for a linear whose input
+ *     comes from an operator the factor cannot be folded into);
  *   residual_f16 != NULL: y[m,n] = fp16( residual[m,n] + sum ), [M,N] fp16 (device); it may be
  *     y_f16 itself (in-place accumulation into the hidden state).
- * A call with one linear and no normalisation runs at every decode shape.  Otherwise every
+ * A call with one linear and pre_op == AWQ_PRE_NONE runs at every decode shape.  Otherwise every
  * linear must fit the streaming decode kernel at this M: its activations stay in the
  * registers of the at most eight waves that share a row block, 8192 / M' columns per wave with
  * M' = M rounded up to a power of two (so K <= 65536 / M', and K not so short that a wave would
@@ -191,10 +194,11 @@ int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, i
  * M <= 16, count <= AWQ_FUSED_MAX.  `descs` is a HOST array, read before the call returns. */
 #define AWQ_PRE_NONE 0
 #define AWQ_PRE_RMSNORM 1
+#define AWQ_PRE_SCALE 2
 #define AWQ_FUSED_MAX 24
 typedef struct awq_fused_desc {
     awq_linear_desc linear;
-    const void *pre_f16;        /* AWQ_PRE_RMSNORM: [K] fp16 factors; else ignored */
+    const void *pre_f16;        /* AWQ_PRE_RMSNORM, AWQ_PRE_SCALE: [K] fp16 factors; else ignored */
     const void *residual_f16;   /* [M,N] fp16 or NULL */
     float eps;
     int pre_op;

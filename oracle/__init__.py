@@ -395,3 +395,11 @@ def silu_mul(gate, up) -> np.ndarray:
     g = np.asarray(gate, dtype=np.float16).astype(np.float64)
     u = np.asarray(up, dtype=np.float16).astype(np.float64)
     return (g / (1.0 + np.exp(-g)) * u).astype(np.float32).astype(np.float16)
+
+
+def scale_columns(x, w) -> np.ndarray:
+    """Sec. 3.2, Eq. 4, the diag(s)^-1 factor applied as a multiplication by w = 1/s given in
+    fp16: x'[m,k] = fp16(x[m,k] * w[k]), the product formed exactly (fp64) and rounded once."""
+    x = np.asarray(x, dtype=np.float16).astype(np.float64)
+    w = np.asarray(w, dtype=np.float16).astype(np.float64)
+    return (x * w[None, :]).astype(np.float16)

@@ -54,7 +54,7 @@ class FusedDesc(ctypes.Structure):
                 ("eps", ctypes.c_float), ("pre_op", ctypes.c_int)]
 
 
-PRE_NONE, PRE_RMSNORM, FUSED_MAX = 0, 1, 24
+PRE_NONE, PRE_RMSNORM, PRE_SCALE, FUSED_MAX = 0, 1, 2, 24
 
 
 class AwqError(RuntimeError):
@@ -571,7 +571,8 @@ def awq_silu_mul(gate: torch.Tensor, up: torch.Tensor, out: torch.Tensor | None 
 def prepare_linear_fused_multi(linears, group: int = GROUP):
     """Marshal one fused grouped decode call.  `linears` is a list of dicts with the keys
     x, qweight, scales, zeros, y, N and optionally norm (fp16 [K] factors: the linear then runs on
-    the RMS-normalised x times these), eps, residual (fp16 [M,N], added to the output; may be y).
+    the RMS-normalised x times these) with eps, or scale (fp16 [K]: the linear runs on x times
+    these), and residual (fp16 [M,N], added to the output; may be y).
     Returns a zero-argument callable that enqueues ONE awq_w4a16_linear_fused_multi."""
     if not 1 <= len(linears) <= FUSED_MAX:
         raise ValueError(f"1..{FUSED_MAX} linears per fused call")
@@ -591,20 +592,24 @@ def prepare_linear_fused_multi(linears, group: int = GROUP):
         if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
                 or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
             raise ValueError("buffer sizes do not match the shape")
-        norm, res = l.get("norm"), l.get("residual")
-        if norm is not None:
-            _dev(norm, torch.float16, "norm")
-            if norm.numel() != K:
-                raise ValueError("norm must have K elements")
+        norm, res, scale = l.get("norm"), l.get("residual"), l.get("scale")
+        if norm is not None and scale is not None:
+            raise ValueError("a linear takes a normalisation or a column scale, not both")
+        pre = norm if norm is not None else scale
+        if pre is not None:
+            _dev(pre, torch.float16, "norm/scale")
+            if pre.numel() != K:
+                raise ValueError("norm / scale must have K elements")
         if res is not None:
             _dev(res, torch.float16, "residual")
             if res.numel() != M * N:
                 raise ValueError("residual must be [M,N]")
         descs[i] = FusedDesc(LinearDesc(x.data_ptr(), qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
                                         y.data_ptr(), N, K),
-                             norm.data_ptr() if norm is not None else None,
+                             pre.data_ptr() if pre is not None else None,
                              res.data_ptr() if res is not None else None,
-                             float(l.get("eps", 1e-5)), PRE_RMSNORM if norm is not None else PRE_NONE)
+                             float(l.get("eps", 1e-5)),
+                             PRE_RMSNORM if norm is not None else (PRE_SCALE if scale is not None else PRE_NONE))
     fn = load().awq_w4a16_linear_fused_multi
     count = len(linears)
     keep = list(linears)

@@ -35,9 +35,9 @@ static_assert(sizeof(GemvLaunch) <= 4096, "kernel arguments are limited to 4 KB"
 
 // Operators fused into a linear of a grouped launch (Sec. 4.2, kernel fusion).
 constexpr int GEMV_MAX_FUSED = 24;        // linears per fused launch (24 more bytes each)
-constexpr int GEMV_PRE_NONE = 0, GEMV_PRE_RMSNORM = 1;
+constexpr int GEMV_PRE_NONE = 0, GEMV_PRE_RMSNORM = 1, GEMV_PRE_SCALE = 2;
 struct GemvFusedExtra {
-    const half_t *pre;        // RMSNORM: [K] fp16 factors (gamma / s); else unused
+    const half_t *pre;        // RMSNORM, SCALE: [K] fp16 factors (gamma / s, 1 / s); else unused
     const half_t *res;        // [M,N] fp16 added to the output, or null
     float eps;
     int pre_op;

@@ -46,6 +46,18 @@
 // Output.  The running sums are folded across slots with cross-lane permutes; waves that
 // share a row block (KS > 1) meet in LDS (one barrier per iteration), are added in a
 // fixed order (deterministic), rounded once to fp16 and stored.
+//
+// Start-up.  A launch lives for 10-25 us, so the microsecond before the first weight request
+// counts: the linear's entry of the kernel-argument block is fetched with vector loads (lane l
+// takes entry l, a ballot and readlanes pick the workgroup's), and the activation fragments
+// with unconditional loads from clamped addresses, so that everything is in flight in two
+// rounds instead of a chain of misses.
+//
+// FUSED form (Sec. 4.2, fusion of the small operators around a linear).  The activations of a
+// wave are already in its registers, so an RMS normalisation in front of the linear is a sum of
+// squares over them (lanes of one token by shuffles, waves that split K through LDS) and one
+// rescaling pass with mixed-precision fma instructions; a residual is added to the fp32 sums
+// right before the one rounding to fp16.  Neither needs a launch or a pass over memory.
 #include "awq_common.h"
 #include "awq_gemv_stream.h"
 
@@ -436,7 +448,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
             for (int j = 0; j < 4; ++j)
                 xa[4 * u + j] = __builtin_bit_cast(uint4, *(gbl_u32x4_t *)(xrow + gs * 128 + 32 * j));
         }
-        if (FUSED && pre_op == GEMV_PRE_RMSNORM) {   // the factors of the same columns
+        if (FUSED && pre_op != GEMV_PRE_NONE) {      // the factors of the same columns
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int gs = okx[u] ? 4 * bl + u : 0;
@@ -468,29 +480,33 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
     // FUSED, RMS normalisation in front of the linear: x' = fp16(x * rsqrt(mean_k x^2 + eps) * w_k).
     // The fragments of a wave hold its K-slice of token r % Mpad once (lanes of the same token
     // differ in c and in the slot bits of r); the waves that split K meet in LDS.
-    if (FUSED && pre_op == GEMV_PRE_RMSNORM) {
-        float ss = 0.f;
+    // (SCALE: the rescaling pass alone, x' = fp16(x * w_k).)
+    if (FUSED && pre_op != GEMV_PRE_NONE) {
+        float rinv = 1.0f;
+        if (pre_op == GEMV_PRE_RMSNORM) {
+            float ss = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            ss = mix_sum_squares(xa[i].x, ss);
-            ss = mix_sum_squares(xa[i].y, ss);
-            ss = mix_sum_squares(xa[i].z, ss);
-            ss = mix_sum_squares(xa[i].w, ss);
+            for (int i = 0; i < 16; ++i) {
+                ss = mix_sum_squares(xa[i].x, ss);
+                ss = mix_sum_squares(xa[i].y, ss);
+                ss = mix_sum_squares(xa[i].z, ss);
+                ss = mix_sum_squares(xa[i].w, ss);
+            }
+            ss += __shfl_xor(ss, 16);
+            ss += __shfl_xor(ss, 32);
+            if (mlog < 4) ss += __shfl_xor(ss, 8);
+            if (mlog < 3) ss += __shfl_xor(ss, 4);
+            if (mlog < 2) ss += __shfl_xor(ss, 2);
+            if (mlog < 1) ss += __shfl_xor(ss, 1);
+            if (KS > 1) {
+                float *nred = red + 2 * red_floats;                 // [wave][16]
+                if (c == 0) nred[wave * 16 + r] = ss;
+                __syncthreads();
+                ss = 0.f;
+                for (int k = 0; k < KS; ++k) ss += nred[((ri << ksl) + k) * 16 + r];
+            }
+            rinv = rsqrtf(ss / (float)K + eps);
         }
-        ss += __shfl_xor(ss, 16);
-        ss += __shfl_xor(ss, 32);
-        if (mlog < 4) ss += __shfl_xor(ss, 8);
-        if (mlog < 3) ss += __shfl_xor(ss, 4);
-        if (mlog < 2) ss += __shfl_xor(ss, 2);
-        if (mlog < 1) ss += __shfl_xor(ss, 1);
-        if (KS > 1) {
-            float *nred = red + 2 * red_floats;                 // [wave][16]
-            if (c == 0) nred[wave * 16 + r] = ss;
-            __syncthreads();
-            ss = 0.f;
-            for (int k = 0; k < KS; ++k) ss += nred[((ri << ksl) + k) * 16 + r];
-        }
-        const float rinv = rsqrtf(ss / (float)K + eps);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             xa[i].x = mix_scale_pair(xa[i].x, rinv, wn[i].x);

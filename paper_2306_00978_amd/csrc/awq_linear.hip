@@ -135,10 +135,10 @@ extern "C" int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int cou
         if (!awq_aligned16(d.x_f16) || !awq_aligned16(d.qweight) || !awq_aligned16(d.scales) ||
             !awq_aligned16(d.zeros) || !awq_aligned16(d.y_f16))
             return AWQ_ERR_MISALIGNED;
-        if (descs[i].pre_op == AWQ_PRE_RMSNORM) {
+        if (descs[i].pre_op == AWQ_PRE_RMSNORM || descs[i].pre_op == AWQ_PRE_SCALE) {
             if (!descs[i].pre_f16) return AWQ_ERR_NULL_POINTER;
             if (!awq_aligned16(descs[i].pre_f16)) return AWQ_ERR_MISALIGNED;
-            if (!(descs[i].eps >= 0.0f)) return AWQ_ERR_BAD_ARGUMENT;
+            if (descs[i].pre_op == AWQ_PRE_RMSNORM && !(descs[i].eps >= 0.0f)) return AWQ_ERR_BAD_ARGUMENT;
         } else if (descs[i].pre_op != AWQ_PRE_NONE) {
             return AWQ_ERR_BAD_ARGUMENT;
         }
@@ -152,7 +152,8 @@ extern "C" int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int cou
         e[i].pre = (const half_t *)descs[i].pre_f16;
         e[i].res = (const half_t *)descs[i].residual_f16;
         e[i].eps = descs[i].eps;
-        e[i].pre_op = descs[i].pre_op == AWQ_PRE_RMSNORM ? GEMV_PRE_RMSNORM : GEMV_PRE_NONE;
+        e[i].pre_op = descs[i].pre_op == AWQ_PRE_RMSNORM ? GEMV_PRE_RMSNORM
+                      : descs[i].pre_op == AWQ_PRE_SCALE ? GEMV_PRE_SCALE : GEMV_PRE_NONE;
     }
     // a lone linear without a normalisation: the batch kernel (every shape, and the faster one
     // for a single small matrix)

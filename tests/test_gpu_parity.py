@@ -1009,7 +1009,7 @@ def test_silu_mul(awq):
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -10 + 1e-7)
 
 
-def check_fused(awq, problems, M, norm=(), residual=(), in_place=()):
+def check_fused(awq, problems, M, norm=(), residual=(), in_place=(), scale=()):
     """One awq_w4a16_linear_fused_multi call over `problems` (as for check_multi).  Linears
     whose index is in `norm` run on the RMS-normalised input times seeded factors, those in
     `residual` add a seeded [M,N] tensor (those in `in_place` pass y itself as the residual).
@@ -1029,6 +1029,10 @@ def check_fused(awq, problems, M, norm=(), residual=(), in_place=()):
             w = g.uniform(0.25, 1.75, size=K).astype(np.float16)
             d["norm"], d["eps"] = dev(w), 1e-5
             x_eff = oracle.rmsnorm_inv_scale(h, w, None, 1e-5)
+        elif i in scale:
+            w = g.uniform(0.25, 1.75, size=K).astype(np.float16)
+            d["scale"] = dev(w)
+            x_eff = oracle.scale_columns(h, w)
         y_ref = oracle.matmul(x_eff, Wdq)
         if i in residual or i in in_place:
             res = (g.standard_normal((M, N)) * 2).astype(np.float16)
@@ -1061,6 +1065,7 @@ def test_fused_norm_and_residual_small(awq, small_group, M):
     group = group if len(group) == 4 else group * 2
     check_fused(awq, group, M, norm=(0, 2), residual=(1, 2), in_place=(3,))
     check_fused(awq, group, M, norm=(0, 1, 2, 3))
+    check_fused(awq, group, M, norm=(0,), scale=(1, 3), residual=(3,))
     check_fused(awq, group, M)                                         # nothing fused: plain grouped call
     check_fused(awq, group[:1], M, norm=(0,), in_place=(0,))
 

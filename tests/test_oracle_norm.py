@@ -49,3 +49,13 @@ def test_silu_mul_special_values():
     assert y[0] == 0.0 and abs(y[1] - 40.0) < 0.05 and abs(y[2]) < 1e-6
     assert abs(y[3] - 0.7310585786) < 1e-3 and abs(y[4] + 0.2689414214) < 1e-3     # x * sigmoid(x)
     assert abs(y[3] + y[4] - 0.4621171573) < 1e-3                                      # silu(x) + silu(-x) = x tanh(x/2)
+
+
+def test_scale_columns_rounds_once():
+    x = np.array([[1.0, 3.0, 0.333251953125, 65504.0, 6e-8]], np.float16)
+    w = np.array([0.5, 0.333251953125, 3.0, 0.5, 0.5], np.float16)
+    y = oracle.scale_columns(x, w)[0]
+    assert y[0] == np.float16(0.5) and y[3] == np.float16(32752.0)
+    assert y[1] == y[2]                                         # commutative, one rounding
+    assert abs(float(y[1]) - 0.999755859375) <= 2.0 ** -11      # 3 * fp16(1/3) rounded to fp16
+    assert float(y[4]) in (0.0, 5.960464477539063e-08)         # subnormal result stays representable
