@@ -112,25 +112,27 @@ __device__ __forceinline__ half8_t w3_halves(const uint32_t (&w)[3], uint32_t la
     return __builtin_bit_cast(half8_t, make_uint4(t[0], t[1], t[2], t[3]));
 }
 
-constexpr int GEMV_STAGE_MAX_M = 4;   // activations of up to this many rows go through LDS
+constexpr int GEMV_STAGE_MAX_M = 16;  // activations of up to this many rows go through LDS
 
 // Decode kernel.
 // U     = tiles (groups) per batch, a divisor of G: 1, 2 or 4.  A wave owns whole batches.
 // PIPE  = double-buffer the batches (only worth its registers when a wave has several).
-// MS > 0 (M <= MS <= 4): each wave copies the slice of x that its batch needs (MS rows x
-//   U*128 halves; rows >= M repeat row M-1) into a private LDS area with ONE coalesced
-//   16-byte load per lane and row, issued before the weight loads so that it returns first,
+// MS > 0 (M <= MS <= 16): each wave copies the slice of x that its batch needs (MS rows x
+//   U*128 halves; rows >= M repeat row M-1) into a private LDS area with one coalesced
+//   16-byte load per lane for every 64/(16 U) rows, issued before the weight loads so that it returns first,
 //   and then reads its A fragments from LDS.  No workgroup barrier is involved, so a wave
 //   starts computing as soon as its own weights arrive.  With few rows most lanes of an A
 //   fragment are duplicates, which is why this is cheaper than loading fragments from
 //   global memory.
-// MS == 0 (M > 4): A fragments are loaded straight from global memory (L2 hits).
+// MS == 0: A fragments are loaded straight from global memory (L2 hits); kept for reference,
+//   the launcher stages every decode M (fragment loads at the point of use are round trips
+//   to L2 in the middle of a batch).
 //
 // The workgroup has W = 2^logW waves; wave w owns batches [NB*w/W, NB*(w+1)/W), NB = G/U.
 // Dynamic LDS: [W][MS rows x (U*256 + 16) bytes], then 16*M outputs x 16 wave slots of
 // fp32 for the cross-wave reduction.
 template <int BITS, int U, int MS, bool PIPE>
-__global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void gemv_kernel(
+__global__ __launch_bounds__(1024, (MS >= 8 || (U == 4 && (PIPE || MS == 0 || (BITS == 3 && MS == 4)))) ? 4 : 6) void gemv_kernel(
     const half_t *__restrict__ x, const uint32_t *__restrict__ qweight,
     const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
     half_t *y, int M, int N, int K, int G, int logW, const half_t *res)
@@ -143,7 +145,10 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
                  "s"(logW), "s"(res));
     const ExpandConsts kc = expand_consts();
     constexpr bool STAGE = MS > 0;
-    constexpr int NS = STAGE ? MS : 1;
+    // staging: a row of the batch is U*16 lanes wide, so one 16-byte load per lane covers
+    // RPP = 64 / (U*16) rows; NS passes cover the MS rows
+    constexpr int LPR = U * 16, RPP = 64 / LPR;
+    constexpr int NS = STAGE ? (MS + RPP - 1) / RPP : 1;
     constexpr int ROW_BYTES = U * 256 + 16;           // +16: rows land on different banks
     constexpr int WAVE_BYTES = MS * ROW_BYTES;
     const int lane = threadIdx.x & 63;
@@ -166,13 +171,20 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
     unsigned char *xw = smem + (size_t)wave * WAVE_BYTES;                 // this wave's x slice
     const uint4 *xl = reinterpret_cast<const uint4 *>(xw + mrow * ROW_BYTES) + c;
     const uint4 *xg = reinterpret_cast<const uint4 *>(x + (int64_t)mrow * K) + c;
-    const bool stager = STAGE && (U == 4 || lane < U * 16);
-
-    // staging source of this lane: row m (clamped to M-1), 16-byte chunk `lane` of the batch
-    const uint4 *xsrc[NS];
-#pragma unroll
-    for (int m = 0; m < NS; ++m)
-        xsrc[m] = reinterpret_cast<const uint4 *>(x + (int64_t)(m < M ? m : M - 1) * K) + lane;
+    // staging source of this lane in pass i: row i*RPP + lane/LPR (clamped to M-1 for the load,
+    // not stored when >= MS), 16-byte chunk lane%LPR of the batch
+    const int srow = lane / LPR, schunk = lane % LPR;
+    const uint4 *xstage = reinterpret_cast<const uint4 *>(x) + schunk;
+    const int64_t K8 = (int64_t)K >> 3;
+    auto stage_src = [&](int i, int g) -> const uint4 & {
+        const int m = i * RPP + srow;
+        return xstage[(int64_t)(m < M ? m : M - 1) * K8 + g * 16];
+    };
+    auto stage_store = [&](int i, const uint4 &v) {
+        const int m = i * RPP + srow;
+        if (MS % RPP == 0 || m < MS) reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[schunk] = v;
+    };
+    constexpr bool stager = STAGE;
 
     TileBatch<BITS, U> cur;
     uint4 xs[NS];
@@ -181,7 +193,7 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
     if (g0 < g1) {
         if (stager) {                              // first: it must not wait for the weights
 #pragma unroll
-            for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][g0 * 16];
+            for (int m = 0; m < NS; ++m) xs[m] = stage_src(m, g0);
         }
         load_batch<BITS, U>(cur, qt, sc, zp, g0);
     }
@@ -190,7 +202,7 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
     for (int base = g0; base < g1; base += U) {
         if (stager) {                              // LDS ops of one wave execute in order
 #pragma unroll
-            for (int m = 0; m < NS; ++m) reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[lane] = xs[m];
+            for (int m = 0; m < NS; ++m) stage_store(m, xs[m]);
         }
         // PIPE: the next batch is requested before this one is consumed
         TileBatch<BITS, U> nxt;
@@ -198,7 +210,7 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
         if (PIPE && more) {
             if (stager) {
 #pragma unroll
-                for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][(base + U) * 16];
+                for (int m = 0; m < NS; ++m) xs[m] = stage_src(m, base + U);
             }
             load_batch<BITS, U>(nxt, qt, sc, zp, base + U);
         }
@@ -256,7 +268,7 @@ __global__ __launch_bounds__(1024, (U == 4 && (PIPE || MS == 0)) ? 4 : 6) void g
         } else if (more) {
             if (stager) {
 #pragma unroll
-                for (int m = 0; m < NS; ++m) xs[m] = xsrc[m][(base + U) * 16];
+                for (int m = 0; m < NS; ++m) xs[m] = stage_src(m, base + U);
             }
             load_batch<BITS, U>(cur, qt, sc, zp, base + U);
         }
@@ -313,6 +325,23 @@ int pick_unroll(int G)
 
 namespace {
 
+// one instantiation: raises its dynamic-LDS limit once if the launch needs more than 64 KB
+template <int BITS, int U, int MS, bool PIPE>
+int gemv_launch_one(dim3 grid, dim3 block, size_t lds, hipStream_t stream, const half_t *x,
+                    const uint32_t *qweight, const uint16_t *scales, const uint8_t *zeros, half_t *y, int M,
+                    int N, int K, int G, int logW, const half_t *res)
+{
+    static bool raised = false;
+    if (lds > 64 * 1024 && !raised) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_kernel<BITS, U, MS, PIPE>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return AWQ_ERR_HIP;
+        raised = true;
+    }
+    gemv_kernel<BITS, U, MS, PIPE><<<grid, block, lds, stream>>>(x, qweight, scales, zeros, y, M, N, K, G, logW, res);
+    return awq_launch_status();
+}
+
 template <int BITS>
 int gemv_launch_bits(const void *x, const void *qweight, const void *scales, const void *zeros,
                      void *y, int M, int N, int K, hipStream_t stream, const void *res = nullptr)
@@ -320,40 +349,43 @@ int gemv_launch_bits(const void *x, const void *qweight, const void *scales, con
     const int G = K / AWQ_GROUP;
     const int logW = pick_log_waves(G);
     const int W = 1 << logW;
-    const int U = pick_unroll(G);
+    // every decode M stages its activations through LDS: 1, 2, 4, 8 or 16 rows per wave
+    const int MS = M == 1 ? 1 : (M == 2 ? 2 : (M <= 4 ? 4 : (M <= 8 ? 8 : 16)));
+    int U = pick_unroll(G);
+    if (MS == 16 && U == 4) U = 2;                  // 16 waves x 16 rows x 4 groups would not fit in LDS
     const dim3 grid(N / 16), block(W * 64);
     const bool pipe = (G / U + W - 1) / W > 1;      // some wave has more than one batch
-    const int MS = M > GEMV_STAGE_MAX_M ? 0 : (M == 1 ? 1 : (M == 2 ? 2 : 4));
     // reduction area: 16*M outputs x 16 wave slots x 4 bytes, after the staging areas
     // (a lane parks four token rows at once: the area covers M rounded up to a multiple of 4)
     const size_t lds = (size_t)((M + 3) / 4 * 4) * 1024 + (size_t)W * MS * (U * 256 + 16);
-#define AWQ_GEMV_ARGS (const half_t *)x, (const uint32_t *)qweight, (const uint16_t *)scales, \
-                      (const uint8_t *)zeros, (half_t *)y, M, N, K, G, logW, (const half_t *)res
-#define AWQ_GEMV_LAUNCH(UU, MM, PP) gemv_kernel<BITS, UU, MM, PP><<<grid, block, lds, stream>>>(AWQ_GEMV_ARGS)
-#define AWQ_GEMV_CASE(UU)                                                                   \
-    case UU:                                                                                \
-        if (pipe) {                                                                         \
-            if (MS == 1) AWQ_GEMV_LAUNCH(UU, 1, true);                                      \
-            else if (MS == 2) AWQ_GEMV_LAUNCH(UU, 2, true);                                 \
-            else if (MS == 4) AWQ_GEMV_LAUNCH(UU, 4, true);                                 \
-            else AWQ_GEMV_LAUNCH(UU, 0, true);                                              \
-        } else {                                                                            \
-            if (MS == 1) AWQ_GEMV_LAUNCH(UU, 1, false);                                     \
-            else if (MS == 2) AWQ_GEMV_LAUNCH(UU, 2, false);                                \
-            else if (MS == 4) AWQ_GEMV_LAUNCH(UU, 4, false);                                \
-            else AWQ_GEMV_LAUNCH(UU, 0, false);                                             \
-        }                                                                                   \
-        break;
-    switch (U) {
-    AWQ_GEMV_CASE(1)
-    AWQ_GEMV_CASE(2)
-    default:
-    AWQ_GEMV_CASE(4)
+    if (lds > (size_t)160 * 1024) return AWQ_ERR_BAD_SHAPE;
+#define AWQ_GEMV_LAUNCH(UU, MM, PP)                                                                   \
+    return gemv_launch_one<BITS, UU, MM, PP>(grid, block, lds, stream, (const half_t *)x,             \
+                                             (const uint32_t *)qweight, (const uint16_t *)scales,     \
+                                             (const uint8_t *)zeros, (half_t *)y, M, N, K, G, logW,   \
+                                             (const half_t *)res)
+#define AWQ_GEMV_ROWS(UU, PP)                                                               \
+    switch (MS) {                                                                           \
+    case 1: AWQ_GEMV_LAUNCH(UU, 1, PP);                                                     \
+    case 2: AWQ_GEMV_LAUNCH(UU, 2, PP);                                                     \
+    case 4: AWQ_GEMV_LAUNCH(UU, 4, PP);                                                     \
+    case 8: AWQ_GEMV_LAUNCH(UU, 8, PP);                                                     \
+    default: break;                                                                         \
     }
-#undef AWQ_GEMV_CASE
+    switch (U) {
+    case 1:
+        if (pipe) { AWQ_GEMV_ROWS(1, true) AWQ_GEMV_LAUNCH(1, 16, true); }
+        else { AWQ_GEMV_ROWS(1, false) AWQ_GEMV_LAUNCH(1, 16, false); }
+    case 2:
+        if (pipe) { AWQ_GEMV_ROWS(2, true) AWQ_GEMV_LAUNCH(2, 16, true); }
+        else { AWQ_GEMV_ROWS(2, false) AWQ_GEMV_LAUNCH(2, 16, false); }
+    default:                                        // U == 4: never with 16 rows
+        if (pipe) { AWQ_GEMV_ROWS(4, true) }
+        else { AWQ_GEMV_ROWS(4, false) }
+    }
+#undef AWQ_GEMV_ROWS
 #undef AWQ_GEMV_LAUNCH
-#undef AWQ_GEMV_ARGS
-    return awq_launch_status();
+    return AWQ_ERR_BAD_SHAPE;
 }
 
 }  // namespace
