@@ -2,7 +2,7 @@
 "SIMD-aware weight packing": a pure index permutation of the 4-bit codes).
 
 The expected offsets below were worked out by hand from the layout text in the
-design document, not computed by the oracle:
+library header (include/awq_mi355x.h), not computed by the oracle:
   tile (16 rows x 128 cols, 1024 B) index = (n // 16) * G + (k // 128)
   slot  = (n % 16) + 16 * ((k % 32) // 8), 16 B each; word j = (k % 128) // 32
   element e = k % 8 sits in nibble {0,4,1,5,2,6,3,7}[e] of the little-endian word
