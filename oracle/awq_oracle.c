@@ -17,7 +17,7 @@
  *     dequant(q) = (q - zero) * scale, written out here as a plain loop.
  *   - Sec. 4.2 "SIMD-aware weight packing": the packed byte layout is a pure
  *     index permutation; pack/unpack below are written from the layout text
- *     in the library's header (include/awq_mi355x.h), with plain index arithmetic.
+ *     in the public header of the library under test, with plain index arithmetic.
  *
  * Arithmetic: the quantizer decides integers, so both sides take those
  * decisions in IEEE binary32, one operation per statement, no FMA contraction
