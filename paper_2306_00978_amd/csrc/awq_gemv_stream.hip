@@ -106,6 +106,16 @@ struct Landed {
     uint4 s, z;
 };
 
+// Workgroup barrier for data exchanged through LDS with ordinary ds_write / ds_read: waits for
+// this wave's LDS operations only.  __syncthreads() also waits for every outstanding memory
+// request, and here those are the weight jobs on their way into the wave's private ring,
+// which no other wave reads: waiting for them at each meeting of the waves would undo the
+// prefetch.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int PENDING>
 __device__ __forceinline__ void wait_loads()
 {
@@ -501,7 +511,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
             if (KS > 1) {
                 float *nred = red + 2 * red_floats;                 // [wave][16]
                 if (c == 0) nred[wave * 16 + r] = ss;
-                __syncthreads();
+                lds_barrier();
                 ss = 0.f;
                 for (int k = 0; k < KS; ++k) ss += nred[((ri << ksl) + k) * 16 + r];
             }
@@ -614,7 +624,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
                 if (v < Mpad) rbuf[((ri * KS + ks) * Mpad + 4 * c + v) * 16 + r] = total[v];
         }
         total = floatx4{0.f, 0.f, 0.f, 0.f};
-        __syncthreads();
+        lds_barrier();
         // one output per thread and pass: (row block tri, token m, column n) = bits of t
         for (int t = tid; t < (RW << (mlog + 4)); t += W * 64) {
             const int tri = t >> (mlog + 4), rem = t & ((16 << mlog) - 1), m = rem >> 4;
