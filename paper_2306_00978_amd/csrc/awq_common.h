@@ -35,3 +35,15 @@ static inline int awq_launch_status()
 {
     return hipGetLastError() == hipSuccess ? AWQ_OK : AWQ_ERR_HIP;
 }
+
+// "Done once on this device" flag for settings that belong to a (kernel, device) pair, such as a
+// raised dynamic-LDS limit.  Setting such a thing twice is harmless, so the flag needs no lock.
+struct AwqOncePerDevice {
+    bool done[64] = {};
+    bool &here()
+    {
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        return done[dev & 63];
+    }
+};

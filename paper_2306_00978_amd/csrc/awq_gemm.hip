@@ -491,7 +491,8 @@ int awq_gemm_launch(const void *x, const void *qweight, const void *scales, cons
     const int64_t tiles_total = (int64_t)tiles_n * ((M + BM - 1) / BM);
     if (tiles_total > (1 << 30)) return AWQ_ERR_BAD_SHAPE;
     const dim3 grid((unsigned)((tiles_total + 7) / 8 * 8)), block(512);
-    static bool attr_set = false;
+    static AwqOncePerDevice once;
+    bool &attr_set = once.here();
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)

@@ -331,7 +331,8 @@ int gemv_launch_one(dim3 grid, dim3 block, size_t lds, hipStream_t stream, const
                     const uint32_t *qweight, const uint16_t *scales, const uint8_t *zeros, half_t *y, int M,
                     int N, int K, int G, int logW, const half_t *res)
 {
-    static bool raised = false;
+    static AwqOncePerDevice once;
+    bool &raised = once.here();
     if (lds > 64 * 1024 && !raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_kernel<BITS, U, MS, PIPE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)

@@ -774,7 +774,8 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
         if (wg <= wg_cap || f_iters > 0 || f_jobs > 0) break;
         T *= 1.04;
     }
-    static bool attr_set = false;
+    static AwqOncePerDevice once;
+    bool &attr_set = once.here();
     if (!attr_set) {
         const int cap = 160 * 1024;
         const void *kernels[] = {reinterpret_cast<const void *>(gemv_stream_kernel<2, BITS, FUSED>),
