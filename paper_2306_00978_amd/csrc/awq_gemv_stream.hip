@@ -706,7 +706,7 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
     static const int f_jobs = env_int("AWQ_GEMV_JOBS", -1);
     if (count < 1 || count > (FUSED ? GEMV_MAX_FUSED : GEMV_MAX_PROBLEMS)) return AWQ_ERR_BAD_ARGUMENT;
 
-    GemvArgs<FUSED> A;
+    GemvArgs<FUSED> A{};          // the kernel fetches whole table rows: no uninitialised bytes in them
     if constexpr (FUSED)
         for (int i = 0; i < count; ++i) A.e[i] = extra[i];
     GemvLaunch &L = A.L;
