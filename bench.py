@@ -194,13 +194,17 @@ def main():
 
         for i in range(len(starts)):       # set-up: every layer's weights touched once (page tables)
             one(i)
-        for i in range(warmup):
-            one(i)
-        torch.cuda.synchronize()
-        # events around batches of steps as well: the spread of the per-step time
+        # events around batches of steps as well: the spread of the per-step time.  They are
+        # created (and recorded once) before the warm-up, so that nothing but the mandated
+        # synchronisation lies between the warm-up and the first timed launch.
         nbat = min(20, steps)
         bounds = [steps * b // nbat for b in range(nbat + 1)]
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(nbat + 1)]
+        for ev in evs:
+            ev.record()
+        for i in range(warmup):
+            one(i)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         evs[0].record()
         for b in range(nbat):
