@@ -219,3 +219,43 @@ def test_rejects_bad_shapes():
     with pytest.raises(ValueError):
         oracle.pack(np.zeros((8, 128), np.uint8), np.zeros((8, 1), np.float16),
                     np.zeros((8, 1), np.uint8))
+
+
+def test_scale_study_table_structure_on_the_oracle():
+    """The table of Sec. 3.2 (1 % salient channels multiplied by s): its printed rows obey
+    Err ratio = (Delta'/Delta) / s of Eq. 3, and the oracle's quantizer shows the same structure
+    on seeded weights: no step shrinks, the share of changed steps and the mean step ratio grow
+    with s, the error of the salient channels falls as (mean step ratio) / s."""
+    import os
+    rows = [tuple(float(v) for v in ln.split()) for ln in
+            open(os.path.join(os.path.dirname(__file__), "golden", "table2_scale_study.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    assert [r[0] for r in rows] == [1.0, 1.25, 1.5, 2.0, 4.0]
+    for sval, changed, ratio, reduction in rows:
+        assert abs(ratio / sval - reduction) <= 0.0015             # printed to three decimals
+    assert all(a[1] < b[1] and a[2] < b[2] and a[3] > b[3] for a, b in zip(rows, rows[1:]))
+
+    N, K = 2048, 1024
+    W = gauss(N, K, seed=21)
+    Wf = W.astype(np.float64)
+    salient = np.sort(np.random.default_rng(22).choice(K, size=K // 100, replace=False))
+    c0, s0, z0 = oracle.quantize(W)
+    d0 = s0.astype(np.float64)
+    e0 = np.abs(oracle.dequant(c0, s0, z0).astype(np.float64) - Wf)[:, salient].mean()
+    prev = (0.0, 1.0)
+    for sval, _, _, _ in rows:
+        sv = np.ones(K, dtype=np.float32)
+        sv[salient] = sval
+        c1, s1, z1 = oracle.quantize(W, sv)
+        d1 = s1.astype(np.float64)
+        assert np.all(d1 >= d0)
+        changed, ratio = float((d1 != d0).mean()), float((d1 / d0).mean())
+        e1 = np.abs(oracle.dequant(c1, s1, z1).astype(np.float64) / sv[None, :] - Wf)[:, salient].mean()
+        grp = salient // G
+        predicted = (d1 / d0)[:, grp].mean() / sval
+        if sval == 1.0:
+            assert changed == 0.0 and ratio == 1.0 and e1 == e0
+        else:
+            assert changed > prev[0] and ratio > prev[1]
+            assert abs((e1 / e0) / predicted - 1.0) < 0.10
+        prev = (changed, ratio)
