@@ -693,6 +693,150 @@ bool awq_gemv_stream_fits(int N, int K, int M)
 
 namespace {
 
+// Paired plan of a grouped launch with M = 1.
+//
+// All workgroups of a launch are resident at once (two fit on a CU), and the hardware places
+// workgroup w and workgroup w + 256 on the same CU.  With one size of workgroup per linear their
+// number is whatever the row-block steps give (428 for a Llama-2-7B layer): 172 CUs then carry
+// two workgroups and 84 one, and the launch ends with a run-out in which only the loaded CUs
+// still stream.  Here every linear is cut into workgroups of two sizes (lo or lo + 1 steps) so
+// that 512 come out, the 256 largest first and the rest in ascending order behind them: each
+// CU gets a large and a small one.  A run of equal workgroups of one linear becomes one entry of
+// the launch table: with M = 1 a range of row blocks of a linear is a linear of its own (packed
+// arrays and output are contiguous per row block), so the kernel needs nothing new.
+struct PairedRun {
+    int lin, iters, count, load;
+};
+
+template <int BITS>
+bool plan_paired(const GemvProblem *problems, int count, const int *ksl_of, int W, GemvLaunch &L, int &wg_total)
+{
+    constexpr int TARGET = 512, ROUND = 256;
+    int S[GEMV_MAX_PROBLEMS], nbw[GEMV_MAX_PROBLEMS], RW[GEMV_MAX_PROBLEMS], lo[GEMV_MAX_PROBLEMS];
+    int hN[GEMV_MAX_PROBLEMS], lN[GEMV_MAX_PROBLEMS], removable[GEMV_MAX_PROBLEMS], rem[GEMV_MAX_PROBLEMS];
+    long long U = 0;
+    for (int i = 0; i < count; ++i) {
+        const int NBT = (problems[i].K / 128 + 3) / 4;
+        nbw[i] = (NBT + (1 << ksl_of[i]) - 1) >> ksl_of[i];
+        RW[i] = W >> ksl_of[i];
+        S[i] = (problems[i].N / 16 + RW[i] - 1) / RW[i];
+        U += (long long)S[i] * nbw[i];
+    }
+    const double tstar = (double)U / TARGET;
+    if (tstar < 6.0) return false;                        // too small a launch for two workgroups per CU
+    int w_lo = 0, w_hi = 0;
+    for (int i = 0; i < count; ++i) {
+        lo[i] = std::max(1, (int)(tstar / nbw[i]));
+        const int a = (S[i] + lo[i] - 1) / lo[i], b = (S[i] + lo[i]) / (lo[i] + 1);
+        removable[i] = a - b;
+        rem[i] = 0;
+        w_lo += a;
+        w_hi += b;
+    }
+    if (w_hi > TARGET || w_lo < TARGET) return false;
+    // take the surplus workgroups away where the larger size is smallest (equal sizes share in
+    // proportion to what they can give)
+    int R = w_lo - TARGET;
+    bool done[GEMV_MAX_PROBLEMS] = {};
+    while (R > 0) {
+        int best = -1;
+        for (int i = 0; i < count; ++i)
+            if (!done[i] && removable[i] > 0 && (best < 0 || (lo[i] + 1) * nbw[i] < (lo[best] + 1) * nbw[best])) best = i;
+        if (best < 0) return false;
+        const int load = (lo[best] + 1) * nbw[best];
+        int cap = 0;
+        for (int i = 0; i < count; ++i)
+            if (!done[i] && (lo[i] + 1) * nbw[i] == load) cap += removable[i];
+        const int take = std::min(R, cap);
+        int given = 0;
+        for (int i = 0; i < count; ++i)
+            if (!done[i] && (lo[i] + 1) * nbw[i] == load) {
+                rem[i] = (int)((long long)take * removable[i] / cap);
+                given += rem[i];
+            }
+        for (int i = 0; i < count && given < take; ++i)
+            if (!done[i] && (lo[i] + 1) * nbw[i] == load && rem[i] < removable[i]) {
+                ++rem[i];
+                ++given;
+            }
+        for (int i = 0; i < count; ++i)
+            if ((lo[i] + 1) * nbw[i] == load) done[i] = true;
+        R -= take;
+    }
+    int total = 0;
+    for (int i = 0; i < count; ++i) {
+        hN[i] = std::min(rem[i] * lo[i], S[i] / (lo[i] + 1));
+        const int left = S[i] - hN[i] * (lo[i] + 1);
+        lN[i] = left > 0 ? (left + lo[i] - 1) / lo[i] : 0;
+        total += hN[i] + lN[i];
+    }
+    if (total > TARGET || total <= ROUND) return false;
+
+    // runs of equal workgroups, largest first
+    PairedRun runs[2 * GEMV_MAX_PROBLEMS];
+    int nruns = 0;
+    for (int i = 0; i < count; ++i) {
+        if (hN[i] > 0) runs[nruns++] = {i, lo[i] + 1, hN[i], (lo[i] + 1) * nbw[i]};
+        if (lN[i] > 0) runs[nruns++] = {i, lo[i], lN[i], lo[i] * nbw[i]};
+    }
+    std::stable_sort(runs, runs + nruns, [](const PairedRun &a, const PairedRun &b) { return a.load > b.load; });
+    // the first 256 in this order, then the others smallest first
+    PairedRun order[2 * GEMV_MAX_PROBLEMS + 2];
+    int norder = 0, seen = 0, split_at = -1;
+    PairedRun tail[2 * GEMV_MAX_PROBLEMS + 1];
+    int ntail = 0;
+    for (int r = 0; r < nruns; ++r) {
+        if (seen >= ROUND) {
+            tail[ntail++] = runs[r];
+        } else if (seen + runs[r].count <= ROUND) {
+            order[norder++] = runs[r];
+        } else {
+            PairedRun first = runs[r], second = runs[r];
+            first.count = ROUND - seen;
+            second.count = runs[r].count - first.count;
+            order[norder++] = first;
+            tail[ntail++] = second;
+            split_at = r;
+        }
+        seen += runs[r].count;
+    }
+    (void)split_at;
+    for (int r = ntail - 1; r >= 0; --r) order[norder++] = tail[r];
+    if (norder > GEMV_MAX_PROBLEMS) return false;
+
+    // entries: consecutive row-block ranges of their linear
+    int cursor[GEMV_MAX_PROBLEMS] = {};
+    int wg = 0, ne = 0;
+    for (int r = 0; r < norder; ++r) {
+        const PairedRun &run = order[r];
+        const GemvProblem &src = problems[run.lin];
+        const int NRB = src.N / 16, G = src.K / 128;
+        const int rb0 = cursor[run.lin];
+        const int nrb = std::min(run.count * run.iters * RW[run.lin], NRB - rb0);
+        if (nrb <= 0) continue;
+        cursor[run.lin] += nrb;
+        GemvProblem p = src;
+        p.q = reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(src.q) +
+                                              (size_t)rb0 * G * Slot<BITS>::TILE);
+        p.sc = src.sc + (size_t)rb0 * G * 16;
+        p.zp = src.zp + (size_t)rb0 * G * 8;
+        p.y = src.y + (size_t)rb0 * 16;
+        p.N = nrb * 16;
+        p.ks_log = ksl_of[run.lin];
+        p.iters = run.iters;
+        const int steps = (nrb + RW[run.lin] - 1) / RW[run.lin];
+        L.wg_begin[ne] = wg;
+        L.p[ne] = p;
+        wg += (steps + run.iters - 1) / run.iters;
+        ++ne;
+    }
+    for (int i = 0; i < count; ++i)
+        if (cursor[i] != problems[i].N / 16) return false;          // every row block exactly once
+    L.count = ne;
+    wg_total = wg;
+    return true;
+}
+
 template <int BITS, bool FUSED>
 int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra, int count, int M,
                        hipStream_t stream)
@@ -752,7 +896,18 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
     // is raised until it does not.
     const int wg_cap = lds * 2 > 160 * 1024 ? 256 : (1 << 30);
     int wg = 0;
-    for (int attempt = 0; attempt < 64; ++attempt) {
+    static const int f_paired = env_int("AWQ_GEMV_PAIRED", 1);
+    bool paired = false;
+    if (!FUSED && M == 1 && logW == 2 && stages == 2 && f_paired && f_logw < 0 && f_iters < 0 && f_ksl < 0 &&
+        f_jobs < 0 && f_slots == 1792 && count * 3 <= GEMV_MAX_PROBLEMS) {
+        paired = plan_paired<BITS>(problems, count, ksl_of, W, L, wg);
+        if (!paired) {                                  // the table may be half written: start again
+            for (int i = 0; i < GEMV_MAX_PROBLEMS; ++i) L.wg_begin[i] = 0x7fffffff;
+            L.count = count;
+            wg = 0;
+        }
+    }
+    for (int attempt = 0; attempt < 64 && !paired; ++attempt) {
         wg = 0;
         for (int i = 0; i < count; ++i) {
             GemvProblem p = problems[i];
