@@ -14,9 +14,10 @@ struct GemvProblem {
     const uint16_t *sc;       // steps
     const uint8_t *zp;        // zero points
     half_t *y;                // [M,N]
-    int N, K;
-    int ks_log;               // log2 of the waves that split K for one row block
-    int iters;                // row-block iterations per workgroup
+    int N, K;                 // N: features of the whole linear = row stride of y
+    int plan;                 // log2 of the waves that split K for one row block, and
+                              // (<< 4) the row-block iterations per workgroup
+    int nrb;                  // 16-row blocks of this entry (q, sc, zp, y point at its first one)
 };
 
 struct GemvLaunch {

@@ -353,8 +353,8 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
         P.zp = reinterpret_cast<const uint8_t *>(((uint64_t)g[7] << 32) | g[6]);
         P.N = (int)g[10];
         P.K = (int)g[11];
-        P.ks_log = (int)g[12];
-        P.iters = (int)g[13];
+        P.plan = (int)g[12];
+        P.nrb = (int)g[13];
         wg0 = __builtin_amdgcn_readlane(begin, pi);
         if (FUSED) {
             static_assert(sizeof(GemvFusedExtra) == 24 && offsetof(GemvArgs<true>, e) == sizeof(GemvLaunch), "layout");
@@ -370,10 +370,10 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
 
     const int M = L.M, mlog = L.mlog, Mpad = 1 << mlog;
     const int K = P.K, N = P.N;
-    const int G = K >> 7, NRB = N >> 4, NBT = (G + 3) >> 2;
-    const int ksl = P.ks_log, KS = 1 << ksl;
+    const int G = K >> 7, NRB = P.nrb, NBT = (G + 3) >> 2;
+    const int ksl = P.plan & 15, KS = 1 << ksl;
     const int W = 1 << L.logW, RW = W >> ksl;
-    const int iters = P.iters;
+    const int iters = P.plan >> 4;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ks = wave & (KS - 1), ri = wave >> ksl;
@@ -693,7 +693,7 @@ bool awq_gemv_stream_fits(int N, int K, int M)
 
 namespace {
 
-// Paired plan of a grouped launch with M = 1.
+// Paired plan of a grouped launch.
 //
 // All workgroups of a launch are resident at once (two fit on a CU), and the hardware places
 // workgroup w and workgroup w + 256 on the same CU.  With one size of workgroup per linear their
@@ -702,8 +702,8 @@ namespace {
 // still stream.  Here every linear is cut into workgroups of two sizes (lo or lo + 1 steps) so
 // that 512 come out, the 256 largest first and the rest in ascending order behind them: each
 // CU gets a large and a small one.  A run of equal workgroups of one linear becomes one entry of
-// the launch table: with M = 1 a range of row blocks of a linear is a linear of its own (packed
-// arrays and output are contiguous per row block), so the kernel needs nothing new.
+// the launch table: a range of row blocks of a linear is a linear of its own (its packed arrays
+// are contiguous, its outputs a column range of y).
 struct PairedRun {
     int lin, iters, count, load;
 };
@@ -821,9 +821,8 @@ bool plan_paired(const GemvProblem *problems, int count, const int *ksl_of, int 
         p.sc = src.sc + (size_t)rb0 * G * 16;
         p.zp = src.zp + (size_t)rb0 * G * 8;
         p.y = src.y + (size_t)rb0 * 16;
-        p.N = nrb * 16;
-        p.ks_log = ksl_of[run.lin];
-        p.iters = run.iters;
+        p.plan = ksl_of[run.lin] | (run.iters << 4);
+        p.nrb = nrb;
         const int steps = (nrb + RW[run.lin] - 1) / RW[run.lin];
         L.wg_begin[ne] = wg;
         L.p[ne] = p;
@@ -898,7 +897,7 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
     int wg = 0;
     static const int f_paired = env_int("AWQ_GEMV_PAIRED", 1);
     bool paired = false;
-    if (!FUSED && M == 1 && logW == 2 && stages == 2 && f_paired && f_logw < 0 && f_iters < 0 && f_ksl < 0 &&
+    if (!FUSED && logW == 2 && stages == 2 && f_paired && f_logw < 0 && f_iters < 0 && f_ksl < 0 &&
         f_jobs < 0 && f_slots == 1792 && count * 3 <= GEMV_MAX_PROBLEMS) {
         paired = plan_paired<BITS>(problems, count, ksl_of, W, L, wg);
         if (!paired) {                                  // the table may be half written: start again
@@ -920,8 +919,8 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
             const int steps = (NRB + RW - 1) / RW;            // row-block steps of the whole linear
             const int iters = std::min(it, steps);
             iters_of[i] = iters;
-            p.ks_log = ksl_of[i];
-            p.iters = iters;
+            p.plan = ksl_of[i] | (iters << 4);
+            p.nrb = NRB;
             L.wg_begin[i] = wg;
             wg += (steps + iters - 1) / iters;
             L.p[i] = p;
