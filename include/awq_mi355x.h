@@ -207,6 +207,12 @@ int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int count, int64_t
                                  void *stream);
 int awq_w4a16_linear_fused_fits(int64_t N, int64_t K, int64_t M, int group);
 
+/* Diagnostic: how the last grouped decode launch of this process (awq_w4a16_linear_multi,
+ * awq_w3a16_linear_multi, awq_w4a16_linear_fused_multi through the streaming kernel) laid out its
+ * workgroups: 0 = none yet, 1 = one size of workgroup per linear, 2 = two sizes per linear, paired
+ * large with small on every CU.  Not synchronised between threads. */
+int awq_last_grouped_plan(void);
+
 /* ---- INT3-g128 variant (Sec. 5: INT4/INT3 with group size 128) ----------------------------
  * The 8-level form of the quantizer (15 -> 7 in the formulas of awq_quantize_pack) and its own
  * packed layout, version 1:

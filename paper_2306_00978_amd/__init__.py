@@ -36,6 +36,7 @@ EXPORTS = [
     "awq_decode_attention_workspace_bytes", "awq_decode_attention", "awq_silu_mul",
     "awq_w4a16_linear_fused_multi", "awq_w4a16_linear_fused_fits",
     "awq_repack_w3_to_w4", "awq_w3a16_prefill_workspace_bytes", "awq_w3a16_linear_prefill",
+    "awq_last_grouped_plan",
 ]
 MULTI_MAX = 56
 
@@ -121,6 +122,8 @@ def load() -> ctypes.CDLL:
     lib.awq_w3a16_prefill_workspace_bytes.argtypes = [i64, i64, i32]
     lib.awq_w3a16_linear_prefill.restype = i32
     lib.awq_w3a16_linear_prefill.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
+    lib.awq_last_grouped_plan.restype = i32
+    lib.awq_last_grouped_plan.argtypes = []
     lib.awq_silu_mul.restype = i32
     lib.awq_silu_mul.argtypes = [vp, vp, i64, vp, vp]
     lib.awq_read_probe.restype = i32
@@ -630,3 +633,9 @@ def awq_w4a16_linear_fused_multi(linears, group: int = GROUP):
 def awq_w4a16_linear_fused_fits(N: int, K: int, M: int, group: int = GROUP) -> bool:
     """Whether a linear of this shape can be part of a fused grouped call at this M."""
     return bool(load().awq_w4a16_linear_fused_fits(N, K, M, group))
+
+
+def awq_last_grouped_plan() -> int:
+    """Diagnostic: 1 if the last grouped decode launch used one size of workgroup per linear, 2 if
+    it used the paired plan, 0 if there was none yet."""
+    return int(load().awq_last_grouped_plan())

@@ -708,6 +708,8 @@ struct PairedRun {
     int lin, iters, count, load;
 };
 
+int g_last_plan = 0;             // diagnostic: 1 = one size of workgroup per linear, 2 = paired plan
+
 template <int BITS>
 bool plan_paired(const GemvProblem *problems, int count, const int *ksl_of, int W, GemvLaunch &L, int &wg_total)
 {
@@ -906,6 +908,7 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
             wg = 0;
         }
     }
+    g_last_plan = paired ? 2 : 1;
     for (int attempt = 0; attempt < 64 && !paired; ++attempt) {
         wg = 0;
         for (int i = 0; i < count; ++i) {
@@ -963,4 +966,9 @@ int awq_gemv_stream_launch_fused(const GemvProblem *problems, const GemvFusedExt
                                  int M, hipStream_t stream)
 {
     return stream_launch_bits<4, true>(problems, extra, count, M, stream);
+}
+
+extern "C" int awq_last_grouped_plan(void)
+{
+    return g_last_plan;
 }

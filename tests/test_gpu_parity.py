@@ -376,6 +376,44 @@ def test_multi_llama70b_shapes_full_size(awq):
             check_multi(awq, probs + probs[1:], M)
 
 
+def test_multi_paired_plan_ragged_shapes(awq):
+    """Launches large enough for the plan that cuts every linear into workgroups of two sizes
+    (row-block ranges of a linear as entries of their own), with row-block counts that are no
+    multiple of the rows a workgroup takes per step, ragged group counts and K split over two
+    or four waves: every output against the oracle, and bit-identical on a second call."""
+    import oracle
+    g = np.random.default_rng(31)
+    sets = [
+        [(4112, 4096), (2064, 4096), (8208, 2048), (1040, 8192), (4112, 1408), (6160, 4096), (6160, 4096),
+         (6160, 4096), (3088, 11008)],
+        [(11024, 4096), (11024, 4096), (4112, 11008), (4112, 4096), (272, 28672), (16, 4096)],
+    ]
+    expected_plan = [{1: 2, 2: 2}, {1: 2, 2: 1}]        # K = 28672 at M = 2 needs eight-wave workgroups
+    for shapes, expected in zip(sets, expected_plan):
+        probs = []
+        for N, K in shapes:
+            codes = g.integers(0, 16, size=(N, K), dtype=np.uint8)
+            scales = g.uniform(0.002, 0.02, size=(N, K // 128)).astype(np.float16)
+            zeros = g.integers(0, 16, size=(N, K // 128), dtype=np.uint8)
+            q, sp, zp = oracle.pack(codes, scales, zeros)
+            xs = g.standard_normal((2, K)).astype(np.float16)
+            probs.append((xs, oracle.dequant(codes, scales, zeros), (dev(q), dev(sp.view(np.float16)), dev(zp)), N))
+            del codes
+        for M in (1, 2):
+            check_multi(awq, probs, M)
+            assert awq.awq_last_grouped_plan() == expected[M]
+        check_multi(awq, probs[:2], 1)
+        assert awq.awq_last_grouped_plan() == 1                  # a small launch keeps the plain plan
+        import torch
+        linears = [(dev(xs[:1]), *gpu, torch.empty((1, N), dtype=torch.float16, device="cuda"), N)
+                   for xs, Wdq, gpu, N in probs]
+        first = [host(y).copy() for y in awq.awq_w4a16_linear_multi(linears)]
+        second = [host(y).copy() for y in awq.awq_w4a16_linear_multi(linears)]
+        for a, b in zip(first, second):
+            assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+        del probs
+
+
 # ------------------------------------------------------------------- the full stack (config 4)
 
 def test_config4_full_stack(awq):
