@@ -502,6 +502,22 @@ def main():
                                                 "bound": "mfma", "achieved": round(tf, 1),
                                                 "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                                 "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}}
+        # a short prefill: 64 tokens, 4096 x 4096 (decode kernels on blocks of 16 tokens, one grouped launch)
+        x64 = x_by_k[4096][:64].contiguous()
+        y64 = torch.empty((64, 4096), dtype=torch.float16, device=dev)
+        for i in range(4):
+            awq.awq_w4a16_linear(x64, *layers[i % L][0], 4096, out=y64)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(40):
+            awq.awq_w4a16_linear(x64, *layers[i % L][0], 4096, out=y64)
+        e1.record()
+        torch.cuda.synchronize()
+        ms64 = e0.elapsed_time(e1) / 40
+        extras["prefill_m64_4096x4096"] = {"us": round(ms64 * 1e3, 2),
+                                           "TFLOP/s": round(workloads.flops(64, 4096, 4096) / (ms64 * 1e-3) / 1e12, 1),
+                                           "note": "17..128 tokens: blocks of 16 through the decode kernels"}
         extras["quantize_pack"] = {"matrices": L * len(shapes), "ms_total": round(quant_ms, 3),
                                    "GB/s": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
                                    "pct_of_hbm_peak": round(100 * quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}

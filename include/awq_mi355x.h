@@ -142,8 +142,10 @@ size_t awq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
  *   y[m,n] = fp16( sum_k fp32(x[m,k]) * (q[n,k] - zero[n,k/128]) * scale[n,k/128] )
  * with fp32 accumulation.  x_f16 [M,K] fp16 row-major, already divided by s;
  * qweight/scales/zeros as written by awq_quantize_pack; y_f16 [M,N] fp16 row-major
- * (written).  M <= 16 takes the decode path (streams the packed weights once),
- * larger M the prefill path (MFMA tiles).  `workspace` may be NULL when
+ * (written).  M <= 16 takes the decode path (streams the packed weights once), 17..128 tokens
+ * go through the decode kernels in blocks of 16 (one grouped launch where the shape allows it;
+ * the last block is moved back to hold 16 tokens, so a few tokens are computed twice with
+ * identical results), larger M the prefill path (MFMA tiles).  `workspace` may be NULL when
  * awq_linear_workspace_bytes() is 0; its contents are undefined afterwards. */
 int awq_w4a16_linear(const void *x_f16, const void *qweight, const void *scales,
                      const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,

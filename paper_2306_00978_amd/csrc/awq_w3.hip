@@ -221,6 +221,23 @@ extern "C" int awq_w3a16_linear_prefill(const void *x_f16, const void *qweight, 
         !awq_aligned16(zeros) || !awq_aligned16(y_f16) || !awq_aligned16(workspace))
         return AWQ_ERR_MISALIGNED;
     if (workspace_bytes < (size_t)(N * K / 2)) return AWQ_ERR_WORKSPACE_TOO_SMALL;
+    if (M <= 128) {
+        // a few dozen tokens: blocks of 16 through the 3-bit decode kernels in one grouped call
+        // (see awq_w4a16_linear); the workspace is not touched
+        const int blocks = (int)((M + 15) / 16);
+        awq_linear_desc d[8];
+        for (int b = 0; b < blocks; ++b) {
+            const int64_t m0 = b + 1 < blocks ? 16 * (int64_t)b : M - 16;
+            d[b].x_f16 = (const half_t *)x_f16 + m0 * K;
+            d[b].qweight = qweight;
+            d[b].scales = scales;
+            d[b].zeros = zeros;
+            d[b].y_f16 = (half_t *)y_f16 + m0 * N;
+            d[b].N = N;
+            d[b].K = K;
+        }
+        return awq_w3a16_linear_multi(d, blocks, 16, group, stream);
+    }
     st = awq_repack_w3_to_w4(qweight, N, K, group, workspace, stream);
     if (st != AWQ_OK) return st;
     return awq_gemm_launch(x_f16, workspace, scales, zeros, y_f16, (int)M, (int)N, (int)K, (hipStream_t)stream);

@@ -226,6 +226,21 @@ def test_decode_every_m(awq, small, M):
     check_linear(awq, xs[:M], Wdq, gpu, N)
 
 
+@pytest.mark.parametrize("M", [24, 100])
+def test_small_prefill_full_size_blocks_of_16(awq, M):
+    """17..128 tokens run through the decode kernels in blocks of 16 (the last block moved back):
+    full-size shapes, every row against the oracle, twice bit for bit alike."""
+    for N, K in [(4096, 4096), (4096, 11008)]:
+        case, s, xs16, ref, gpu, Wdq = config_case(awq, N, K, 0.02, 1)
+        g = np.random.default_rng(M)
+        xs = (np.tile(xs16, ((M + 15) // 16, 1))[:M].astype(np.float32)
+              * g.uniform(0.5, 1.5, size=(M, 1)).astype(np.float32)).astype(np.float16)
+        check_linear(awq, xs, Wdq, gpu, N)
+        a = host(awq.awq_w4a16_linear(dev(xs), *gpu, N)).copy()
+        b = host(awq.awq_w4a16_linear(dev(xs), *gpu, N)).copy()
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
 @pytest.mark.parametrize("M", [17, 64, 127, 128, 129, 300])
 def test_prefill_ragged_m(awq, small, M):
     N, K, xs, Wdq, gpu = small
