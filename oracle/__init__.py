@@ -344,6 +344,71 @@ def unpack_w3(qweight, scales_p, zeros_p, N: int, K: int, group: int = GROUP):
     return codes, scales.view(np.float16), zeros
 
 
+# ---------------------------------------------------------------- INT2-g64 variant
+
+GROUP_W2 = 64
+
+
+def quantize_w2(W, s=None, group: int = GROUP_W2):
+    """Sec. 5 (INT2-g64 of the extreme low-bit table): the 4-level form of `quantize` over groups
+    of 64 input channels.  Returns codes[N,K] u8 in 0..3, scales[N,K/64] f16, zeros[N,K/64] u8."""
+    Wb = _as_f16_bits(W)
+    N, K = Wb.shape
+    if K % group:
+        raise ValueError("K must be a multiple of the group size")
+    G = K // group
+    sp = None
+    if s is not None:
+        s = np.ascontiguousarray(s, dtype=np.float32)
+        assert s.shape == (K,)
+        sp = _p(s)
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, G), dtype=np.uint16)
+    zeros = np.empty((N, G), dtype=np.uint8)
+    _chk(_load().awq_oracle_quantize_w2(_p(Wb), sp, _i64(N), _i64(K), ctypes.c_int(group),
+                                        _p(codes), _p(scales), _p(zeros)), "quantize_w2")
+    return codes, scales.view(np.float16), zeros
+
+
+def packed_sizes_w2(N: int, K: int, group: int = GROUP_W2):
+    G = K // group
+    return N * K // 4, N * G * 2, N * G // 4
+
+
+def pack_w2(codes, scales, zeros, group: int = GROUP_W2):
+    """The 2-bit packed layout of this library (see the C file); K a multiple of 256."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, K = codes.shape
+    G = K // group
+    sb = _as_f16_bits(scales)
+    zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+    assert sb.shape == (N, G) and zeros.shape == (N, G)
+    qb, sbytes, zb = packed_sizes_w2(N, K, group)
+    qweight = np.empty(qb, dtype=np.uint8)
+    scales_p = np.empty(sbytes // 2, dtype=np.uint16)
+    zeros_p = np.empty(zb, dtype=np.uint8)
+    _chk(_load().awq_oracle_pack_w2(_p(codes), _p(sb), _p(zeros), _i64(N), _i64(K),
+                                    ctypes.c_int(group), _p(qweight), _p(scales_p), _p(zeros_p)),
+         "pack_w2")
+    return qweight, scales_p, zeros_p
+
+
+def unpack_w2(qweight, scales_p, zeros_p, N: int, K: int, group: int = GROUP_W2):
+    qweight = np.ascontiguousarray(qweight, dtype=np.uint8)
+    scales_p = _as_f16_bits(scales_p).reshape(-1)
+    zeros_p = np.ascontiguousarray(zeros_p, dtype=np.uint8)
+    G = K // group
+    qb, sbytes, zb = packed_sizes_w2(N, K, group)
+    assert qweight.size == qb and scales_p.size * 2 == sbytes and zeros_p.size == zb
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, G), dtype=np.uint16)
+    zeros = np.empty((N, G), dtype=np.uint8)
+    _chk(_load().awq_oracle_unpack_w2(_p(qweight), _p(scales_p), _p(zeros_p), _i64(N), _i64(K),
+                                      ctypes.c_int(group), _p(codes), _p(scales), _p(zeros)),
+         "unpack_w2")
+    return codes, scales.view(np.float16), zeros
+
+
 # ---------------------------------------------------------------- decode attention (Sec. 4.2 fusion)
 
 def rope_rotate(x, pos: int, theta: float = 10000.0) -> np.ndarray:

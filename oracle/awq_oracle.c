@@ -551,6 +551,132 @@ int awq_oracle_unpack_w3(const uint8_t *qweight, const uint16_t *scales_p,
     return 0;
 }
 
+/* ---------- INT2-g64 variant (Sec. 5, the extreme low-bit table: INT2 with group size 64).
+ * The same asymmetric min/max quantizer with 4 levels over groups of 64 input channels:
+ *   scale = fp16(clamp((max-min)/3, 2^-14, 65504)); zero = clamp(rint(-min/scale), 0, 3);
+ *   q = clamp(rint(w'/scale) + zero, 0, 3),  binary32, one rounding per operation.        */
+#define ORACLE_GROUP_W2 64
+
+int awq_oracle_quantize_w2(const uint16_t *W, const float *s, int64_t N, int64_t K,
+                           int group, uint8_t *codes, uint16_t *scales, uint8_t *zeros)
+{
+    if (!W || !codes || !scales || !zeros) return -1;
+    if (group != ORACLE_GROUP_W2 || N <= 0 || K <= 0 || K % group) return -2;
+    const int64_t G = K / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float wp[ORACLE_GROUP_W2];
+        for (int64_t g = 0; g < G; ++g) {
+            const int64_t k0 = g * group;
+            for (int j = 0; j < group; ++j) {
+                float w = awq_oracle_f16_to_f32(W[n * K + k0 + j]);
+                float sk = s ? s[k0 + j] : 1.0f;
+                wp[j] = w * sk;
+            }
+            float mx = wp[0], mn = wp[0];
+            for (int j = 1; j < group; ++j) {
+                if (wp[j] > mx) mx = wp[j];
+                if (wp[j] < mn) mn = wp[j];
+            }
+            float range = mx - mn;
+            float sc32 = range / 3.0f;
+            sc32 = clampf(sc32, 6.103515625e-05f, 65504.0f);
+            uint16_t sc_h = awq_oracle_f32_to_f16(sc32);
+            float scale = awq_oracle_f16_to_f32(sc_h);
+            float nmn = -mn;
+            float zr = nmn / scale;
+            float zero = clampf(rintf(zr), 0.0f, 3.0f);
+            scales[n * G + g] = sc_h;
+            zeros[n * G + g] = (uint8_t)zero;
+            for (int j = 0; j < group; ++j) {
+                float r = wp[j] / scale;
+                float q = rintf(r);
+                q = q + zero;
+                q = clampf(q, 0.0f, 3.0f);
+                codes[n * K + k0 + j] = (uint8_t)q;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Packed layout of the 2-bit codes (written from the layout text).  K is a multiple of 256:
+ * qweight: blocks of 16 rows x 256 columns (four groups of 64), 1024 bytes each, block index
+ *          (n/16)*(K/256) + k/256.  Inside a block, 64 slots of 16 bytes = four little-endian
+ *          32-bit words; slot l = (n%16) + 16*c owns row n%16 and, in word t (0..3), the 16
+ *          codes of group t of the block: columns 64*t + 32*j + 8*c + e (j = 0..1, e = 0..7).
+ *          Code i = 8*j + e belongs to pair p = i/2, member h = i%2, and sits at bits
+ *          [2p, 2p+2) of the low (h = 0) or high (h = 1) 16-bit half of the word.
+ * scales : [N/16][K/256][16 rows][4 groups] binary16 (the group of the block innermost)
+ * zeros  : [N/16][K/256][16 rows] bytes; the byte of a row holds the zero point of group t of
+ *          the block at bits [2t, 2t+2).                                                   */
+int awq_oracle_pack_w2(const uint8_t *codes, const uint16_t *scales, const uint8_t *zeros,
+                       int64_t N, int64_t K, int group, uint8_t *qweight,
+                       uint16_t *scales_p, uint8_t *zeros_p)
+{
+    if (!codes || !scales || !zeros || !qweight || !scales_p || !zeros_p) return -1;
+    if (group != ORACLE_GROUP_W2 || N <= 0 || K <= 0 || K % 256 || N % 16) return -2;
+    const int64_t G = K / group, B = K / 256;
+    memset(qweight, 0, (size_t)(N * K / 4));
+    memset(zeros_p, 0, (size_t)(N * G / 4));
+    for (int64_t n = 0; n < N; ++n) {
+        const int64_t rb = n / 16;
+        const int r = (int)(n % 16);
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t block = rb * B + k / 256;
+            int kk = (int)(k % 256);
+            int t = kk / 64, j = (kk % 64) / 32, c = (kk % 32) / 8, e = kk % 8;
+            int slot = r + 16 * c;
+            int i = 8 * j + e, p = i / 2, h = i % 2;
+            int pos = 16 * h + 2 * p;
+            uint8_t code = codes[n * K + k] & 0x3;
+            qweight[block * 1024 + slot * 16 + t * 4 + pos / 8] |= (uint8_t)(code << (pos % 8));
+        }
+        for (int64_t g = 0; g < G; ++g) {
+            int64_t block = rb * B + g / 4;
+            int t = (int)(g % 4);
+            scales_p[(block * 16 + r) * 4 + t] = scales[n * G + g];
+            zeros_p[block * 16 + r] |= (uint8_t)((zeros[n * G + g] & 0x3) << (2 * t));
+        }
+    }
+    return 0;
+}
+
+int awq_oracle_unpack_w2(const uint8_t *qweight, const uint16_t *scales_p,
+                         const uint8_t *zeros_p, int64_t N, int64_t K, int group,
+                         uint8_t *codes, uint16_t *scales, uint8_t *zeros)
+{
+    if (!codes || !scales || !zeros || !qweight || !scales_p || !zeros_p) return -1;
+    if (group != ORACLE_GROUP_W2 || N <= 0 || K <= 0 || K % 256 || N % 16) return -2;
+    const int64_t G = K / group, B = K / 256;
+    /* walk the packed bytes in storage order and scatter to [n,k] */
+    for (int64_t block = 0; block < (N / 16) * B; ++block) {
+        int64_t rb = block / B, b = block % B;
+        for (int slot = 0; slot < 64; ++slot) {
+            int r = slot % 16, c = slot / 16;
+            int64_t n = rb * 16 + r;
+            for (int t = 0; t < 4; ++t) {
+                const uint8_t *wb = qweight + block * 1024 + slot * 16 + t * 4;
+                uint32_t word = (uint32_t)wb[0] | ((uint32_t)wb[1] << 8) |
+                                ((uint32_t)wb[2] << 16) | ((uint32_t)wb[3] << 24);
+                for (int i = 0; i < 16; ++i) {
+                    int p = i / 2, h = i % 2;
+                    int64_t k = b * 256 + 64 * t + 32 * (i / 8) + 8 * c + (i % 8);
+                    codes[n * K + k] = (uint8_t)((word >> (16 * h + 2 * p)) & 0x3);
+                }
+            }
+        }
+        for (int r = 0; r < 16; ++r) {
+            int64_t n = rb * 16 + r;
+            for (int t = 0; t < 4; ++t) {
+                scales[n * G + 4 * b + t] = scales_p[(block * 16 + r) * 4 + t];
+                zeros[n * G + 4 * b + t] = (uint8_t)((zeros_p[block * 16 + r] >> (2 * t)) & 0x3);
+            }
+        }
+    }
+    return 0;
+}
+
 /* ---------- a6/a7: y[m,n] = sum_k x[m,k] * Wdq[n,k] ----------
  * x [M,K] binary16; Wdq [N,K] binary32; y [M,N] binary64.
  * acc32 != 0 switches to sequential binary32 accumulation (reported variant). */
