@@ -258,6 +258,39 @@ int awq_w3a16_linear_prefill(const void *x_f16, const void *qweight, const void 
 int awq_w3a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
                            void *stream);
 
+/* ---- INT2-g64 variant (Sec. 5, the extreme low-bit table: INT2 with group size 64) ----------
+ * The 4-level form of the quantizer (15 -> 3 in the formulas of awq_quantize_pack) over groups of
+ * AWQ_GROUP_W2 = 64 input channels, and its own packed layout, version 1.  `group` must be 64, N a
+ * multiple of 16, K a multiple of 256 (AWQ_ERR_UNSUPPORTED_GROUP / AWQ_ERR_BAD_SHAPE otherwise):
+ *   qweight : N*K/4 bytes; blocks of 16 rows x 256 columns (four groups, 1 KB), block index
+ *             (n/16)*(K/256) + k/256.  A block is 64 slots of 16 B = four little-endian 32-bit
+ *             words; slot (n%16) + 16*c holds, in word t, the 16 codes of columns
+ *             64*t + 32*j + 8*c + e (j = 0..1, e = 0..7) of the block.  Code i = 8*j + e is member
+ *             h = i%2 of pair p = i/2, at bits [2p, 2p+2) of the low (h = 0) or high (h = 1)
+ *             16-bit half.
+ *   scales  : N*(K/64)*2 bytes; [N/16][K/256][16 rows][4 groups] binary16.
+ *   zeros   : N*(K/64)/4 bytes; [N/16][K/256][16 rows]; the byte of a row holds the zero point of
+ *             group t of the block at bits [2t, 2t+2).
+ * Arguments, ownership and errors as for the 4-bit calls of the same name.  awq_unpack_w2 returns
+ * codes u8[N,K], scales f16[N,K/64], zeros u8[N,K/64] (each optional).
+ * awq_w2a16_linear: y = x' * dequant(q)^T with fp32 accumulation for 1 <= M <= 128 (the decode
+ * kernel; 17..128 rows run as blocks of 16 rows in one launch).  There is no 2-bit prefill kernel:
+ * larger M returns AWQ_ERR_BAD_SHAPE.  awq_w2a16_linear_multi: as awq_w4a16_linear_multi
+ * (1 <= M <= 16, up to AWQ_MULTI_MAX linears, eight per launch). */
+#define AWQ_GROUP_W2 64
+int awq_packed_sizes_w2(int64_t N, int64_t K, int group, size_t *qweight_bytes,
+                        size_t *scales_bytes, size_t *zeros_bytes);
+int awq_quantize_pack_w2(const void *W_f16, const float *s, int64_t N, int64_t K, int group,
+                         void *qweight, void *scales, void *zeros, void *stream);
+int awq_unpack_w2(const void *qweight, const void *scales, const void *zeros, int64_t N,
+                  int64_t K, int group, uint8_t *codes, void *scales_f16, uint8_t *zeros_u8,
+                  void *stream);
+int awq_w2a16_linear(const void *x_f16, const void *qweight, const void *scales,
+                     const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K, int group,
+                     void *stream);
+int awq_w2a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
+                           void *stream);
+
 /* ---- decode attention (Sec. 4.2 "Kernel fusion": positional embedding computed on the fly,
  * pre-allocated KV caches updated inside the attention kernel) --------------------------
  * One decode step of one sequence.  q [H,D], k, v [Hkv,D] fp16: the projections of the token at

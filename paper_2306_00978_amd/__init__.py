@@ -14,6 +14,7 @@ Function names and argument order mirror the C ABI:
     awq_quantize_pack_clip                        (Sec. 3.2 weight clipping)
     awq_decode_attention                          (Sec. 4.2 fused attention: rotary embedding, cache update)
     awq_*_w3                                      (Sec. 5, INT3-g128 variant: quantize, unpack, decode)
+    awq_*_w2                                      (Sec. 5, INT2-g64 variant: quantize, unpack, decode)
 """
 from __future__ import annotations
 
@@ -36,6 +37,8 @@ EXPORTS = [
     "awq_decode_attention_workspace_bytes", "awq_decode_attention", "awq_silu_mul",
     "awq_w4a16_linear_fused_multi", "awq_w4a16_linear_fused_fits",
     "awq_repack_w3_to_w4", "awq_w3a16_prefill_workspace_bytes", "awq_w3a16_linear_prefill",
+    "awq_packed_sizes_w2", "awq_quantize_pack_w2", "awq_unpack_w2", "awq_w2a16_linear",
+    "awq_w2a16_linear_multi",
     "awq_last_grouped_plan",
 ]
 MULTI_MAX = 56
@@ -130,6 +133,16 @@ def load() -> ctypes.CDLL:
     lib.awq_read_probe.argtypes = [vp, sz, vp, vp]
     lib.awq_rmsnorm_inv_scale.restype = i32
     lib.awq_rmsnorm_inv_scale.argtypes = [vp, vp, vp, i64, i64, ctypes.c_float, vp, vp]
+    lib.awq_packed_sizes_w2.restype = i32
+    lib.awq_packed_sizes_w2.argtypes = [i64, i64, i32, szp, szp, szp]
+    lib.awq_quantize_pack_w2.restype = i32
+    lib.awq_quantize_pack_w2.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.awq_unpack_w2.restype = i32
+    lib.awq_unpack_w2.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.awq_w2a16_linear.restype = i32
+    lib.awq_w2a16_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
+    lib.awq_w2a16_linear_multi.restype = i32
+    lib.awq_w2a16_linear_multi.argtypes = [ctypes.POINTER(LinearDesc), i32, i64, i32, vp]
     lib.awq_w3a16_linear_multi.restype = i32
     lib.awq_w3a16_linear_multi.argtypes = [ctypes.POINTER(LinearDesc), i32, i64, i32, vp]
     lib.awq_search_scale_workspace_bytes.restype = sz
@@ -473,6 +486,103 @@ def awq_w3a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int
     _check(load().awq_w3a16_linear(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(out), M, N, K,
                                    group, _stream()), "awq_w3a16_linear")
     return out
+
+
+# ---------------------------------------------------------------- INT2-g64 variant
+
+GROUP_W2 = 64
+
+
+def awq_packed_sizes_w2(N: int, K: int, group: int = GROUP_W2):
+    q, s, z = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load().awq_packed_sizes_w2(N, K, group, ctypes.byref(q), ctypes.byref(s), ctypes.byref(z)),
+           "awq_packed_sizes_w2")
+    return q.value, s.value, z.value
+
+
+def awq_quantize_pack_w2(W: torch.Tensor, s: torch.Tensor | None = None, group: int = GROUP_W2, out=None):
+    """W [N,K] fp16, s [K] fp32 or None -> (qweight u8[N*K/4], scales f16, zeros u8), 2-bit layout."""
+    _dev(W, torch.float16, "W")
+    N, K = W.shape
+    if s is not None:
+        _dev(s, torch.float32, "s")
+        if s.numel() != K:
+            raise ValueError("s must have K elements")
+    qb, sb, zb = awq_packed_sizes_w2(N, K, group)
+    if out is None:
+        out = (torch.empty(qb, dtype=torch.uint8, device=W.device),
+               torch.empty(sb // 2, dtype=torch.float16, device=W.device),
+               torch.empty(max(zb, 16), dtype=torch.uint8, device=W.device)[:zb])
+    qweight, scales, zeros = out
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * 2 < sb \
+            or zeros.numel() * zeros.element_size() < zb:
+        raise ValueError("output buffers are too small")
+    _check(load().awq_quantize_pack_w2(_ptr(W), _ptr(s), N, K, group, _ptr(qweight), _ptr(scales),
+                                       _ptr(zeros), _stream()), "awq_quantize_pack_w2")
+    return qweight, scales, zeros
+
+
+def awq_unpack_w2(qweight, scales, zeros, N: int, K: int, group: int = GROUP_W2):
+    """Canonical arrays of the 2-bit layout: codes u8[N,K], scales f16[N,K/64], zeros u8[N,K/64]."""
+    dev = qweight.device
+    codes = torch.empty((N, K), dtype=torch.uint8, device=dev)
+    sc = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+    zp = torch.empty((N, K // group), dtype=torch.uint8, device=dev)
+    _check(load().awq_unpack_w2(_ptr(qweight), _ptr(scales), _ptr(zeros), N, K, group, _ptr(codes),
+                                _ptr(sc), _ptr(zp), _stream()), "awq_unpack_w2")
+    return codes, sc, zp
+
+
+def awq_w2a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int = GROUP_W2, out=None):
+    """y [M,N] fp16 = x [M,K] fp16 (already divided by s) times the 2-bit packed weight, M <= 128."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _dev(out, torch.float16, "y")
+    qb, sb, zb = awq_packed_sizes_w2(N, K, group)
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+            or zeros.numel() * zeros.element_size() < zb or out.numel() != M * N:
+        raise ValueError("buffer sizes do not match the shape")
+    _check(load().awq_w2a16_linear(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(out), M, N, K,
+                                   group, _stream()), "awq_w2a16_linear")
+    return out
+
+
+def prepare_linear_multi_w2(linears, group: int = GROUP_W2):
+    """As prepare_linear_multi for linears in the 2-bit layout."""
+    if not 1 <= len(linears) <= MULTI_MAX:
+        raise ValueError(f"1..{MULTI_MAX} linears per grouped call")
+    descs = (LinearDesc * len(linears))()
+    M = None
+    for i, (x, qweight, scales, zeros, y, N) in enumerate(linears):
+        _dev(x, torch.float16, "x")
+        _dev(y, torch.float16, "y")
+        m, K = x.shape
+        if M is None:
+            M = m
+        if m != M:
+            raise ValueError("all linears of a grouped call share M")
+        qb, sb, zb = awq_packed_sizes_w2(N, K, group)
+        if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+                or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
+            raise ValueError("buffer sizes do not match the shape")
+        descs[i] = LinearDesc(x.data_ptr(), qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
+                              y.data_ptr(), N, K)
+    fn = load().awq_w2a16_linear_multi
+    count = len(linears)
+    keep = list(linears)
+
+    def call(_keep=keep):
+        st = fn(descs, count, M, group, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_w2a16_linear_multi")
+    return call
+
+
+def awq_w2a16_linear_multi(linears, group: int = GROUP_W2):
+    prepare_linear_multi_w2(linears, group)()
+    return [l[4] for l in linears]
 
 
 def prepare_linear_multi_w3(linears, group: int = GROUP):

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libawq_mi355x.so")
 SOURCES = ["awq_api.hip", "awq_prep.hip", "awq_quantize.hip", "awq_gemv.hip", "awq_gemv_stream.hip", "awq_gemm.hip",
-           "awq_linear.hip", "awq_search.hip", "awq_w3.hip", "awq_attention.hip"]
+           "awq_linear.hip", "awq_search.hip", "awq_w3.hip", "awq_w2.hip", "awq_attention.hip"]
 
 COMMON = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -21,7 +21,7 @@ COMMON = [
 ]
 # the quantizer decides integers: one rounding per operation, as on the CPU side
 PER_FILE = {"awq_quantize.hip": ["-ffp-contract=off"], "awq_prep.hip": ["-ffp-contract=off"],
-            "awq_w3.hip": ["-ffp-contract=off"]}
+            "awq_w3.hip": ["-ffp-contract=off"], "awq_w2.hip": ["-ffp-contract=off"]}
 
 
 def hipcc() -> str:

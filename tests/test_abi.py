@@ -212,6 +212,24 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert lib.awq_w3a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 0, 16, 128, 128, None) == -2
     assert lib.awq_w3a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(odd), 1, 16, 128, 128, None) == -4
 
+    # INT2-g64 variant
+    q2, s2, z2 = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.awq_packed_sizes_w2(4096, 4096, 64, ctypes.byref(q2), ctypes.byref(s2), ctypes.byref(z2)) == 0
+    assert (q2.value, s2.value, z2.value) == (4096 * 4096 // 4, 4096 * 64 * 2, 4096 * 64 // 4)
+    assert (q2.value + s2.value + z2.value) * 256 == 4096 * 4096 * 73          # 0.28515625 B per weight
+    assert lib.awq_packed_sizes_w2(4096, 4096 + 128, 64, None, None, None) == -2      # K % 256
+    assert lib.awq_packed_sizes_w2(4096, 4096, 128, None, None, None) == -3
+    assert lib.awq_quantize_pack_w2(None, None, 16, 256, 64, Pq(ok), Pq(ok), Pq(ok), None) == -1
+    assert lib.awq_quantize_pack_w2(Pq(ok), None, 16, 256, 128, Pq(ok), Pq(ok), Pq(ok), None) == -3
+    assert lib.awq_quantize_pack_w2(Pq(odd), None, 16, 256, 64, Pq(ok), Pq(ok), Pq(ok), None) == -4
+    assert lib.awq_unpack_w2(Pq(ok), None, Pq(ok), 16, 256, 64, Pq(ok), Pq(ok), Pq(ok), None) == -1
+    assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), None, 1, 16, 256, 64, None) == -1
+    assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 129, 16, 256, 64, None) == -2
+    assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 0, 16, 256, 64, None) == -2
+    assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 1, 16, 384, 64, None) == -2
+    assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(odd), 1, 16, 256, 64, None) == -4
+    assert lib.awq_w2a16_linear_multi(None, 1, 1, 64, None) == -1
+
     g = lib.awq_search_scale
     wsb = lib.awq_search_scale_workspace_bytes
     al = (ctypes.c_float * 3)(0.0, 0.5, 1.0)
