@@ -437,6 +437,38 @@ def main():
                     "weights), then the 4-bit prefill kernel"}
         del graphs3, lay3, y3, ws3
 
+        # INT2-g64 variant: the seven projections of a layer in one launch of its decode kernel,
+        # M = 1 (0.28515625 B per weight), L distinct layers cycled
+        lay2 = []
+        for l in range(min(L, 8)):
+            packed = []
+            for name, N, K in shapes:
+                W = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
+                     * workloads.SIGMA_7B).to(torch.float16)
+                packed.append(awq.awq_quantize_pack_w2(W, s_by_k[K]))
+                del W
+            lay2.append(packed)
+        ys2 = [torch.empty((1, N), dtype=torch.float16, device=dev) for _, N, K in shapes]
+        calls2 = [awq.prepare_linear_multi_w2([(x_by_k[K][:1], *lay2[l][p], ys2[p], N)
+                                               for p, (_, N, K) in enumerate(shapes)]) for l in range(len(lay2))]
+        for i in range(2 * len(calls2)):
+            calls2[i % len(calls2)]()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(xsteps):
+            calls2[i % len(calls2)]()
+        e1.record()
+        torch.cuda.synchronize()
+        ms2 = e0.elapsed_time(e1) / xsteps
+        b2g = sum(sum(awq.awq_packed_sizes_w2(N, K)) + 2 * K + 2 * N for _, N, K in shapes)
+        extras["decode_m1_int2_g64_grouped"] = {
+            "bytes_per_step": b2g, "ms_per_step": round(ms2, 5), "GB/s": gbs(b2g, ms2),
+            "pct_of_hbm_peak": round(100 * gbs(b2g, ms2) / HBM_PEAK_GBS, 2),
+            "time_vs_int4_grouped": round(ms2 / ev_ms, 3),
+            "note": "one launch of the 7 projections in the 2-bit layout, group size 64 (0.55 of the INT4 bytes)"}
+        del lay2, calls2
+
         # configs[3]: the seven projections of a Llama-2-70B-shaped layer (444.5 MB per launch), M = 1
         # and 8, one grouped launch per step, two distinct layers cycled
         shapes70 = workloads.LLAMA2_70B_LAYER

@@ -15,13 +15,14 @@
 // A row's four steps of a block are stored together (one 8-byte load per lane), its four zero
 // points share a byte.
 //
-// Decode kernel (M <= 16): a workgroup owns one 16-row block of one linear, its waves split the
-// K/256 blocks.  Per block a wave copies the 256-column slice of x it needs into its own LDS
-// area (two rows per pass of 16-byte loads, no workgroup barrier), requests the next block's
-// loads, and runs eight MFMA steps against the codes and eight against the constant code 1:
-//   sum_k x_k (q_k - z) = 2^24 * (MFMA(x, q 2^-24) - z * MFMA(x, 2^-24)),  per group of 64,
-// then applies the group's step in fp32.  Partial sums of the waves are combined through LDS in
-// a fixed order.  Several linears (different shapes, same M) can share one launch.
+// Decode kernel (M <= 16): a wave owns a 16-row block of one linear, or a slice of its K/256
+// blocks where rows are long.  Per batch of up to four blocks a wave requests everything at once, copies the
+// slice of x it needs into its own LDS area (16-byte loads, no workgroup barrier), and runs per
+// block eight MFMA steps against the codes and eight against the constant -z 2^-24 of the lane's
+// row (a negative subnormal), all in one accumulator per group:
+//   sum_k x_k (q_k - z) = 2^24 * (MFMA(x, q 2^-24) + MFMA(x, -z 2^-24)),  per group of 64,
+// then applies the group's step with one fp32 FMA per output.  Partial sums of the slices of a row block are combined
+// through LDS in a fixed order.  Several linears (different shapes, same M) can share one launch.
 //
 // This file is compiled with -ffp-contract=off (integer decisions in the quantizer).
 #include "awq_common.h"
@@ -177,40 +178,57 @@ struct W2Problem {
     int N, K;
 };
 
+constexpr int W2_WAVES = 4;               // waves per workgroup
+
 struct W2Args {
     W2Problem p[W2_MAX_PROBLEMS];
     int wg_begin[W2_MAX_PROBLEMS];     // first workgroup of each problem (wg_begin[0] = 0)
-    int count, M, logW;
+    int logS[W2_MAX_PROBLEMS];         // log2 of the K slices per row block: 0, 1 or 2
+    int count, M;
 };
 
-// MS = rows of x a wave stages per block (M <= MS, one of 1, 2, 4, 8, 16); rows >= M repeat row
-// M-1 (row m of the MFMA result depends on row m of A only, and rows >= M are never stored).
-// Dynamic LDS: [W][MS rows x 528 bytes], then 16*M outputs x 16 wave slots of fp32.
-template <int MS>
-__global__ __launch_bounds__(1024) void gemv_w2_kernel(const W2Args a)
+// A workgroup has four waves; for a linear with S = 2^logS slices of K per row block it owns 4/S
+// row blocks, wave w taking slice w % S of row block w / S.  Short rows (S = 1) give every wave a
+// row block of its own and no exchange between waves at all; long rows are cut so that the waves
+// of all linears of a launch have about the same number of blocks.
+// MS = rows of x a wave stages (M <= MS, one of 1, 2, 4, 8, 16); rows >= M repeat row M-1 (row m
+// of the MFMA result depends on row m of A only, and rows >= M are never stored).
+// U = blocks per batch: all loads of a batch (its slice of x first, then steps, zero points and
+// codes) are requested before anything is consumed, so a wave has U KB of codes in flight.  The
+// blocks of a batch past the end of the wave's range repeat the range's last block (loads from
+// addresses that are in bounds) and are skipped by a wave-uniform branch.
+// Dynamic LDS: [4 waves][MS rows x (U*512 + 16) bytes], then [4/S row blocks][16*M outputs][4
+// slots] of fp32 for the sum over the slices.
+template <int MS, int U, bool PF>
+__global__ __launch_bounds__(256, 4) void gemv_w2_kernel(const W2Args a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int NS = (MS + 1) / 2;               // 32 lanes x 16 B cover one row: two rows per pass
-    constexpr int ROW_BYTES = 512 + 16;            // +16: rows land on different banks
+    constexpr int CHUNKS = MS * U * 32;            // 16-byte chunks of x per batch
+    constexpr int NS = (CHUNKS + 63) / 64;         // passes of one load per lane
+    constexpr int ROW_BYTES = U * 512 + 16;        // +16: rows land on different banks
     constexpr int WAVE_BYTES = MS * ROW_BYTES;
     // the linear this workgroup works on: scalar selects over the argument table
     W2Problem P = a.p[0];
-    int first = 0;
+    int first = 0, logS = a.logS[0];
 #pragma unroll
     for (int i = 1; i < W2_MAX_PROBLEMS; ++i)
         if (i < a.count && (int)blockIdx.x >= a.wg_begin[i]) {
             P = a.p[i];
             first = a.wg_begin[i];
+            logS = a.logS[i];
         }
-    const int M = a.M, logW = a.logW;
+    const int M = a.M;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int W = 1 << logW;
-    const int rb = blockIdx.x - first;
-    const int r = lane & 15, c = lane >> 4;
+    const int S = 1 << logS, RBW = W2_WAVES >> logS;
+    const int slice = wave & (S - 1), rbi = wave >> logS;
     const int K = P.K, N = P.N;
     const int B = K >> 8;
-    const int b0 = (B * wave) >> logW, b1 = (B * (wave + 1)) >> logW;
+    const int rb_raw = ((int)blockIdx.x - first) * RBW + rbi;
+    const bool active = rb_raw < (N >> 4);         // the last workgroup of a linear may have spare waves
+    const int rb = active ? rb_raw : 0;
+    const int r = lane & 15, c = lane >> 4;
+    const int b0 = active ? (B * slice) >> logS : 0, b1 = active ? (B * (slice + 1)) >> logS : 0;
 
     const uint4 *qt = P.q + (int64_t)rb * B * 64 + lane;
     const uint2 *sc = P.sc + (int64_t)rb * B * 16 + r;
@@ -218,105 +236,128 @@ __global__ __launch_bounds__(1024) void gemv_w2_kernel(const W2Args a)
     const int mrow = r < M ? r : M - 1;
     unsigned char *xw = smem + (size_t)wave * WAVE_BYTES;
     const uint4 *xl = reinterpret_cast<const uint4 *>(xw + mrow * ROW_BYTES) + c;
-    const int srow = lane >> 5, schunk = lane & 31;
-    const uint4 *xstage = reinterpret_cast<const uint4 *>(P.x) + schunk;
+    const uint4 *xg = reinterpret_cast<const uint4 *>(P.x);
     const int64_t K8 = (int64_t)K >> 3;
 
-    // One block as loaded from global memory: the staging rows of x (requested first, so that
-    // they return first), the row's four steps and zero points, the codes.
-    uint4 xs[NS], q_cur;
-    uint2 s_cur;
-    uint32_t z_cur;
+    // opaque to the optimizer, so that (v & mask) | sign is selected as one v_and_or_b32
+    uint32_t kmask = 0x00030003u, ksign = 0x80008000u;
+    asm("" : "+s"(kmask));
+    asm("" : "+v"(ksign));
+    floatx4 total = {0.f, 0.f, 0.f, 0.f};
+    // chunk ci = 64 i + lane of a batch's slice of x: row ci / (32 U), block (ci / 32) % U,
+    // 16-byte chunk ci % 32 of the block
+    uint4 xs[NS], q[U];
+    uint2 sv[U];
+    uint32_t z[U];
+    auto request = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int ci = 64 * i + lane;
+            const int m = ci / (32 * U), u = (ci >> 5) % U;
+            const int bu = b + u < b1 ? b + u : b1 - 1;
+            xs[i] = xg[(int64_t)(m < M ? m : M - 1) * K8 + bu * 32 + (ci & 31)];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int bu = b + u < b1 ? b + u : b1 - 1;
+            sv[u] = sc[bu * 16];
+            z[u] = zp[bu * 16];
+            q[u] = qt[bu * 64];
+        }
+    };
 #pragma unroll
     for (int i = 0; i < NS; ++i) xs[i] = make_uint4(0, 0, 0, 0);
-    q_cur = make_uint4(0, 0, 0, 0);
-    s_cur = make_uint2(0, 0);
-    z_cur = 0;
-    if (b0 < b1) {
 #pragma unroll
-        for (int i = 0; i < NS; ++i) {
-            const int m = 2 * i + srow;
-            xs[i] = xstage[(int64_t)(m < M ? m : M - 1) * K8 + b0 * 32];
-        }
-        s_cur = sc[b0 * 16];
-        z_cur = zp[b0 * 16];
-        q_cur = qt[b0 * 64];
+    for (int u = 0; u < U; ++u) {
+        q[u] = make_uint4(0, 0, 0, 0);
+        sv[u] = make_uint2(0, 0);
+        z[u] = 0;
     }
-    const half8_t ones = __builtin_bit_cast(half8_t, make_uint4(0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u));
-    floatx4 total = {0.f, 0.f, 0.f, 0.f};
-    for (int b = b0; b < b1; ++b) {
-        // LDS operations of one wave execute in order: these stores follow the previous block's reads
+    if (b0 < b1) request(b0);
+    for (int b = b0; b < b1; b += U) {
+        // LDS operations of one wave execute in order: these stores follow the previous batch's reads
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            const int m = 2 * i + srow;
-            if (m < MS) reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[schunk] = xs[i];
+            const int ci = 64 * i + lane;
+            const int m = ci / (32 * U), cc = ci % (32 * U);
+            reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[cc] = xs[i];
         }
-        const uint32_t w[4] = {q_cur.x, q_cur.y, q_cur.z, q_cur.w};
-        const uint32_t sraw[4] = {s_cur.x & 0xFFFFu, s_cur.x >> 16, s_cur.y & 0xFFFFu, s_cur.y >> 16};
-        const uint32_t z = z_cur;
-        // the next block is requested before this one is consumed (the last block of a wave
-        // requests itself again: an unconditional load from an address that is in bounds)
-        const int bn = b + 1 < b1 ? b + 1 : b;
+        // PF: this batch's codes move to registers of their own and the next batch is requested
+        // before this one is consumed (where the registers allow it); otherwise after it
+        uint4 qc[U];
+        uint2 svc[U];
+        uint32_t zc[U];
 #pragma unroll
-        for (int i = 0; i < NS; ++i) {
-            const int m = 2 * i + srow;
-            xs[i] = xstage[(int64_t)(m < M ? m : M - 1) * K8 + bn * 32];
+        for (int u = 0; u < U; ++u) {
+            qc[u] = q[u];
+            svc[u] = sv[u];
+            zc[u] = z[u];
         }
-        s_cur = sc[bn * 16];
-        z_cur = zp[bn * 16];
-        q_cur = qt[bn * 64];
-        uint4 xa[8];
+        if (PF && b + U < b1) request(b + U);      // wave-uniform
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) xa[jj] = xl[4 * jj];      // k = 32 jj + 8 c + 0..7
+        for (int u = 0; u < U; ++u) {
+            if (b + u < b1) {                      // wave-uniform
+                uint4 xa[8];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            floatx4 acc = {0.f, 0.f, 0.f, 0.f}, xsum = {0.f, 0.f, 0.f, 0.f};
+                for (int jj = 0; jj < 8; ++jj) xa[jj] = xl[u * 32 + 4 * jj];      // k = 256 u + 32 jj + 8 c + 0..7
+                const uint32_t w[4] = {qc[u].x, qc[u].y, qc[u].z, qc[u].w};
+                const uint32_t sraw[4] = {svc[u].x & 0xFFFFu, svc[u].x >> 16, svc[u].y & 0xFFFFu, svc[u].y >> 16};
+                const uint32_t zz = zc[u] * 0x00010001u;            // the zero-point byte in both halves
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const half8_t av = __builtin_bit_cast(half8_t, xa[2 * t + j]);
-                const half8_t bv = __builtin_bit_cast(half8_t, w2_fragment(w[t], j));
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc, 0, 0, 0);
-                xsum = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, ones, xsum, 0, 0, 0);
+                for (int t = 0; t < 4; ++t) {
+                    // -z * 2^-24 in every column of this lane's row: a negative fp16 subnormal
+                    const uint32_t zt = zz >> (2 * t);
+                    const half8_t zv = __builtin_bit_cast(half8_t, make_uint4((zt & kmask) | ksign, (zt & kmask) | ksign,
+                                                                              (zt & kmask) | ksign, (zt & kmask) | ksign));
+                    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const half8_t av = __builtin_bit_cast(half8_t, xa[2 * t + j]);
+                        const half8_t bv = __builtin_bit_cast(half8_t, w2_fragment(w[t], j));
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, zv, acc, 0, 0, 0);
+                    }
+                    const float s24 = (float)__builtin_bit_cast(half_t, (uint16_t)sraw[t]) * 16777216.f;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) total[v] = __builtin_fmaf(s24, acc[v], total[v]);
+                }
             }
-            const float zf = (float)((z >> (2 * t)) & 3u);
-            const float s24 = (float)__builtin_bit_cast(half_t, (uint16_t)sraw[t]) * 16777216.f;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) total[v] += s24 * (acc[v] - zf * xsum[v]);
         }
+        if (!PF && b + U < b1) request(b + U);
     }
 
-    // lane holds the partial y[m = 4c + v][n = 16 rb + r]; combine the waves in fixed order.
-    // red[t][w], t = 16 m + n: the 16 partials of one output are contiguous.
-    float *red = reinterpret_cast<float *>(smem + (size_t)W * WAVE_BYTES);
+    // lane holds y[m = 4c + v][n = 16 rb + r], complete (S = 1) or one slice's share of it
+    if (logS == 0) {                               // uniform over the workgroup: no barrier below
+        if (active) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (4 * c + v < M) P.y[(int64_t)(4 * c + v) * N + rb * 16 + r] = (half_t)total[v];
+        }
+        return;
+    }
+    // red[rbi][t][slot], t = 16 m + n: the partials of one output are contiguous, summed in fixed order
+    const int MP = (M + 3) & ~3;
+    float *red = reinterpret_cast<float *>(smem + (size_t)W2_WAVES * WAVE_BYTES);
     if (4 * c < M) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) red[((4 * c + v) * 16 + r) * 16 + wave] = total[v];
+        for (int v = 0; v < 4; ++v) red[((rbi * MP + 4 * c + v) * 16 + r) * 4 + slice] = total[v];
     }
     __syncthreads();
-    for (int t = threadIdx.x; t < 16 * M; t += blockDim.x) {
-        const float4 *p = reinterpret_cast<const float4 *>(red + t * 16);
-        const float4 a0 = p[0], a1 = p[1], a2 = p[2], a3 = p[3];
-        const float part[16] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w,
-                                a2.x, a2.y, a2.z, a2.w, a3.x, a3.y, a3.z, a3.w};
-        float sum = 0.f;
-#pragma unroll
-        for (int w2 = 0; w2 < 16; ++w2) sum += (w2 < W) ? part[w2] : 0.f;
-        P.y[(int64_t)(t >> 4) * N + rb * 16 + (t & 15)] = (half_t)sum;
+    for (int t = threadIdx.x; t < RBW * 16 * M; t += blockDim.x) {
+        const int ri = t / (16 * M), o = t - ri * 16 * M;       // row block of the workgroup, output in it
+        const int rbo = ((int)blockIdx.x - first) * RBW + ri;
+        if (rbo < (N >> 4)) {
+            const float4 pr = *reinterpret_cast<const float4 *>(red + ((ri * MP + (o >> 4)) * 16 + (o & 15)) * 4);
+            const float sum = S == 2 ? pr.x + pr.y : (pr.x + pr.y) + (pr.z + pr.w);
+            P.y[(int64_t)(o >> 4) * N + rbo * 16 + (o & 15)] = (half_t)sum;
+        }
     }
 }
 
-template <int MS>
+template <int MS, int U, bool PF>
 int launch_w2_one(const W2Args &a, int total_wgs, size_t lds, hipStream_t stream)
 {
-    static AwqOncePerDevice once;
-    bool &raised = once.here();
-    if (lds > 64 * 1024 && !raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_w2_kernel<MS>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return AWQ_ERR_HIP;
-        raised = true;
-    }
-    gemv_w2_kernel<MS><<<dim3(total_wgs), dim3(64 << a.logW), lds, stream>>>(a);
+    gemv_w2_kernel<MS, U, PF><<<dim3(total_wgs), dim3(64 * W2_WAVES), lds, stream>>>(a);
     return awq_launch_status();
 }
 
@@ -333,28 +374,33 @@ int launch_w2(const W2Problem *probs, int count, int M, hipStream_t stream)
             order[j] = order[j - 1];
             order[j - 1] = t;
         }
-    int total = 0, maxB = 0;
+    int64_t row_blocks = 0;
+    for (int i = 0; i < count; ++i) row_blocks += probs[i].N / 16;
+    // enough row blocks to give every CU several waves: about 16 blocks (four batches) per wave;
+    // otherwise K is cut as far as it goes so that the launch has more waves
+    const bool wide = row_blocks > 1024;
+    int total = 0;
     for (int i = 0; i < count; ++i) {
         a.p[i] = probs[order[i]];
+        const int B = a.p[i].K / 256;
+        const int logS = wide ? (B <= 16 ? 0 : (B <= 32 ? 1 : 2)) : (B >= 4 ? 2 : (B >= 2 ? 1 : 0));
+        a.logS[i] = logS;
         a.wg_begin[i] = total;
-        total += a.p[i].N / 16;
-        if (a.p[i].K / 256 > maxB) maxB = a.p[i].K / 256;
+        const int rbw = W2_WAVES >> logS;
+        total += (a.p[i].N / 16 + rbw - 1) / rbw;
     }
     a.count = count;
     a.M = M;
     const int MS = M == 1 ? 1 : (M == 2 ? 2 : (M <= 4 ? 4 : (M <= 8 ? 8 : 16)));
-    // about two blocks per wave, 1..16 waves; 16 rows x 16 waves of staging would leave no LDS
-    int logW = maxB >= 32 ? 4 : (maxB >= 16 ? 3 : (maxB >= 8 ? 2 : (maxB >= 4 ? 1 : 0)));
-    if (MS == 16 && logW > 3) logW = 3;
-    a.logW = logW;
-    const size_t lds = (size_t)((M + 3) / 4 * 4) * 1024 + (size_t)(1 << logW) * MS * 528;
-    if (lds > (size_t)160 * 1024) return AWQ_ERR_BAD_SHAPE;
+    // blocks per batch: at most eight passes of staging loads per lane
+    const int U = MS <= 4 ? 4 : (MS == 8 ? 2 : 1);
+    const size_t lds = (size_t)W2_WAVES * MS * (U * 512 + 16) + (size_t)W2_WAVES * ((M + 3) / 4 * 4) * 256;
     switch (MS) {
-    case 1: return launch_w2_one<1>(a, total, lds, stream);
-    case 2: return launch_w2_one<2>(a, total, lds, stream);
-    case 4: return launch_w2_one<4>(a, total, lds, stream);
-    case 8: return launch_w2_one<8>(a, total, lds, stream);
-    default: return launch_w2_one<16>(a, total, lds, stream);
+    case 1: return launch_w2_one<1, 4, true>(a, total, lds, stream);
+    case 2: return launch_w2_one<2, 4, false>(a, total, lds, stream);
+    case 4: return launch_w2_one<4, 4, false>(a, total, lds, stream);
+    case 8: return launch_w2_one<8, 2, true>(a, total, lds, stream);
+    default: return launch_w2_one<16, 1, true>(a, total, lds, stream);
     }
 }
 
