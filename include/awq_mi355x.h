@@ -264,10 +264,10 @@ int awq_w3a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, i
  * multiple of 16, K a multiple of 256 (AWQ_ERR_UNSUPPORTED_GROUP / AWQ_ERR_BAD_SHAPE otherwise):
  *   qweight : N*K/4 bytes; blocks of 16 rows x 256 columns (four groups, 1 KB), block index
  *             (n/16)*(K/256) + k/256.  A block is 64 slots of 16 B = four little-endian 32-bit
- *             words; slot (n%16) + 16*c holds, in word t, the 16 codes of columns
- *             64*t + 32*j + 8*c + e (j = 0..1, e = 0..7) of the block.  Code i = 8*j + e is member
- *             h = i%2 of pair p = i/2, at bits [2p, 2p+2) of the low (h = 0) or high (h = 1)
- *             16-bit half.
+ *             words; slot (n%16) + 16*c holds the 64 codes of columns 64*t + 32*j + 8*c + 2*i + h
+ *             of the block (group t = 0..3, half of the group j = 0..1, i = 0..3, h = 0..1): word
+ *             i holds the codes with that i, the code of (t, j, h) in field f = t + 4*j, bits
+ *             [2f, 2f+2), of the low (h = 0) or high (h = 1) 16-bit half.
  *   scales  : N*(K/64)*2 bytes; [N/16][K/256][16 rows][4 groups] binary16.
  *   zeros   : N*(K/64)/4 bytes; [N/16][K/256][16 rows]; the byte of a row holds the zero point of
  *             group t of the block at bits [2t, 2t+2).

@@ -603,10 +603,11 @@ int awq_oracle_quantize_w2(const uint16_t *W, const float *s, int64_t N, int64_t
 /* Packed layout of the 2-bit codes (written from the layout text).  K is a multiple of 256:
  * qweight: blocks of 16 rows x 256 columns (four groups of 64), 1024 bytes each, block index
  *          (n/16)*(K/256) + k/256.  Inside a block, 64 slots of 16 bytes = four little-endian
- *          32-bit words; slot l = (n%16) + 16*c owns row n%16 and, in word t (0..3), the 16
- *          codes of group t of the block: columns 64*t + 32*j + 8*c + e (j = 0..1, e = 0..7).
- *          Code i = 8*j + e belongs to pair p = i/2, member h = i%2, and sits at bits
- *          [2p, 2p+2) of the low (h = 0) or high (h = 1) 16-bit half of the word.
+ *          32-bit words; slot l = (n%16) + 16*c owns row n%16 and the 64 codes of columns
+ *          64*t + 32*j + 8*c + 2*i + h of the block (group t = 0..3, half of the group j = 0..1,
+ *          i = 0..3, h = 0..1).  Word i holds the codes with that i: the code of (t, j, h) sits
+ *          in field f = t + 4*j, bits [2f, 2f+2), of the low (h = 0) or high (h = 1) 16-bit
+ *          half of the word.
  * scales : [N/16][K/256][16 rows][4 groups] binary16 (the group of the block innermost)
  * zeros  : [N/16][K/256][16 rows] bytes; the byte of a row holds the zero point of group t of
  *          the block at bits [2t, 2t+2).                                                   */
@@ -627,10 +628,10 @@ int awq_oracle_pack_w2(const uint8_t *codes, const uint16_t *scales, const uint8
             int kk = (int)(k % 256);
             int t = kk / 64, j = (kk % 64) / 32, c = (kk % 32) / 8, e = kk % 8;
             int slot = r + 16 * c;
-            int i = 8 * j + e, p = i / 2, h = i % 2;
-            int pos = 16 * h + 2 * p;
+            int i = e / 2, h = e % 2, f = t + 4 * j;
+            int pos = 16 * h + 2 * f;
             uint8_t code = codes[n * K + k] & 0x3;
-            qweight[block * 1024 + slot * 16 + t * 4 + pos / 8] |= (uint8_t)(code << (pos % 8));
+            qweight[block * 1024 + slot * 16 + i * 4 + pos / 8] |= (uint8_t)(code << (pos % 8));
         }
         for (int64_t g = 0; g < G; ++g) {
             int64_t block = rb * B + g / 4;
@@ -655,15 +656,16 @@ int awq_oracle_unpack_w2(const uint8_t *qweight, const uint16_t *scales_p,
         for (int slot = 0; slot < 64; ++slot) {
             int r = slot % 16, c = slot / 16;
             int64_t n = rb * 16 + r;
-            for (int t = 0; t < 4; ++t) {
-                const uint8_t *wb = qweight + block * 1024 + slot * 16 + t * 4;
+            for (int i = 0; i < 4; ++i) {
+                const uint8_t *wb = qweight + block * 1024 + slot * 16 + i * 4;
                 uint32_t word = (uint32_t)wb[0] | ((uint32_t)wb[1] << 8) |
                                 ((uint32_t)wb[2] << 16) | ((uint32_t)wb[3] << 24);
-                for (int i = 0; i < 16; ++i) {
-                    int p = i / 2, h = i % 2;
-                    int64_t k = b * 256 + 64 * t + 32 * (i / 8) + 8 * c + (i % 8);
-                    codes[n * K + k] = (uint8_t)((word >> (16 * h + 2 * p)) & 0x3);
-                }
+                for (int h = 0; h < 2; ++h)
+                    for (int f = 0; f < 8; ++f) {
+                        int t = f % 4, j = f / 4;
+                        int64_t k = b * 256 + 64 * t + 32 * j + 8 * c + 2 * i + h;
+                        codes[n * K + k] = (uint8_t)((word >> (16 * h + 2 * f)) & 0x3);
+                    }
             }
         }
         for (int r = 0; r < 16; ++r) {

@@ -7,21 +7,24 @@
 //
 // Packed layout.  The unit is a block of 16 rows x 256 columns = four groups, 1 KB, so that a lane
 // still fetches 16 bytes and a wave 1 KB of contiguous codes per load.  Lane l = (row l%16, column
-// block c = l/16) owns, in word t of its 16-byte slot, the 16 codes of group t of the block:
-// columns 64 t + 32 j + 8 c + e (j = 0..1, e = 0..7).  Code i = 8 j + e is member h = i%2 of pair
-// p = i/2 and sits at bits [2p, 2p+2) of the low (h = 0) or high (h = 1) half of the word, so
-// that (word >> 2p) & 0x00030003 is the pair as two fp16 SUBNORMALS q * 2^-24 -- the B-operand
-// register of v_mfma_f32_16x16x32_f16 for columns (k, k+1), with no integer-to-float conversion.
-// A row's four steps of a block are stored together (one 8-byte load per lane), its four zero
-// points share a byte.
+// block c = l/16) owns the 64 codes of columns 64 t + 32 j + 8 c + 2 i + h (group t, half of the
+// group j, i = 0..3, h = 0..1).  Word i of its 16-byte slot holds the codes with that i: the code
+// of (t, j, h) in field f = t + 4 j, bits [2f, 2f+2), of the low (h = 0) or high (h = 1) half.
+// Then  (word >> 8 j) & (0x00030003 << 2 t)  -- one AND, and one shift per word for j = 1 -- is
+// the pair of columns (2i, 2i+1) of MFMA step (t, j) as two fp16 SUBNORMALS q * 4^t * 2^-24: the
+// B-operand register i of v_mfma_f32_16x16x32_f16, with no integer-to-float conversion and no
+// shift to the low bits.  The factor 4^t is the same for the whole group and is divided out
+// together with the group's step.  A row's four steps of a block are stored together (one 8-byte
+// load per lane), its four zero points share a byte, zero point t at bits [2t, 2t+2) -- the same
+// place as the codes of group t, so the zero point needs no shift either.
 //
 // Decode kernel (M <= 16): a wave owns a 16-row block of one linear, or a slice of its K/256
 // blocks where rows are long.  Per batch of up to four blocks a wave requests everything at once, copies the
 // slice of x it needs into its own LDS area (16-byte loads, no workgroup barrier), and runs per
-// block eight MFMA steps against the codes and eight against the constant -z 2^-24 of the lane's
-// row (a negative subnormal), all in one accumulator per group:
-//   sum_k x_k (q_k - z) = 2^24 * (MFMA(x, q 2^-24) + MFMA(x, -z 2^-24)),  per group of 64,
-// then applies the group's step with one fp32 FMA per output.  Partial sums of the slices of a row block are combined
+// block eight MFMA steps against the codes and eight against the constant -z 4^t 2^-24 of the
+// lane's row (a negative subnormal), all in one accumulator per group:
+//   sum_k x_k (q_k - z) = 2^24 4^-t * (MFMA(x, q 4^t 2^-24) + MFMA(x, -z 4^t 2^-24)),  per group,
+// then applies the group's step (times 2^(24 - 2t)) with one fp32 FMA per output.  Partial sums of the slices of a row block are combined
 // through LDS in a fixed order.  Several linears (different shapes, same M) can share one launch.
 //
 // This file is compiled with -ffp-contract=off (integer decisions in the quantizer).
@@ -67,7 +70,7 @@ __global__ __launch_bounds__(256) void quantize_pack_w2_kernel(
 #pragma unroll
     for (int i = 0; i < 8; ++i) raw[i] = W[n * K8 + b * 32 + 4 * i + c];     // i = 2 t + j
 
-    uint32_t words[4], zbyte = 0;
+    uint32_t words[4] = {0u, 0u, 0u, 0u}, zbyte = 0;
     uint16_t sc_bits[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -105,15 +108,13 @@ __global__ __launch_bounds__(256) void quantize_pack_w2_kernel(
         const float zr = nmn / scale;
         const float zero = clamp2(__builtin_rintf(zr), 0.0f, 3.0f);
 
-        uint32_t word = 0;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 16; ++i) {             // i = 8 j + e, e = 2 (word) + h
             float v = __builtin_rintf(wp[i] / scale);
             v = v + zero;
             v = clamp2(v, 0.0f, 3.0f);
-            word |= (uint32_t)v << (16 * (i % 2) + 2 * (i / 2));
+            words[(i % 8) / 2] |= (uint32_t)v << (16 * (i % 2) + 2 * (t + 4 * (i / 8)));
         }
-        words[t] = word;
         sc_bits[t] = __builtin_bit_cast(uint16_t, sc_h);
         zbyte |= (uint32_t)zero << (2 * t);
     }
@@ -125,11 +126,11 @@ __global__ __launch_bounds__(256) void quantize_pack_w2_kernel(
     }
 }
 
-// the eight codes (four subnormal fp16 pairs) of MFMA step j (0..1) of a group's word
-__device__ __forceinline__ uint4 w2_fragment(uint32_t w, int j)
+// register i of the B fragment of MFMA step (t, j): the column pair (2i, 2i+1) as two fp16
+// subnormals q * 4^t * 2^-24
+__device__ __forceinline__ uint32_t w2_pair(uint32_t word, int t, int j)
 {
-    const uint32_t v = w >> (8 * j);
-    return make_uint4(v & 0x00030003u, (v >> 2) & 0x00030003u, (v >> 4) & 0x00030003u, (v >> 6) & 0x00030003u);
+    return (word >> (8 * j)) & (0x00030003u << (2 * t));
 }
 
 __global__ __launch_bounds__(256) void unpack_w2_kernel(
@@ -151,12 +152,11 @@ __global__ __launch_bounds__(256) void unpack_w2_kernel(
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const uint4 f = w2_fragment(w[t], j);
-                const uint32_t pr[4] = {f.x, f.y, f.z, f.w};
                 uint32_t lo = 0, hi = 0;               // bytes e = 0..3 and 4..7
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const uint32_t two = (pr[i] & 0xFFu) | ((pr[i] >> 16) << 8);     // codes 2i, 2i+1
+                    const uint32_t pr = w2_pair(w[i], t, j) >> (2 * t);
+                    const uint32_t two = (pr & 0xFFu) | ((pr >> 16) << 8);           // codes 2i, 2i+1
                     if (i < 2) lo |= two << (16 * i);
                     else hi |= two << (16 * (i - 2));
                 }
@@ -200,7 +200,7 @@ struct W2Args {
 // Dynamic LDS: [4 waves][MS rows x (U*512 + 16) bytes], then [4/S row blocks][16*M outputs][4
 // slots] of fp32 for the sum over the slices.
 template <int MS, int U, bool PF>
-__global__ __launch_bounds__(256, 4) void gemv_w2_kernel(const W2Args a)
+__global__ __launch_bounds__(256, PF ? 3 : 4) void gemv_w2_kernel(const W2Args a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int CHUNKS = MS * U * 32;            // 16-byte chunks of x per batch
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(256, 4) void gemv_w2_kernel(const W2Args a)
     uint32_t kmask = 0x00030003u, ksign = 0x80008000u;
     asm("" : "+s"(kmask));
     asm("" : "+v"(ksign));
-    floatx4 total = {0.f, 0.f, 0.f, 0.f};
+    float tot[4][4] = {};                          // [group of the block][output]: sums of step * acc
     // chunk ci = 64 i + lane of a batch's slice of x: row ci / (32 U), block (ci / 32) % U,
     // 16-byte chunk ci % 32 of the block
     uint4 xs[NS], q[U];
@@ -301,31 +301,39 @@ __global__ __launch_bounds__(256, 4) void gemv_w2_kernel(const W2Args a)
 #pragma unroll
                 for (int jj = 0; jj < 8; ++jj) xa[jj] = xl[u * 32 + 4 * jj];      // k = 256 u + 32 jj + 8 c + 0..7
                 const uint32_t w[4] = {qc[u].x, qc[u].y, qc[u].z, qc[u].w};
-                const uint32_t sraw[4] = {svc[u].x & 0xFFFFu, svc[u].x >> 16, svc[u].y & 0xFFFFu, svc[u].y >> 16};
+                const uint32_t wh[4] = {w[0] >> 8, w[1] >> 8, w[2] >> 8, w[3] >> 8};
+                const half2_t s01 = __builtin_bit_cast(half2_t, svc[u].x), s23 = __builtin_bit_cast(half2_t, svc[u].y);
+                const half_t sh[4] = {s01[0], s01[1], s23[0], s23[1]};
                 const uint32_t zz = zc[u] * 0x00010001u;            // the zero-point byte in both halves
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    // -z * 2^-24 in every column of this lane's row: a negative fp16 subnormal
-                    const uint32_t zt = zz >> (2 * t);
-                    const half8_t zv = __builtin_bit_cast(half8_t, make_uint4((zt & kmask) | ksign, (zt & kmask) | ksign,
-                                                                              (zt & kmask) | ksign, (zt & kmask) | ksign));
+                    const uint32_t mt = kmask << (2 * t);          // wave-uniform
+                    // -z * 4^t * 2^-24 in every column of this lane's row: a negative fp16 subnormal
+                    const uint32_t nz = (zz & mt) | ksign;
+                    const half8_t zv = __builtin_bit_cast(half8_t, make_uint4(nz, nz, nz, nz));
+                    const half8_t b0v = __builtin_bit_cast(half8_t, make_uint4(w[0] & mt, w[1] & mt, w[2] & mt, w[3] & mt));
+                    const half8_t b1v = __builtin_bit_cast(half8_t, make_uint4(wh[0] & mt, wh[1] & mt, wh[2] & mt, wh[3] & mt));
+                    const half8_t a0v = __builtin_bit_cast(half8_t, xa[2 * t]);
+                    const half8_t a1v = __builtin_bit_cast(half8_t, xa[2 * t + 1]);
                     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0v, b0v, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0v, zv, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1v, b1v, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1v, zv, acc, 0, 0, 0);
+                    // the group's step; the factor 2^24 / 4^t is applied after the loop
+                    const float st = (float)sh[t];
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const half8_t av = __builtin_bit_cast(half8_t, xa[2 * t + j]);
-                        const half8_t bv = __builtin_bit_cast(half8_t, w2_fragment(w[t], j));
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, zv, acc, 0, 0, 0);
-                    }
-                    const float s24 = (float)__builtin_bit_cast(half_t, (uint16_t)sraw[t]) * 16777216.f;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) total[v] = __builtin_fmaf(s24, acc[v], total[v]);
+                    for (int v = 0; v < 4; ++v) tot[t][v] = __builtin_fmaf(st, acc[v], tot[t][v]);
                 }
             }
         }
         if (!PF && b + U < b1) request(b + U);
     }
 
+    floatx4 total;
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        total[v] = (tot[0][v] * 16777216.f + tot[1][v] * 4194304.f) + (tot[2][v] * 1048576.f + tot[3][v] * 262144.f);
     // lane holds y[m = 4c + v][n = 16 rb + r], complete (S = 1) or one slice's share of it
     if (logS == 0) {                               // uniform over the workgroup: no barrier below
         if (active) {
@@ -376,14 +384,15 @@ int launch_w2(const W2Problem *probs, int count, int M, hipStream_t stream)
         }
     int64_t row_blocks = 0;
     for (int i = 0; i < count; ++i) row_blocks += probs[i].N / 16;
-    // enough row blocks to give every CU several waves: about 16 blocks (four batches) per wave;
-    // otherwise K is cut as far as it goes so that the launch has more waves
+    // enough row blocks to give every CU several waves: at most 8..11 blocks (two or three batches)
+    // per wave, which keeps the waves of short and long rows alike; otherwise K is cut as far as it
+    // goes so that the launch has more waves
     const bool wide = row_blocks > 1024;
     int total = 0;
     for (int i = 0; i < count; ++i) {
         a.p[i] = probs[order[i]];
         const int B = a.p[i].K / 256;
-        const int logS = wide ? (B <= 16 ? 0 : (B <= 32 ? 1 : 2)) : (B >= 4 ? 2 : (B >= 2 ? 1 : 0));
+        const int logS = wide ? (B <= 8 ? 0 : (B <= 16 ? 1 : 2)) : (B >= 4 ? 2 : (B >= 2 ? 1 : 0));
         a.logS[i] = logS;
         a.wg_begin[i] = total;
         const int rbw = W2_WAVES >> logS;
@@ -399,7 +408,7 @@ int launch_w2(const W2Problem *probs, int count, int M, hipStream_t stream)
     case 1: return launch_w2_one<1, 4, true>(a, total, lds, stream);
     case 2: return launch_w2_one<2, 4, false>(a, total, lds, stream);
     case 4: return launch_w2_one<4, 4, false>(a, total, lds, stream);
-    case 8: return launch_w2_one<8, 2, true>(a, total, lds, stream);
+    case 8: return launch_w2_one<8, 2, false>(a, total, lds, stream);
     default: return launch_w2_one<16, 1, true>(a, total, lds, stream);
     }
 }

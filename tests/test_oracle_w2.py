@@ -72,7 +72,7 @@ def test_pack_round_trip_and_sizes():
     c2, s2, z2 = oracle.unpack_w2(q, sp, zp, N, K)
     assert np.array_equal(c2, codes) and np.array_equal(z2, zeros)
     assert np.array_equal(s2.view(np.uint16), scales.view(np.uint16))
-    # flipping one code changes exactly its two bits, in the word of its group in its slot
+    # flipping one code changes exactly its two bits, in the word of its column pair in its slot
     n, k = 17, 600
     codes2 = codes.copy()
     codes2[n, k] ^= 3
@@ -80,9 +80,10 @@ def test_pack_round_trip_and_sizes():
     changed = np.flatnonzero(q != q2)
     block = (n // 16) * (K // 256) + k // 256
     slot = n % 16 + 16 * ((k % 32) // 8)
-    word = (k % 256) // 64
+    word, half, field = (k % 8) // 2, k % 2, (k % 256) // 64 + 4 * ((k % 64) // 32)
     assert changed.size == 1 and changed[0] // 4 == (block * 64 + slot) * 4 + word
-    assert bin(int(q[changed[0]] ^ q2[changed[0]])).count("1") == 2
+    assert changed[0] % 4 == (16 * half + 2 * field) // 8
+    assert int(q[changed[0]] ^ q2[changed[0]]) == 3 << ((16 * half + 2 * field) % 8)
     # one scale and one zero point: their places
     scales2 = scales.copy()
     scales2[n, 9] = np.float16(7.0)
@@ -98,18 +99,22 @@ def test_pack_round_trip_and_sizes():
 
 
 def test_hand_written_bytes_of_one_slot():
-    """One block, row 5, column block c = 2, group t = 1: code i -> value i % 4; every other code 0.
-    Expected word written out by hand from the layout text."""
+    """One block, row 5, column block c = 2, word i = 1 (columns 64t + 32j + 16 + 2 + h): the code
+    of (t, j, h) is (t + j + h) % 4; every other code 0.  Expected word written out by hand from
+    the layout text."""
     codes = np.zeros((16, 256), np.uint8)
-    for i in range(16):
-        codes[5, 64 * 1 + 32 * (i // 8) + 8 * 2 + (i % 8)] = i % 4
+    for t in range(4):
+        for j in range(2):
+            for h in range(2):
+                codes[5, 64 * t + 32 * j + 8 * 2 + 2 * 1 + h] = (t + j + h) % 4
     q, _, _ = oracle.pack_w2(codes, np.ones((16, 4), np.float16), np.zeros((16, 4), np.uint8))
     slot = 5 + 16 * 2
     words = q[slot * 16: slot * 16 + 16].view("<u4")
-    # pair p = (code 2p, code 2p+1) = (0,1) for even p, (2,3) for odd p:
-    # low half: fields 0,2,0,2,0,2,0,2 at bits 2p -> 0b10_00_10_00_10_00_10_00 = 0x8888
-    # high half: fields 1,3,1,3,...           -> 0b11_01_11_01_11_01_11_01 = 0xDDDD
-    assert [int(w) for w in words] == [0, 0xDDDD8888, 0, 0]
+    # low half (h = 0), fields f = t + 4j hold (t + j) % 4: f0..f7 = 0,1,2,3, 1,2,3,0
+    #   = 1<<2 | 2<<4 | 3<<6 | 1<<8 | 2<<10 | 3<<12 = 4 + 32 + 192 + 256 + 2048 + 12288 = 0x39E4
+    # high half (h = 1) holds (t + j + 1) % 4: f0..f7 = 1,2,3,0, 2,3,0,1
+    #   = 1 | 2<<2 | 3<<4 | 2<<8 | 3<<10 | 1<<14 = 1 + 8 + 48 + 512 + 3072 + 16384 = 0x4E39
+    assert [int(w) for w in words] == [0, 0x4E3939E4, 0, 0]
     everything_else = np.delete(q, np.arange(slot * 16, slot * 16 + 16))
     assert not everything_else.any()
 
