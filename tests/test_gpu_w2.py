@@ -48,7 +48,8 @@ def check_linear_w2(awq, xs, Wdq, gpu_packed, N):
 
 @pytest.mark.parametrize("N,K", [(16, 256), (48, 768), (176, 1280), (272, 2304), (32, 8192)])
 def test_w2_small_shapes_every_m(awq, N, K):
-    """One block per row, odd block counts, more waves than blocks, 16 waves (K = 8192)."""
+    """One block per row (three of a workgroup's four waves idle), odd block counts, K cut into four
+    slices with ragged batches, long rows (K = 8192: eight blocks per wave)."""
     import oracle
     case, s, xs = make_case(N, K, 16, 0.02, cfg=0, proj=40)
     ref, gpu = quantize_w2_bit_exact(awq, case.W, s)
@@ -128,8 +129,8 @@ def check_multi_w2(awq, problems, M):
 
 
 def test_w2_grouped_small_every_m(awq):
-    """Linears of different K in one launch (the wave count follows the longest rows, so the
-    short ones leave waves without work), more than eight linears (several launches)."""
+    """Linears of different K in one launch (each with its own number of K slices), more than
+    eight linears (several launches)."""
     import oracle
     probs = []
     for i, (N, K) in enumerate([(176, 1280), (64, 256), (48, 2048), (320, 512), (32, 8192)]):
@@ -140,6 +141,21 @@ def test_w2_grouped_small_every_m(awq):
         check_multi_w2(awq, probs, M)
     check_multi_w2(awq, probs[:1], 3)
     check_multi_w2(awq, probs[:4] * 5, 2)                     # 20 entries: three launches
+
+
+def test_w2_grouped_many_rows_ragged_row_block_counts(awq):
+    """More than 1024 row blocks in the launch: K is cut by the length of the rows (5 blocks: one
+    slice, four row blocks per workgroup; 9 blocks: two slices, two row blocks; 17 blocks: four
+    slices), and no linear has a multiple of four row blocks, so the last workgroup of each has
+    waves without a row block."""
+    import oracle
+    probs = []
+    for i, (N, K) in enumerate([(6000, 1280), (5008, 2304), (5520, 256), (2000, 4352)]):
+        case, s, xs = make_case(N, K, 16, 0.02, cfg=0, proj=60 + i)
+        ref, gpu = quantize_w2_bit_exact(awq, case.W, s)
+        probs.append((xs, oracle.dequant(*ref, group=64), gpu, N))
+    for M in (1, 3, 8, 16):
+        check_multi_w2(awq, probs, M)
 
 
 @pytest.mark.parametrize("N,K", [(4096, 4096), (4096, 11008)])
