@@ -273,9 +273,10 @@ int awq_w3a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, i
  *             group t of the block at bits [2t, 2t+2).
  * Arguments, ownership and errors as for the 4-bit calls of the same name.  awq_unpack_w2 returns
  * codes u8[N,K], scales f16[N,K/64], zeros u8[N,K/64] (each optional).
- * awq_w2a16_linear: y = x' * dequant(q)^T with fp32 accumulation for 1 <= M <= 128 (the decode
- * kernel; 17..128 rows run as blocks of 16 rows in one launch).  There is no 2-bit prefill kernel:
- * larger M returns AWQ_ERR_BAD_SHAPE.  awq_w2a16_linear_multi: as awq_w4a16_linear_multi
+ * awq_w2a16_linear: y = x' * dequant(q)^T with fp32 accumulation, any M >= 1, through the decode
+ * kernel: more than 16 rows run as blocks of 16 rows, 128 rows per launch.  There is no 2-bit
+ * matrix-matrix kernel, so the time grows with M/128 launches that each read the packed weights
+ * again (sized for prompts of a few hundred tokens).  awq_w2a16_linear_multi: as awq_w4a16_linear_multi
  * (1 <= M <= 16, up to AWQ_MULTI_MAX linears, eight per launch). */
 #define AWQ_GROUP_W2 64
 int awq_packed_sizes_w2(int64_t N, int64_t K, int group, size_t *qweight_bytes,

@@ -534,7 +534,8 @@ def awq_unpack_w2(qweight, scales, zeros, N: int, K: int, group: int = GROUP_W2)
 
 
 def awq_w2a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int = GROUP_W2, out=None):
-    """y [M,N] fp16 = x [M,K] fp16 (already divided by s) times the 2-bit packed weight, M <= 128."""
+    """y [M,N] fp16 = x [M,K] fp16 (already divided by s) times the 2-bit packed weight (any M; the
+    decode kernel, 128 rows per launch)."""
     _dev(x, torch.float16, "x")
     M, K = x.shape
     if out is None:

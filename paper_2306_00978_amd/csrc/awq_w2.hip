@@ -489,19 +489,31 @@ extern "C" int awq_w2a16_linear(const void *x_f16, const void *qweight, const vo
     W2Problem p;
     int st = fill_problem(p, x_f16, qweight, scales, zeros, y_f16, N, K, group);
     if (st != AWQ_OK) return st;
-    if (M <= 0 || M > 128) return AWQ_ERR_BAD_SHAPE;
-    if (M <= 16) return launch_w2(&p, 1, (int)M, (hipStream_t)stream);
-    // a few dozen tokens: blocks of 16 rows through the decode kernel, eight blocks per launch; the
-    // last block is moved back to end at row M (its overlap is computed twice, same values)
-    const int blocks = (int)((M + 15) / 16);
-    W2Problem d[W2_MAX_PROBLEMS];
-    for (int b = 0; b < blocks; ++b) {
-        const int64_t m0 = b + 1 < blocks ? 16 * (int64_t)b : M - 16;
-        d[b] = p;
-        d[b].x = p.x + m0 * K;
-        d[b].y = p.y + m0 * N;
+    if (M <= 0 || M > 0x7fffffff) return AWQ_ERR_BAD_SHAPE;
+    // up to 16 rows: one launch.  More: blocks of 16 rows through the same kernel, eight blocks
+    // (128 rows) per launch; the last block of a launch is moved back to end at its last row (the
+    // overlap is computed twice, same values)
+    for (int64_t r0 = 0; r0 < M; r0 += 128) {
+        const int64_t rows = M - r0 < 128 ? M - r0 : 128;
+        W2Problem c = p;
+        c.x = p.x + r0 * K;
+        c.y = p.y + r0 * N;
+        if (rows <= 16) {
+            st = launch_w2(&c, 1, (int)rows, (hipStream_t)stream);
+        } else {
+            const int blocks = (int)((rows + 15) / 16);
+            W2Problem d[W2_MAX_PROBLEMS];
+            for (int b = 0; b < blocks; ++b) {
+                const int64_t m0 = b + 1 < blocks ? 16 * (int64_t)b : rows - 16;
+                d[b] = c;
+                d[b].x = c.x + m0 * K;
+                d[b].y = c.y + m0 * N;
+            }
+            st = launch_w2(d, blocks, 16, (hipStream_t)stream);
+        }
+        if (st != AWQ_OK) return st;
     }
-    return launch_w2(d, blocks, 16, (hipStream_t)stream);
+    return AWQ_OK;
 }
 
 extern "C" int awq_w2a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,

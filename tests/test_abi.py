@@ -224,7 +224,7 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert lib.awq_quantize_pack_w2(Pq(odd), None, 16, 256, 64, Pq(ok), Pq(ok), Pq(ok), None) == -4
     assert lib.awq_unpack_w2(Pq(ok), None, Pq(ok), 16, 256, 64, Pq(ok), Pq(ok), Pq(ok), None) == -1
     assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), None, 1, 16, 256, 64, None) == -1
-    assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 129, 16, 256, 64, None) == -2
+    assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 1 << 31, 16, 256, 64, None) == -2
     assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 0, 16, 256, 64, None) == -2
     assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(ok), 1, 16, 384, 64, None) == -2
     assert lib.awq_w2a16_linear(Pq(ok), Pq(ok), Pq(ok), Pq(ok), Pq(odd), 1, 16, 256, 64, None) == -4

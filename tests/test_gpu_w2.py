@@ -59,6 +59,10 @@ def test_w2_small_shapes_every_m(awq, N, K):
         check_linear_w2(awq, xs[:M], Wdq, gpu, N)
     check_linear_w2(awq, np.tile(xs, (3, 1))[:37], Wdq, gpu, N)       # blocks of 16 rows, last moved back
     check_linear_w2(awq, np.tile(xs, (8, 1)), Wdq, gpu, N)            # 128 rows: eight blocks
+    if K <= 1280:
+        big = np.tile(xs, (19, 1))
+        check_linear_w2(awq, big[:300], Wdq, gpu, N)                  # 128 + 128 + 44 rows
+        check_linear_w2(awq, big[:261], Wdq, gpu, N)                  # 128 + 128 + 5 rows (a plain launch)
 
 
 def test_w2_edge_groups_and_exactness_on_integer_data(awq):
@@ -103,9 +107,8 @@ def test_w2_rejects_what_it_cannot_run(awq):
     q = torch.zeros(16 * 256 // 4, dtype=torch.uint8, device="cuda")
     sc = torch.zeros(16 * 4, dtype=torch.float16, device="cuda")
     zp = torch.zeros(16, dtype=torch.uint8, device="cuda")
-    with pytest.raises(awq.AwqError) as e:
-        awq.awq_w2a16_linear(torch.zeros((129, 256), dtype=torch.float16, device="cuda"), q, sc, zp, 16)
-    assert e.value.status == -2
+    with pytest.raises(ValueError):
+        awq.awq_w2a16_linear(torch.zeros((1, 256), dtype=torch.float16, device="cuda"), q[:512], sc, zp, 16)
     del x
 
 
