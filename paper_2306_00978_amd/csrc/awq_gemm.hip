@@ -164,23 +164,35 @@ __device__ __forceinline__ uint32_t word_of(const u32x4 &v, int j)
     return v[j];
 }
 
+// SPLIT: K is cut into `ksplit` ranges of whole groups, one workgroup per (tile, range); each
+// writes its partial tile in fp32 to part[range][M][N] and a second kernel adds the ranges.  For
+// a few hundred tokens there are far fewer tiles than CUs (ceil(M/128) * N/256), and a workgroup
+// per tile would leave most of the chip idle while a handful of CUs walk all of K.
+template <bool SPLIT>
 __global__ __launch_bounds__(512, 1) void gemm_kernel(
     const half_t *__restrict__ x, const unsigned char *__restrict__ qweight,
     const unsigned char *__restrict__ scales, const unsigned char *__restrict__ zeros,
-    half_t *__restrict__ y, int M, int N, int K, int G, int tiles_n, int tiles_total)
+    half_t *__restrict__ y, int M, int N, int K, int G, int tiles_n, int tiles_total,
+    float *__restrict__ part, int ksplit)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     // all arguments fetched in one round (otherwise one scalar-cache miss per first use)
     asm volatile("" ::"s"(x), "s"(qweight), "s"(scales), "s"(zeros), "s"(y), "s"(M), "s"(N), "s"(K), "s"(G),
-                 "s"(tiles_n), "s"(tiles_total));
+                 "s"(tiles_n), "s"(tiles_total), "s"(part), "s"(ksplit));
     // Workgroups are handed to the eight XCDs round-robin by their linear id, and each XCD has
     // its own L2.  The tile a workgroup computes is therefore chosen so that an XCD gets a
     // contiguous range of tiles in token-block-major order: its workgroups then share a few x
     // row blocks and sweep the same weight groups at about the same time, which keeps the
     // operand traffic inside that L2.
-    const int per_xcd = (tiles_total + 7) >> 3;
-    const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (tile >= tiles_total) return;
+    const int units_total = SPLIT ? tiles_total * ksplit : tiles_total;      // (tile, K range) pairs
+    const int per_xcd = (units_total + 7) >> 3;
+    const int unit = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (unit >= units_total) return;
+    const int tile = SPLIT ? unit / ksplit : unit;
+    const int ks = SPLIT ? unit - tile * ksplit : 0;
+    // groups [gofs, gofs + GL) of the G of a row
+    const int gofs = SPLIT ? (int)(((int64_t)G * ks) / ksplit) : 0;
+    const int GL = SPLIT ? (int)(((int64_t)G * (ks + 1)) / ksplit) - gofs : G;
     const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
     const DqConsts kc = dq_consts();
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
@@ -206,7 +218,8 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(
         int xr = m0 + 32 * nq + 8 * q + (lane >> 3);
         xr = xr < M ? xr : M - 1;
         const int chunk = (lane & 7) ^ (((8 * q + (lane >> 3)) >> 1) & 7);
-        xsrc[q] = reinterpret_cast<const unsigned char *>(x) + ((size_t)xr * K + 8 * chunk) * 2 + kh * 128;
+        xsrc[q] = reinterpret_cast<const unsigned char *>(x) + ((size_t)xr * K + 8 * chunk) * 2 + kh * 128 +
+                  (size_t)gofs * 256;
     }
     // weights: block b (32 out-features = tiles nt0+2b, nt0+2b+1), half kh
     const unsigned char *qsrc[2];
@@ -214,7 +227,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(
     for (int b = 0; b < 2; ++b) {
         int t = nt0 + 2 * b + (l32 >> 4);
         t = t < NT ? t : NT - 1;                             // ragged N: repeat the last tile
-        qsrc[b] = qweight + ((size_t)t * G * 64 + (l32 & 15) + 16 * hi) * 16 + kh * 512;
+        qsrc[b] = qweight + ((size_t)t * G * 64 + (l32 & 15) + 16 * hi) * 16 + kh * 512 + (size_t)gofs * 1024;
     }
     // steps (fetched by the kh = 0 wave): lane -> block lane/32, row l32;
     // zero points (kh = 1 wave): lane < 32 -> block lane/16, byte lane%16
@@ -222,11 +235,11 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(
     if (kh == 0) {
         int t = nt0 + 2 * hi + (l32 >> 4);
         t = t < NT ? t : NT - 1;
-        msrc = scales + ((size_t)t * G * 16 + (l32 & 15)) * 2;
+        msrc = scales + ((size_t)t * G * 16 + (l32 & 15)) * 2 + (size_t)gofs * 32;
     } else {
         int tz = nt0 + 2 * ((lane >> 4) & 1) + ((lane >> 3) & 1);
         tz = tz < NT ? tz : NT - 1;
-        msrc = zeros + (size_t)tz * G * 8 + (lane & 7);
+        msrc = zeros + (size_t)tz * G * 8 + (lane & 7) + (size_t)gofs * 8;
     }
 
     const uint32_t a_ring = lds0;
@@ -236,7 +249,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(
     // They are issued one at a time from the issue shadow of the MFMAs.
     auto issue_piece = [&](auto piece_tag, int g, int stage) {
         constexpr int PIECE = decltype(piece_tag)::value;
-        g = g < G ? g : G - 1;                               // past the end: a harmless repeat
+        g = g < GL ? g : GL - 1;                             // past the end: a harmless repeat
         if constexpr (PIECE < 4) {
             // LDS: [row block 4][column half 2][32 rows x 128 B]
             const uint32_t adst = a_ring + (uint32_t)stage * A_STAGE + (uint32_t)nq * 8192 + (uint32_t)kh * 4096;
@@ -354,7 +367,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(
     __builtin_amdgcn_sched_barrier(0);
 
     int stage = 0;
-    for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < GL; ++g) {
         int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;    // stage of group g+1
         int fstage = nstage + 1 == NSTAGE ? 0 : nstage + 1;  // stage to fill with group g+2; it was
                                                              // last read in group g-1, which every
@@ -450,6 +463,22 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(
         __syncthreads();
     }
 
+    if (SPLIT) {
+        // partial sums leave in fp32, 32 consecutive columns per half-wave and accumulator
+        float *dst = part + (size_t)ks * M * N;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + 64 * kh + 32 * ii + 8 * (v >> 2) + 4 * hi + (v & 3);
+                    const int n = nt0 * 16 + 32 * b + l32;
+                    const float val = kh ? acc[2 + ii][b][v] : acc[ii][b][v];
+                    if (m < M && n < N) dst[(size_t)m * N + n] = val;
+                }
+        return;
+    }
     // Epilogue.  Accumulator v of tile (i, b) is y[m0 + 32 i + 8 (v/4) + 4 hi + v%4][16 nt0 + 32 b
     // + l32]: a lane holds single columns, which would leave as 2-byte stores.  Each wave turns
     // its 64 x 64 part around through its own 9 KB of LDS (rows of 128 + 16 bytes: the padding
@@ -480,27 +509,91 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(
     }
 }
 
+// y = fp16(sum over the K ranges of the fp32 partial tiles), four outputs per thread
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float4 *__restrict__ part, uint2 *__restrict__ y,
+                                                          int64_t quads, int ksplit)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= quads) return;
+    float4 a = part[i];
+    for (int k = 1; k < ksplit; ++k) {
+        const float4 b = part[(int64_t)k * quads + i];
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    const half2_t lo = {(half_t)a.x, (half_t)a.y}, hi = {(half_t)a.z, (half_t)a.w};
+    y[i] = make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+}
+
+}  // namespace
+
+// How many K ranges the prefill launch of this shape is cut into when a workspace is given: the
+// count (1..8, at least four groups per range) with the smallest estimated time.  A workgroup
+// takes about 4 us + 1.4 us per group, workgroups run in rounds of 256 (one per CU), and the
+// second kernel moves (ranges + 1/2) * M * N * 4 bytes at about 3.5 TB/s after a launch of
+// 2.5 us -- figures measured on the three Llama-2-7B shapes at 160..2048 tokens.  Cutting K pays
+// while the tiles (ceil(M/128) * N/256) are fewer than the CUs, or just over a multiple of them.
+int awq_gemm_ksplit(int M, int N, int K, double *estimate_us)
+{
+    const int G = K / AWQ_GROUP;
+    const int64_t tiles = (int64_t)((N + BN - 1) / BN) * ((M + BM - 1) / BM);
+    int best = 1;
+    double best_us = 0.0;
+    for (int ks = 1; ks <= 8 && (ks == 1 || G / ks >= 4); ++ks) {
+        const double rounds = (double)((tiles * ks + 255) / 256);
+        const double gl = (double)((G + ks - 1) / ks);
+        double us = rounds * (4.0 + 1.4 * gl);
+        if (ks > 1) us += 2.5 + (ks + 0.5) * (double)M * (double)N * 4.0 / 3.5e6;
+        if (ks == 1 || us < 0.95 * best_us) {       // a split has to win by a margin
+            best = ks;
+            best_us = us;
+        }
+    }
+    if (estimate_us) *estimate_us = best_us;
+    return best;
+}
+
+namespace {
+
+template <bool SPLIT>
+int gemm_launch_any(const void *x, const void *qweight, const void *scales, const void *zeros,
+                    void *y, int M, int N, int K, float *part, int ksplit, hipStream_t stream)
+{
+    const int G = K / AWQ_GROUP;
+    const int tiles_n = (N + BN - 1) / BN;
+    const int64_t tiles_total = (int64_t)tiles_n * ((M + BM - 1) / BM);
+    if (tiles_total * ksplit > (1 << 30)) return AWQ_ERR_BAD_SHAPE;
+    const dim3 grid((unsigned)((tiles_total * ksplit + 7) / 8 * 8)), block(512);
+    static AwqOncePerDevice once;
+    bool &attr_set = once.here();
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel<SPLIT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+            return AWQ_ERR_HIP;
+        attr_set = true;
+    }
+    gemm_kernel<SPLIT><<<grid, block, LDS_BYTES, stream>>>(
+        (const half_t *)x, (const unsigned char *)qweight, (const unsigned char *)scales,
+        (const unsigned char *)zeros, (half_t *)y, M, N, K, G, tiles_n, (int)tiles_total, part, ksplit);
+    return awq_launch_status();
+}
+
 }  // namespace
 
 // Host side of the prefill path; arguments were validated by awq_w4a16_linear.
 int awq_gemm_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
                     void *y, int M, int N, int K, hipStream_t stream)
 {
-    const int G = K / AWQ_GROUP;
-    const int tiles_n = (N + BN - 1) / BN;
-    const int64_t tiles_total = (int64_t)tiles_n * ((M + BM - 1) / BM);
-    if (tiles_total > (1 << 30)) return AWQ_ERR_BAD_SHAPE;
-    const dim3 grid((unsigned)((tiles_total + 7) / 8 * 8)), block(512);
-    static AwqOncePerDevice once;
-    bool &attr_set = once.here();
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-            return AWQ_ERR_HIP;
-        attr_set = true;
-    }
-    gemm_kernel<<<grid, block, LDS_BYTES, stream>>>(
-        (const half_t *)x, (const unsigned char *)qweight, (const unsigned char *)scales,
-        (const unsigned char *)zeros, (half_t *)y, M, N, K, G, tiles_n, (int)tiles_total);
+    return gemm_launch_any<false>(x, qweight, scales, zeros, y, M, N, K, nullptr, 1, stream);
+}
+
+// The same with K cut into awq_gemm_ksplit() ranges; part: ksplit * M * N floats, 16-byte aligned.
+int awq_gemm_launch_split(const void *x, const void *qweight, const void *scales, const void *zeros,
+                          void *y, int M, int N, int K, void *part, int ksplit, hipStream_t stream)
+{
+    int st = gemm_launch_any<true>(x, qweight, scales, zeros, y, M, N, K, (float *)part, ksplit, stream);
+    if (st != AWQ_OK) return st;
+    const int64_t quads = (int64_t)M * N / 4;
+    gemm_reduce_kernel<<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream>>>(
+        (const float4 *)part, (uint2 *)y, quads, ksplit);
     return awq_launch_status();
 }

@@ -14,10 +14,25 @@ int awq_gemv_launch(const void *x, const void *qweight, const void *scales, cons
 int awq_gemm_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
                     void *y, int M, int N, int K, hipStream_t stream);
 
+int awq_gemm_launch_split(const void *x, const void *qweight, const void *scales, const void *zeros,
+                          void *y, int M, int N, int K, void *part, int ksplit, hipStream_t stream);
+int awq_gemm_ksplit(int M, int N, int K, double *estimate_us);
+
+// Only the prefill kernel at a few hundred tokens uses scratch: fp32 partial tiles of its K ranges.
 extern "C" size_t awq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
-    (void)M; (void)N; (void)K; (void)group;
-    return 0;   // both paths reduce inside the workgroup; no global scratch
+    if (awq_check_weight_shape(N, K, group) != AWQ_OK || M <= 48 || M > (int64_t)1 << 22) return 0;
+    double split_us = 0.0;
+    const int ks = awq_gemm_ksplit((int)M, (int)N, (int)K, &split_us);
+    // 49..128 tokens run through the decode kernels in blocks of 16 -- one grouped launch that
+    // takes about 7 us + blocks * (packed bytes at 6 TB/s, the repeats come from cache) -- unless
+    // the prefill kernel with K cut into ranges is estimated to be clearly faster, or the shape
+    // does not fit the grouped launch (then it would be one launch per block)
+    if (M <= 128 && awq_gemv_stream_fits((int)N, (int)K, 16)) {
+        const double blocked_us = 7.0 + (double)((M + 15) / 16) * ((double)N * (double)K * 0.53125) / 6.0e6;
+        if (ks < 2 || split_us > 0.85 * blocked_us) return 0;
+    }
+    return ks > 1 ? (size_t)ks * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
 extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const void *scales,
@@ -32,12 +47,10 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
     if (!awq_aligned16(x_f16) || !awq_aligned16(qweight) || !awq_aligned16(scales) ||
         !awq_aligned16(zeros) || !awq_aligned16(y_f16))
         return AWQ_ERR_MISALIGNED;
+    // the workspace is optional: without it (NULL or too small) K is not split
     const size_t need = awq_linear_workspace_bytes(M, N, K, group);
-    if (need > 0) {
-        if (!workspace) return AWQ_ERR_NULL_POINTER;
-        if (workspace_bytes < need) return AWQ_ERR_WORKSPACE_TOO_SMALL;
-        if (!awq_aligned16(workspace)) return AWQ_ERR_MISALIGNED;
-    }
+    const bool split = need > 0 && workspace && workspace_bytes >= need;
+    if (split && !awq_aligned16(workspace)) return AWQ_ERR_MISALIGNED;
     if (M <= 16) {
         // a single linear is a short kernel dominated by one memory round trip: the batch
         // kernel (everything requested at once) is the faster one; the streaming kernel is
@@ -63,10 +76,12 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
     // once per block (the repeats come from cache) but keeps the whole chip busy, all blocks in one
     // grouped launch where the shape allows it.  The last block is moved back so that it has 16
     // tokens too; the tokens it shares with its neighbour are computed twice, bit for bit alike.
-    // (4096 x 4096: 43 us -> 12-19 us for 17..128 tokens; 4096 x 11008: 105 us -> 20-72 us.)
+    // (4096 x 4096: 43 us -> 12-19 us for 17..128 tokens; 4096 x 11008: 105 us -> 20-72 us -- that
+    // shape does not fit the grouped launch, and from 49 tokens on the prefill kernel with K cut
+    // into ranges is faster when the caller brings its workspace: 36 us.)
     static const int small_env = getenv("AWQ_SMALL_M_MAX") ? atoi(getenv("AWQ_SMALL_M_MAX")) : -1;
     const int64_t small_max = small_env >= 0 ? std::min(small_env, 128) : 128;
-    if (M <= small_max) {
+    if (M <= small_max && !split) {
         const int blocks = (int)((M + 15) / 16);
         awq_linear_desc d[8];
         for (int b = 0; b < blocks; ++b) {
@@ -81,6 +96,9 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
         }
         return awq_w4a16_linear_multi(d, blocks, 16, group, nullptr, 0, stream);
     }
+    if (split)
+        return awq_gemm_launch_split(x_f16, qweight, scales, zeros, y_f16, (int)M, (int)N, (int)K, workspace,
+                                     awq_gemm_ksplit((int)M, (int)N, (int)K, nullptr), (hipStream_t)stream);
     return awq_gemm_launch(x_f16, qweight, scales, zeros, y_f16, (int)M, (int)N, (int)K,
                            (hipStream_t)stream);
 }

@@ -90,6 +90,15 @@ def test_argument_validation_happens_before_any_launch(lib):
     # workspace query never fails
     assert lib.awq_linear_workspace_bytes(1, 4096, 4096, 128) >= 0
     assert lib.awq_linear_workspace_bytes(-1, 0, 7, 3) == 0
+    # K is cut into ranges only where the prefill kernel has too few tiles for the chip
+    wsb = lib.awq_linear_workspace_bytes
+    assert wsb(16, 4096, 4096, 128) == 0 and wsb(48, 4096, 11008, 128) == 0
+    assert wsb(2048, 4096, 4096, 128) == 0 and wsb(2048, 11008, 4096, 128) == 0
+    assert wsb(200, 4096, 4096, 128) == 7 * 200 * 4096 * 4          # 32 tiles of 32 groups: seven ranges
+    assert wsb(512, 4096, 4096, 128) == 4 * 512 * 4096 * 4
+    assert wsb(128, 4096, 4096, 128) == 0                           # blocks of 16 through the decode kernels
+    assert wsb(128, 4096, 11008, 128) == 8 * 128 * 4096 * 4         # does not fit their grouped launch
+    assert wsb(300, 176, 1408, 128) == 2 * 300 * 176 * 4            # 11 groups: two ranges at most
 
 
 def test_grouped_and_search_calls_validate_before_any_launch(lib):

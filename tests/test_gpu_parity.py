@@ -241,6 +241,42 @@ def test_small_prefill_full_size_blocks_of_16(awq, M):
         assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
 
 
+@pytest.mark.parametrize("M,ksplit", [(200, None), (512, 4), (2048, 1)])
+def test_mid_prefill_split_k_full_size(awq, M, ksplit):
+    """A few hundred tokens: with the workspace the prefill kernel cuts K into ranges (one
+    workgroup per tile and range, fp32 partial tiles summed by a second kernel).  Full-size
+    shapes, sampled rows against the oracle, the workspace between canaries, and the result
+    next to that of the unsplit kernel."""
+    import torch
+    for N, K in [(4096, 4096), (4096, 11008)]:
+        case, s, xs16, ref, gpu, Wdq = config_case(awq, N, K, 0.02, 1)
+        g = np.random.default_rng(M)
+        xs = (np.tile(xs16, ((M + 15) // 16, 1))[:M].astype(np.float32)
+              * g.uniform(0.5, 1.5, size=(M, 1)).astype(np.float32)).astype(np.float16)
+        need = awq.awq_linear_workspace_bytes(M, N, K)
+        ks = ksplit
+        if ks is None:                                       # chosen by the library's estimate
+            ks = need // (M * N * 4)
+            assert 2 <= ks <= 8
+        assert need == (ks * M * N * 4 if ks > 1 else 0)
+        rows = np.sort(g.choice(M, size=40, replace=False))
+        check_linear(awq, xs, Wdq, gpu, N, rows=rows)            # the binding brings the workspace
+        ws, cw = guarded(max(need, 16), torch.uint8)
+        y_split = host(awq.awq_w4a16_linear(dev(xs), *gpu, N, workspace=ws)).copy()
+        cw()
+        tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
+        y_plain = host(awq.awq_w4a16_linear(dev(xs), *gpu, N, workspace=tiny)).copy()
+        import oracle
+        for y in (y_split, y_plain):
+            err = oracle.norm_error(y[rows], oracle.matmul(xs[rows], Wdq), xs[rows], Wdq)
+            assert err.max() <= TOL
+        # the two differ by the order of the fp32 sums only: a rounding of the fp16 result at most
+        d = np.abs(y_split.astype(np.float32) - y_plain.astype(np.float32))
+        assert d.max() <= 2.0 ** -9 * max(1.0, float(np.abs(y_plain.astype(np.float32)).max()))
+        if ks == 1:
+            assert np.array_equal(y_split.view(np.uint16), y_plain.view(np.uint16))
+
+
 @pytest.mark.parametrize("M", [17, 64, 127, 128, 129, 300])
 def test_prefill_ragged_m(awq, small, M):
     N, K, xs, Wdq, gpu = small
