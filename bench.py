@@ -550,6 +550,32 @@ def main():
         extras["prefill_m64_4096x4096"] = {"us": round(ms64 * 1e3, 2),
                                            "TFLOP/s": round(workloads.flops(64, 4096, 4096) / (ms64 * 1e-3) / 1e12, 1),
                                            "note": "17..128 tokens: blocks of 16 through the decode kernels"}
+        # a prompt of 512 tokens, the three distinct shapes: the prefill kernel with K cut into ranges
+        # (the workspace of awq_w4a16_linear), next to the same call without the workspace
+        pre512 = {}
+        for p in (0, 4, 6):
+            name, N, K = shapes[p]
+            x512 = x_by_k[K][:512].contiguous()
+            y512 = torch.empty((512, N), dtype=torch.float16, device=dev)
+            need = awq.awq_linear_workspace_bytes(512, N, K)
+            us = []
+            for ws in (torch.empty(max(need, 16), dtype=torch.uint8, device=dev),
+                       torch.empty(16, dtype=torch.uint8, device=dev)):
+                for i in range(4):
+                    awq.awq_w4a16_linear(x512, *layers[i % L][p], N, out=y512, workspace=ws)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(40):
+                    awq.awq_w4a16_linear(x512, *layers[i % L][p], N, out=y512, workspace=ws)
+                e1.record()
+                torch.cuda.synchronize()
+                us.append(e0.elapsed_time(e1) / 40 * 1e3)
+            pre512[f"{N}x{K}"] = {"k_ranges": max(1, need // (512 * N * 4)), "us": round(us[0], 2),
+                                  "us_without_workspace": round(us[1], 2),
+                                  "TFLOP/s": round(workloads.flops(512, N, K) / us[0] / 1e6, 1)}
+            del x512, y512
+        extras["prefill_m512"] = pre512
         extras["quantize_pack"] = {"matrices": L * len(shapes), "ms_total": round(quant_ms, 3),
                                    "GB/s": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
                                    "pct_of_hbm_peak": round(100 * quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
