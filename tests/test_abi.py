@@ -86,6 +86,8 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert lib.awq_quantize_pack(odd, None, 16, 128, 128, ok, ok, ok, None) == -4
     assert lib.awq_quantize_pack(ok, odd, 16, 128, 128, ok, ok, ok, None) == -4
     assert lib.awq_w4a16_linear(ok, ok, ok, ok, odd, 1, 16, 128, 128, None, 0, None) == -4
+    # a workspace that would be used has to be aligned
+    assert lib.awq_w4a16_linear(ok, ok, ok, ok, ok, 200, 4096, 4096, 128, odd, 1 << 30, None) == -4
     assert lib.awq_unpack(ok, ok, ok, 16, 128, 128, odd, None, None, None) == -4
     # workspace query never fails
     assert lib.awq_linear_workspace_bytes(1, 4096, 4096, 128) >= 0
