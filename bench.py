@@ -559,8 +559,7 @@ def main():
             y512 = torch.empty((512, N), dtype=torch.float16, device=dev)
             need = awq.awq_linear_workspace_bytes(512, N, K)
             us = []
-            for ws in (torch.empty(max(need, 16), dtype=torch.uint8, device=dev),
-                       torch.empty(16, dtype=torch.uint8, device=dev)):
+            for ws in (torch.empty(max(need, 16), dtype=torch.uint8, device=dev), False):
                 for i in range(4):
                     awq.awq_w4a16_linear(x512, *layers[i % L][p], N, out=y512, workspace=ws)
                 torch.cuda.synchronize()

@@ -139,7 +139,7 @@ int awq_unpack(const void *qweight, const void *scales, const void *zeros, int64
  * matrix-matrix kernel has far fewer output tiles (ceil(M/128) * N/256) than the chip has CUs, and
  * with the workspace it cuts K into 2..8 ranges, one workgroup per tile and range, whose fp32
  * partial tiles (ranges * M * N * 4 bytes) a second kernel adds.  The workspace is optional: with
- * NULL or fewer bytes the call runs without it (1.2 to 2.9 times slower at 50..1000 tokens). */
+ * NULL the call runs without it (1.2 to 2.9 times slower at 50..1000 tokens). */
 size_t awq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
 
 /* Sec. 4.2 (on-the-fly dequantization fused into the MV / MM kernel):
@@ -150,8 +150,9 @@ size_t awq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
  * go through the decode kernels in blocks of 16 (one grouped launch where the shape allows it;
  * the last block is moved back to hold 16 tokens, so a few tokens are computed twice with
  * identical results), larger M the prefill path (MFMA tiles; with the workspace also from 49 tokens on where that
- * is estimated to be faster).  `workspace` (device, 16-byte aligned, AWQ_ERR_MISALIGNED otherwise)
- * may be NULL; its contents are undefined afterwards.  Results with and without the workspace
+ * is estimated to be faster).  `workspace` may be NULL; if it is given where
+ * awq_linear_workspace_bytes() is not 0 it must hold that many bytes (AWQ_ERR_WORKSPACE_TOO_SMALL)
+ * and be 16-byte aligned (AWQ_ERR_MISALIGNED); its contents are undefined afterwards.  Results with and without the workspace
  * differ by the order of the fp32 sums only. */
 int awq_w4a16_linear(const void *x_f16, const void *qweight, const void *scales,
                      const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,

@@ -290,7 +290,9 @@ def awq_linear_workspace_bytes(M: int, N: int, K: int, group: int = GROUP) -> in
 def awq_w4a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int = GROUP,
                      out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
     """y[M,N] = x[M,K] . dequant(qweight, scales, zeros)^T (fp16 in, fp32 accumulate, fp16 out).
-    x must already be divided by the activation-aware scale s."""
+    x must already be divided by the activation-aware scale s.  `workspace`: a uint8 tensor of
+    awq_linear_workspace_bytes() bytes, None (allocated here when the shape uses one) or False
+    (run without it)."""
     _dev(x, torch.float16, "x")
     M, K = x.shape
     qb, sb, zb = awq_packed_sizes(N, K, group)
@@ -303,12 +305,14 @@ def awq_w4a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int
         raise ValueError("y must have M*N elements")
     need = awq_linear_workspace_bytes(M, N, K, group)
     ws_bytes = 0
-    if need:
+    if workspace is False or not need:
+        workspace = None                              # False: run without the K split
+    else:
         if workspace is None:
             workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
         ws_bytes = workspace.numel() * workspace.element_size()
     _check(load().awq_w4a16_linear(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(y),
-                                   M, N, K, group, _ptr(workspace) if need else None, ws_bytes,
+                                   M, N, K, group, _ptr(workspace), ws_bytes,
                                    _stream()), "awq_w4a16_linear")
     return y
 

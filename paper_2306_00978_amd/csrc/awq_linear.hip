@@ -47,9 +47,10 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
     if (!awq_aligned16(x_f16) || !awq_aligned16(qweight) || !awq_aligned16(scales) ||
         !awq_aligned16(zeros) || !awq_aligned16(y_f16))
         return AWQ_ERR_MISALIGNED;
-    // the workspace is optional: without it (NULL or too small) K is not split
+    // the workspace is optional: with NULL, K is not split
     const size_t need = awq_linear_workspace_bytes(M, N, K, group);
-    const bool split = need > 0 && workspace && workspace_bytes >= need;
+    const bool split = need > 0 && workspace;
+    if (split && workspace_bytes < need) return AWQ_ERR_WORKSPACE_TOO_SMALL;
     if (split && !awq_aligned16(workspace)) return AWQ_ERR_MISALIGNED;
     if (M <= 16) {
         // a single linear is a short kernel dominated by one memory round trip: the batch

@@ -88,6 +88,7 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert lib.awq_w4a16_linear(ok, ok, ok, ok, odd, 1, 16, 128, 128, None, 0, None) == -4
     # a workspace that would be used has to be aligned
     assert lib.awq_w4a16_linear(ok, ok, ok, ok, ok, 200, 4096, 4096, 128, odd, 1 << 30, None) == -4
+    assert lib.awq_w4a16_linear(ok, ok, ok, ok, ok, 200, 4096, 4096, 128, ok, 7 * 200 * 4096 * 4 - 1, None) == -5
     assert lib.awq_unpack(ok, ok, ok, 16, 128, 128, odd, None, None, None) == -4
     # workspace query never fails
     assert lib.awq_linear_workspace_bytes(1, 4096, 4096, 128) >= 0

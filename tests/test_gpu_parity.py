@@ -264,8 +264,11 @@ def test_mid_prefill_split_k_full_size(awq, M, ksplit):
         ws, cw = guarded(max(need, 16), torch.uint8)
         y_split = host(awq.awq_w4a16_linear(dev(xs), *gpu, N, workspace=ws)).copy()
         cw()
-        tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
-        y_plain = host(awq.awq_w4a16_linear(dev(xs), *gpu, N, workspace=tiny)).copy()
+        y_plain = host(awq.awq_w4a16_linear(dev(xs), *gpu, N, workspace=False)).copy()
+        if need:
+            with pytest.raises(awq.AwqError) as e:
+                awq.awq_w4a16_linear(dev(xs), *gpu, N, workspace=ws[:need - 16])
+            assert e.value.status == -5
         import oracle
         for y in (y_split, y_plain):
             err = oracle.norm_error(y[rows], oracle.matmul(xs[rows], Wdq), xs[rows], Wdq)
