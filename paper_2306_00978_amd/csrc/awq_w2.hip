@@ -199,8 +199,8 @@ struct W2Args {
 // addresses that are in bounds) and are skipped by a wave-uniform branch.
 // Dynamic LDS: [4 waves][MS rows x (U*512 + 16) bytes], then [4/S row blocks][16*M outputs][4
 // slots] of fp32 for the sum over the slices.
-template <int MS, int U, bool PF>
-__global__ __launch_bounds__(256, PF ? 3 : 4) void gemv_w2_kernel(const W2Args a)
+template <int MS, int U>
+__global__ __launch_bounds__(256, 3) void gemv_w2_kernel(const W2Args a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int CHUNKS = MS * U * 32;            // 16-byte chunks of x per batch
@@ -282,8 +282,8 @@ __global__ __launch_bounds__(256, PF ? 3 : 4) void gemv_w2_kernel(const W2Args a
             const int m = ci / (32 * U), cc = ci % (32 * U);
             reinterpret_cast<uint4 *>(xw + m * ROW_BYTES)[cc] = xs[i];
         }
-        // PF: this batch's codes move to registers of their own and the next batch is requested
-        // before this one is consumed (where the registers allow it); otherwise after it
+        // this batch's codes move to registers of their own and the next batch is requested
+        // before this one is consumed (three waves per SIMD leave the registers for that)
         uint4 qc[U];
         uint2 svc[U];
         uint32_t zc[U];
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(256, PF ? 3 : 4) void gemv_w2_kernel(const W2Args a
             svc[u] = sv[u];
             zc[u] = z[u];
         }
-        if (PF && b + U < b1) request(b + U);      // wave-uniform
+        if (b + U < b1) request(b + U);            // wave-uniform
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (b + u < b1) {                      // wave-uniform
@@ -327,7 +327,6 @@ __global__ __launch_bounds__(256, PF ? 3 : 4) void gemv_w2_kernel(const W2Args a
                 }
             }
         }
-        if (!PF && b + U < b1) request(b + U);
     }
 
     floatx4 total;
@@ -362,10 +361,10 @@ __global__ __launch_bounds__(256, PF ? 3 : 4) void gemv_w2_kernel(const W2Args a
     }
 }
 
-template <int MS, int U, bool PF>
+template <int MS, int U>
 int launch_w2_one(const W2Args &a, int total_wgs, size_t lds, hipStream_t stream)
 {
-    gemv_w2_kernel<MS, U, PF><<<dim3(total_wgs), dim3(64 * W2_WAVES), lds, stream>>>(a);
+    gemv_w2_kernel<MS, U><<<dim3(total_wgs), dim3(64 * W2_WAVES), lds, stream>>>(a);
     return awq_launch_status();
 }
 
@@ -405,11 +404,11 @@ int launch_w2(const W2Problem *probs, int count, int M, hipStream_t stream)
     const int U = MS <= 4 ? 4 : (MS == 8 ? 2 : 1);
     const size_t lds = (size_t)W2_WAVES * MS * (U * 512 + 16) + (size_t)W2_WAVES * ((M + 3) / 4 * 4) * 256;
     switch (MS) {
-    case 1: return launch_w2_one<1, 4, true>(a, total, lds, stream);
-    case 2: return launch_w2_one<2, 4, false>(a, total, lds, stream);
-    case 4: return launch_w2_one<4, 4, false>(a, total, lds, stream);
-    case 8: return launch_w2_one<8, 2, false>(a, total, lds, stream);
-    default: return launch_w2_one<16, 1, true>(a, total, lds, stream);
+    case 1: return launch_w2_one<1, 4>(a, total, lds, stream);
+    case 2: return launch_w2_one<2, 4>(a, total, lds, stream);
+    case 4: return launch_w2_one<4, 4>(a, total, lds, stream);
+    case 8: return launch_w2_one<8, 2>(a, total, lds, stream);
+    default: return launch_w2_one<16, 1>(a, total, lds, stream);
     }
 }
 
