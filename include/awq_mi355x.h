@@ -254,7 +254,10 @@ int awq_w3a16_linear(const void *x_f16, const void *qweight, const void *scales,
  *     calls with the 3-bit linear's scales and zeros.
  *   awq_w3a16_linear_prefill: the two steps in one call; workspace (device, 16-byte aligned,
  *     awq_w3a16_prefill_workspace_bytes() = N*K/2 bytes) holds the re-packed codes, contents
- *     undefined afterwards.  M <= 16 returns AWQ_ERR_BAD_SHAPE (use awq_w3a16_linear). */
+ *     undefined afterwards.  With N*K/2 rounded up to a multiple of 256, plus
+ *     awq_linear_workspace_bytes(M, N, K, group) bytes, the prefill kernel also cuts K into
+ *     ranges for a few hundred tokens, as awq_w4a16_linear does with its workspace.
+ *     M <= 16 returns AWQ_ERR_BAD_SHAPE (use awq_w3a16_linear). */
 int awq_repack_w3_to_w4(const void *qweight_w3, int64_t N, int64_t K, int group, void *qweight_w4,
                         void *stream);
 size_t awq_w3a16_prefill_workspace_bytes(int64_t N, int64_t K, int group);

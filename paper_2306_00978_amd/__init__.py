@@ -481,6 +481,8 @@ def awq_w3a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int
     if M > 16:
         need = int(load().awq_w3a16_prefill_workspace_bytes(N, K, group))
         if workspace is None:
+            # re-packed codes, then the fp32 partial tiles of the K ranges (if the shape uses them)
+            need = (need + 255) // 256 * 256 + awq_linear_workspace_bytes(M, N, K, group)
             workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
         _check(load().awq_w3a16_linear_prefill(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(out),
                                                M, N, K, group, _ptr(workspace),

@@ -189,6 +189,9 @@ __global__ __launch_bounds__(256) void repack_w3_to_w4_kernel(const uint32_t *__
 
 int awq_gemm_launch(const void *x, const void *qweight, const void *scales, const void *zeros,
                     void *y, int M, int N, int K, hipStream_t stream);
+int awq_gemm_launch_split(const void *x, const void *qweight, const void *scales, const void *zeros,
+                          void *y, int M, int N, int K, void *part, int ksplit, hipStream_t stream);
+int awq_gemm_ksplit(int M, int N, int K, double *estimate_us);
 
 extern "C" int awq_repack_w3_to_w4(const void *qweight_w3, int64_t N, int64_t K, int group,
                                    void *qweight_w4, void *stream)
@@ -240,6 +243,14 @@ extern "C" int awq_w3a16_linear_prefill(const void *x_f16, const void *qweight, 
     }
     st = awq_repack_w3_to_w4(qweight, N, K, group, workspace, stream);
     if (st != AWQ_OK) return st;
+    // a few hundred tokens: with room behind the re-packed codes (rounded up to 256 bytes) for the
+    // fp32 partial tiles, the prefill kernel cuts K into ranges as in awq_w4a16_linear
+    const size_t repacked = ((size_t)(N * K / 2) + 255) & ~(size_t)255;
+    const size_t partials = awq_linear_workspace_bytes(M, N, K, group);
+    if (partials > 0 && workspace_bytes >= repacked + partials)
+        return awq_gemm_launch_split(x_f16, workspace, scales, zeros, y_f16, (int)M, (int)N, (int)K,
+                                     (unsigned char *)workspace + repacked,
+                                     awq_gemm_ksplit((int)M, (int)N, (int)K, nullptr), (hipStream_t)stream);
     return awq_gemm_launch(x_f16, workspace, scales, zeros, y_f16, (int)M, (int)N, (int)K, (hipStream_t)stream);
 }
 

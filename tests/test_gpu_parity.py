@@ -932,6 +932,19 @@ def test_w3_repack_and_prefill(awq, N, K):
         yh = host(y.view(M, N))
         err = oracle.norm_error(yh, oracle.matmul(x, Wdq), x, Wdq)
         assert err.max() <= TOL, f"max normalised error {err.max():.3e} (M={M})"
+        if M > 128:
+            # the binding's workspace has room for the K ranges where the shape uses them; with
+            # the re-packed codes alone the unsplit kernel runs: same result up to the order of sums
+            small_ws, cws = guarded(N * K // 2, torch.uint8)
+            y2 = host(awq.awq_w3a16_linear(dev(x), *gpu, N, workspace=small_ws)).copy()
+            cws()
+            err2 = oracle.norm_error(y2, oracle.matmul(x, Wdq), x, Wdq)
+            assert err2.max() <= TOL
+            full = (N * K // 2 + 255) // 256 * 256 + awq.awq_linear_workspace_bytes(M, N, K)
+            big_ws, cwb = guarded(full, torch.uint8)
+            y3 = host(awq.awq_w3a16_linear(dev(x), *gpu, N, workspace=big_ws)).copy()
+            cwb()
+            assert np.array_equal(y3.view(np.uint16), yh.view(np.uint16))
     with pytest.raises(awq.AwqError) as e:          # too small a workspace is refused
         awq.awq_w3a16_linear(dev(np.tile(xs, (2, 1))), *gpu, N, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.status == -5
