@@ -19,13 +19,16 @@
 // place as the codes of group t, so the zero point needs no shift either.
 //
 // Decode kernel (M <= 16): a wave owns a 16-row block of one linear, or a slice of its K/256
-// blocks where rows are long.  Per batch of up to four blocks a wave requests everything at once, copies the
-// slice of x it needs into its own LDS area (16-byte loads, no workgroup barrier), and runs per
-// block eight MFMA steps against the codes and eight against the constant -z 4^t 2^-24 of the
-// lane's row (a negative subnormal), all in one accumulator per group:
+// blocks where rows are long.  Per batch of up to four blocks a wave requests everything at once,
+// copies the slice of x it needs into its own LDS area (16-byte loads, no workgroup barrier),
+// requests the next batch, and runs per block eight MFMA steps against the codes and eight
+// against the constant -z 4^t 2^-24 of the lane's row (a negative subnormal), all in one
+// accumulator per group:
 //   sum_k x_k (q_k - z) = 2^24 4^-t * (MFMA(x, q 4^t 2^-24) + MFMA(x, -z 4^t 2^-24)),  per group,
-// then applies the group's step (times 2^(24 - 2t)) with one fp32 FMA per output.  Partial sums of the slices of a row block are combined
-// through LDS in a fixed order.  Several linears (different shapes, same M) can share one launch.
+// then adds step * accumulator to the running sum of group position t with one mixed-precision
+// FMA per output; the factors 2^(24 - 2t) are applied once after the loop.  Partial sums of the
+// slices of a row block are combined through LDS in a fixed order.  Several linears (different
+// shapes, same M) can share one launch.
 //
 // This file is compiled with -ffp-contract=off (integer decisions in the quantizer).
 #include "awq_common.h"
