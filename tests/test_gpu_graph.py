@@ -81,3 +81,42 @@ def test_graph_replay_of_decode_prefill_and_low_bit_calls(awq):
     xb = host(xbig)
     err = oracle.norm_error(host(ybig), oracle.matmul(xb, Wdq), xb, Wdq)
     assert err.max() <= 2e-3
+
+
+def test_calls_on_two_streams_do_not_share_anything(awq):
+    """The library keeps no scratch of its own: calls issued on two streams at the same time give
+    the results of the same calls issued one after the other."""
+    import torch
+    cases = []
+    for i, (N, K) in enumerate([(2048, 2048), (1024, 4096)]):
+        case, s, xs = make_case(N, K, 16, 0.02, cfg=0, proj=80 + i)
+        W, sd = dev(case.W), dev(s)
+        cases.append((N, K, dev(xs), awq.awq_quantize_pack(W, sd), awq.awq_quantize_pack_w2(W, sd)))
+
+    def work(c, outs):
+        N, K, x, p4, p2 = c
+        for rep in range(6):
+            awq.awq_w4a16_linear_multi([(x[:1], *p4, outs[0], N), (x[:1], *p4, outs[1], N)])
+            awq.awq_w4a16_linear(x, *p4, N, out=outs[2])
+            awq.awq_w2a16_linear(x[:4], *p2, N, out=outs[3])
+
+    def fresh(c):
+        N = c[0]
+        return [torch.zeros((m, N), dtype=torch.float16, device="cuda") for m in (1, 1, 16, 4)]
+
+    want = []
+    for c in cases:
+        o = fresh(c)
+        work(c, o)
+        torch.cuda.synchronize()
+        want.append(o)
+    got = [fresh(c) for c in cases]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for c, o, st in zip(cases, got, streams):
+        with torch.cuda.stream(st):
+            work(c, o)
+    torch.cuda.synchronize()
+    for w, g_ in zip(want, got):
+        for a, b in zip(w, g_):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))
