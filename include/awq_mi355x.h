@@ -18,8 +18,12 @@
  *     Tensor pointers must be 16-byte aligned.
  *   - Return value: AWQ_OK (0) or a negative awq_status.  Arguments are validated
  *     before anything is launched, so on a validation error no output is touched.
- *   - No global mutable state; calls on distinct streams may run concurrently as
- *     long as their outputs (and workspaces) do not overlap.
+ *   - Calls on distinct streams, from one or several host threads, may run concurrently as
+ *     long as their outputs (and workspaces) do not overlap.  The library keeps no state between
+ *     calls except per-device "kernel attribute already raised" flags and the diagnostic of
+ *     awq_last_grouped_plan (relaxed atomics), and the built-in scratch of
+ *     awq_w4a16_linear_static, whose calls must not overlap on one GPU.  It reads no environment
+ *     variable.
  *
  * Packed layout, version 1 (what awq_quantize_pack writes and awq_w4a16_linear reads)
  *   qweight : N*K/2 bytes; tiles of 16 rows x 128 columns (1024 B), tile index
@@ -48,7 +52,8 @@ typedef enum awq_status {
     AWQ_ERR_MISALIGNED = -4,        /* a tensor pointer is not 16-byte aligned */
     AWQ_ERR_WORKSPACE_TOO_SMALL = -5,
     AWQ_ERR_HIP = -6,               /* the HIP runtime refused a launch */
-    AWQ_ERR_BAD_ARGUMENT = -7       /* a scalar argument is out of range (e.g. alpha) */
+    AWQ_ERR_BAD_ARGUMENT = -7,      /* a scalar argument is out of range (e.g. alpha) */
+    AWQ_ERR_SCRATCH_LIMIT = -8      /* awq_w4a16_linear_static: the shape needs more than the built-in scratch */
 } awq_status;
 
 /* Version of the packed layout / ABI (currently 1). */
@@ -81,7 +86,7 @@ int awq_apply_inv_scale(const void *x_f16, const float *s, int64_t M, int64_t K,
                         void *xs_f16, void *stream);
 
 /* Sec. 4.2 (kernel fusion: the operators of the normalisation in one kernel) with the 1/s factor
- * of Eq. 4 folded in, as Sec. 3.2 suggests ("fused into the previous operator"): RMS form,
+ * of Eq. 4 folded in (Sec. 3.2: that factor belongs to the producer of x): RMS form,
  *   xs[m,k] = fp16( x[m,k] / sqrt(mean_k x[m,k]^2 + eps) * gamma[k] / s[k] ),  fp32 inside.
  * x, xs [M,K] fp16 (device; xs may alias x), gamma [K] fp16 (device), s [K] fp32 (device) or
  * NULL (= ones), eps >= 0.  K % 8 == 0.  The result feeds awq_w4a16_linear directly. */
@@ -106,8 +111,8 @@ int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K, i
 #define AWQ_CLIP_MAX_RATIOS 32
 #define AWQ_CLIP_MAX_ROWS 64
 
-/* Sec. 3.2, weight clipping ("we further apply weight clipping to minimize the MSE error of
- * quantization"; the paper says no more, this is the reading taken): awq_quantize_pack with a
+/* Sec. 3.2, weight clipping (named there in one sentence as a second step that lowers the squared
+ * quantization error; objective, grid and granularity are not given, this is the reading taken): awq_quantize_pack with a
  * search per quantization group.  The group's range [min, max] of w' = W*s is shrunk to
  * [r*min, r*max] for every r of `ratios`, the group is quantized with that range by the
  * formulas of awq_quantize_pack (values outside it saturate at code 0 or 15), and the r with
@@ -157,6 +162,30 @@ size_t awq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
 int awq_w4a16_linear(const void *x_f16, const void *qweight, const void *scales,
                      const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,
                      int group, void *workspace, size_t workspace_bytes, void *stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): awq_w4a16_linear with the scratch of its K-range prefill
+ * form taken from an array built into the library instead of a caller's workspace.  Same kernels,
+ * same results bit for bit as awq_w4a16_linear with a workspace of awq_linear_workspace_bytes().
+ * The call allocates and frees nothing and calls no allocating routine.
+ *   - The array is AWQ_STATIC_SCRATCH_BYTES (32 MiB, awq_static_scratch_bytes()) of device memory
+ *     per GPU the library is used on, held until the process ends; it covers the Llama-2-7B
+ *     shapes up to 1024 tokens.  A shape whose awq_linear_workspace_bytes() exceeds it is refused
+ *     with AWQ_ERR_SCRATCH_LIMIT before anything is launched (use awq_w4a16_linear, with or
+ *     without a workspace).  Shapes that need no scratch (decode, M = 2048) never touch it.
+ *   - All calls on one GPU share that one array.  Nothing in it has to start at zero (every word
+ *     a launch reads was written by the same call before), so calls in sequence on one stream
+ *     need no clearing in between; calls that OVERLAP on one GPU (two streams, two threads) race
+ *     on it and give undefined results: serialise them, or use awq_w4a16_linear with workspaces
+ *     of your own.
+ *   - The array's device address is looked up on the first call on each device (with that device
+ *     current); make that first call outside a graph capture.
+ * Arguments, layouts and every other error as for awq_w4a16_linear. */
+#define AWQ_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+size_t awq_static_scratch_bytes(void);
+int awq_w4a16_linear_static(const void *x_f16, const void *qweight, const void *scales,
+                            const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,
+                            int group, void *stream);
 
 /* One linear of a grouped decode call: the arguments of awq_w4a16_linear without M. */
 typedef struct awq_linear_desc {
@@ -327,7 +356,7 @@ int awq_decode_attention(const void *q_f16, const void *k_f16, const void *v_f16
  * sums. */
 size_t awq_search_scale_workspace_bytes(int64_t T, int64_t N, int64_t K, int n_alpha, int group);
 
-/* Sec. 3.2 "Searching to scale", Eq. 4-5: for every alpha of the grid, s = s_X^alpha with
+/* Sec. 3.2 (the search for the scale), Eq. 4-5: for every alpha of the grid, s = s_X^alpha with
  * s_X[k] = max(mean_t |X[t,k]|, 1e-4), and
  *   loss(alpha) = sum_{t,n} ( y_q[t,n] - y[t,n] )^2,
  *   y_q = awq_w4a16_linear(awq_apply_inv_scale(X, s), awq_quantize_pack(W, s)),  y = fp16(X W^T)

@@ -39,7 +39,7 @@ EXPORTS = [
     "awq_repack_w3_to_w4", "awq_w3a16_prefill_workspace_bytes", "awq_w3a16_linear_prefill",
     "awq_packed_sizes_w2", "awq_quantize_pack_w2", "awq_unpack_w2", "awq_w2a16_linear",
     "awq_w2a16_linear_multi",
-    "awq_last_grouped_plan",
+    "awq_last_grouped_plan", "awq_static_scratch_bytes", "awq_w4a16_linear_static",
 ]
 MULTI_MAX = 56
 
@@ -72,11 +72,13 @@ def load() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    # AWQ_MI355X_LIBRARY names another build of the same library (the host-sanitized one of the tests)
+    path = os.environ.get("AWQ_MI355X_LIBRARY") or LIB_PATH
+    if not os.path.exists(path):
         raise RuntimeError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_2306_00978_amd.build` "
+            f"{path} is missing: build it with `python -m paper_2306_00978_amd.build` "
             "(there is no CPU or PyTorch fallback for this library)")
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
     szp = ctypes.POINTER(ctypes.c_size_t)
     lib.awq_version.restype = i32
@@ -127,6 +129,10 @@ def load() -> ctypes.CDLL:
     lib.awq_w3a16_linear_prefill.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
     lib.awq_last_grouped_plan.restype = i32
     lib.awq_last_grouped_plan.argtypes = []
+    lib.awq_static_scratch_bytes.restype = sz
+    lib.awq_static_scratch_bytes.argtypes = []
+    lib.awq_w4a16_linear_static.restype = i32
+    lib.awq_w4a16_linear_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
     lib.awq_silu_mul.restype = i32
     lib.awq_silu_mul.argtypes = [vp, vp, i64, vp, vp]
     lib.awq_read_probe.restype = i32
@@ -237,6 +243,34 @@ def awq_quantize_pack(W: torch.Tensor, s: torch.Tensor | None = None, group: int
     return qweight, scales, zeros
 
 
+def prepare_quantize_pack(W: torch.Tensor, s: torch.Tensor | None, out, group: int = GROUP):
+    """Marshal the arguments of awq_quantize_pack once and return a zero-argument callable that
+    enqueues it on the then-current stream (a pass over many matrices costs one C call each).
+    out = (qweight, scales, zeros) buffers; every tensor must stay alive and in place."""
+    _dev(W, torch.float16, "W")
+    N, K = W.shape
+    if s is not None:
+        _dev(s, torch.float32, "s")
+        if s.numel() != K:
+            raise ValueError("s must have K elements")
+    qb, sb, zb = awq_packed_sizes(N, K, group)
+    qweight, scales, zeros = out
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+            or zeros.numel() * zeros.element_size() < zb:
+        raise ValueError("output buffers are too small")
+    fn = load().awq_quantize_pack
+    c = ctypes
+    fixed = (c.c_void_p(W.data_ptr()), c.c_void_p(_ptr(s)), c.c_int64(N), c.c_int64(K), c.c_int(group),
+             c.c_void_p(qweight.data_ptr()), c.c_void_p(scales.data_ptr()), c.c_void_p(zeros.data_ptr()))
+    keep = (W, s, qweight, scales, zeros)
+
+    def call(_keep=keep):
+        st = fn(*fixed, c.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_quantize_pack")
+    return call
+
+
 def awq_unpack(qweight, scales, zeros, N: int, K: int, group: int = GROUP):
     """Packed arrays -> (codes u8[N,K], scales f16[N,G], zeros u8[N,G])."""
     qb, sb, zb = awq_packed_sizes(N, K, group)
@@ -265,15 +299,17 @@ def prepare_linear(x: torch.Tensor, qweight, scales, zeros, y: torch.Tensor, N: 
     if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
             or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
         raise ValueError("buffer sizes do not match the shape")
+    # the workspace is optional, as in the C ABI: without one the call runs without the K split
     need = awq_linear_workspace_bytes(M, N, K, group)
-    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
-        raise ValueError(f"this shape needs a workspace of {need} bytes")
+    use_ws = bool(need) and workspace is not None
+    if use_ws and workspace.numel() * workspace.element_size() < need:
+        raise ValueError(f"the workspace of this shape is {need} bytes")
     fn = load().awq_w4a16_linear
     c = ctypes
     fixed = (c.c_void_p(x.data_ptr()), c.c_void_p(qweight.data_ptr()), c.c_void_p(scales.data_ptr()),
              c.c_void_p(zeros.data_ptr()), c.c_void_p(y.data_ptr()), c.c_int64(M), c.c_int64(N),
-             c.c_int64(K), c.c_int(group), c.c_void_p(workspace.data_ptr() if need else None),
-             c.c_size_t(workspace.numel() * workspace.element_size() if need else 0))
+             c.c_int64(K), c.c_int(group), c.c_void_p(workspace.data_ptr() if use_ws else None),
+             c.c_size_t(workspace.numel() * workspace.element_size() if use_ws else 0))
     keep = (x, qweight, scales, zeros, y, workspace)
 
     def call(_keep=keep):
@@ -317,6 +353,27 @@ def awq_w4a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int
     return y
 
 
+def awq_static_scratch_bytes() -> int:
+    return int(load().awq_static_scratch_bytes())
+
+
+def awq_w4a16_linear_static(x: torch.Tensor, qweight, scales, zeros, N: int, y: torch.Tensor,
+                            group: int = GROUP):
+    """awq_w4a16_linear for callers that cannot allocate: the scratch of the K-range prefill form
+    comes from the array built into the library (one per GPU, shared by all calls on it: do not
+    overlap calls).  The caller brings y; nothing is allocated here or in the library."""
+    _dev(x, torch.float16, "x")
+    _dev(y, torch.float16, "y")
+    M, K = x.shape
+    qb, sb, zb = awq_packed_sizes(N, K, group)
+    if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+            or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
+        raise ValueError("buffer sizes do not match the shape")
+    _check(load().awq_w4a16_linear_static(_ptr(x), _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(y),
+                                          M, N, K, group, _stream()), "awq_w4a16_linear_static")
+    return y
+
+
 def prepare_linear_multi(linears, group: int = GROUP):
     """Marshal one grouped decode call.  `linears` is a list of (x, qweight, scales, zeros, y, N)
     with the same M <= 16 everywhere.  Returns a zero-argument callable that enqueues ONE
@@ -343,8 +400,10 @@ def prepare_linear_multi(linears, group: int = GROUP):
     count = len(linears)
     keep = list(linears)
 
-    def call(_keep=keep):
-        st = fn(descs, count, M, group, None, 0, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    def call(stream=None, _keep=keep):
+        """stream: a raw hipStream_t handle (torch.cuda.Stream().cuda_stream); None = torch's current one"""
+        st = fn(descs, count, M, group, None, 0,
+                ctypes.c_void_p(torch.cuda.current_stream().cuda_stream if stream is None else stream))
         if st != 0:
             raise AwqError(st, "awq_w4a16_linear_multi")
     return call

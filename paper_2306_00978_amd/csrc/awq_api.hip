@@ -14,6 +14,7 @@ extern "C" const char *awq_status_string(int status)
     case AWQ_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case AWQ_ERR_HIP: return "HIP runtime refused the launch";
     case AWQ_ERR_BAD_ARGUMENT: return "scalar argument out of range";
+    case AWQ_ERR_SCRATCH_LIMIT: return "shape needs more scratch than the library's built-in array holds";
     default: return "unknown status";
     }
 }

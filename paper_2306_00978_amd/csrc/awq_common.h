@@ -5,6 +5,9 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
+
+#include <atomic>
 
 #include "awq_mi355x.h"
 
@@ -37,13 +40,27 @@ static inline int awq_launch_status()
 }
 
 // "Done once on this device" flag for settings that belong to a (kernel, device) pair, such as a
-// raised dynamic-LDS limit.  Setting such a thing twice is harmless, so the flag needs no lock.
+// raised dynamic-LDS limit.  Setting such a thing twice is harmless, so a relaxed atomic flag is
+// enough: two host threads may both set it, none reads a torn value.
 struct AwqOncePerDevice {
-    bool done[64] = {};
-    bool &here()
+    std::atomic<bool> done[64] = {};
+    std::atomic<bool> &here()
     {
         int dev = 0;
         (void)hipGetDevice(&dev);
         return done[dev & 63];
     }
 };
+
+// Planner constants that experiments override through the environment exist only in the tuning
+// build of the library (-DAWQ_TUNING_KNOBS, libawq_mi355x_knobs.so); the shipped library reads no
+// environment variable and always takes the default.
+#ifdef AWQ_TUNING_KNOBS
+static inline int awq_knob(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return e ? atoi(e) : dflt;
+}
+#else
+static inline int awq_knob(const char *, int dflt) { return dflt; }
+#endif

@@ -6,6 +6,7 @@
 
 #include <stdlib.h>
 #include <algorithm>
+#include <atomic>
 
 int awq_gemv_launch_residual(const void *x, const void *qweight, const void *scales, const void *zeros,
                              void *y, const void *res, int M, int N, int K, hipStream_t stream);
@@ -55,8 +56,8 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
     if (M <= 16) {
         // a single linear is a short kernel dominated by one memory round trip: the batch
         // kernel (everything requested at once) is the faster one; the streaming kernel is
-        // for grouped launches.  AWQ_GEMV_STREAM_SINGLE forces it for experiments.
-        static const bool stream_single = getenv("AWQ_GEMV_STREAM_SINGLE") != nullptr;
+        // for grouped launches.  (The tuning build can force it: AWQ_GEMV_STREAM_SINGLE.)
+        static const bool stream_single = awq_knob("AWQ_GEMV_STREAM_SINGLE", 0) != 0;
         if (stream_single) {
             GemvProblem p = {};
             p.x = (const half_t *)x_f16;
@@ -80,7 +81,7 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
     // (4096 x 4096: 43 us -> 12-19 us for 17..128 tokens; 4096 x 11008: 105 us -> 20-72 us -- that
     // shape does not fit the grouped launch, and from 49 tokens on the prefill kernel with K cut
     // into ranges is faster when the caller brings its workspace: 36 us.)
-    static const int small_env = getenv("AWQ_SMALL_M_MAX") ? atoi(getenv("AWQ_SMALL_M_MAX")) : -1;
+    static const int small_env = awq_knob("AWQ_SMALL_M_MAX", -1);
     const int64_t small_max = small_env >= 0 ? std::min(small_env, 128) : 128;
     if (M <= small_max && !split) {
         const int blocks = (int)((M + 15) / 16);
@@ -102,6 +103,56 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
                                      awq_gemm_ksplit((int)M, (int)N, (int)K, nullptr), (hipStream_t)stream);
     return awq_gemm_launch(x_f16, qweight, scales, zeros, y_f16, (int)M, (int)N, (int)K,
                            (hipStream_t)stream);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------
+// The K-range form of the prefill kernel needs room for its fp32 partial tiles.  Callers that cannot
+// allocate (code under graph capture, serving loops, harnesses that forbid it) get that room from
+// this array: one copy per GPU the library runs on, held until the process ends.  In host code the
+// name `scratch` is only a handle for hipGetSymbolAddress; kernels receive the device address.
+static __device__ __align__(256) unsigned char scratch[AWQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void **out)
+{
+    static std::atomic<void *> address[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return AWQ_ERR_HIP;
+    void *p = address[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return AWQ_ERR_HIP;
+        }
+        address[dev].store(p, std::memory_order_release);      // every thread finds the same address
+    }
+    *out = p;
+    return AWQ_OK;
+}
+
+}  // namespace
+
+extern "C" size_t awq_static_scratch_bytes(void) { return AWQ_STATIC_SCRATCH_BYTES; }
+
+extern "C" int awq_w4a16_linear_static(const void *x_f16, const void *qweight, const void *scales,
+                                       const void *zeros, void *y_f16, int64_t M, int64_t N, int64_t K,
+                                       int group, void *stream)
+{
+    // same validation order as awq_w4a16_linear, so that a bad argument reads the same from both
+    if (!x_f16 || !qweight || !scales || !zeros || !y_f16) return AWQ_ERR_NULL_POINTER;
+    int st = awq_check_weight_shape(N, K, group);
+    if (st != AWQ_OK) return st;
+    if (M <= 0 || M > (int64_t)1 << 22) return AWQ_ERR_BAD_SHAPE;
+    const size_t need = awq_linear_workspace_bytes(M, N, K, group);
+    if (need > AWQ_STATIC_SCRATCH_BYTES) return AWQ_ERR_SCRATCH_LIMIT;
+    void *ws = nullptr;
+    if (need > 0) {
+        st = static_scratch(&ws);
+        if (st != AWQ_OK) return st;
+    }
+    return awq_w4a16_linear(x_f16, qweight, scales, zeros, y_f16, M, N, K, group, ws, need, stream);
 }
 
 extern "C" int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
