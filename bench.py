@@ -100,10 +100,10 @@ def main():
     gen.manual_seed(workloads.BASE_SEED)
     layers = []
     W0 = {}
-    quant_bytes = 0
-    quant_ms = 0.0
     arena_bytes = sum((b + 255) // 256 * 256 for _, N, K in shapes for b in awq.awq_packed_sizes(N, K))
     arenas = []
+    quant_calls = []
+    quant_bytes = 0
     for l in range(L):
         packed = []
         arena = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)   # one buffer per layer
@@ -123,18 +123,26 @@ def main():
                 views.append(arena[off:off + nb_])
                 off += (nb_ + 255) // 256 * 256
             out = (views[0], views[1].view(torch.float16), views[2])
-            if l == 0:
-                awq.awq_quantize_pack(W, s_by_k[K], out=out)       # warm-up of the kernel
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            awq.awq_quantize_pack(W, s_by_k[K], out=out)
-            e1.record()
-            torch.cuda.synchronize()
-            quant_ms += e0.elapsed_time(e1)
+            quant_calls.append(awq.prepare_quantize_pack(W, s_by_k[K], out))     # keeps W alive
             quant_bytes += 2 * N * K + qb + sb + zb + 4 * K
             packed.append(out)
             del W
         layers.append(packed)
+    # configs[4]: ONE awq_quantize_pack pass over all the weight matrices (7 per layer), the fp16
+    # sources resident in HBM (13 GB for 32 layers), one call per matrix back to back.  The first
+    # pass is the warm-up (code objects, page tables), the second one is timed.
+    for call in quant_calls:
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for call in quant_calls:
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    quant_ms = e0.elapsed_time(e1)
+    del quant_calls                                                              # frees the fp16 sources
+    torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ decode launch modes
     # "grouped": ONE awq_w4a16_linear_multi per `span` layers (span = 1: the 7 projections of
@@ -363,6 +371,11 @@ def main():
         },
     }
 
+    result["config"]["quantize_pack_pass"] = {
+        "what": f"configs[4]: one awq_quantize_pack call per matrix over all {L * len(shapes)} matrices, back to back",
+        "ms_total": round(quant_ms, 3), "GB/s": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
+        "pct_of_hbm_peak": round(100 * quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+
     # ---- the same layer the way the benchmark spec's call is named (one awq_w4a16_linear per projection) and
     # the way a decoder orders it (Q,K,V | o | gate,up | down: four dependent launches)
     msteps, mwarm = max(2, min(args.steps, 6)), max(1, min(args.warmup, 2))
@@ -380,6 +393,41 @@ def main():
                     "data dependences allow, replayed from a graph",
             "launches_per_step": n, "us_per_layer": round(e * 1e3 / L, 2),
             "GB/s": gbs(bytes_step, e), "pct_of_hbm_peak": pct(gbs(bytes_step, e))}
+
+        # the layers of this benchmark do not depend on each other (configs[1] and configs[4] model
+        # no dependence): issued alternately on two streams of equal priority, the run-out of one
+        # launch overlaps the start of the next.  Whole-job throughput only: two launches share
+        # the chip, so a launch's own duration is about twice the step time per launch.
+        sA, sB = torch.cuda.Stream(), torch.cuda.Stream()
+        cur = torch.cuda.current_stream()
+        calls2s = [plan("grouped", l, 1)[0] for l in range(L)]
+        hA, hB = sA.cuda_stream, sB.cuda_stream
+
+        def two_stream_pass():
+            for i, c in enumerate(calls2s):
+                c(hA if (i & 1) == 0 else hB)
+        sA.wait_stream(cur)
+        sB.wait_stream(cur)
+        for _ in range(20):
+            two_stream_pass()
+        sA.synchronize()
+        sB.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(cur)
+        sA.wait_event(e0)
+        sB.wait_event(e0)
+        npass = 20
+        for _ in range(npass):
+            two_stream_pass()
+        cur.wait_stream(sA)
+        cur.wait_stream(sB)
+        e1.record(cur)
+        torch.cuda.synchronize()
+        e2s = e0.elapsed_time(e1) / npass
+        result["config"]["independent_layers_on_two_streams"] = {
+            "what": "the headline launches issued alternately on two streams (the benchmark's layers are "
+                    "independent); whole-job throughput, not a per-launch duration",
+            "us_per_layer": round(e2s * 1e3 / L, 3), "GB/s": gbs(bytes_step, e2s), "pct_of_hbm_peak": pct(gbs(bytes_step, e2s))}
 
     # ---- prefill GEMM, M = 2048, the three distinct shapes (the second half of the metric)
     if "prefill" in legs:
@@ -648,9 +696,6 @@ def main():
                                   "TFLOP/s": round(workloads.flops(512, N, K) / us[0] / 1e6, 1)}
             del x512, y512
         extras["prefill_m512"] = pre512
-        extras["quantize_pack"] = {"matrices": L * len(shapes), "ms_total": round(quant_ms, 3),
-                                   "GB/s": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
-                                   "pct_of_hbm_peak": round(100 * quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
         # quantize with the clipping search (11 range ratios) on the three distinct shapes
         ratios = [1.0 - 0.05 * i for i in range(11)]
         cms, cbytes = 0.0, 0

@@ -33,11 +33,24 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(out_dir: str) -> str:
+    """The same source under AddressSanitizer + UndefinedBehaviorSanitizer (gcc), for a process
+    that has gcc's libasan preloaded; AWQ_ORACLE_LIBRARY then names the result."""
+    out = os.path.join(out_dir, "libawq_oracle_san.so")
+    cmd = ["gcc", "-std=c11", "-O1", "-g", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-shared", "-fPIC", "-o", out, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return out
+
+
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        other = os.environ.get("AWQ_ORACLE_LIBRARY")
+        if not other:
+            build()
+        lib = ctypes.CDLL(other or _LIB)
         lib.awq_oracle_f16_to_f32.restype = ctypes.c_float
         lib.awq_oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
         lib.awq_oracle_f32_to_f16.restype = ctypes.c_uint16

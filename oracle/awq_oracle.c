@@ -13,7 +13,7 @@
  *     q = clamp(round(w/scale)+zero, 0, 15), group = 128 consecutive input
  *     channels of one output row (Sec. 4.1 "group size of 128").
  *   - Sec. 3.2, Eq. 4: W x == (W diag(s)) (diag(s)^-1 x); the caller divides x.
- *   - Sec. 4.2 "on-the-fly weight dequantization": y = x * dequant(q)^T with
+ *   - Sec. 4.2 (dequantization fused into the linear's kernel): y = x * dequant(q)^T with
  *     dequant(q) = (q - zero) * scale, written out here as a plain loop.
  *   - Sec. 4.2 "SIMD-aware weight packing": the packed byte layout is a pure
  *     index permutation; pack/unpack below are written from the layout text
@@ -113,7 +113,7 @@ int awq_oracle_act_scale(const uint16_t *X, int64_t T, int64_t K, double alpha,
 }
 
 /* x'[m,k] = fp16( fp32(x[m,k]) / s[k] ) : the inverse scale of Eq. 4 applied to
- * the activation by the caller ("fused into the previous operator").            */
+ * the activation by the caller (Sec. 3.2: the factor belongs to the producer of x). */
 int awq_oracle_apply_inv_scale(const uint16_t *x, const float *s, int64_t M,
                                int64_t K, uint16_t *xs)
 {
@@ -134,7 +134,7 @@ int awq_oracle_apply_inv_scale(const uint16_t *x, const float *s, int64_t M,
  * zeros  [N,G] one zero point per byte, 0..15                                   */
 /* ---------- normalisation fused with the inverse scale (Sec. 4.2 "Kernel fusion": all
  * operators of the layer normalisation in one kernel; Sec. 3.2: the diag(s)^-1 factor of Eq. 4
- * "can usually be fused into the previous operator").  RMS form, as the Llama-2-shaped layers
+ * belongs to the operator that produces x).  RMS form, as the Llama-2-shaped layers
  * of the workloads use it:
  *   xs[m,k] = fp16( x[m,k] / sqrt(mean_k x[m,k]^2 + eps) * gamma[k] / s[k] ),  binary64 inside.
  * gamma [K] binary16; s [K] binary32 or NULL (= ones).                                  */
@@ -213,8 +213,8 @@ int awq_oracle_quantize(const uint16_t *W, const float *s, int64_t N, int64_t K,
     return 0;
 }
 
-/* ---------- weight clipping (Sec. 3.2: "we further apply weight clipping to minimize the
- * MSE error of quantization").  The paper gives no more than that sentence; the reading
+/* ---------- weight clipping (Sec. 3.2 names it in one sentence, as a second step that lowers
+ * the squared quantization error).  The paper gives no more than that sentence; the reading
  * taken here: per quantization group, the range [min, max] of w*s is shrunk to
  * [r*min, r*max] for every r of a given grid, the group is quantized with that range (values
  * outside it saturate at code 0 or 15), and the r with the smallest sum of squared

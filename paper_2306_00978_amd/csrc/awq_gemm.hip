@@ -564,12 +564,12 @@ int gemm_launch_any(const void *x, const void *qweight, const void *scales, cons
     if (tiles_total * ksplit > (1 << 30)) return AWQ_ERR_BAD_SHAPE;
     const dim3 grid((unsigned)((tiles_total * ksplit + 7) / 8 * 8)), block(512);
     static AwqOncePerDevice once;
-    bool &attr_set = once.here();
-    if (!attr_set) {
+    std::atomic<bool> &attr_set = once.here();
+    if (!attr_set.load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel<SPLIT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
             return AWQ_ERR_HIP;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_relaxed);
     }
     gemm_kernel<SPLIT><<<grid, block, LDS_BYTES, stream>>>(
         (const half_t *)x, (const unsigned char *)qweight, (const unsigned char *)scales,

@@ -296,16 +296,10 @@ __global__ __launch_bounds__(1024, (MS >= 8 || (U == 4 && (PIPE || MS == 0 || (B
     }
 }
 
-int env_int(const char *name)
-{
-    const char *e = getenv(name);
-    return e ? atoi(e) : 0;
-}
-
 // log2 of the waves per workgroup: about four tiles per wave, 4..16 waves
 int pick_log_waves(int G)
 {
-    static const int forced = env_int("AWQ_GEMV_WAVES");
+    static const int forced = awq_knob("AWQ_GEMV_WAVES", 0);
     if (forced == 1 || forced == 2 || forced == 4 || forced == 8 || forced == 16)
         return forced == 1 ? 0 : forced == 2 ? 1 : forced == 4 ? 2 : forced == 8 ? 3 : 4;
     if (G >= 64) return 4;
@@ -316,7 +310,7 @@ int pick_log_waves(int G)
 // tiles per batch: the largest of 4, 2, 1 that divides G
 int pick_unroll(int G)
 {
-    static const int forced = env_int("AWQ_GEMV_UNROLL");
+    static const int forced = awq_knob("AWQ_GEMV_UNROLL", 0);
     if ((forced == 1 || forced == 2 || forced == 4) && G % forced == 0) return forced;
     return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
 }
@@ -332,12 +326,12 @@ int gemv_launch_one(dim3 grid, dim3 block, size_t lds, hipStream_t stream, const
                     int N, int K, int G, int logW, const half_t *res)
 {
     static AwqOncePerDevice once;
-    bool &raised = once.here();
-    if (lds > 64 * 1024 && !raised) {
+    std::atomic<bool> &raised = once.here();
+    if (lds > 64 * 1024 && !raised.load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_kernel<BITS, U, MS, PIPE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return AWQ_ERR_HIP;
-        raised = true;
+        raised.store(true, std::memory_order_relaxed);
     }
     gemv_kernel<BITS, U, MS, PIPE><<<grid, block, lds, stream>>>(x, qweight, scales, zeros, y, M, N, K, G, logW, res);
     return awq_launch_status();

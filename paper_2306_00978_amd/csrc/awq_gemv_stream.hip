@@ -662,12 +662,6 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
     }
 }
 
-int env_int(const char *name, int dflt)
-{
-    const char *e = getenv(name);
-    return e ? atoi(e) : dflt;
-}
-
 int ceil_log2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 }  // namespace
@@ -708,7 +702,7 @@ struct PairedRun {
     int lin, iters, count, load;
 };
 
-int g_last_plan = 0;             // diagnostic: 1 = one size of workgroup per linear, 2 = paired plan
+std::atomic<int> g_last_plan{0};   // diagnostic: 1 = one size of workgroup per linear, 2 = paired plan
 
 template <int BITS>
 bool plan_paired(const GemvProblem *problems, int count, const int *ksl_of, int W, GemvLaunch &L, int &wg_total)
@@ -843,12 +837,12 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
                        hipStream_t stream)
 {
     constexpr int STAGE_BYTES = Slot<BITS>::BYTES;
-    static const int f_logw = env_int("AWQ_GEMV_LOGW", -1);
-    static const int f_iters = env_int("AWQ_GEMV_ITERS", -1);
-    static const int f_ksl = env_int("AWQ_GEMV_KSL", -1);
-    static const int f_stages = env_int("AWQ_GEMV_STAGES", 2);
-    static const int f_slots = env_int("AWQ_GEMV_SLOTS", 1792);
-    static const int f_jobs = env_int("AWQ_GEMV_JOBS", -1);
+    static const int f_logw = awq_knob("AWQ_GEMV_LOGW", -1);
+    static const int f_iters = awq_knob("AWQ_GEMV_ITERS", -1);
+    static const int f_ksl = awq_knob("AWQ_GEMV_KSL", -1);
+    static const int f_stages = awq_knob("AWQ_GEMV_STAGES", 2);
+    static const int f_slots = awq_knob("AWQ_GEMV_SLOTS", 1792);
+    static const int f_jobs = awq_knob("AWQ_GEMV_JOBS", -1);
     if (count < 1 || count > (FUSED ? GEMV_MAX_FUSED : GEMV_MAX_PROBLEMS)) return AWQ_ERR_BAD_ARGUMENT;
 
     GemvArgs<FUSED> A{};          // the kernel fetches whole table rows: no uninitialised bytes in them
@@ -897,7 +891,7 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
     // is raised until it does not.
     const int wg_cap = lds * 2 > 160 * 1024 ? 256 : (1 << 30);
     int wg = 0;
-    static const int f_paired = env_int("AWQ_GEMV_PAIRED", 1);
+    static const int f_paired = awq_knob("AWQ_GEMV_PAIRED", 1);
     bool paired = false;
     if (!FUSED && logW == 2 && stages == 2 && f_paired && f_logw < 0 && f_iters < 0 && f_ksl < 0 &&
         f_jobs < 0 && f_slots == 1792 && count * 3 <= GEMV_MAX_PROBLEMS) {
@@ -908,7 +902,7 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
             wg = 0;
         }
     }
-    g_last_plan = paired ? 2 : 1;
+    g_last_plan.store(paired ? 2 : 1, std::memory_order_relaxed);
     for (int attempt = 0; attempt < 64 && !paired; ++attempt) {
         wg = 0;
         for (int i = 0; i < count; ++i) {
@@ -932,8 +926,8 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
         T *= 1.04;
     }
     static AwqOncePerDevice once;
-    bool &attr_set = once.here();
-    if (!attr_set) {
+    std::atomic<bool> &attr_set = once.here();
+    if (!attr_set.load(std::memory_order_relaxed)) {
         const int cap = 160 * 1024;
         const void *kernels[] = {reinterpret_cast<const void *>(gemv_stream_kernel<2, BITS, FUSED>),
                                  reinterpret_cast<const void *>(gemv_stream_kernel<3, BITS, FUSED>),
@@ -941,7 +935,7 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
         for (int k = 0; k < (FUSED ? 1 : 3); ++k)
             if (hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
                 return AWQ_ERR_HIP;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_relaxed);
     }
     if (lds > (size_t)160 * 1024) return AWQ_GEMV_STREAM_UNFIT;
     if (stages == 4 && !FUSED) gemv_stream_kernel<4, BITS, FUSED><<<dim3(wg), dim3(W * 64), lds, stream>>>(A);
@@ -970,5 +964,5 @@ int awq_gemv_stream_launch_fused(const GemvProblem *problems, const GemvFusedExt
 
 extern "C" int awq_last_grouped_plan(void)
 {
-    return g_last_plan;
+    return g_last_plan.load(std::memory_order_relaxed);
 }

@@ -79,8 +79,8 @@ __global__ __launch_bounds__(256) void apply_inv_scale_kernel(const uint4 *__res
 }
 
 // RMS normalisation with the 1/s factor of Eq. 4 folded in (Sec. 4.2: the operators of the
-// normalisation fused into a single kernel; Sec. 3.2: diag(s)^-1 X fused into the previous
-// operator).  One workgroup per row: sum of squares with 16-byte loads (the row is read a second
+// normalisation in one kernel; Sec. 3.2, Eq. 4: the diag(s)^-1 factor belongs to the producer
+// of x).  One workgroup per row: sum of squares with 16-byte loads (the row is read a second
 // time from cache for the output), wave shuffles and one pass through LDS, then
 // x * rsqrt(mean + eps) * gamma / s in fp32, rounded once to fp16.
 __global__ __launch_bounds__(256) void rmsnorm_inv_scale_kernel(const uint4 *__restrict__ x,

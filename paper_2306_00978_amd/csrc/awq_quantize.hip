@@ -17,21 +17,28 @@
 
 namespace {
 
+// clamp of a finite value (weights must be finite): one v_med3_f32
 __device__ __forceinline__ float clampf(float v, float lo, float hi)
 {
-    if (v < lo) v = lo;
-    if (v > hi) v = hi;
-    return v;
+    return __builtin_amdgcn_fmed3f(v, lo, hi);
 }
 
 // nibble position of element e inside a packed word: {0,4,1,5,2,6,3,7}
 __device__ __forceinline__ int nib_shift(int e) { return 4 * ((e >> 1) + 4 * (e & 1)); }
 
-// Correctly rounded n / d for a divisor shared by many numerators: the refinement of the
-// reciprocal (which depends on d only) is done once, the numerator-dependent tail is the
-// same Newton-residual sequence the compiler emits for an IEEE division, without the
-// range-scaling steps.  Valid when neither operand nor the quotient comes near the ends of the
-// fp32 range, which the caller checks per group (otherwise it divides with `/`).
+// rint(n / d) for a divisor d shared by many numerators, with the IEEE quotient deciding.
+//
+// The codes are rint(fl(n / d)) with fl the correctly rounded binary32 division (what the CPU side
+// computes).  A full IEEE division costs about ten instructions per weight and this kernel is
+// bound by instruction issue, so the quotient is first formed as q0 = fl(n * r) with r the
+// reciprocal of d refined once (r depends on d only).  With the hardware reciprocal within one ulp,
+// |r - 1/d| <= 2^-23 / d, so |q0 - n/d| <= |n/d| (2^-24 + 2^-23 + 2^-47) and, with the rounding of
+// the IEEE quotient itself, |q0 - fl(n/d)| < 2^-22 |n/d|: for |q0| < 32 that is below 2^-17.
+// rint(q0) can therefore differ from rint(fl(n/d)) only if q0 lies within 2^-17 of a half-integer;
+// `band` collects the smallest distance |fract(q0) - 1/2| over a lane's weights, and when any lane of
+// the wave comes within 2^-16 the whole tile is redone with the plain `/`.  (For |q0| >= 32 both
+// roundings end up clamped to the same end code, whatever their difference.)  About 6 % of the
+// tiles of a Gaussian matrix take the second pass.
 struct Reciprocal {
     float d, r;
 };
@@ -41,17 +48,16 @@ __device__ __forceinline__ Reciprocal make_reciprocal(float d)
     const float e0 = __builtin_fmaf(-d, r0, 1.0f);
     return {d, __builtin_fmaf(e0, r0, r0)};
 }
-__device__ __forceinline__ float divide(float n, const Reciprocal &k)
+constexpr float AWQ_TIE_BAND = 1.52587890625e-05f;          // 2^-16
+__device__ __forceinline__ float fast_rint_quotient(float n, const Reciprocal &k, float &band)
 {
     const float q0 = n * k.r;
-    const float e1 = __builtin_fmaf(-k.d, q0, n);
-    const float q1 = __builtin_fmaf(e1, k.r, q0);
-    const float e2 = __builtin_fmaf(-k.d, q1, n);
-    return __builtin_fmaf(e2, k.r, q1);
+    band = fminf(band, fabsf(__builtin_amdgcn_fractf(q0) - 0.5f));
+    return __builtin_rintf(q0);
 }
 
-// Range ratios of the clipping search (Sec. 3.2, "weight clipping to minimize the MSE error of
-// quantization").
+// Range ratios of the clipping search (Sec. 3.2, weight clipping; objective and grid not
+// specified there: per group, squared error of the weights or of the outputs on given rows).
 struct ClipRatios {
     float v[AWQ_CLIP_MAX_RATIOS];
     int n;
@@ -152,10 +158,6 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         mn = fminf(mn, __shfl_xor(mn, 32));
 
-        // scale is in [2^-14, 65504]; with |w'| below 1e18 the shared-reciprocal division is exact
-        // IEEE division.  Otherwise (never with real weights) the whole wave divides with `/`.
-        const bool tame = __all(fmaxf(fabsf(mx), fabsf(mn)) < 1.0e18f);
-
         int best = 0;
         if (CLIP) {
             double best_err = 0.0;
@@ -171,23 +173,25 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
                 const uint32_t sbits = __builtin_bit_cast(uint32_t, tscale);
                 const float down = __builtin_bit_cast(float, (254u - ((sbits >> 23) & 255u)) << 23);
                 half_t eh[4][8];
-                auto accumulate = [&](auto quotient) {
+                // q - zero = clamp(rint(w'/step), -zero, 15 - zero): the same integers as
+                // clamp(rint(w'/step) + zero, 0, 15) - zero
+                const float tlo = -tzero, thi = 15.0f - tzero;
+                auto accumulate = [&](auto rint_quotient) {
+                    err = 0.0;
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
-                            float q = __builtin_rintf(quotient(wp[j][e]));
-                            q = q + tzero;
-                            q = clampf(q, 0.0f, 15.0f);
-                            const float lv = q - tzero;
+                            const float lv = clampf(rint_quotient(wp[j][e]), tlo, thi);
                             const float dq = lv * tscale;
                             const float d = dq - wp[j][e];
                             if (ACT) eh[j][e] = (half_t)(d * down);
                             else err += (double)d * (double)d;
                         }
                 };
-                if (tame) accumulate([&](float n) { return divide(n, trc); });
-                else accumulate([&](float n) { return n / tscale; });
+                float tband = 1.0f;
+                accumulate([&](float n) { return fast_rint_quotient(n, trc, tband); });
+                if (__any(tband < AWQ_TIE_BAND)) accumulate([&](float n) { return __builtin_rintf(n / tscale); });
                 if (ACT) {
                     for (int tb = 0; tb < tblocks; ++tb) {
                         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -228,27 +232,29 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
         const float zero = clampf(__builtin_rintf(zr), 0.0f, 15.0f);
         const Reciprocal rc = make_reciprocal(scale);
 
-        // a word is assembled as two exact fp32 integers of 16 bits (four nibbles each)
+        // a word is assembled as two exact fp32 integers of 16 bits (four nibbles each): the sums
+        // of (q - zero) 16^i, with q - zero = clamp(rint(w'/step), -zero, 15 - zero) (the same
+        // integers as clamp(rint(w'/step) + zero, 0, 15) - zero), plus zero * 0x1111 at the end
         uint32_t words[4];
-        auto assemble = [&](auto quotient) {
+        const float klo = -zero, khi = 15.0f - zero, zfill = zero * 4369.0f;
+        auto assemble = [&](auto rint_quotient) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float lo = 0.0f, hi = 0.0f;
+                float lo = zfill, hi = zfill;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    float q = __builtin_rintf(quotient(wp[j][e]));
-                    q = q + zero;
-                    q = clampf(q, 0.0f, 15.0f);
+                    const float k = clampf(rint_quotient(wp[j][e]), klo, khi);
                     const int sh = nib_shift(e);            // 0,16,4,20,8,24,12,28
                     const float weight = (float)(1u << (sh & 15));
-                    if (sh < 16) lo = __builtin_fmaf(q, weight, lo);
-                    else hi = __builtin_fmaf(q, weight, hi);
+                    if (sh < 16) lo = __builtin_fmaf(k, weight, lo);
+                    else hi = __builtin_fmaf(k, weight, hi);
                 }
                 words[j] = (uint32_t)lo | ((uint32_t)hi << 16);
             }
         };
-        if (tame) assemble([&](float n) { return divide(n, rc); });
-        else assemble([&](float n) { return n / scale; });
+        float band = 1.0f;
+        assemble([&](float n) { return fast_rint_quotient(n, rc, band); });
+        if (__any(band < AWQ_TIE_BAND)) assemble([&](float n) { return __builtin_rintf(n / scale); });
         const int64_t tile = (int64_t)rb * G + g;
         qweight[tile * 64 + lane] = make_uint4(words[0], words[1], words[2], words[3]);
 

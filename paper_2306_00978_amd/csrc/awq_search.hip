@@ -1,6 +1,6 @@
 // awq_search_scale for gfx950: the grid search for the activation-aware scale.
 //
-// AWQ Sec. 3.2, "Searching to scale".  Eq. 4 asks for the per-input-channel scale s that
+// AWQ Sec. 3.2, the search for the scale.  Eq. 4 asks for the per-input-channel scale s that
 // minimises the output difference of one layer after quantization,
 //     L(s) = || Q(W diag(s)) (diag(s)^-1 X) - W X ||,
 // on calibration rows X cached for that layer; Eq. 5 restricts s to s_X^alpha (s_X = mean |X|

@@ -595,13 +595,17 @@ def test_config4_full_stack(awq):
     {"AWQ_GEMV_STREAM_SINGLE": "1"},
 ])
 def test_grouped_decode_under_planner_overrides(awq, overrides):
-    """The planner's constants can be overridden through the environment (read once per
-    process); every such plan must give the same results.  Runs the check in a child process."""
+    """In the tuning build of the library (libawq_mi355x_knobs.so, -DAWQ_TUNING_KNOBS) the planner's
+    constants can be overridden through the environment (read once per process); every such plan
+    must give the same results.  Runs the check in a child process that loads that build."""
     import os
     import subprocess
     import sys
+    from paper_2306_00978_amd import build as hip_build
+    assert os.path.exists(hip_build.LIB_KNOBS), "build the tuning library first (paper_2306_00978_amd.build)"
     env = dict(os.environ)
     env.update(overrides)
+    env["AWQ_MI355X_LIBRARY"] = hip_build.LIB_KNOBS
     child = os.path.join(os.path.dirname(os.path.abspath(__file__)), "child_grouped_decode.py")
     res = subprocess.run([sys.executable, child], env=env, capture_output=True, text=True, timeout=300)
     assert res.returncode == 0 and res.stdout.strip().endswith("OK"), res.stdout[-2000:] + res.stderr[-2000:]

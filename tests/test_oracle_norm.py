@@ -1,5 +1,5 @@
 """Pins for the oracle's RMS normalisation with the inverse scale folded in (AWQ Sec. 4.2 kernel
-fusion of the normalisation; Sec. 3.2: diag(s)^-1 X fused into the previous operator)."""
+fusion of the normalisation; Sec. 3.2, Eq. 4: the diag(s)^-1 factor belongs to the producer of x)."""
 import numpy as np
 
 import oracle
