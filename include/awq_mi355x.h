@@ -108,6 +108,25 @@ int awq_silu_mul(const void *gate_f16, const void *up_f16, int64_t n, void *out_
 int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, int64_t K, int group,
                       void *qweight, void *scales, void *zeros, void *stream);
 
+/* One matrix of awq_quantize_pack_multi: the arguments of awq_quantize_pack. */
+typedef struct awq_quantize_desc {
+    const void *W_f16;     /* [N,K] fp16 row-major, device */
+    const float *s;        /* [K] fp32, device, or NULL (= ones) */
+    int64_t N, K;
+    void *qweight;         /* device buffers of awq_packed_sizes(N, K) bytes, written */
+    void *scales;
+    void *zeros;
+} awq_quantize_desc;
+
+#define AWQ_QUANTIZE_MULTI_MAX 64
+
+/* The same computation as `count` calls of awq_quantize_pack (Sec. 3.2, Eq. 1-2; Sec. 4.2 packing),
+ * bit for bit, in one kernel launch per 16 matrices: quantizing a 4096 x 4096 matrix takes about
+ * as long as a launch, so a pass over a model's matrices (seven per decoder layer) runs faster
+ * grouped.  The matrices may differ in shape; outputs must not overlap.  `descs` is a HOST array
+ * of 1..AWQ_QUANTIZE_MULTI_MAX entries, read before the call returns. */
+int awq_quantize_pack_multi(const awq_quantize_desc *descs, int count, int group, void *stream);
+
 #define AWQ_CLIP_MAX_RATIOS 32
 #define AWQ_CLIP_MAX_ROWS 64
 

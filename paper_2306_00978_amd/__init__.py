@@ -40,6 +40,7 @@ EXPORTS = [
     "awq_packed_sizes_w2", "awq_quantize_pack_w2", "awq_unpack_w2", "awq_w2a16_linear",
     "awq_w2a16_linear_multi",
     "awq_last_grouped_plan", "awq_static_scratch_bytes", "awq_w4a16_linear_static",
+    "awq_quantize_pack_multi",
 ]
 MULTI_MAX = 56
 
@@ -51,6 +52,16 @@ class LinearDesc(ctypes.Structure):
                 ("y_f16", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64)]
 
 _lib = None
+
+
+class QuantizeDesc(ctypes.Structure):
+    """awq_quantize_desc of the C ABI."""
+    _fields_ = [("W_f16", ctypes.c_void_p), ("s", ctypes.c_void_p), ("N", ctypes.c_int64),
+                ("K", ctypes.c_int64), ("qweight", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("zeros", ctypes.c_void_p)]
+
+
+QUANTIZE_MULTI_MAX = 64
 
 
 class FusedDesc(ctypes.Structure):
@@ -129,6 +140,8 @@ def load() -> ctypes.CDLL:
     lib.awq_w3a16_linear_prefill.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
     lib.awq_last_grouped_plan.restype = i32
     lib.awq_last_grouped_plan.argtypes = []
+    lib.awq_quantize_pack_multi.restype = i32
+    lib.awq_quantize_pack_multi.argtypes = [ctypes.POINTER(QuantizeDesc), i32, i32, vp]
     lib.awq_static_scratch_bytes.restype = sz
     lib.awq_static_scratch_bytes.argtypes = []
     lib.awq_w4a16_linear_static.restype = i32
@@ -269,6 +282,51 @@ def prepare_quantize_pack(W: torch.Tensor, s: torch.Tensor | None, out, group: i
         if st != 0:
             raise AwqError(st, "awq_quantize_pack")
     return call
+
+
+def prepare_quantize_pack_multi(matrices, group: int = GROUP):
+    """Marshal one awq_quantize_pack_multi call.  `matrices` is a list of (W, s or None,
+    (qweight, scales, zeros)); returns a zero-argument callable that enqueues the call on the
+    then-current stream.  Every tensor must stay alive and in place."""
+    if not 1 <= len(matrices) <= QUANTIZE_MULTI_MAX:
+        raise ValueError(f"1..{QUANTIZE_MULTI_MAX} matrices per call")
+    descs = (QuantizeDesc * len(matrices))()
+    for i, (W, s, out) in enumerate(matrices):
+        _dev(W, torch.float16, "W")
+        N, K = W.shape
+        if s is not None:
+            _dev(s, torch.float32, "s")
+            if s.numel() != K:
+                raise ValueError("s must have K elements")
+        qb, sb, zb = awq_packed_sizes(N, K, group)
+        qweight, scales, zeros = out
+        if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
+                or zeros.numel() * zeros.element_size() < zb:
+            raise ValueError("output buffers are too small")
+        descs[i] = QuantizeDesc(W.data_ptr(), _ptr(s), N, K, qweight.data_ptr(), scales.data_ptr(),
+                                zeros.data_ptr())
+    fn = load().awq_quantize_pack_multi
+    count = len(matrices)
+    keep = list(matrices)
+
+    def call(_keep=keep):
+        st = fn(descs, count, group, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_quantize_pack_multi")
+    return call
+
+
+def awq_quantize_pack_multi(matrices, group: int = GROUP):
+    """[(W, s or None), ...] -> [(qweight, scales, zeros), ...], all in one call of the library."""
+    full = []
+    for W, s in matrices:
+        N, K = W.shape
+        qb, sb, zb = awq_packed_sizes(N, K, group)
+        full.append((W, s, (torch.empty(qb, dtype=torch.uint8, device=W.device),
+                            torch.empty(sb // 2, dtype=torch.float16, device=W.device),
+                            torch.empty(zb, dtype=torch.uint8, device=W.device))))
+    prepare_quantize_pack_multi(full, group)()
+    return [m[2] for m in full]
 
 
 def awq_unpack(qweight, scales, zeros, N: int, K: int, group: int = GROUP):

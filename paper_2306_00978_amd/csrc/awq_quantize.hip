@@ -15,6 +15,8 @@
 // correctly rounded division and round-half-even, bit for bit.
 #include "awq_common.h"
 
+#include <algorithm>
+
 namespace {
 
 // clamp of a finite value (weights must be finite): one v_med3_f32
@@ -34,11 +36,12 @@ __device__ __forceinline__ int nib_shift(int e) { return 4 * ((e >> 1) + 4 * (e 
 // reciprocal of d refined once (r depends on d only).  With the hardware reciprocal within one ulp,
 // |r - 1/d| <= 2^-23 / d, so |q0 - n/d| <= |n/d| (2^-24 + 2^-23 + 2^-47) and, with the rounding of
 // the IEEE quotient itself, |q0 - fl(n/d)| < 2^-22 |n/d|: for |q0| < 32 that is below 2^-17.
-// rint(q0) can therefore differ from rint(fl(n/d)) only if q0 lies within 2^-17 of a half-integer;
-// `band` collects the smallest distance |fract(q0) - 1/2| over a lane's weights, and when any lane of
-// the wave comes within 2^-16 the whole tile is redone with the plain `/`.  (For |q0| >= 32 both
-// roundings end up clamped to the same end code, whatever their difference.)  About 6 % of the
-// tiles of a Gaussian matrix take the second pass.
+// rint(q0) can therefore differ from rint(fl(n/d)) only if q0 lies within 2^-17 of a half-integer,
+// i.e. if |q0 - rint(q0)| > 1/2 - 2^-17; `off` collects the largest |q0 - rint(q0)| over a lane's
+// weights (the difference is exact), and when any lane of the wave exceeds 1/2 - 2^-16 the whole
+// tile is redone with the plain `/`.  (For |q0| >= 32 both roundings end up clamped to the same end
+// code, whatever their difference.)  About 6 % of the tiles of a Gaussian matrix take the second
+// pass.  tests/quotient_filter_check.c proves the claim exhaustively on the CPU.
 struct Reciprocal {
     float d, r;
 };
@@ -49,11 +52,23 @@ __device__ __forceinline__ Reciprocal make_reciprocal(float d)
     return {d, __builtin_fmaf(e0, r0, r0)};
 }
 constexpr float AWQ_TIE_BAND = 1.52587890625e-05f;          // 2^-16
-__device__ __forceinline__ float fast_rint_quotient(float n, const Reciprocal &k, float &band)
+__device__ __forceinline__ float fast_rint_quotient(float n, const Reciprocal &k, float &off)
 {
     const float q0 = n * k.r;
-    band = fminf(band, fabsf(__builtin_amdgcn_fractf(q0) - 0.5f));
-    return __builtin_rintf(q0);
+    const float kq = __builtin_rintf(q0);
+    off = fmaxf(off, fabsf(q0 - kq));
+    return kq;
+}
+__device__ __forceinline__ bool near_tie(float off) { return off > 0.5f - AWQ_TIE_BAND; }
+
+// fl(fp32(h) * s) for the two halves of a packed pair: the conversion is exact, so the mixed-
+// precision multiply-add with a zero addend rounds once, exactly like convert-then-multiply
+__device__ __forceinline__ void scaled_pair(uint32_t h2, float s_lo, float s_hi, float &lo, float &hi)
+{
+    asm("v_fma_mix_f32 %0, %2, %3, 0 op_sel_hi:[1,0,0]\n\t"
+        "v_fma_mix_f32 %1, %2, %4, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
+        : "=&v"(lo), "=&v"(hi)
+        : "v"(h2), "v"(s_lo), "v"(s_hi));
 }
 
 // Range ratios of the clipping search (Sec. 3.2, weight clipping; objective and grid not
@@ -78,21 +93,53 @@ struct ClipRatios {
 // range, against the rows of xs held in registers as A operands for the wave's whole life (its
 // group never changes).  Lane l receives the sums of its own row for tokens 4 (l/16) + 0..3 of
 // every block of 16 rows; squares are added in fp64 and combined over the four lanes of the row.
+// One matrix of a launch.  A launch quantizes up to QUANT_MAX_PROBLEMS matrices: its waves are
+// numbered through all of them (`unit_begin` = first wave of a matrix), so that a pass over many
+// small matrices (one decoder layer is seven) pays one launch and one run-out instead of one each.
+struct QuantProblem {
+    const uint4 *W;        // [N, K/8] runs of eight fp16
+    const float4 *s;       // [K/4] or nullptr
+    uint4 *qweight;
+    uint16_t *scales;
+    uint8_t *zeros;
+    uint8_t *choice;       // CLIP: [N, G] or nullptr
+    const uint4 *xs;       // ACT: [T, K/8]
+    int G, NRB, rb_per_wave, unit_begin;
+    int T, pad;
+};
+constexpr int QUANT_MAX_PROBLEMS = 16;
+struct QuantArgs {
+    QuantProblem p[QUANT_MAX_PROBLEMS];
+    int count, num_units;
+};
+
+// Waves per SIMD the plain kernel is compiled for.  It needs about 130 registers, i.e. three waves
+// per SIMD; forced into 128 for a fourth wave it spills four values per tile and the 224-matrix
+// pass was measured slower (4.4 against 4.8 TB/s), so no minimum is requested.
+#ifndef AWQ_QUANT_MIN_WAVES
+#define AWQ_QUANT_MIN_WAVES 1
+#endif
+
 template <bool CLIP, bool ACT>
-__global__ __launch_bounds__(256) void quantize_pack_kernel(
-    const uint4 *__restrict__ W,   // [N, K/8] runs of eight fp16
-    const float4 *__restrict__ s,  // [K/4] or nullptr
-    uint4 *__restrict__ qweight, uint16_t *__restrict__ scales, uint8_t *__restrict__ zeros,
-    int G, int NRB, int rb_per_wave, int num_units, ClipRatios ratios, uint8_t *__restrict__ choice,
-    const uint4 *__restrict__ xs, int T)
+__global__ __launch_bounds__(256, CLIP ? 1 : AWQ_QUANT_MIN_WAVES) void quantize_pack_kernel(const QuantArgs A, const ClipRatios ratios)
 {
-    // every argument fetched in one round (otherwise: one scalar-cache miss per first use)
-    asm volatile("" ::"s"(W), "s"(s), "s"(qweight), "s"(scales), "s"(zeros), "s"(G), "s"(NRB), "s"(rb_per_wave),
-                 "s"(num_units), "s"(choice), "s"(xs), "s"(T));
     const int lane = threadIdx.x & 63;
-    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (unit >= num_units) return;                 // whole wave leaves together
-    const int g = unit % G, part = unit / G;
+    const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
+    if (unit >= A.num_units) return;               // whole wave leaves together
+    int pi = 0;
+    for (int i = 1; i < A.count; ++i)
+        if (unit >= A.p[i].unit_begin) pi = i;
+    const QuantProblem &P = A.p[pi];
+    const uint4 *__restrict__ W = P.W;
+    const float4 *__restrict__ s = P.s;
+    uint4 *__restrict__ qweight = P.qweight;
+    uint16_t *__restrict__ scales = P.scales;
+    uint8_t *__restrict__ zeros = P.zeros;
+    uint8_t *__restrict__ choice = P.choice;
+    const uint4 *__restrict__ xs = P.xs;
+    const int G = P.G, NRB = P.NRB, rb_per_wave = P.rb_per_wave, T = P.T;
+    const int local = unit - P.unit_begin;
+    const int g = local % G, part = local / G;
     const int rb0 = part * rb_per_wave;
     const int rb1 = min(NRB, rb0 + rb_per_wave);
     const int r = lane & 15, c = lane >> 4;
@@ -140,9 +187,9 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
         float wp[4][8];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const half_t *h = reinterpret_cast<const half_t *>(&cur[j]);
+            const uint32_t h2[4] = {cur[j].x, cur[j].y, cur[j].z, cur[j].w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) wp[j][e] = (float)h[e] * sv[j][e];
+            for (int e = 0; e < 8; e += 2) scaled_pair(h2[e >> 1], sv[j][e], sv[j][e + 1], wp[j][e], wp[j][e + 1]);
         }
 
         float mx = wp[0][0], mn = wp[0][0];
@@ -189,9 +236,9 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
                             else err += (double)d * (double)d;
                         }
                 };
-                float tband = 1.0f;
-                accumulate([&](float n) { return fast_rint_quotient(n, trc, tband); });
-                if (__any(tband < AWQ_TIE_BAND)) accumulate([&](float n) { return __builtin_rintf(n / tscale); });
+                float toff = 0.0f;
+                accumulate([&](float n) { return fast_rint_quotient(n, trc, toff); });
+                if (__any(near_tie(toff))) accumulate([&](float n) { return __builtin_rintf(n / tscale); });
                 if (ACT) {
                     for (int tb = 0; tb < tblocks; ++tb) {
                         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -252,9 +299,9 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
                 words[j] = (uint32_t)lo | ((uint32_t)hi << 16);
             }
         };
-        float band = 1.0f;
-        assemble([&](float n) { return fast_rint_quotient(n, rc, band); });
-        if (__any(band < AWQ_TIE_BAND)) assemble([&](float n) { return __builtin_rintf(n / scale); });
+        float off = 0.0f;
+        assemble([&](float n) { return fast_rint_quotient(n, rc, off); });
+        if (__any(near_tie(off))) assemble([&](float n) { return __builtin_rintf(n / scale); });
         const int64_t tile = (int64_t)rb * G + g;
         qweight[tile * 64 + lane] = make_uint4(words[0], words[1], words[2], words[3]);
 
@@ -309,38 +356,71 @@ __global__ __launch_bounds__(256) void unpack_kernel(
 
 namespace {
 
-int quantize_launch(const void *W_f16, const float *s, int64_t N, int64_t K, int group, void *qweight,
-                    void *scales, void *zeros, const ClipRatios *ratios, uint8_t *choice,
-                    const void *xs_f16, int64_t T, void *stream)
+// One matrix as the host sees it.
+struct QuantJob {
+    const void *W;
+    const float *s;
+    int64_t N, K;
+    void *qweight, *scales, *zeros;
+    uint8_t *choice;
+    const void *xs;
+    int64_t T;
+};
+
+int quantize_check(const QuantJob &j, int group)
 {
-    if (!W_f16 || !qweight || !scales || !zeros) return AWQ_ERR_NULL_POINTER;
-    int st = awq_check_weight_shape(N, K, group);
+    if (!j.W || !j.qweight || !j.scales || !j.zeros) return AWQ_ERR_NULL_POINTER;
+    int st = awq_check_weight_shape(j.N, j.K, group);
     if (st != AWQ_OK) return st;
-    if (!awq_aligned16(W_f16) || !awq_aligned16(qweight) || !awq_aligned16(scales) ||
-        !awq_aligned16(zeros) || (s && !awq_aligned16(s)))
+    if (!awq_aligned16(j.W) || !awq_aligned16(j.qweight) || !awq_aligned16(j.scales) ||
+        !awq_aligned16(j.zeros) || (j.s && !awq_aligned16(j.s)))
         return AWQ_ERR_MISALIGNED;
-    const int G = (int)(K / AWQ_GROUP);
-    const int NRB = (int)(N / 16);
-    // about 16 waves per CU in flight; a wave keeps its group and walks down the row blocks
-    int parts = (4096 + G - 1) / G;
-    parts = parts < 1 ? 1 : (parts > NRB ? NRB : parts);
-    const int rb_per_wave = (NRB + parts - 1) / parts;
-    parts = (NRB + rb_per_wave - 1) / rb_per_wave;
-    const int num_units = parts * G;
-    const int blocks = (num_units + 3) / 4;
-    if (ratios && xs_f16)
-        quantize_pack_kernel<true, true><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
-            (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
-            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, *ratios, choice, (const uint4 *)xs_f16, (int)T);
-    else if (ratios)
-        quantize_pack_kernel<true, false><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
-            (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
-            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, *ratios, choice, nullptr, 0);
-    else
-        quantize_pack_kernel<false, false><<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(
-            (const uint4 *)W_f16, (const float4 *)s, (uint4 *)qweight, (uint16_t *)scales,
-            (uint8_t *)zeros, G, NRB, rb_per_wave, num_units, ClipRatios{}, nullptr, nullptr, 0);
-    return awq_launch_status();
+    return AWQ_OK;
+}
+
+// Launches for `count` validated matrices, QUANT_MAX_PROBLEMS per launch.  A wave keeps one group
+// and walks down `rb_per_wave` row blocks; that number is chosen so that the waves of a launch
+// about fill the chip once (three waves per SIMD, the kernel's register budget): more waves
+// would queue behind the resident ones as a second, nearly empty round.
+int quantize_launch(const QuantJob *jobs, int count, const ClipRatios *ratios, hipStream_t stream)
+{
+    const int RESIDENT_WAVES = 256 * 4 * (ratios ? 3 : AWQ_QUANT_MIN_WAVES == 4 ? 4 : 3);
+    for (int first = 0; first < count; first += QUANT_MAX_PROBLEMS) {
+        const int n = std::min(QUANT_MAX_PROBLEMS, count - first);
+        int64_t tiles = 0;
+        for (int i = 0; i < n; ++i) tiles += (jobs[first + i].N / 16) * (jobs[first + i].K / AWQ_GROUP);
+        const int64_t per_wave = std::max<int64_t>(1, (tiles + RESIDENT_WAVES - 1) / RESIDENT_WAVES);
+        QuantArgs A = {};
+        int units = 0;
+        bool act = false;
+        for (int i = 0; i < n; ++i) {
+            const QuantJob &j = jobs[first + i];
+            QuantProblem &P = A.p[i];
+            P.W = (const uint4 *)j.W;
+            P.s = (const float4 *)j.s;
+            P.qweight = (uint4 *)j.qweight;
+            P.scales = (uint16_t *)j.scales;
+            P.zeros = (uint8_t *)j.zeros;
+            P.choice = j.choice;
+            P.xs = (const uint4 *)j.xs;
+            P.T = (int)j.T;
+            P.G = (int)(j.K / AWQ_GROUP);
+            P.NRB = (int)(j.N / 16);
+            P.rb_per_wave = (int)std::min<int64_t>(per_wave, P.NRB);
+            P.unit_begin = units;
+            units += ((P.NRB + P.rb_per_wave - 1) / P.rb_per_wave) * P.G;
+            act = act || j.xs;
+        }
+        A.count = n;
+        A.num_units = units;
+        const dim3 grid((unsigned)((units + 3) / 4)), block(256);
+        if (ratios && act) quantize_pack_kernel<true, true><<<grid, block, 0, stream>>>(A, *ratios);
+        else if (ratios) quantize_pack_kernel<true, false><<<grid, block, 0, stream>>>(A, *ratios);
+        else quantize_pack_kernel<false, false><<<grid, block, 0, stream>>>(A, ClipRatios{});
+        const int st = awq_launch_status();
+        if (st != AWQ_OK) return st;
+    }
+    return AWQ_OK;
 }
 
 }  // namespace
@@ -349,8 +429,23 @@ extern "C" int awq_quantize_pack(const void *W_f16, const float *s, int64_t N, i
                                  int group, void *qweight, void *scales, void *zeros,
                                  void *stream)
 {
-    return quantize_launch(W_f16, s, N, K, group, qweight, scales, zeros, nullptr, nullptr, nullptr, 0,
-                           stream);
+    const QuantJob j = {W_f16, s, N, K, qweight, scales, zeros, nullptr, nullptr, 0};
+    const int st = quantize_check(j, group);
+    return st != AWQ_OK ? st : quantize_launch(&j, 1, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int awq_quantize_pack_multi(const awq_quantize_desc *descs, int count, int group, void *stream)
+{
+    if (!descs) return AWQ_ERR_NULL_POINTER;
+    if (count < 1 || count > AWQ_QUANTIZE_MULTI_MAX) return AWQ_ERR_BAD_ARGUMENT;
+    QuantJob jobs[AWQ_QUANTIZE_MULTI_MAX];
+    for (int i = 0; i < count; ++i) {
+        jobs[i] = {descs[i].W_f16, descs[i].s, descs[i].N, descs[i].K, descs[i].qweight, descs[i].scales,
+                   descs[i].zeros, nullptr, nullptr, 0};
+        const int st = quantize_check(jobs[i], group);
+        if (st != AWQ_OK) return st;
+    }
+    return quantize_launch(jobs, count, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int awq_quantize_pack_clip(const void *W_f16, const float *s, int64_t N, int64_t K,
@@ -368,7 +463,9 @@ extern "C" int awq_quantize_pack_clip(const void *W_f16, const float *s, int64_t
         if (!(ratios[i] > 0.0f && ratios[i] <= 1.0f)) return AWQ_ERR_BAD_ARGUMENT;
         r.v[i] = ratios[i];
     }
-    return quantize_launch(W_f16, s, N, K, group, qweight, scales, zeros, &r, choice, xs_f16, T, stream);
+    const QuantJob j = {W_f16, s, N, K, qweight, scales, zeros, choice, xs_f16, T};
+    const int st = quantize_check(j, group);
+    return st != AWQ_OK ? st : quantize_launch(&j, 1, &r, (hipStream_t)stream);
 }
 
 extern "C" int awq_unpack(const void *qweight, const void *scales, const void *zeros,

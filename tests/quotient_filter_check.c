@@ -5,7 +5,7 @@
  * correctly rounded binary32 division and d the group's step, a positive normal binary16 value.
  * The kernel forms q0 = fl(n * r), r = fma(fma(-d, r0, 1), r0, r0), r0 the hardware reciprocal of
  * d (within one ulp of 1/d), and keeps rint(q0) unless q0 lies within BAND = 2^-16 of a
- * half-integer, in which case it divides properly.  Claim checked here: for EVERY step d, every r0
+ * half-integer (|q0 - rint(q0)| > 1/2 - BAND), in which case it divides properly.  Claim checked here: for EVERY step d, every r0
  * within one ulp of the correctly rounded reciprocal, every half-integer h = k + 1/2 with
  * |h| < 34 and every binary32 numerator within WINDOW ulps of h * d (the only numerators whose
  * rounding can be in doubt, plus a margin), whenever q0 is outside the band, rint(q0) equals
@@ -57,9 +57,9 @@ int main(void)
                     for (int w = 0; w < WINDOW; ++w) n = nextafterf(n, -INFINITY);
                     for (int w = -WINDOW; w <= WINDOW; ++w, n = nextafterf(n, INFINITY)) {
                         const float q0 = n * r, qe = n / d;
-                        const float dist = fabsf((q0 - floorf(q0)) - 0.5f);
+                        const float off = fabsf(q0 - rintf(q0));        /* exact; what the kernel tracks */
                         ++checked;
-                        if (dist < BAND) { ++in_band; continue; }   /* the kernel divides properly */
+                        if (off > 0.5f - BAND) { ++in_band; continue; } /* the kernel divides properly */
                         if (fabsf(q0) < 32.0f && rintf(q0) != rintf(qe)) {
                             if (bad++ < 10)
                                 printf("MISS d=%a r0=%a n=%a q0=%a qe=%a\n", d, cand[c], n, q0, qe);

@@ -126,6 +126,24 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert f(descs(2), 2, 1, 64, None, 0, None) == -3
     assert f(descs(2, x_f16=odd), 2, 1, 128, None, 0, None) == -4
 
+    def qdescs(n, **kw):
+        arr = (awq.QuantizeDesc * max(n, 1))()
+        for i in range(n):
+            d = dict(W_f16=ok, s=None, N=16, K=128, qweight=ok, scales=ok, zeros=ok)
+            d.update(kw)
+            arr[i] = awq.QuantizeDesc(**d)
+        return arr
+    qm = lib.awq_quantize_pack_multi
+    assert qm(None, 1, 128, None) == -1
+    assert qm(qdescs(1), 0, 128, None) == -7
+    assert qm(qdescs(1), awq.QUANTIZE_MULTI_MAX + 1, 128, None) == -7
+    assert qm(qdescs(3, zeros=None), 3, 128, None) == -1
+    assert qm(qdescs(3, K=192), 3, 128, None) == -2
+    assert qm(qdescs(3, N=24), 3, 128, None) == -2
+    assert qm(qdescs(3), 3, 64, None) == -3
+    assert qm(qdescs(3, s=odd), 3, 128, None) == -4
+    assert qm(qdescs(3, W_f16=odd), 3, 128, None) == -4
+
     c = lib.awq_quantize_pack_clip
     rat = (ctypes.c_float * 3)(1.0, 0.9, 0.8)
     Pq = ctypes.c_void_p

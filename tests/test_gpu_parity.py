@@ -145,6 +145,43 @@ def test_quantize_near_ties_and_wide_ranges(awq):
     assert_quantize_bit_exact(awq, W, s_huge)
 
 
+def test_quantize_pack_multi_equals_the_oracle_on_every_matrix(awq):
+    """awq_quantize_pack_multi: matrices of different shapes in one call (more than one launch's
+    worth: 19 matrices = 16 + 3), with and without s, ragged group counts, one matrix much larger
+    than the rest -- every packed array bit for bit the oracle's, and nothing written around them."""
+    import torch
+    import oracle
+    g = np.random.default_rng(4242)
+    shapes = [(64, 512), (16, 128), (176, 1408), (1024, 4096), (48, 384), (320, 256), (16, 4096)] * 3
+    shapes = shapes[:19]
+    mats, refs, outs, guards = [], [], [], []
+    for i, (N, K) in enumerate(shapes):
+        W = (g.standard_normal((N, K)) * 0.02).astype(np.float16)
+        s = None if i % 3 == 2 else g.uniform(0.3, 5.0, size=K).astype(np.float32)
+        codes, scales, zeros = oracle.quantize(W, s)
+        refs.append(oracle.pack(codes, scales, zeros))
+        bufs = []
+        for nb, dt in zip(awq.awq_packed_sizes(N, K), (torch.uint8, torch.float16, torch.uint8)):
+            pad = 256 // (2 if dt == torch.float16 else 1)
+            whole = torch.full((nb // (2 if dt == torch.float16 else 1) + 2 * pad,), 7, dtype=dt, device="cuda")
+            guards.append((whole, pad))
+            bufs.append(whole[pad:whole.numel() - pad])
+        outs.append(tuple(bufs))
+        mats.append((dev(W), None if s is None else dev(s), outs[-1]))
+    awq.prepare_quantize_pack_multi(mats)()
+    torch.cuda.synchronize()
+    for i, ((q, sc, zp), (q_ref, s_ref, z_ref)) in enumerate(zip(outs, refs)):
+        assert np.array_equal(host(q), q_ref), f"matrix {i}: codes"
+        assert np.array_equal(host(sc).view(np.uint16), s_ref), f"matrix {i}: steps"
+        assert np.array_equal(host(zp), z_ref), f"matrix {i}: zero points"
+    for whole, pad in guards:
+        assert bool((whole[:pad] == 7).all()) and bool((whole[whole.numel() - pad:] == 7).all())
+    # the single call is the one-matrix case of the same launch
+    W, s, _ = mats[3]
+    q1, s1, z1 = awq.awq_quantize_pack(W, s)
+    assert torch.equal(q1, outs[3][0]) and torch.equal(s1.view(torch.int16), outs[3][1].view(torch.int16))
+
+
 CONFIG_SHAPES = [
     # (N, K, sigma, cfg)
     (4096, 4096, 0.02, 1), (11008, 4096, 0.02, 1), (4096, 11008, 0.02, 1),
