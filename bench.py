@@ -411,6 +411,41 @@ def main():
             "launches_per_step": n, "us_per_layer": round(e * 1e3 / L, 2),
             "GB/s": gbs(bytes_step, e), "pct_of_hbm_peak": pct(gbs(bytes_step, e))}
 
+        # the same four stages in ONE launch (awq_w4a16_linear_chain), now with real data dependences:
+        # o reads v's output, gate and up read o's, down reads gate's
+        ysc = outputs(1)
+        sync = awq.chain_sync()
+
+        def chain_for(l):
+            w = layers[l]
+            def lin(p, x):
+                return dict(x=x, qweight=w[p][0], scales=w[p][1], zeros=w[p][2], y=ysc[p], N=shapes[p][1])
+            x0 = x_by_k[4096][:1]
+            return awq.prepare_linear_chain([[lin(0, x0), lin(1, x0), lin(2, x0)], [lin(3, ysc[2])],
+                                             [lin(4, ysc[3]), lin(5, ysc[3])], [lin(6, ysc[4])]], sync)
+        chains = [chain_for(l) for l in range(L)]
+        for c in chains:
+            c()
+        torch.cuda.synchronize()
+        assert int(sync.cpu().abs().sum()) == 0, "a chained launch gave up"
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(mwarm):
+            for c in chains:
+                c()
+        e0.record()
+        for _ in range(msteps):
+            for c in chains:
+                c()
+        e1.record()
+        torch.cuda.synchronize()
+        ech = e0.elapsed_time(e1) / msteps
+        assert int(sync.cpu().abs().sum()) == 0, "a chained launch gave up"
+        result["config"]["dependent_chain_mode"] = {
+            "what": "awq_w4a16_linear_chain: Q,K,V -> o -> gate,up -> down with their data dependences in ONE "
+                    "launch per layer (resident workgroups, weights of the next stage requested before the wait)",
+            "launches_per_step": L, "us_per_layer": round(ech * 1e3 / L, 2),
+            "GB/s": gbs(bytes_step, ech), "pct_of_hbm_peak": pct(gbs(bytes_step, ech))}
+
         # the layers of this benchmark do not depend on each other (configs[1] and configs[4] model
         # no dependence): issued alternately on two streams of equal priority, the run-out of one
         # launch overlaps the start of the next.  Whole-job throughput only: two launches share

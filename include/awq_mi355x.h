@@ -264,6 +264,40 @@ int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int count, int64_t
                                  void *stream);
 int awq_w4a16_linear_fused_fits(int64_t N, int64_t K, int64_t M, int group);
 
+/* Sec. 4.2 (kernel fusion; the generation stage is memory-bound and its kernels are as short as a
+ * launch): the linears of a decode step in the order their data dependences impose, in ONE launch.
+ * A chain is 1..AWQ_CHAIN_MAX_STAGES stages; a stage is a list of 1..AWQ_CHAIN_MAX_LINEARS linears
+ * that do not depend on each other (described as for awq_w4a16_linear_fused_multi: optional
+ * normalisation or column scale in front, optional residual behind); a linear of stage s may read,
+ * as x or as residual, anything a linear of a stage before s writes.  Example: {o (+residual, in
+ * place into the hidden state)} -> {gate, up (RMS normalisation of that hidden state in front)}.
+ * The results obey the tolerance of the separate calls (they equal those of
+ * awq_w4a16_linear_fused_multi on the same stage wherever that call runs the streaming kernel); a
+ * given call is deterministic.
+ *   How: every workgroup of the launch is resident; one that has finished its share of a stage
+ *   requests its first weights of the next stage at once (they do not depend on the stage) and
+ *   then waits, for a bounded number of polls, until all workgroups have finished the stage.
+ *   sync: AWQ_CHAIN_SYNC_BYTES of device memory, 16-byte aligned, ZERO before the first use; a
+ *     call that ends normally leaves it zero again, so consecutive calls on one stream (and
+ *     replays of a captured graph) can share it.  Calls that may overlap need one each.
+ *   spin_limit: polls a workgroup spends on one wait before it gives up (0 = default, some
+ *     seconds).  A wait can only run out if the launch's workgroups are not all resident, i.e. if
+ *     another kernel occupies the GPU at the same time; then, or when sync was not zero, word 0 of
+ *     sync is set to a non-zero value, every workgroup leaves, the outputs are undefined and sync
+ *     must be zeroed again.  The launch always ends.
+ *   M <= 16; every linear must fit the streaming decode kernel (awq_w4a16_linear_fused_fits),
+ *   AWQ_ERR_BAD_SHAPE otherwise, also when a stage would need more workgroups than the GPU holds
+ *   at once.  `stages` and the arrays it points to are HOST memory, read before the call returns. */
+#define AWQ_CHAIN_MAX_STAGES 4
+#define AWQ_CHAIN_MAX_LINEARS 10
+#define AWQ_CHAIN_SYNC_BYTES 8192
+typedef struct awq_chain_stage {
+    const awq_fused_desc *descs;
+    int count;
+} awq_chain_stage;
+int awq_w4a16_linear_chain(const awq_chain_stage *stages, int n_stages, int64_t M, int group, void *sync,
+                           int spin_limit, void *stream);
+
 /* Diagnostic: how the last grouped decode launch of this process (awq_w4a16_linear_multi,
  * awq_w3a16_linear_multi, awq_w4a16_linear_fused_multi through the streaming kernel) laid out its
  * workgroups: 0 = none yet, 1 = one size of workgroup per linear, 2 = two sizes per linear, paired

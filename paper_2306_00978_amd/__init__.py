@@ -40,7 +40,7 @@ EXPORTS = [
     "awq_packed_sizes_w2", "awq_quantize_pack_w2", "awq_unpack_w2", "awq_w2a16_linear",
     "awq_w2a16_linear_multi",
     "awq_last_grouped_plan", "awq_static_scratch_bytes", "awq_w4a16_linear_static",
-    "awq_quantize_pack_multi",
+    "awq_quantize_pack_multi", "awq_w4a16_linear_chain",
 ]
 MULTI_MAX = 56
 
@@ -142,6 +142,8 @@ def load() -> ctypes.CDLL:
     lib.awq_last_grouped_plan.argtypes = []
     lib.awq_quantize_pack_multi.restype = i32
     lib.awq_quantize_pack_multi.argtypes = [ctypes.POINTER(QuantizeDesc), i32, i32, vp]
+    lib.awq_w4a16_linear_chain.restype = i32
+    lib.awq_w4a16_linear_chain.argtypes = [ctypes.c_void_p, i32, i64, i32, vp, i32, vp]
     lib.awq_static_scratch_bytes.restype = sz
     lib.awq_static_scratch_bytes.argtypes = []
     lib.awq_w4a16_linear_static.restype = i32
@@ -805,16 +807,9 @@ def awq_silu_mul(gate: torch.Tensor, up: torch.Tensor, out: torch.Tensor | None 
     return out
 
 
-def prepare_linear_fused_multi(linears, group: int = GROUP):
-    """Marshal one fused grouped decode call.  `linears` is a list of dicts with the keys
-    x, qweight, scales, zeros, y, N and optionally norm (fp16 [K] factors: the linear then runs on
-    the RMS-normalised x times these) with eps, or scale (fp16 [K]: the linear runs on x times
-    these), and residual (fp16 [M,N], added to the output; may be y).
-    Returns a zero-argument callable that enqueues ONE awq_w4a16_linear_fused_multi."""
-    if not 1 <= len(linears) <= FUSED_MAX:
-        raise ValueError(f"1..{FUSED_MAX} linears per fused call")
+def _fused_descs(linears, group, M=None):
+    """FusedDesc array of a list of dicts (see prepare_linear_fused_multi); returns (descs, M)."""
     descs = (FusedDesc * len(linears))()
-    M = None
     for i, l in enumerate(linears):
         x, y, N = l["x"], l["y"], l["N"]
         _dev(x, torch.float16, "x")
@@ -847,6 +842,18 @@ def prepare_linear_fused_multi(linears, group: int = GROUP):
                              res.data_ptr() if res is not None else None,
                              float(l.get("eps", 1e-5)),
                              PRE_RMSNORM if norm is not None else (PRE_SCALE if scale is not None else PRE_NONE))
+    return descs, M
+
+
+def prepare_linear_fused_multi(linears, group: int = GROUP):
+    """Marshal one fused grouped decode call.  `linears` is a list of dicts with the keys
+    x, qweight, scales, zeros, y, N and optionally norm (fp16 [K] factors: the linear then runs on
+    the RMS-normalised x times these) with eps, or scale (fp16 [K]: the linear runs on x times
+    these), and residual (fp16 [M,N], added to the output; may be y).
+    Returns a zero-argument callable that enqueues ONE awq_w4a16_linear_fused_multi."""
+    if not 1 <= len(linears) <= FUSED_MAX:
+        raise ValueError(f"1..{FUSED_MAX} linears per fused call")
+    descs, M = _fused_descs(linears, group)
     fn = load().awq_w4a16_linear_fused_multi
     count = len(linears)
     keep = list(linears)
@@ -855,6 +862,48 @@ def prepare_linear_fused_multi(linears, group: int = GROUP):
         st = fn(descs, count, M, group, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
         if st != 0:
             raise AwqError(st, "awq_w4a16_linear_fused_multi")
+    return call
+
+
+class ChainStage(ctypes.Structure):
+    """awq_chain_stage of the C ABI."""
+    _fields_ = [("descs", ctypes.POINTER(FusedDesc)), ("count", ctypes.c_int)]
+
+
+CHAIN_MAX_STAGES, CHAIN_MAX_LINEARS, CHAIN_SYNC_BYTES = 4, 10, 8192
+
+
+def chain_sync(device="cuda") -> torch.Tensor:
+    """A zeroed sync area for awq_w4a16_linear_chain."""
+    return torch.zeros(CHAIN_SYNC_BYTES // 4, dtype=torch.int32, device=device)
+
+
+def prepare_linear_chain(stages, sync: torch.Tensor, group: int = GROUP, spin_limit: int = 0):
+    """Marshal one awq_w4a16_linear_chain call.  `stages` is a list of stages, each a list of dicts
+    as for prepare_linear_fused_multi; a linear may read (as x or residual) what a linear of an
+    earlier stage writes.  `sync`: chain_sync() (zeroed, CHAIN_SYNC_BYTES); it is zero again after every
+    call that ends normally, and sync[0] != 0 afterwards means a wait ran out (outputs invalid).
+    Returns a zero-argument callable that enqueues the ONE launch on the then-current stream."""
+    if not 1 <= len(stages) <= CHAIN_MAX_STAGES:
+        raise ValueError(f"1..{CHAIN_MAX_STAGES} stages per chain")
+    if not (sync.is_cuda and sync.is_contiguous() and sync.numel() * sync.element_size() >= CHAIN_SYNC_BYTES):
+        raise TypeError(f"sync: a contiguous GPU tensor of at least {CHAIN_SYNC_BYTES} bytes")
+    arr = (ChainStage * len(stages))()
+    keep, M = [sync], None
+    for s, linears in enumerate(stages):
+        if not 1 <= len(linears) <= CHAIN_MAX_LINEARS:
+            raise ValueError(f"1..{CHAIN_MAX_LINEARS} linears per stage")
+        descs, M = _fused_descs(linears, group, M)
+        arr[s] = ChainStage(ctypes.cast(descs, ctypes.POINTER(FusedDesc)), len(linears))
+        keep += [descs, list(linears)]
+    fn = load().awq_w4a16_linear_chain
+    n = len(stages)
+    sync_ptr = ctypes.c_void_p(sync.data_ptr())
+
+    def call(_keep=keep):
+        st = fn(arr, n, M, group, sync_ptr, spin_limit, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_w4a16_linear_chain")
     return call
 
 

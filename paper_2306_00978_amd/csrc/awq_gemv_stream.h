@@ -53,6 +53,17 @@ template <> struct GemvArgs<true> {
 };
 static_assert(sizeof(GemvArgs<true>) <= 4096, "kernel arguments are limited to 4 KB");
 
+// Chained launch: up to CHAIN_MAX_STAGES stages of up to CHAIN_MAX_ENTRIES linears each, a stage
+// may read what earlier stages wrote.  sync: CHAIN_SYNC_BYTES of zeroed device memory.
+constexpr int CHAIN_MAX_STAGES = 4, CHAIN_MAX_ENTRIES = 10;
+#ifndef AWQ_CHAIN_SHARDS
+#define AWQ_CHAIN_SHARDS 16
+#endif
+constexpr int CHAIN_SHARDS = AWQ_CHAIN_SHARDS, CHAIN_SHARD_STRIDE = 32;            // words: one cache line per shard
+constexpr int CHAIN_SYNC_BYTES = 4 * CHAIN_SHARD_STRIDE * (1 + CHAIN_SHARDS * (CHAIN_MAX_STAGES - 1));
+int awq_gemv_chain_launch(const GemvProblem *const *problems, const GemvFusedExtra *const *extras, const int *counts,
+                          int nstages, int M, uint32_t *sync, int spin_limit, hipStream_t stream);
+
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream);
 // the same for linears in the 3-bit packed layout (q then points at 12-byte slots)
 int awq_gemv_stream_launch_w3(const GemvProblem *problems, int count, int M, hipStream_t stream);

@@ -285,13 +285,28 @@ __device__ __forceinline__ uint32_t mix_scale_pair(uint32_t x2, float f, uint32_
     return out;
 }
 
-template <int STAGES, int BITS, bool FUSED>
-__global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSED> A)
+// What a stage of a chained launch waits for before it may read its activations: a counter in
+// global memory that every workgroup of the launch increments when it has finished the stage
+// before, the value it has to reach, and the give-up flag of the launch.
+struct ChainWait {
+    const uint32_t *counter;      // nullptr: nothing to wait for
+    uint32_t target;
+    uint32_t *gave_up;            // set (never cleared here) by a workgroup whose wait ran out
+    int spin_limit;
+};
+
+// The work of one workgroup of a grouped launch.  `ka` points at a launch table inside the
+// kernel-argument block: int wg_begin[MAXP] at OFF_BEGIN, GemvProblem p[MAXP] at OFF_P and, FUSED,
+// GemvFusedExtra e[MAXF] at OFF_E; `vwg` is the workgroup's index within that table's launch.
+// CHAIN: the table is one stage of a chained launch (see chain_kernel); the first weight jobs are
+// requested before the wait for the stage in front, the activations are read after it.  Returns
+// false if that wait ran out (the workgroup then leaves the launch).
+template <int STAGES, int BITS, bool FUSED, bool CHAIN, int OFF_BEGIN, int OFF_P, int OFF_E, int MAXP, int MAXF>
+__device__ __forceinline__ bool stream_body(const unsigned char *ka, const int M, const int mlog, const int logW,
+                                            const int vwg, unsigned char *smem, const ChainWait cw)
 {
-    const GemvLaunch &L = A.L;
     constexpr int STAGE_BYTES = Slot<BITS>::BYTES, STAGE_SC = Slot<BITS>::SC, STAGE_ZP = Slot<BITS>::ZP;
     constexpr int TILE_BYTES = Slot<BITS>::TILE, LOADS_PER_JOB = Slot<BITS>::LOADS;
-    extern __shared__ __align__(16) unsigned char smem[];
     uint32_t mask_lo = 0x000F000Fu, mask_hi = 0x00F000F0u;      // kept in SGPRs
     asm("" : "+s"(mask_lo));
     asm("" : "+s"(mask_hi));
@@ -315,11 +330,10 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
     float eps = 0.f;
     int pre_op = GEMV_PRE_NONE;
     {
-        const unsigned char *ka = (const unsigned char *)__builtin_amdgcn_kernarg_segment_ptr();
-        const int l = threadIdx.x & 63, le = l < GEMV_MAX_PROBLEMS ? l : GEMV_MAX_PROBLEMS - 1;
+        const int l = threadIdx.x & 63, le = l < MAXP ? l : MAXP - 1;
         typedef const __attribute__((address_space(1))) int gbl_int_t;
-        const int begin = *(gbl_int_t *)(uintptr_t)(ka + offsetof(GemvLaunch, wg_begin) + 4 * le);
-        gbl_u32x2_t *pe = (gbl_u32x2_t *)(uintptr_t)(ka + offsetof(GemvLaunch, p) + sizeof(GemvProblem) * le);
+        const int begin = *(gbl_int_t *)(uintptr_t)(ka + OFF_BEGIN + 4 * le);
+        gbl_u32x2_t *pe = (gbl_u32x2_t *)(uintptr_t)(ka + OFF_P + sizeof(GemvProblem) * le);
         uint32_t f[14];
 #pragma unroll
         for (int d = 0; d < 7; ++d) {
@@ -329,8 +343,8 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
         }
         uint32_t fe[6] = {};
         if (FUSED) {
-            const int lf = l < GEMV_MAX_FUSED ? l : GEMV_MAX_FUSED - 1;
-            gbl_u32x2_t *ee = (gbl_u32x2_t *)(uintptr_t)(ka + sizeof(GemvLaunch) + sizeof(GemvFusedExtra) * lf);
+            const int lf = l < MAXF ? l : MAXF - 1;
+            gbl_u32x2_t *ee = (gbl_u32x2_t *)(uintptr_t)(ka + OFF_E + sizeof(GemvFusedExtra) * lf);
 #pragma unroll
             for (int d = 0; d < 3; ++d) {
                 const u32x2_t t = ee[d];
@@ -338,7 +352,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
                 fe[2 * d + 1] = t.y;
             }
         }
-        const uint64_t mine = __ballot(l < GEMV_MAX_PROBLEMS && (int)blockIdx.x >= begin);
+        const uint64_t mine = __ballot(l < MAXP && vwg >= begin);
         const int pi = __builtin_amdgcn_readfirstlane(__popcll(mine) - 1);     // wg_begin is ascending from 0
         uint32_t g[14];
 #pragma unroll
@@ -357,7 +371,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
         P.nrb = (int)g[13];
         wg0 = __builtin_amdgcn_readlane(begin, pi);
         if (FUSED) {
-            static_assert(sizeof(GemvFusedExtra) == 24 && offsetof(GemvArgs<true>, e) == sizeof(GemvLaunch), "layout");
+            static_assert(sizeof(GemvFusedExtra) == 24, "layout");
             uint32_t ge[6];
 #pragma unroll
             for (int d = 0; d < 6; ++d) ge[d] = __builtin_amdgcn_readlane(fe[d], pi);
@@ -368,17 +382,17 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
         }
     }
 
-    const int M = L.M, mlog = L.mlog, Mpad = 1 << mlog;
+    const int Mpad = 1 << mlog;
     const int K = P.K, N = P.N;
     const int G = K >> 7, NRB = P.nrb, NBT = (G + 3) >> 2;
     const int ksl = P.plan & 15, KS = 1 << ksl;
-    const int W = 1 << L.logW, RW = W >> ksl;
+    const int W = 1 << logW, RW = W >> ksl;
     const int iters = P.plan >> 4;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ks = wave & (KS - 1), ri = wave >> ksl;
     const int b0 = (NBT * ks) >> ksl, b1 = (NBT * (ks + 1)) >> ksl;      // 1..16/Mpad batches (host)
-    const int unit = (int)blockIdx.x - wg0;
+    const int unit = vwg - wg0;
     const int rb_wg = unit * iters * RW;                                 // first row block of the WG
     const int r = lane & 15, c = lane >> 4;
     const int zshift = (r & 1) * 4;
@@ -437,13 +451,39 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
         }
     };
 
+    // CHAIN: what one stage writes another workgroup reads within the same launch, and the L2
+    // caches of the eight XCDs are not kept coherent for ordinary accesses.  Outputs are therefore
+    // written, and activations and residuals read, as device-scope atomic accesses (they go to the
+    // memory side instead of staying in one XCD's L2); with that no cache has to be written back or
+    // invalidated as a whole between stages, which was measured at about 30 us per stage.
+    auto coherent_load16 = [](gbl_half_t *p) -> uint4 {
+        const uint64_t *q = (const uint64_t *)(uintptr_t)p;
+        const uint64_t lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+    };
+    auto load_res = [](gbl_half_t *p) -> float {
+        if (CHAIN) {
+            const uint16_t b = __hip_atomic_load((const uint16_t *)(uintptr_t)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return (float)__builtin_bit_cast(half_t, b);
+        }
+        return (float)*p;
+    };
+    auto store_out = [](__attribute__((address_space(1))) half_t *p, float v) {
+        const half_t h = (half_t)v;
+        if (CHAIN) __hip_atomic_store((uint16_t *)(uintptr_t)p, __builtin_bit_cast(uint16_t, h), __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+        else *p = h;
+    };
+
     // activation fragments (see the header comment), loaded once.  Their loads go out first:
     // they are tiny, and behind the first weight requests of the whole grid they would wait
-    // for megabytes that are of no use before the fragments are there.
+    // for megabytes that are of no use before the fragments are there.  (CHAIN: the other way
+    // round -- the weights do not depend on the stage in front, the activations do.)
     uint4 xa[16];
     uint4 wn[16];                // FUSED: normalisation factors, alive until the fragments are final
     bool okx[4];                 // whether tile u of the lane's slot exists (else its fragments are 0)
-    {
+    auto load_fragments = [&]() {
         const int slot = r >> mlog;
         int m = r & (Mpad - 1);
         m = m < M ? m : M - 1;
@@ -456,7 +496,8 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
             const int gs = okx[u] ? g : 0;          // always a valid address: no branch, no wait
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                xa[4 * u + j] = __builtin_bit_cast(uint4, *(gbl_u32x4_t *)(xrow + gs * 128 + 32 * j));
+                if (CHAIN) xa[4 * u + j] = coherent_load16(xrow + gs * 128 + 32 * j);
+                else xa[4 * u + j] = __builtin_bit_cast(uint4, *(gbl_u32x4_t *)(xrow + gs * 128 + 32 * j));
         }
         if (FUSED && pre_op != GEMV_PRE_NONE) {      // the factors of the same columns
 #pragma unroll
@@ -467,7 +508,8 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
                     wn[4 * u + j] = __builtin_bit_cast(uint4, *(gbl_u32x4_t *)(ppre + 8 * c + gs * 128 + 32 * j));
             }
         }
-    }
+    };
+    if (!CHAIN) load_fragments();
 
     // the first weight requests
     const int nbw = b1 - b0;
@@ -482,6 +524,50 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (nj < J) issue_next();
+
+    if (CHAIN) {
+        // Wait (bounded) until every workgroup of the launch has finished the stage in front: its
+        // outputs are this stage's activations.  The weights requested above travel meanwhile.
+        // The decision to go on or to give up is taken by the workgroup as a whole, since its
+        // waves meet at barriers later on.
+        if (cw.counter) {
+            // one wave polls for the workgroup (2048 waves polling one address slow down the very
+            // atomics they wait for); lane h reads shard h of the counter
+            uint32_t *vote = reinterpret_cast<uint32_t *>(red + 2 * red_floats + W * 16);
+            if (wave == 0) {
+                bool ok = true;
+                int spins = 0;
+                for (;;) {
+                    uint32_t part = 0;
+                    if (lane < CHAIN_SHARDS)
+                        part = __hip_atomic_load(cw.counter + CHAIN_SHARD_STRIDE * lane, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int d = 1; d < CHAIN_SHARDS; d <<= 1) part += __shfl_xor(part, d);
+                    // the flag first: once it is set no wait of the launch succeeds any more
+                    const uint32_t stop = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(cw.gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                    const uint32_t seen = __builtin_amdgcn_readfirstlane(part);
+                    if (stop != 0) { ok = false; break; }
+                    if (seen >= cw.target) break;
+                    if (++spins > cw.spin_limit) { ok = false; break; }
+                    __builtin_amdgcn_s_sleep(8);
+                }
+                if (lane == 0) vote[0] = ok ? 1u : 0u;
+            }
+            lds_barrier();
+            const bool all_ok = vote[0] != 0;
+            if (!all_ok) {
+                if (tid == 0) __hip_atomic_store(cw.gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                wait_loads<0>();                   // nothing may still be on its way into this LDS
+                return false;
+            }
+            // the counter was read at device scope and so are the activations below; the fence keeps
+            // the compiler from moving them in front of the wait (no cache operation at this scope)
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        load_fragments();
+    }
 
 #pragma unroll
     for (int i = 0; i < 16; ++i)
@@ -610,7 +696,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
                     const int m = 4 * c + v;
                     if (v < Mpad && m < M) {
                         const size_t at = (size_t)m * N + rbo * 16 + r;
-                        py[at] = (half_t)(FUSED && pres ? total[v] + (float)pres[at] : total[v]);
+                        store_out(py + at, FUSED && pres ? total[v] + load_res(pres + at) : total[v]);
                     }
                 }
             }
@@ -634,7 +720,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
             const int rbo = rb_wg + it * RW + tri;
             if (rbo < NRB && m < M) {
                 const size_t at = (size_t)m * N + rbo * 16 + (rem & 15);
-                py[at] = (half_t)(FUSED && pres ? sum + (float)pres[at] : sum);
+                store_out(py + at, FUSED && pres ? sum + load_res(pres + at) : sum);
             }
         }
     };
@@ -659,6 +745,91 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
 #pragma unroll
         for (int v = 0; v < 4; ++v) total[v] += slotv[v] == slot ? bacc[v] : 0.f;
         if (++cb == b1) { finish_block(cit); cb = b0; ++cit; }
+    }
+    return true;
+}
+
+template <int STAGES, int BITS, bool FUSED>
+__global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSED> A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const unsigned char *ka = (const unsigned char *)__builtin_amdgcn_kernarg_segment_ptr();
+    static_assert(!FUSED || offsetof(GemvArgs<true>, e) == sizeof(GemvLaunch), "layout");
+    stream_body<STAGES, BITS, FUSED, false, offsetof(GemvLaunch, wg_begin), offsetof(GemvLaunch, p), sizeof(GemvLaunch),
+                GEMV_MAX_PROBLEMS, GEMV_MAX_FUSED>(ka, A.L.M, A.L.mlog, A.L.logW, (int)blockIdx.x, smem,
+                                                   ChainWait{nullptr, 0, nullptr, 0});
+}
+
+// Chained launch (Sec. 4.2, kernel fusion carried across the data dependences of a decoder layer).
+// A decode step orders its linears (Q,K,V | o | gate,up | down); as separate launches each of them
+// pays a launch, a ramp-up of the memory pipeline and a run-out, which together exceed the time
+// the weights need.  Here ONE launch of resident workgroups runs the stages one after the other.
+// What makes that pay: the weights of a stage do not depend on the stage in front, so a workgroup
+// that has finished its share of stage s requests its first jobs of stage s + 1 at once and only
+// then waits until every workgroup has finished stage s (a counter in global memory, incremented
+// by each workgroup once its outputs have been acknowledged, polled with a bounded number of spins).  Every
+// workgroup must be resident for that (the launcher checks the occupancy); a wait that runs out
+// sets the give-up flag, on which all others leave as well, so the launch always ends.
+//   sync (32-bit words): [0] give-up flag, [1] workgroups that finished the launch (the last of
+//   those sets all counters back to zero); the count of the workgroups that finished stage s is
+//   kept in CHAIN_SHARDS parts, part h in word 32 (1 + CHAIN_SHARDS s + h), each in a cache line of
+//   its own: a workgroup adds to part blockIdx % CHAIN_SHARDS, so that the atomics of the 512
+//   workgroups do not all queue at one address, and the polling wave sums the parts.
+// Ring slots per wave in a chained launch: CHAIN_RING - 1 jobs (4.2 KB each) are on their way while
+// a workgroup waits for the stage in front, so that the memory system keeps working through the
+// wait (the round trips of a wait go to a memory that is busy with the weights and take
+// several microseconds).
+#ifndef AWQ_CHAIN_RING
+#define AWQ_CHAIN_RING 4
+#endif
+constexpr int CHAIN_RING = AWQ_CHAIN_RING;
+
+struct ChainStage {
+    int wg_begin[CHAIN_MAX_ENTRIES];
+    int count, wgs;
+    GemvProblem p[CHAIN_MAX_ENTRIES];
+    GemvFusedExtra e[CHAIN_MAX_ENTRIES];
+};
+struct ChainArgs {
+    ChainStage st[CHAIN_MAX_STAGES];
+    uint32_t *sync;
+    int nstages, M, mlog, logW, spin_limit, pad;
+};
+static_assert(sizeof(ChainArgs) <= 4096, "kernel arguments are limited to 4 KB");
+
+__global__ __launch_bounds__(512, 2) void chain_kernel(const ChainArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const unsigned char *ka = (const unsigned char *)__builtin_amdgcn_kernarg_segment_ptr();
+    uint32_t *sync = A.sync;
+    const uint32_t workgroups = gridDim.x;
+    for (int s = 0; s < A.nstages; ++s) {
+        if ((int)blockIdx.x < A.st[s].wgs) {
+            const ChainWait cw = {s > 0 ? sync + CHAIN_SHARD_STRIDE * (1 + CHAIN_SHARDS * (s - 1)) : nullptr, workgroups,
+                                  sync, A.spin_limit};
+            const bool ok = stream_body<CHAIN_RING, 4, true, true, offsetof(ChainStage, wg_begin), offsetof(ChainStage, p),
+                                        offsetof(ChainStage, e), CHAIN_MAX_ENTRIES, CHAIN_MAX_ENTRIES>(
+                ka + offsetof(ChainArgs, st) + (size_t)s * sizeof(ChainStage), A.M, A.mlog, A.logW, (int)blockIdx.x,
+                smem, cw);
+            if (!ok) return;                                   // the whole workgroup, see stream_body
+        }
+        if (s + 1 < A.nstages) {
+            // every wave's outputs (device-scope stores) have been acknowledged, then the count
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (threadIdx.x == 0)
+                __hip_atomic_fetch_add(sync + CHAIN_SHARD_STRIDE * (1 + CHAIN_SHARDS * s + (blockIdx.x % CHAIN_SHARDS)), 1u,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if (threadIdx.x == 0) {
+        // every workgroup that arrives here has passed its last wait: the last one may reset
+        const uint32_t before = __hip_atomic_fetch_add(sync + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (before == workgroups - 1) {
+            for (int i = 0; i < CHAIN_SHARDS * (CHAIN_MAX_STAGES - 1); ++i)
+                __hip_atomic_store(sync + CHAIN_SHARD_STRIDE * (1 + i), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(sync + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -945,6 +1116,110 @@ int stream_launch_bits(const GemvProblem *problems, const GemvFusedExtra *extra,
 }
 
 }  // namespace
+
+// Plans and launches a chained decode launch (chain_kernel).  Every stage is planned like a grouped
+// launch of its own with one size of workgroup per linear; all stages share the workgroup size, and
+// no stage may need more workgroups than the chip holds at once, because a workgroup that is not
+// resident cannot report the end of a stage the others wait for.
+int awq_gemv_chain_launch(const GemvProblem *const *problems, const GemvFusedExtra *const *extras, const int *counts,
+                          int nstages, int M, uint32_t *sync, int spin_limit, hipStream_t stream)
+{
+    constexpr int STAGE_BYTES = Slot<4>::BYTES;
+    if (nstages < 1 || nstages > CHAIN_MAX_STAGES) return AWQ_ERR_BAD_ARGUMENT;
+    ChainArgs A{};
+    A.sync = sync;
+    A.nstages = nstages;
+    A.M = M;
+    A.mlog = ceil_log2(M);
+    A.spin_limit = spin_limit > 0 ? spin_limit : 2000000;      // a few seconds of polling
+    const int bpr = 16 >> A.mlog;
+    int ksl_of[CHAIN_MAX_STAGES][CHAIN_MAX_ENTRIES];
+    double T_of[CHAIN_MAX_STAGES];
+    int logW = 2;
+    for (int s = 0; s < nstages; ++s) {
+        if (counts[s] < 1 || counts[s] > CHAIN_MAX_ENTRIES) return AWQ_ERR_BAD_ARGUMENT;
+        double total_batches = 0;
+        for (int i = 0; i < counts[s]; ++i)
+            total_batches += (double)(problems[s][i].N / 16) * ((problems[s][i].K / 128 + 3) / 4);
+        const double T = std::max(1.0, total_batches / 1792);
+        T_of[s] = T;
+        for (int i = 0; i < counts[s]; ++i) {
+            const int NBT = (problems[s][i].K / 128 + 3) / 4;
+            const int ksl_min = ceil_log2((NBT + bpr - 1) / bpr);
+            if (ksl_min > 3) return AWQ_GEMV_STREAM_UNFIT;
+            // a small stage spreads its rows over more waves along K -- but over four at most unless
+            // the registers force eight: all stages share the workgroup size, and with eight waves
+            // per workgroup the wide stages (gate, up) would fill only part of the chip
+            int ksl = ksl_min;
+            while (ksl < 2 && (2 << ksl) <= NBT && ((NBT + (1 << ksl) - 1) >> ksl) > 1.5 * T) ++ksl;
+            while ((1 << ksl) > NBT && ksl > ksl_min) --ksl;
+            if ((1 << ksl) > NBT) return AWQ_GEMV_STREAM_UNFIT;
+            ksl_of[s][i] = ksl;
+            logW = std::max(logW, ksl);
+        }
+    }
+    A.logW = logW;
+    const int W = 1 << logW;
+    const size_t lds = (size_t)W * CHAIN_RING * STAGE_BYTES + 2 * (size_t)W * (16 << A.mlog) * 4 + (size_t)W * 16 * 4 + 64;
+    if (lds > (size_t)160 * 1024) return AWQ_GEMV_STREAM_UNFIT;
+
+    // workgroups the chip holds at once (per device and workgroup size; the query is not free)
+    static std::atomic<int> resident[64][2];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return AWQ_ERR_HIP;
+    static AwqOncePerDevice once;
+    std::atomic<bool> &attr_set = once.here();
+    if (!attr_set.load(std::memory_order_relaxed)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(chain_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                160 * 1024) != hipSuccess)
+            return AWQ_ERR_HIP;
+        attr_set.store(true, std::memory_order_relaxed);
+    }
+    int cap = resident[dev][logW - 2].load(std::memory_order_relaxed);
+    if (cap == 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(chain_kernel), W * 64,
+                                                         lds) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return AWQ_ERR_HIP;
+        cap = std::min(per_cu, 2) * cus;             // two per CU at most: the layout the plans are made for
+        if (cap < 1) return AWQ_GEMV_STREAM_UNFIT;
+        resident[dev][logW - 2].store(cap, std::memory_order_relaxed);
+    }
+
+    int grid = 0;
+    for (int s = 0; s < nstages; ++s) {
+        ChainStage &S = A.st[s];
+        double T = T_of[s];
+        int wg = 0;
+        for (int attempt = 0; attempt < 400; ++attempt) {
+            wg = 0;
+            for (int i = 0; i < counts[s]; ++i) {
+                GemvProblem p = problems[s][i];
+                const int NBT = (p.K / 128 + 3) / 4;
+                const int nbw = (NBT + (1 << ksl_of[s][i]) - 1) >> ksl_of[s][i];
+                const int NRB = p.N / 16, RW = W >> ksl_of[s][i];
+                const int steps = (NRB + RW - 1) / RW;
+                const int iters = std::min(std::max(1, (int)(T / nbw + 0.5)), steps);
+                p.plan = ksl_of[s][i] | (iters << 4);
+                p.nrb = NRB;
+                S.wg_begin[i] = wg;
+                S.p[i] = p;
+                S.e[i] = extras[s][i];
+                wg += (steps + iters - 1) / iters;
+            }
+            if (wg <= cap) break;
+            T *= 1.04;
+        }
+        if (wg > cap) return AWQ_GEMV_STREAM_UNFIT;
+        for (int i = counts[s]; i < CHAIN_MAX_ENTRIES; ++i) S.wg_begin[i] = 0x7fffffff;
+        S.count = counts[s];
+        S.wgs = wg;
+        grid = std::max(grid, wg);
+    }
+    chain_kernel<<<dim3(grid), dim3(W * 64), lds, stream>>>(A);
+    return awq_launch_status();
+}
 
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream)
 {

@@ -213,14 +213,11 @@ extern "C" int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, i
     return AWQ_OK;
 }
 
-extern "C" int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int count, int64_t M, int group,
-                                            void *stream)
+namespace {
+
+// validation of the linears of a fused / chained call and their translation for the launcher
+int fused_problems(const awq_fused_desc *descs, int count, int group, GemvProblem *p, GemvFusedExtra *e)
 {
-    if (!descs) return AWQ_ERR_NULL_POINTER;
-    if (count < 1 || count > AWQ_FUSED_MAX) return AWQ_ERR_BAD_ARGUMENT;
-    if (M <= 0 || M > 16) return AWQ_ERR_BAD_SHAPE;
-    GemvProblem p[GEMV_MAX_FUSED] = {};
-    GemvFusedExtra e[GEMV_MAX_FUSED] = {};
     for (int i = 0; i < count; ++i) {
         const awq_linear_desc &d = descs[i].linear;
         if (!d.x_f16 || !d.qweight || !d.scales || !d.zeros || !d.y_f16) return AWQ_ERR_NULL_POINTER;
@@ -236,6 +233,7 @@ extern "C" int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int cou
         } else if (descs[i].pre_op != AWQ_PRE_NONE) {
             return AWQ_ERR_BAD_ARGUMENT;
         }
+        p[i] = GemvProblem{};
         p[i].x = (const half_t *)d.x_f16;
         p[i].q = (const uint4 *)d.qweight;
         p[i].sc = (const uint16_t *)d.scales;
@@ -248,6 +246,53 @@ extern "C" int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int cou
         e[i].eps = descs[i].eps;
         e[i].pre_op = descs[i].pre_op == AWQ_PRE_RMSNORM ? GEMV_PRE_RMSNORM
                       : descs[i].pre_op == AWQ_PRE_SCALE ? GEMV_PRE_SCALE : GEMV_PRE_NONE;
+    }
+    return AWQ_OK;
+}
+
+}  // namespace
+
+extern "C" int awq_w4a16_linear_chain(const awq_chain_stage *stages, int n_stages, int64_t M, int group, void *sync,
+                                      int spin_limit, void *stream)
+{
+    if (!stages || !sync) return AWQ_ERR_NULL_POINTER;
+    if (n_stages < 1 || n_stages > AWQ_CHAIN_MAX_STAGES || spin_limit < 0) return AWQ_ERR_BAD_ARGUMENT;
+    if (M <= 0 || M > 16) return AWQ_ERR_BAD_SHAPE;
+    if (!awq_aligned16(sync)) return AWQ_ERR_MISALIGNED;
+    GemvProblem p[AWQ_CHAIN_MAX_STAGES][AWQ_CHAIN_MAX_LINEARS];
+    GemvFusedExtra e[AWQ_CHAIN_MAX_STAGES][AWQ_CHAIN_MAX_LINEARS];
+    const GemvProblem *pp[AWQ_CHAIN_MAX_STAGES];
+    const GemvFusedExtra *ee[AWQ_CHAIN_MAX_STAGES];
+    int counts[AWQ_CHAIN_MAX_STAGES];
+    static_assert(AWQ_CHAIN_MAX_STAGES == CHAIN_MAX_STAGES && AWQ_CHAIN_MAX_LINEARS == CHAIN_MAX_ENTRIES &&
+                  AWQ_CHAIN_SYNC_BYTES >= CHAIN_SYNC_BYTES, "limits");
+    for (int s = 0; s < n_stages; ++s) {
+        if (!stages[s].descs) return AWQ_ERR_NULL_POINTER;
+        if (stages[s].count < 1 || stages[s].count > AWQ_CHAIN_MAX_LINEARS) return AWQ_ERR_BAD_ARGUMENT;
+        const int st = fused_problems(stages[s].descs, stages[s].count, group, p[s], e[s]);
+        if (st != AWQ_OK) return st;
+        for (int i = 0; i < stages[s].count; ++i)
+            if (!awq_gemv_stream_fits(p[s][i].N, p[s][i].K, (int)M)) return AWQ_ERR_BAD_SHAPE;
+        pp[s] = p[s];
+        ee[s] = e[s];
+        counts[s] = stages[s].count;
+    }
+    const int st = awq_gemv_chain_launch(pp, ee, counts, n_stages, (int)M, (uint32_t *)sync, spin_limit,
+                                         (hipStream_t)stream);
+    return st == AWQ_GEMV_STREAM_UNFIT ? AWQ_ERR_BAD_SHAPE : st;
+}
+
+extern "C" int awq_w4a16_linear_fused_multi(const awq_fused_desc *descs, int count, int64_t M, int group,
+                                            void *stream)
+{
+    if (!descs) return AWQ_ERR_NULL_POINTER;
+    if (count < 1 || count > AWQ_FUSED_MAX) return AWQ_ERR_BAD_ARGUMENT;
+    if (M <= 0 || M > 16) return AWQ_ERR_BAD_SHAPE;
+    GemvProblem p[GEMV_MAX_FUSED] = {};
+    GemvFusedExtra e[GEMV_MAX_FUSED] = {};
+    {
+        const int st = fused_problems(descs, count, group, p, e);
+        if (st != AWQ_OK) return st;
     }
     // a lone linear without a normalisation: the batch kernel (every shape, and the faster one
     // for a single small matrix)

@@ -144,6 +144,39 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert qm(qdescs(3, s=odd), 3, 128, None) == -4
     assert qm(qdescs(3, W_f16=odd), 3, 128, None) == -4
 
+    def fdescs(n, **kw):
+        arr = (awq.FusedDesc * max(n, 1))()
+        for i in range(n):
+            d = dict(x_f16=ok, qweight=ok, scales=ok, zeros=ok, y_f16=ok, N=16, K=128)
+            d.update(kw)
+            arr[i] = awq.FusedDesc(awq.LinearDesc(**d), None, None, 1e-5, 0)
+        return arr
+    def stages(n, per=1, **kw):
+        arr = (awq.ChainStage * max(n, 1))()
+        keep = []
+        for i in range(n):
+            fd = fdescs(per, **kw)
+            keep.append(fd)
+            arr[i] = awq.ChainStage(ctypes.cast(fd, ctypes.POINTER(awq.FusedDesc)), per)
+        return arr, keep
+    ch = lib.awq_w4a16_linear_chain
+    Pv = ctypes.c_void_p
+    st2, k2 = stages(2)
+    assert ch(None, 2, 1, 128, Pv(ok), 0, None) == -1
+    assert ch(st2, 2, 1, 128, None, 0, None) == -1
+    assert ch(st2, 0, 1, 128, Pv(ok), 0, None) == -7
+    assert ch(st2, 5, 1, 128, Pv(ok), 0, None) == -7
+    assert ch(st2, 2, 1, 128, Pv(ok), -1, None) == -7
+    assert ch(st2, 2, 17, 128, Pv(ok), 0, None) == -2
+    assert ch(st2, 2, 1, 128, Pv(odd), 0, None) == -4
+    assert ch(st2, 2, 1, 64, Pv(ok), 0, None) == -3
+    bad, kb = stages(2, per=1, K=100)
+    assert ch(bad, 2, 1, 128, Pv(ok), 0, None) == -2
+    bad, kb = stages(2, per=1, y_f16=None)
+    assert ch(bad, 2, 1, 128, Pv(ok), 0, None) == -1
+    many, km = stages(1, per=11)
+    assert ch(many, 1, 1, 128, Pv(ok), 0, None) == -7
+
     c = lib.awq_quantize_pack_clip
     rat = (ctypes.c_float * 3)(1.0, 0.9, 0.8)
     Pq = ctypes.c_void_p
