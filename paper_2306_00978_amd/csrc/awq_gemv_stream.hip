@@ -757,7 +757,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
     static_assert(!FUSED || offsetof(GemvArgs<true>, e) == sizeof(GemvLaunch), "layout");
     stream_body<STAGES, BITS, FUSED, false, offsetof(GemvLaunch, wg_begin), offsetof(GemvLaunch, p), sizeof(GemvLaunch),
                 GEMV_MAX_PROBLEMS, GEMV_MAX_FUSED>(ka, A.L.M, A.L.mlog, A.L.logW, (int)blockIdx.x, smem,
-                                                   ChainWait{nullptr, 0, nullptr, 0});
+                                                   ChainWait{});
 }
 
 // Chained launch (Sec. 4.2, kernel fusion carried across the data dependences of a decoder layer).
@@ -780,7 +780,7 @@ __global__ __launch_bounds__(512, 2) void gemv_stream_kernel(const GemvArgs<FUSE
 // wait (the round trips of a wait go to a memory that is busy with the weights and take
 // several microseconds).
 #ifndef AWQ_CHAIN_RING
-#define AWQ_CHAIN_RING 4
+#define AWQ_CHAIN_RING 2
 #endif
 constexpr int CHAIN_RING = AWQ_CHAIN_RING;
 
