@@ -674,17 +674,24 @@ def main():
         # configs[3]: the seven projections of a Llama-2-70B-shaped layer (444.5 MB per launch), M = 1
         # and 8, one grouped launch per step, two distinct layers cycled
         shapes70 = workloads.LLAMA2_70B_LAYER
+        # inputs by the recipe of configs[3]: 1 % outlier channels x 20, s from 64 calibration rows per
+        # distinct input width, weights quantized with that s, activations divided by it
+        s70, x70 = {}, {}
+        for K70 in (8192, 28672):
+            out70 = workloads.outlier_channels(K70, 3, 0, 0)
+            cal70 = workloads.activations(workloads.CALIB_TOKENS, K70, 3, 0, 0, workloads.ROLE_CALIB, out70)
+            s70[K70] = awq.awq_act_scale(torch.from_numpy(cal70).to(dev), 0.5)
+            xr = workloads.activations(8, K70, 3, 0, 0, workloads.ROLE_X, out70)
+            x70[K70] = awq.awq_apply_inv_scale(torch.from_numpy(xr).to(dev), s70[K70])
         lay70 = []
         for l in range(2):
             packed = []
             for name, N, K in shapes70:
                 W = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
                      * workloads.SIGMA_70B).to(torch.float16)
-                packed.append(awq.awq_quantize_pack(W))
+                packed.append(awq.awq_quantize_pack(W, s70[K]))
                 del W
             lay70.append(packed)
-        x70 = {K: (torch.randn((8, K), generator=gen, device=dev, dtype=torch.float32)).to(torch.float16)
-               for K in (8192, 28672)}
         for M70 in (1, 8):
             ys70 = [torch.empty((M70, N), dtype=torch.float16, device=dev) for _, N, K in shapes70]
             calls70 = [awq.prepare_linear_multi([(x70[K][:M70], *lay70[l][p], ys70[p], N)

@@ -62,6 +62,22 @@ int awq_version(void);
 /* Static, human-readable name of a status code (never NULL). */
 const char *awq_status_string(int status);
 
+/* Export aid, not part of the method: a 64-byte header for a file that stores packed arrays
+ * (magic, version of the packed layout, bit width, group size, shape, bytes of the three arrays).
+ * awq_blob_header_init fills it for bits in {4, 3, 2} (the layouts of awq_quantize_pack, _w3, _w2),
+ * with the shape rules of that layout; awq_blob_header_check accepts exactly what init would have
+ * written for the header's own bits / N / K / group with this library's layout version, and
+ * returns AWQ_ERR_BAD_ARGUMENT for anything else (another version, a damaged field).  HOST
+ * pointers; nothing is launched. */
+typedef struct awq_blob_header {
+    char magic[8];                  /* "AWQgfx95" */
+    uint32_t layout_version, bits, group, reserved;
+    int64_t N, K;
+    uint64_t qweight_bytes, scales_bytes, zeros_bytes;
+} awq_blob_header;
+int awq_blob_header_init(awq_blob_header *h, int bits, int64_t N, int64_t K, int group);
+int awq_blob_header_check(const awq_blob_header *h);
+
 /* Measurement aid, not part of the method: streams `bytes` (rounded down to a multiple of 16) of
  * a device buffer with 128-bit loads and discards them -- the read bandwidth this machine
  * reaches on a buffer of that size, against which the decode kernels are stated.  sink: device

@@ -40,7 +40,7 @@ EXPORTS = [
     "awq_packed_sizes_w2", "awq_quantize_pack_w2", "awq_unpack_w2", "awq_w2a16_linear",
     "awq_w2a16_linear_multi",
     "awq_last_grouped_plan", "awq_static_scratch_bytes", "awq_w4a16_linear_static",
-    "awq_quantize_pack_multi", "awq_w4a16_linear_chain",
+    "awq_quantize_pack_multi", "awq_w4a16_linear_chain", "awq_blob_header_init", "awq_blob_header_check",
 ]
 MULTI_MAX = 56
 
@@ -52,6 +52,26 @@ class LinearDesc(ctypes.Structure):
                 ("y_f16", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64)]
 
 _lib = None
+
+
+class BlobHeader(ctypes.Structure):
+    """awq_blob_header of the C ABI (64 bytes)."""
+    _fields_ = [("magic", ctypes.c_char * 8), ("layout_version", ctypes.c_uint32), ("bits", ctypes.c_uint32),
+                ("group", ctypes.c_uint32), ("reserved", ctypes.c_uint32), ("N", ctypes.c_int64),
+                ("K", ctypes.c_int64), ("qweight_bytes", ctypes.c_uint64), ("scales_bytes", ctypes.c_uint64),
+                ("zeros_bytes", ctypes.c_uint64)]
+
+
+def awq_blob_header(bits: int, N: int, K: int, group: int | None = None) -> BlobHeader:
+    """Header for a file holding the packed arrays of an [N,K] weight in the `bits`-bit layout."""
+    h = BlobHeader()
+    _check(load().awq_blob_header_init(ctypes.byref(h), bits, N, K, group or (64 if bits == 2 else GROUP)),
+           "awq_blob_header_init")
+    return h
+
+
+def awq_blob_header_check(h: BlobHeader) -> None:
+    _check(load().awq_blob_header_check(ctypes.byref(h)), "awq_blob_header_check")
 
 
 class QuantizeDesc(ctypes.Structure):
@@ -142,6 +162,10 @@ def load() -> ctypes.CDLL:
     lib.awq_last_grouped_plan.argtypes = []
     lib.awq_quantize_pack_multi.restype = i32
     lib.awq_quantize_pack_multi.argtypes = [ctypes.POINTER(QuantizeDesc), i32, i32, vp]
+    lib.awq_blob_header_init.restype = i32
+    lib.awq_blob_header_init.argtypes = [ctypes.c_void_p, i32, i64, i64, i32]
+    lib.awq_blob_header_check.restype = i32
+    lib.awq_blob_header_check.argtypes = [ctypes.c_void_p]
     lib.awq_w4a16_linear_chain.restype = i32
     lib.awq_w4a16_linear_chain.argtypes = [ctypes.c_void_p, i32, i64, i32, vp, i32, vp]
     lib.awq_static_scratch_bytes.restype = sz
@@ -434,10 +458,9 @@ def awq_w4a16_linear_static(x: torch.Tensor, qweight, scales, zeros, N: int, y: 
     return y
 
 
-def prepare_linear_multi(linears, group: int = GROUP):
-    """Marshal one grouped decode call.  `linears` is a list of (x, qweight, scales, zeros, y, N)
-    with the same M <= 16 everywhere.  Returns a zero-argument callable that enqueues ONE
-    awq_w4a16_linear_multi on the then-current stream; the tensors must stay alive."""
+def _prepare_multi(linears, group, sizes, name, with_workspace):
+    """Marshalling shared by the grouped decode calls of the 4-, 3- and 2-bit layouts: `sizes` gives
+    the packed sizes of the layout, `name` the C entry point."""
     if not 1 <= len(linears) <= MULTI_MAX:
         raise ValueError(f"1..{MULTI_MAX} linears per grouped call")
     descs = (LinearDesc * len(linears))()
@@ -450,23 +473,32 @@ def prepare_linear_multi(linears, group: int = GROUP):
             M = m
         if m != M:
             raise ValueError("all linears of a grouped call share M")
-        qb, sb, zb = awq_packed_sizes(N, K, group)
+        qb, sb, zb = sizes(N, K, group)
         if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
                 or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
             raise ValueError("buffer sizes do not match the shape")
         descs[i] = LinearDesc(x.data_ptr(), qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
                               y.data_ptr(), N, K)
-    fn = load().awq_w4a16_linear_multi
+    fn = getattr(load(), name)
     count = len(linears)
     keep = list(linears)
+    extra = (None, 0) if with_workspace else ()
 
     def call(stream=None, _keep=keep):
         """stream: a raw hipStream_t handle (torch.cuda.Stream().cuda_stream); None = torch's current one"""
-        st = fn(descs, count, M, group, None, 0,
+        st = fn(descs, count, M, group, *extra,
                 ctypes.c_void_p(torch.cuda.current_stream().cuda_stream if stream is None else stream))
         if st != 0:
-            raise AwqError(st, "awq_w4a16_linear_multi")
+            raise AwqError(st, name)
     return call
+
+
+def prepare_linear_multi(linears, group: int = GROUP):
+    """Marshal one grouped decode call.  `linears` is a list of (x, qweight, scales, zeros, y, N)
+    with the same M <= 16 everywhere.  Returns a callable that enqueues ONE
+    awq_w4a16_linear_multi on the then-current stream (or on the raw stream handle passed to it);
+    the tensors must stay alive."""
+    return _prepare_multi(linears, group, awq_packed_sizes, "awq_w4a16_linear_multi", True)
 
 
 def awq_w4a16_linear_multi(linears, group: int = GROUP):
@@ -677,33 +709,7 @@ def awq_w2a16_linear(x: torch.Tensor, qweight, scales, zeros, N: int, group: int
 
 def prepare_linear_multi_w2(linears, group: int = GROUP_W2):
     """As prepare_linear_multi for linears in the 2-bit layout."""
-    if not 1 <= len(linears) <= MULTI_MAX:
-        raise ValueError(f"1..{MULTI_MAX} linears per grouped call")
-    descs = (LinearDesc * len(linears))()
-    M = None
-    for i, (x, qweight, scales, zeros, y, N) in enumerate(linears):
-        _dev(x, torch.float16, "x")
-        _dev(y, torch.float16, "y")
-        m, K = x.shape
-        if M is None:
-            M = m
-        if m != M:
-            raise ValueError("all linears of a grouped call share M")
-        qb, sb, zb = awq_packed_sizes_w2(N, K, group)
-        if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
-                or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
-            raise ValueError("buffer sizes do not match the shape")
-        descs[i] = LinearDesc(x.data_ptr(), qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
-                              y.data_ptr(), N, K)
-    fn = load().awq_w2a16_linear_multi
-    count = len(linears)
-    keep = list(linears)
-
-    def call(_keep=keep):
-        st = fn(descs, count, M, group, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
-        if st != 0:
-            raise AwqError(st, "awq_w2a16_linear_multi")
-    return call
+    return _prepare_multi(linears, group, awq_packed_sizes_w2, "awq_w2a16_linear_multi", False)
 
 
 def awq_w2a16_linear_multi(linears, group: int = GROUP_W2):
@@ -713,33 +719,7 @@ def awq_w2a16_linear_multi(linears, group: int = GROUP_W2):
 
 def prepare_linear_multi_w3(linears, group: int = GROUP):
     """As prepare_linear_multi for linears in the 3-bit layout."""
-    if not 1 <= len(linears) <= MULTI_MAX:
-        raise ValueError(f"1..{MULTI_MAX} linears per grouped call")
-    descs = (LinearDesc * len(linears))()
-    M = None
-    for i, (x, qweight, scales, zeros, y, N) in enumerate(linears):
-        _dev(x, torch.float16, "x")
-        _dev(y, torch.float16, "y")
-        m, K = x.shape
-        if M is None:
-            M = m
-        if m != M:
-            raise ValueError("all linears of a grouped call share M")
-        qb, sb, zb = awq_packed_sizes_w3(N, K, group)
-        if qweight.numel() * qweight.element_size() < qb or scales.numel() * scales.element_size() < sb \
-                or zeros.numel() * zeros.element_size() < zb or y.numel() != M * N:
-            raise ValueError("buffer sizes do not match the shape")
-        descs[i] = LinearDesc(x.data_ptr(), qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(),
-                              y.data_ptr(), N, K)
-    fn = load().awq_w3a16_linear_multi
-    count = len(linears)
-    keep = list(linears)
-
-    def call(_keep=keep):
-        st = fn(descs, count, M, group, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
-        if st != 0:
-            raise AwqError(st, "awq_w3a16_linear_multi")
-    return call
+    return _prepare_multi(linears, group, awq_packed_sizes_w3, "awq_w3a16_linear_multi", False)
 
 
 def awq_w3a16_linear_multi(linears, group: int = GROUP):

@@ -31,6 +31,47 @@ extern "C" int awq_packed_sizes(int64_t N, int64_t K, int group, size_t *qweight
     return AWQ_OK;
 }
 
+// Header of a packed blob (export / checkpoint aid).  Three layouts exist (4-, 3-, 2-bit); a file that
+// stores packed arrays should say which one it holds and for what shape, so that a reader built
+// for another layout version refuses it instead of computing with reshuffled codes.
+extern "C" int awq_blob_header_init(awq_blob_header *h, int bits, int64_t N, int64_t K, int group)
+{
+    if (!h) return AWQ_ERR_NULL_POINTER;
+    size_t q = 0, s = 0, z = 0;
+    int st;
+    if (bits == 4) st = awq_packed_sizes(N, K, group, &q, &s, &z);
+    else if (bits == 3) st = awq_packed_sizes_w3(N, K, group, &q, &s, &z);
+    else if (bits == 2) st = awq_packed_sizes_w2(N, K, group, &q, &s, &z);
+    else return AWQ_ERR_BAD_ARGUMENT;
+    if (st != AWQ_OK) return st;
+    const char magic[8] = {'A', 'W', 'Q', 'g', 'f', 'x', '9', '5'};
+    for (int i = 0; i < 8; ++i) h->magic[i] = magic[i];
+    h->layout_version = (uint32_t)awq_version();
+    h->bits = (uint32_t)bits;
+    h->group = (uint32_t)group;
+    h->reserved = 0;
+    h->N = N;
+    h->K = K;
+    h->qweight_bytes = q;
+    h->scales_bytes = s;
+    h->zeros_bytes = z;
+    return AWQ_OK;
+}
+
+extern "C" int awq_blob_header_check(const awq_blob_header *h)
+{
+    if (!h) return AWQ_ERR_NULL_POINTER;
+    awq_blob_header want;
+    const int st = awq_blob_header_init(&want, (int)h->bits, h->N, h->K, (int)h->group);
+    if (st != AWQ_OK) return st;
+    for (int i = 0; i < 8; ++i)
+        if (h->magic[i] != want.magic[i]) return AWQ_ERR_BAD_ARGUMENT;
+    if (h->layout_version != want.layout_version || h->reserved != 0 || h->qweight_bytes != want.qweight_bytes ||
+        h->scales_bytes != want.scales_bytes || h->zeros_bytes != want.zeros_bytes)
+        return AWQ_ERR_BAD_ARGUMENT;
+    return AWQ_OK;
+}
+
 namespace {
 
 // Read-only reference of the benchmark: every lane streams 16-byte words with a grid stride and

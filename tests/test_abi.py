@@ -320,6 +320,29 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert g(*args(wsb=need - 1)) == -5
 
 
+def test_blob_header_round_trip_and_refusals(lib):
+    import paper_2306_00978_amd as awq
+    assert ctypes.sizeof(awq.BlobHeader) == 64
+    for bits, N, K in ((4, 4096, 11008), (3, 176, 1408), (2, 64, 512)):
+        h = awq.awq_blob_header(bits, N, K)
+        assert h.magic == b"AWQgfx95" and h.layout_version == awq.awq_version() and h.bits == bits
+        sizes = {4: awq.awq_packed_sizes, 3: awq.awq_packed_sizes_w3, 2: awq.awq_packed_sizes_w2}[bits](N, K)
+        assert (h.qweight_bytes, h.scales_bytes, h.zeros_bytes) == tuple(sizes)
+        awq.awq_blob_header_check(h)
+        raw = bytes(h)
+        assert awq.awq_blob_header_check(awq.BlobHeader.from_buffer_copy(raw)) is None
+        for field, value in (("layout_version", 2), ("bits", 5), ("K", K + 1), ("qweight_bytes", 1), ("reserved", 7),
+                             ("magic", b"AWQgfx94")):
+            bad = awq.BlobHeader.from_buffer_copy(raw)
+            setattr(bad, field, value)
+            assert lib.awq_blob_header_check(ctypes.byref(bad)) < 0, field
+    h = awq.BlobHeader()
+    assert lib.awq_blob_header_init(ctypes.byref(h), 4, 100, 128, 128) == -2
+    assert lib.awq_blob_header_init(ctypes.byref(h), 5, 16, 128, 128) == -7
+    assert lib.awq_blob_header_init(None, 4, 16, 128, 128) == -1
+    assert lib.awq_blob_header_check(None) == -1
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     import paper_2306_00978_amd as awq

@@ -507,7 +507,7 @@ def test_multi_paired_plan_ragged_shapes(awq):
 
 # ------------------------------------------------------------------- the full stack (config 4)
 
-def test_config4_full_stack(awq):
+def test_config4_full_stack_calibration_128x512_rows_on_layer0_one_sequence_on_the_others(awq):
     """The 32-layer Llama-2-7B-shaped stack: one awq_quantize_pack pass over all 224 matrices
     (every packed byte, step and zero point against the oracle), then 128 decode steps at M = 1
     over the 224 linears, issued as grouped launches (even steps: 32 launches of one layer's 7
