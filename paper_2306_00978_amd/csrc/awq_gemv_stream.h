@@ -65,6 +65,9 @@ int awq_gemv_chain_launch(const GemvProblem *const *problems, const GemvFusedExt
                           int nstages, int M, uint32_t *sync, int spin_limit, hipStream_t stream);
 
 int awq_gemv_stream_launch(const GemvProblem *problems, int count, int M, hipStream_t stream);
+// grouped decode launch for more than four tokens: activations through LDS, any K
+int awq_gemv_rows_launch(const GemvProblem *problems, int count, int M, hipStream_t stream,
+                         const int *first_row = nullptr);
 // the same for linears in the 3-bit packed layout (q then points at 12-byte slots)
 int awq_gemv_stream_launch_w3(const GemvProblem *problems, int count, int M, hipStream_t stream);
 // the 4-bit launch with a normalisation in front of and/or a residual behind each linear; every

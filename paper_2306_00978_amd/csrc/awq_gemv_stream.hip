@@ -833,6 +833,322 @@ __global__ __launch_bounds__(512, 2) void chain_kernel(const ChainArgs A)
     }
 }
 
+
+// ---- decode kernel for more than four tokens (gemv_rows_kernel) -------------------------------------
+// With 5..16 tokens the register-resident activations of stream_body hold one or two batches per
+// wave, so eight waves have to share a row block and meet in LDS after every job, and K beyond
+// eight batches (the down projection) does not fit at all.  Here the activations go through LDS
+// instead, one chunk of 512 columns (= one batch of four groups) at a time:
+//   * a workgroup is two units of three compute waves and one loader wave, one workgroup per CU.
+//     A compute wave owns `iters` row blocks and keeps their sums in its registers;
+//   * the loader wave of a unit keeps the next two chunks of x (16 token rows x 1 KB each; rows
+//     beyond M repeat row M - 1) in its registers and writes chunk c + 1 into the other of the unit's
+//     two LDS buffers (rows 1040 bytes apart, so that the 16 lanes of a fragment read hit 16
+//     different bank groups) as soon as every compute wave of the unit has copied chunk c - 1 into
+//     its own registers; it also applies the factor 2^-4 to the halves that meet the codes in the
+//     high nibble positions and zeroes columns beyond K, so that the compute waves use the same
+//     fragments, the same constant-code MFMA for the row sums and the same consume_batch as
+//     stream_body;
+//   * a linear is planned in one of two ways.  Whole rows: the two units work on different row
+//     blocks (six per step of the workgroup) and each walks all chunks of K.  Split rows (for long
+//     K, where a whole row would be more jobs than a wave's share of the launch): both units work on
+//     the same three row blocks per step, unit 0 on the first half of the chunks and unit 1 on the
+//     rest; at the end unit 1 hands its sums over through LDS, behind the only barrier of the kernel;
+//   * the chunks of a unit are taken in cyclic order from a start that differs from workgroup to
+//     workgroup;
+//   * no barrier in the steady state: the loader publishes the number of the newest chunk in place
+//     in an LDS word and every compute wave the newest chunk whose fragments it has read into its
+//     registers; the loader overwrites a buffer once all three have read it, a compute wave reads a
+//     chunk once it is published.  The compute waves therefore never wait for each other, only
+//     (rarely) for the loader; a barrier per chunk held all of them to the pace of the slowest
+//     memory response.  The weight jobs run through each compute wave's private ring exactly as
+//     in stream_body (requested ahead, across chunk boundaries).
+// A-operand row m of the MFMA is token m.  Any K (a multiple of 128), 1 <= M <= 16.
+constexpr int ROWS_X_ROW = 1024 + 16;                  // bytes of one token row of a chunk in LDS
+constexpr int ROWS_MAX_ITERS = 8;
+constexpr int ROWS_CW = 3;                             // compute waves of a unit
+constexpr int ROWS_UNITS = 2;
+constexpr int ROWS_THREADS = 64 * ROWS_UNITS * (ROWS_CW + 1);
+// MR = token rows kept in LDS (8 or 16; tokens beyond M repeat token M - 1, and with MR = 8 the
+// MFMA rows 8..15 read the LDS rows 0..7 again).  Half the rows leave room for a fourth ring slot.
+template <int MR>
+struct RowsShape {
+    static constexpr int X_BUF = MR * ROWS_X_ROW;
+    static constexpr int RING = MR == 8 ? 4 : 3;       // ring slots per compute wave
+    static constexpr int UNIT_LDS = ROWS_CW * RING * Slot<4>::BYTES + 2 * X_BUF + 64;   // + the progress words
+    static constexpr int LDS = ROWS_UNITS * UNIT_LDS;
+    static_assert(ROWS_MAX_ITERS * 1024 <= RING * Slot<4>::BYTES, "the hand-over of the sums uses a wave's ring");
+    static_assert(LDS <= 160 * 1024, "one workgroup per CU");
+};
+
+template <int MR>
+__global__ __launch_bounds__(ROWS_THREADS) void gemv_rows_kernel(const GemvArgs<false> A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int ROWS_X_BUF = RowsShape<MR>::X_BUF, ROWS_RING = RowsShape<MR>::RING;
+    constexpr int ROWS_UNIT_LDS = RowsShape<MR>::UNIT_LDS;
+    constexpr int STAGE_BYTES = Slot<4>::BYTES, STAGE_SC = Slot<4>::SC, STAGE_ZP = Slot<4>::ZP;
+    constexpr int LOADS_PER_JOB = Slot<4>::LOADS;
+    typedef const __attribute__((address_space(1))) half_t gbl_half_t;
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(1))) u32x4_t gbl_u32x4_t;
+    uint32_t mask_lo = 0x000F000Fu, mask_hi = 0x00F000F0u;
+    asm("" : "+s"(mask_lo));
+    asm("" : "+s"(mask_hi));
+    const GemvLaunch &L = A.L;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int unit = wave >> 2, role = wave & 3;           // role 3 = loader
+    // the workgroup's entry of the launch table, fetched as in stream_body: lane l reads wg_begin[l]
+    // and entry l with vector loads, a ballot and readlanes pick the right one (one round trip)
+    GemvProblem P;
+    int wg0;
+    {
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        typedef const __attribute__((address_space(1))) u32x2_t gbl_u32x2_t;
+        typedef const __attribute__((address_space(1))) int gbl_int_t;
+        const unsigned char *ka = (const unsigned char *)__builtin_amdgcn_kernarg_segment_ptr();
+        const int le = lane < GEMV_MAX_PROBLEMS ? lane : GEMV_MAX_PROBLEMS - 1;
+        const int begin = *(gbl_int_t *)(uintptr_t)(ka + offsetof(GemvLaunch, wg_begin) + 4 * le);
+        gbl_u32x2_t *pe = (gbl_u32x2_t *)(uintptr_t)(ka + offsetof(GemvLaunch, p) + sizeof(GemvProblem) * le);
+        uint32_t f[14], g[14];
+#pragma unroll
+        for (int d = 0; d < 7; ++d) {
+            const u32x2_t t = pe[d];
+            f[2 * d] = t.x;
+            f[2 * d + 1] = t.y;
+        }
+        const uint64_t mine = __ballot(lane < GEMV_MAX_PROBLEMS && (int)blockIdx.x >= begin);
+        const int pi = __builtin_amdgcn_readfirstlane(__popcll(mine) - 1);
+#pragma unroll
+        for (int d = 0; d < 14; ++d) g[d] = __builtin_amdgcn_readlane(f[d], pi);
+        P.x = reinterpret_cast<const half_t *>(((uint64_t)g[1] << 32) | g[0]);
+        P.q = reinterpret_cast<const uint4 *>(((uint64_t)g[3] << 32) | g[2]);
+        P.sc = reinterpret_cast<const uint16_t *>(((uint64_t)g[5] << 32) | g[4]);
+        P.zp = reinterpret_cast<const uint8_t *>(((uint64_t)g[7] << 32) | g[6]);
+        P.y = reinterpret_cast<half_t *>(((uint64_t)g[9] << 32) | g[8]);
+        P.N = (int)g[10];
+        P.K = (int)g[11];
+        P.plan = (int)g[12];
+        P.nrb = (int)g[13];
+        wg0 = __builtin_amdgcn_readlane(begin, pi);
+    }
+    const int M = L.M, K = P.K, N = P.N, G = K >> 7, NRB = P.nrb, NB = (G + 3) >> 2;
+    const int iters = P.plan >> 8;
+    const bool split = (P.plan & 15) != 0;                 // rows split over the two units
+    const int m_first = (P.plan >> 4) & 15;                // token rows below this one are not written
+    const int rows_per_step = split ? ROWS_CW : ROWS_UNITS * ROWS_CW;
+    const int rb_first = ((int)blockIdx.x - wg0) * iters * rows_per_step + (split ? 0 : unit * ROWS_CW);
+    // the unit's chunks [c0, c0 + NC)
+    const int half_chunks = (NB + 1) >> 1;
+    const int c0 = split && unit ? half_chunks : 0;
+    const int NC = split ? (unit ? NB - half_chunks : half_chunks) : NB;
+    unsigned char *const usmem = smem + unit * ROWS_UNIT_LDS;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)usmem);
+    const uint32_t xbuf = lds0 + ROWS_CW * ROWS_RING * STAGE_BYTES;
+    gbl_half_t *px = (gbl_half_t *)(uintptr_t)P.x;
+    // Every workgroup walks its chunks of K in the same cyclic order but starts at a chunk of its
+    // own.  Started together at chunk 0 all workgroups would read, at any moment, the same 4 KB
+    // window of every row block (addresses a multiple of the row-block size apart), i.e. keep a
+    // fraction of the memory channels busy and leave the rest idle.
+    const int rot = NC > 0 ? (int)blockIdx.x % NC : 0;
+
+    // progress words: [0] newest chunk in place, [1 + w] newest chunk compute wave w has read
+    volatile int *flags = reinterpret_cast<volatile int *>(usmem + ROWS_CW * ROWS_RING * STAGE_BYTES + 2 * ROWS_X_BUF);
+    if (lane == 0) flags[role == ROWS_CW ? 0 : 1 + role] = -1;
+    lds_barrier();
+
+    floatx4 acc[ROWS_MAX_ITERS];
+#pragma unroll
+    for (int i = 0; i < ROWS_MAX_ITERS; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int r = lane & 15, c4 = lane >> 4;
+    const uint32_t lane16 = (uint32_t)lane << 4;
+    const uint32_t ring = lds0 + (uint32_t)role * (ROWS_RING * STAGE_BYTES);
+
+    if (role == ROWS_CW) {
+        // ---- loader wave: lane l owns the 16 bytes at column 8 l of a chunk, for the 16 token rows
+        uint4 regA[MR], regB[MR];
+        const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
+        auto fetch = [&](uint4 (&reg)[MR], int step) {
+            const int chunk = c0 + (step + rot < NC ? step + rot : step + rot - NC);
+            int col = chunk * 512 + lane * 8;
+            col = col < K ? col : K - 8;                           // beyond K: any valid address
+#pragma unroll
+            for (int m = 0; m < MR; ++m) {
+                const int row = m < M ? m : M - 1;
+                reg[m] = __builtin_bit_cast(uint4, *(gbl_u32x4_t *)(px + (size_t)row * K + col));
+            }
+        };
+        auto store = [&](const uint4 (&reg)[MR], int step) {
+            const int chunk = c0 + (step + rot < NC ? step + rot : step + rot - NC);
+            // step goes where step - 2 was: every compute wave must have read step - 2
+            for (;;) {
+                int slowest = flags[1];
+#pragma unroll
+                for (int w = 1; w < ROWS_CW; ++w) slowest = min(slowest, flags[1 + w]);
+                if (slowest >= step - 2) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            const bool valid = chunk * 512 + lane * 8 < K;
+            unsigned char *dst = usmem + ROWS_CW * ROWS_RING * STAGE_BYTES + (step & 1) * ROWS_X_BUF + lane * 16;
+#pragma unroll
+            for (int m = 0; m < MR; ++m) {
+                uint4 v = reg[m];
+                v.y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, v.y) * sixteenth);
+                v.w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, v.w) * sixteenth);
+                if (!valid) v = make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4 *>(dst + m * ROWS_X_ROW) = v;
+            }
+            // LDS operations of a wave are carried out in order: the word follows the data
+            asm volatile("" ::: "memory");
+            if (lane == 0) flags[0] = step;
+        };
+        if (NC > 0) fetch(regA, 0);
+        if (NC > 1) fetch(regB, 1);
+        for (int c = 0; c < NC; c += 2) {
+            store(regA, c);
+            if (c + 2 < NC) fetch(regA, c + 2);
+            if (c + 1 < NC) {
+                store(regB, c + 1);
+                if (c + 3 < NC) fetch(regB, c + 3);
+            }
+        }
+    } else {
+        // ---- compute waves
+        const int zshift = (r & 1) * 4;
+        const unsigned char *qbase = reinterpret_cast<const unsigned char *>(P.q);
+        const unsigned char *scbase = reinterpret_cast<const unsigned char *>(P.sc);
+        const unsigned char *zpbase = reinterpret_cast<const unsigned char *>(P.zp);
+        const uint32_t sc_lane = (uint32_t)(lane & 3) * 32 + (uint32_t)(lane >> 2) * 2;
+        const uint32_t zp_lane = (uint32_t)(lane & 3) * 8 + (uint32_t)((lane >> 2) & 7);
+        const bool ragged = (G & 3) != 0;
+        auto issue = [&](int it, int b, int slot) {
+            int rb = rb_first + it * rows_per_step + role;
+            rb = rb < NRB ? rb : NRB - 1;                       // surplus waves redo the last block
+            const size_t t0 = (size_t)rb * G + (size_t)b * 4;
+            const uint32_t dst = ring + (uint32_t)slot * STAGE_BYTES;
+            const unsigned char *tq = qbase + t0 * 1024, *ts = scbase + t0 * 32, *tz = zpbase + t0 * 8;
+            if (!ragged || b * 4 + 4 <= G) {
+                dma16_to_lds<0>(tq + lane16, dst);
+                dma16_to_lds<1024>(tq + lane16, dst);
+                dma16_to_lds<2048>(tq + lane16, dst);
+                dma16_to_lds<3072>(tq + lane16, dst);
+                dma2_to_lds(ts + sc_lane, dst + STAGE_SC);
+                if (lane < 32) dma1_to_lds(tz + zp_lane, dst + STAGE_ZP);
+            } else {
+                const int last = G - 1 - b * 4;                 // last valid group of this batch (0..2)
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    dma16_to_lds<0>(tq + ((size_t)min(u, last) << 10) + lane16, dst + u * 1024);
+                const int gl = min(lane & 3, last);
+                dma2_to_lds(ts + gl * 32 + (lane >> 2) * 2, dst + STAGE_SC);
+                if (lane < 32) dma1_to_lds(tz + gl * 8 + ((lane >> 2) & 7), dst + STAGE_ZP);
+            }
+        };
+        // jobs in the order (chunk, row block): job j = chunk j / iters, row block j % iters
+        const int J = NC * iters;
+        int nj = 0, nit = 0, nb = 0, nslot = 0;
+        auto issue_next = [&]() {
+            issue(nit, c0 + (nb + rot < NC ? nb + rot : nb + rot - NC), nslot);
+            ++nj;
+            if (++nslot == ROWS_RING) nslot = 0;
+            if (++nit == iters) { nit = 0; ++nb; }
+        };
+#pragma unroll
+        for (int t = 0; t < ROWS_RING - 1; ++t)
+            if (nj < J) issue_next();
+
+        const half8_t ones = __builtin_bit_cast(half8_t, make_uint4(0x00010001u, 0x00100010u, 0x00010001u, 0x00100010u));
+        const uint32_t rd_tile = ring + lane16, rd_sc = ring + 16 * r, rd_zp = ring + 16 * (r >> 1);
+        const uint32_t rd_x = xbuf + (uint32_t)(r & (MR - 1)) * ROWS_X_ROW + (uint32_t)c4 * 16;
+        int cslot = 0, j = 0;
+        for (int c = 0; c < NC; ++c) {
+            while (flags[0] < c) __builtin_amdgcn_s_sleep(1);
+            // fragments of this chunk: token r, columns 128 u + 32 j + 8 c4 + 0..7
+            uint4 xa[16];
+            {
+                const uint32_t xaddr = rd_x + (uint32_t)(c & 1) * ROWS_X_BUF;
+                asm volatile(
+                    "ds_read_b128 %0, %16\n\tds_read_b128 %1, %16 offset:64\n\tds_read_b128 %2, %16 offset:128\n\t"
+                    "ds_read_b128 %3, %16 offset:192\n\tds_read_b128 %4, %16 offset:256\n\tds_read_b128 %5, %16 offset:320\n\t"
+                    "ds_read_b128 %6, %16 offset:384\n\tds_read_b128 %7, %16 offset:448\n\tds_read_b128 %8, %16 offset:512\n\t"
+                    "ds_read_b128 %9, %16 offset:576\n\tds_read_b128 %10, %16 offset:640\n\tds_read_b128 %11, %16 offset:704\n\t"
+                    "ds_read_b128 %12, %16 offset:768\n\tds_read_b128 %13, %16 offset:832\n\tds_read_b128 %14, %16 offset:896\n\t"
+                    "ds_read_b128 %15, %16 offset:960\n\ts_waitcnt lgkmcnt(0)"
+                    : "=&v"(xa[0]), "=&v"(xa[1]), "=&v"(xa[2]), "=&v"(xa[3]), "=&v"(xa[4]), "=&v"(xa[5]), "=&v"(xa[6]),
+                      "=&v"(xa[7]), "=&v"(xa[8]), "=&v"(xa[9]), "=&v"(xa[10]), "=&v"(xa[11]), "=&v"(xa[12]), "=&v"(xa[13]),
+                      "=&v"(xa[14]), "=&v"(xa[15])
+                    : "v"(xaddr)
+                    : "memory");
+                if (lane == 0) flags[1 + role] = c;             // read: the loader may reuse the buffer
+            }
+            floatx4 xsum[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                floatx4 t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    t = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa[4 * u + jj]), ones, t, 0, 0, 0);
+                xsum[u] = t;
+            }
+#pragma unroll
+            for (int it = 0; it < ROWS_MAX_ITERS; ++it) {
+                if (it < iters) {
+                    if (nj < J) issue_next();
+                    const int later = nj - j - 1;               // jobs requested after the one now due
+                    if (ROWS_RING > 3 && later >= 3) wait_loads<3 * LOADS_PER_JOB>();
+                    else if (later >= 2) wait_loads<2 * LOADS_PER_JOB>();
+                    else if (later == 1) wait_loads<LOADS_PER_JOB>();
+                    else wait_loads<0>();
+                    Landed cur;
+                    const uint32_t off = (uint32_t)cslot * STAGE_BYTES;
+                    read_slot(cur, rd_tile + off, rd_sc + off, rd_zp + off);
+                    if (++cslot == ROWS_RING) cslot = 0;
+                    const floatx4 b = consume_batch(cur, xa, xsum, mask_lo, mask_hi, zshift);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[it][v] += b[v];
+                    ++j;
+                }
+            }
+        }
+    }
+    if (split) {
+        // unit 1 hands its sums to the wave of unit 0 with the same row blocks; every job of the ring
+        // has been consumed, so the ring is free to carry them
+        if (unit == 1 && role < ROWS_CW) {
+#pragma unroll
+            for (int it = 0; it < ROWS_MAX_ITERS; ++it)
+                if (it < iters) *reinterpret_cast<floatx4 *>(usmem + role * (ROWS_RING * STAGE_BYTES) + it * 1024 + lane * 16) = acc[it];
+        }
+        lds_barrier();
+        if (unit == 1) return;
+        if (role < ROWS_CW) {
+            const unsigned char *other = smem + ROWS_UNIT_LDS + role * (ROWS_RING * STAGE_BYTES);
+#pragma unroll
+            for (int it = 0; it < ROWS_MAX_ITERS; ++it)
+                if (it < iters) {
+                    const floatx4 o = *reinterpret_cast<const floatx4 *>(other + it * 1024 + lane * 16);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[it][v] += o[v];
+                }
+        }
+    }
+    if (role == ROWS_CW) return;
+    // lane (r, c4) holds tokens 4 c4 + v of column r of each of its row blocks
+    __attribute__((address_space(1))) half_t *py = (__attribute__((address_space(1))) half_t *)(uintptr_t)P.y;
+#pragma unroll
+    for (int it = 0; it < ROWS_MAX_ITERS; ++it) {
+        const int rbo = rb_first + it * rows_per_step + role;
+        if (it < iters && rbo < NRB) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = 4 * c4 + v;
+                if (m >= m_first && m < M) py[(size_t)m * N + rbo * 16 + r] = (half_t)acc[it][v];
+            }
+        }
+    }
+}
+
 int ceil_log2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 }  // namespace
@@ -1218,6 +1534,109 @@ int awq_gemv_chain_launch(const GemvProblem *const *problems, const GemvFusedExt
         grid = std::max(grid, wg);
     }
     chain_kernel<<<dim3(grid), dim3(W * 64), lds, stream>>>(A);
+    return awq_launch_status();
+}
+
+
+// Plans and launches gemv_rows_kernel for `count` linears (any K).  A workgroup takes three row blocks
+// x iters.  Where it works out the paired plan of the streaming kernel is used (two sizes of
+// workgroup per linear, 512 in all, heavy ones paired with light ones on a CU); otherwise one size
+// per linear, chosen so that a compute wave's jobs come close to its share of 512 workgroups.
+// Plan of gemv_rows_kernel.  One workgroup per CU, so at most 256 workgroups; per linear one way
+// of cutting it (whole or split rows, 1..4 row-block steps per workgroup).  A wave's run time is
+// about (jobs) x (time per job), and the time per job falls with the steps per workgroup, because
+// the cost of taking a chunk of x out of LDS is shared by that many jobs (measured: 1.5 us per job
+// with one step, 0.9 us with three).  The plan is the one with the smallest largest such estimate
+// among those with at most 256 workgroups.
+//
+// first_row (optional): per linear, the first token row whose outputs are written.  The sums are
+// taken chunk by chunk in an order that differs between workgroups, so two linears that share
+// weights and tokens need not agree in the last bit: a caller that lets token blocks overlap names
+// here the rows that the block in front has already written.
+int awq_gemv_rows_launch(const GemvProblem *problems, int count, int M, hipStream_t stream, const int *first_row)
+{
+    if (count < 1 || count > GEMV_MAX_PROBLEMS || M < 1 || M > 16) return AWQ_ERR_BAD_ARGUMENT;
+    struct Option {
+        int split, iters, wgs;
+        double cost;
+    };
+    constexpr int MAX_OPTIONS = 2 * ROWS_MAX_ITERS;
+    static const double per_job = awq_knob("AWQ_ROWS_COST_JOB", 850) * 1e-3;
+    static const double per_chunk = awq_knob("AWQ_ROWS_COST_CHUNK", 650) * 1e-3;
+    Option options[GEMV_MAX_PROBLEMS][MAX_OPTIONS];
+    int n_options[GEMV_MAX_PROBLEMS];
+    double caps[GEMV_MAX_PROBLEMS * MAX_OPTIONS];
+    int n_caps = 0;
+    for (int i = 0; i < count; ++i) {
+        const int NB = (problems[i].K / 128 + 3) / 4, NRB = problems[i].N / 16;
+        n_options[i] = 0;
+        for (int split = 0; split < (NB >= 2 ? 2 : 1); ++split) {
+            const int rows = split ? ROWS_CW : ROWS_UNITS * ROWS_CW;
+            const int steps = (NRB + rows - 1) / rows;
+            const int chunks = split ? (NB + 1) / 2 : NB;
+            for (int iters = 1; iters <= std::min(ROWS_MAX_ITERS, steps); ++iters) {
+                const Option o = {split, iters, (steps + iters - 1) / iters, chunks * (iters * per_job + per_chunk)};
+                options[i][n_options[i]++] = o;
+                caps[n_caps++] = o.cost;
+            }
+        }
+    }
+    std::sort(caps, caps + n_caps);
+    Option chosen[GEMV_MAX_PROBLEMS];
+    for (int c = 0; c < n_caps; ++c) {
+        int total = 0;
+        bool ok = true;
+        for (int i = 0; i < count && ok; ++i) {
+            int best = -1;
+            for (int o = 0; o < n_options[i]; ++o) {
+                const Option &t = options[i][o];
+                if (t.cost > caps[c]) continue;
+                if (best < 0 || t.wgs < options[i][best].wgs ||
+                    (t.wgs == options[i][best].wgs && t.cost < options[i][best].cost))
+                    best = o;
+            }
+            if (best < 0) ok = false;
+            else {
+                chosen[i] = options[i][best];
+                total += chosen[i].wgs;
+            }
+        }
+        // beyond one workgroup per CU the rest waits for a second round; the last candidate (the
+        // fewest workgroups there are) is taken whatever their number
+        if (ok && (total <= 256 || c == n_caps - 1)) break;
+    }
+    GemvArgs<false> A{};
+    GemvLaunch &L = A.L;
+    for (int i = 0; i < GEMV_MAX_PROBLEMS; ++i) L.wg_begin[i] = 0x7fffffff;
+    L.count = count;
+    L.M = M;
+    L.mlog = 4;
+    L.logW = 2;
+    int order[GEMV_MAX_PROBLEMS];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    std::stable_sort(order, order + count, [&](int a, int b) { return chosen[a].cost > chosen[b].cost; });
+    int wg = 0;
+    for (int e = 0; e < count; ++e) {
+        GemvProblem p = problems[order[e]];
+        const int skip = first_row ? std::max(0, std::min(15, first_row[order[e]])) : 0;
+        p.plan = chosen[order[e]].split | (skip << 4) | (chosen[order[e]].iters << 8);
+        p.nrb = p.N / 16;
+        L.wg_begin[e] = wg;
+        L.p[e] = p;
+        wg += chosen[order[e]].wgs;
+    }
+    static AwqOncePerDevice once;
+    std::atomic<bool> &attr_set = once.here();
+    if (!attr_set.load(std::memory_order_relaxed)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_rows_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, RowsShape<8>::LDS) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_rows_kernel<16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, RowsShape<16>::LDS) != hipSuccess)
+            return AWQ_ERR_HIP;
+        attr_set.store(true, std::memory_order_relaxed);
+    }
+    if (M <= 8) gemv_rows_kernel<8><<<dim3(wg), dim3(ROWS_THREADS), RowsShape<8>::LDS, stream>>>(A);
+    else gemv_rows_kernel<16><<<dim3(wg), dim3(ROWS_THREADS), RowsShape<16>::LDS, stream>>>(A);
     return awq_launch_status();
 }
 

@@ -36,6 +36,10 @@ extern "C" size_t awq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, in
     return ks > 1 ? (size_t)ks * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
+namespace {
+int grouped_decode(const awq_linear_desc *descs, int count, int64_t M, int group, void *stream, bool token_blocks);
+}
+
 extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const void *scales,
                                 const void *zeros, void *y_f16, int64_t M, int64_t N,
                                 int64_t K, int group, void *workspace, size_t workspace_bytes,
@@ -78,9 +82,9 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
     // once per block (the repeats come from cache) but keeps the whole chip busy, all blocks in one
     // grouped launch where the shape allows it.  The last block is moved back so that it has 16
     // tokens too; the tokens it shares with its neighbour are computed twice, bit for bit alike.
-    // (4096 x 4096: 43 us -> 12-19 us for 17..128 tokens; 4096 x 11008: 105 us -> 20-72 us -- that
-    // shape does not fit the grouped launch, and from 49 tokens on the prefill kernel with K cut
-    // into ranges is faster when the caller brings its workspace: 36 us.)
+    // (4096 x 4096: 43 us -> 9-18 us for 17..128 tokens; 4096 x 11008: 105 us -> 20-43 us; when the
+    // caller brings its workspace, the prefill kernel with K cut into ranges takes over from 49
+    // tokens on: 36 us for that shape.)
     static const int small_env = awq_knob("AWQ_SMALL_M_MAX", -1);
     const int64_t small_max = small_env >= 0 ? std::min(small_env, 128) : 128;
     if (M <= small_max && !split) {
@@ -96,7 +100,7 @@ extern "C" int awq_w4a16_linear(const void *x_f16, const void *qweight, const vo
             d[b].N = N;
             d[b].K = K;
         }
-        return awq_w4a16_linear_multi(d, blocks, 16, group, nullptr, 0, stream);
+        return grouped_decode(d, blocks, 16, group, stream, true);
     }
     if (split)
         return awq_gemm_launch_split(x_f16, qweight, scales, zeros, y_f16, (int)M, (int)N, (int)K, workspace,
@@ -159,6 +163,15 @@ extern "C" int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, i
                                       void *workspace, size_t workspace_bytes, void *stream)
 {
     (void)workspace; (void)workspace_bytes;
+    return grouped_decode(descs, count, M, group, stream, false);
+}
+
+namespace {
+
+// The grouped decode call.  token_blocks: the linears are blocks of 16 tokens of ONE linear (the
+// call comes from awq_w4a16_linear for 17..128 tokens), so the weights are the same for all.
+int grouped_decode(const awq_linear_desc *descs, int count, int64_t M, int group, void *stream, bool token_blocks)
+{
     if (!descs) return AWQ_ERR_NULL_POINTER;
     if (count < 1 || count > AWQ_MULTI_MAX) return AWQ_ERR_BAD_ARGUMENT;
     if (M <= 0 || M > 16) return AWQ_ERR_BAD_SHAPE;
@@ -178,6 +191,24 @@ extern "C" int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, i
         p[i].y = (half_t *)d.y_f16;
         p[i].N = (int)d.N;
         p[i].K = (int)d.K;
+    }
+    // More than four tokens: the kernel that takes the activations through LDS (any K) runs all
+    // linears of the call in one launch.  A lone linear goes there only when it has row blocks
+    // enough for every CU (measured at N = 32000, K = 4096, 16 tokens: 21.5 us against 41 us); a
+    // smaller one stays with the batch kernel, where everything requested at once is the faster way
+    // through a small matrix (N = 4096, K = 11008: 10 us against 20 us).  Token blocks of one linear
+    // go there from 40 M weights on (4096 x 11008 at 128 tokens: 43 us against 70 us; 4096 x 4096 is
+    // faster the other way, 9 us against 11 us at 32 tokens).
+    static const int rows_min_count = awq_knob("AWQ_ROWS_MIN_COUNT", 2);
+    const bool rows = token_blocks ? (int64_t)p[0].N * p[0].K >= (int64_t)40 << 20
+                                   : (count >= rows_min_count || p[0].N >= 16384);
+    if (M > 4 && rows) {
+        // the last token block is moved back over its neighbour; the rows they share are written
+        // by the neighbour alone
+        int first_row[GEMV_MAX_PROBLEMS] = {};
+        if (token_blocks && count > 1)
+            first_row[count - 1] = (int)((p[count - 2].y + 16 * (size_t)p[0].N - p[count - 1].y) / p[0].N);
+        return awq_gemv_rows_launch(p, count, (int)M, (hipStream_t)stream, first_row);
     }
     // The linears whose K fits the register-resident activations of the streaming kernel at
     // this M go out in one launch; the others (and a lone linear) take one launch of the batch
@@ -212,6 +243,8 @@ extern "C" int awq_w4a16_linear_multi(const awq_linear_desc *descs, int count, i
     }
     return AWQ_OK;
 }
+
+}  // namespace
 
 namespace {
 

@@ -454,9 +454,10 @@ def test_multi_llama7b_layer_full_size(awq):
 
 def test_multi_llama70b_shapes_full_size(awq):
     """Llama-2-70B-shaped linears (config 3) through the grouped call at M = 1 and 8, two shapes at
-    a time to bound host memory.  K = 28672 needs four waves along K at M = 1 and does not fit
-    the register slots at M = 8 (the call then runs one launch per linear): both paths are
-    checked against the oracle."""
+    a time to bound host memory.  K = 28672 needs four waves along K at M = 1; at M = 8 the call
+    runs the kernel that stages the activations through LDS (rows split over the two halves of a
+    workgroup, up to eight row-block steps per workgroup): both paths are checked against the
+    oracle."""
     pairs = [((8192, 8192), (1024, 8192)), ((28672, 8192), (1024, 8192)), ((8192, 28672), (1024, 8192))]
     for a, b in pairs:
         probs = []
@@ -622,6 +623,39 @@ def test_config4_full_stack_calibration_128x512_rows_on_layer0_one_sequence_on_t
     for check in canaries:                                      # the decode steps wrote nothing there
         check()
     print(f"config 4: worst normalised error over steps {check_steps}: {worst:.3e}")
+
+
+def test_multi_more_than_four_tokens_ragged_shapes(awq):
+    """5..16 tokens: the grouped call stages the activations through LDS.  Row-block counts that
+    are no multiple of the three or six a workgroup takes per step (down to a single block),
+    ragged group counts, K from one chunk of 512 columns to 56 chunks (whole rows and rows split
+    over the two halves of a workgroup), a lone wide linear: every output against the oracle,
+    canaries around the outputs, and bit-identical on a second call."""
+    import torch
+    import oracle
+    g = np.random.default_rng(47)
+    shapes = [(4112, 4096), (2064, 4096), (1040, 8192), (4112, 1408), (3088, 11008), (272, 28672), (16, 4096),
+              (32, 512), (80, 384)]
+    probs = []
+    for N, K in shapes + [(16400, 640)]:
+        codes = g.integers(0, 16, size=(N, K), dtype=np.uint8)
+        scales = g.uniform(0.002, 0.02, size=(N, K // 128)).astype(np.float16)
+        zeros = g.integers(0, 16, size=(N, K // 128), dtype=np.uint8)
+        q, sp, zp = oracle.pack(codes, scales, zeros)
+        xs = g.standard_normal((16, K)).astype(np.float16)
+        probs.append((xs, oracle.dequant(codes, scales, zeros), (dev(q), dev(sp.view(np.float16)), dev(zp)), N))
+        del codes
+    wide = probs.pop()
+    for M in (5, 8, 9, 16):
+        check_multi(awq, probs, M)
+        check_multi(awq, [wide], M)
+    check_multi(awq, probs[-3:], 13)                              # a launch of a few workgroups
+    linears = [(dev(xs[:11]), *gpu, torch.empty((11, N), dtype=torch.float16, device="cuda"), N)
+               for xs, Wdq, gpu, N in probs]
+    first = [host(y).copy() for y in awq.awq_w4a16_linear_multi(linears)]
+    second = [host(y).copy() for y in awq.awq_w4a16_linear_multi(linears)]
+    for a, b in zip(first, second):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
 
 
 @pytest.mark.parametrize("overrides", [
