@@ -3,9 +3,10 @@
 * the C oracle: built with gcc's sanitizers, and its whole pin suite (tests/test_oracle_*.py) run
   against that build in a child process that has gcc's libasan preloaded;
 * the C-ABI library: its host pass (validation, planners, argument marshalling) built with the HIP
-  compiler's sanitizers, device code as always, and tests/test_abi.py run against that build in a
-  child process that has the compiler's ASan runtime preloaded.  No GPU is involved: the ABI tests
-  only reach code that returns before any launch.
+  compiler's sanitizers, device code as always, and tests/test_abi.py (code that returns before
+  any launch) and tests/test_host_planners.py (every planner and launch table, up to the launch
+  that fails for want of a device) run against that build in a child process that has the
+  compiler's ASan runtime preloaded.  No GPU is involved.
 Any report of either sanitizer ends the child with a non-zero status."""
 import glob
 import os
@@ -48,7 +49,8 @@ def test_c_abi_validation_layer_under_asan_and_ubsan(tmp_path):
     lib = hip_build.build(sanitize_host_into=str(tmp_path))
     runtime = hip_build.sanitizer_runtime()
     p = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                        os.path.join(ROOT, "tests", "test_abi.py")],
+                        os.path.join(ROOT, "tests", "test_abi.py"),
+                        os.path.join(ROOT, "tests", "test_host_planners.py")],
                        cwd=ROOT, env=_child_env(runtime, AWQ_MI355X_LIBRARY=lib),
                        capture_output=True, text=True, timeout=1200)
     assert p.returncode == 0, (p.stdout[-3000:], p.stderr[-3000:])
