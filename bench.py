@@ -452,10 +452,13 @@ def main():
     if "modes" in legs:
         w, e, n = time_decode("single", 1, msteps, mwarm, False)
         wg_, eg_, _ = time_decode("single", 1, msteps, mwarm, True)
+        w2s, e2s, _ = time_decode("single", 1, msteps, mwarm, False, streams=max(2, args.streams))
         result["config"]["per_launch_mode"] = {
             "what": "seven awq_w4a16_linear calls per layer (gemv_kernel), same cycling",
             "launches_per_step": n,
             "on_the_stream": {"us_per_layer": round(e * 1e3 / L, 2), "GB/s": gbs(bytes_step, e), "pct_of_hbm_peak": pct(gbs(bytes_step, e))},
+            "alternating_over_streams": {"streams": max(2, args.streams), "us_per_layer": round(e2s * 1e3 / L, 2),
+                                         "GB/s": gbs(bytes_step, e2s), "pct_of_hbm_peak": pct(gbs(bytes_step, e2s))},
             "graph_replay": {"us_per_layer": round(eg_ * 1e3 / L, 2), "GB/s": gbs(bytes_step, eg_), "pct_of_hbm_peak": pct(gbs(bytes_step, eg_))}}
         w, e, n = time_decode("fused", 1, msteps, mwarm, True)
         result["config"]["dependent_launch_mode"] = {

@@ -373,8 +373,9 @@ def awq_unpack(qweight, scales, zeros, N: int, K: int, group: int = GROUP):
 
 def prepare_linear(x: torch.Tensor, qweight, scales, zeros, y: torch.Tensor, N: int,
                    group: int = GROUP, workspace: torch.Tensor | None = None):
-    """Marshal the arguments of awq_w4a16_linear once and return a zero-argument callable
-    that enqueues the layer on the then-current stream (tight decode loops, graph capture).
+    """Marshal the arguments of awq_w4a16_linear once and return a callable that enqueues the
+    layer on the then-current stream, or on the raw stream handle passed to it (tight decode
+    loops, graph capture).
     The tensors must stay alive and in place for as long as the callable is used."""
     _dev(x, torch.float16, "x")
     _dev(y, torch.float16, "y")
@@ -396,8 +397,8 @@ def prepare_linear(x: torch.Tensor, qweight, scales, zeros, y: torch.Tensor, N: 
              c.c_size_t(workspace.numel() * workspace.element_size() if use_ws else 0))
     keep = (x, qweight, scales, zeros, y, workspace)
 
-    def call(_keep=keep):
-        st = fn(*fixed, c.c_void_p(torch.cuda.current_stream().cuda_stream))
+    def call(stream=None, _keep=keep):
+        st = fn(*fixed, c.c_void_p(torch.cuda.current_stream().cuda_stream if stream is None else stream))
         if st != 0:
             raise AwqError(st, "awq_w4a16_linear")
     return call
