@@ -10,7 +10,7 @@ Function names and argument order mirror the C ABI:
     awq_rmsnorm_inv_scale                         (Sec. 4.2 fused normalisation with the 1/s of Eq. 4)
     awq_quantize_pack, awq_unpack                 (Sec. 3.2, Eq. 1-2; Sec. 4.2 packing)
     awq_w4a16_linear, awq_w4a16_linear_multi      (Sec. 4.2 fused dequantization, kernel fusion)
-    awq_search_scale                              (Sec. 3.2 searching to scale, Eq. 4-5)
+    awq_search_scale                              (Sec. 3.2, the search for the scale, Eq. 4-5)
     awq_quantize_pack_clip                        (Sec. 3.2 weight clipping)
     awq_decode_attention                          (Sec. 4.2 fused attention: rotary embedding, cache update)
     awq_*_w3                                      (Sec. 5, INT3-g128 variant: quantize, unpack, decode)
