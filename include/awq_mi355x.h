@@ -400,8 +400,8 @@ int awq_w2a16_linear(const void *x_f16, const void *qweight, const void *scales,
 int awq_w2a16_linear_multi(const awq_linear_desc *descs, int count, int64_t M, int group,
                            void *stream);
 
-/* ---- decode attention (Sec. 4.2 "Kernel fusion": positional embedding computed on the fly,
- * pre-allocated KV caches updated inside the attention kernel) --------------------------
+/* ---- decode attention (Sec. 4.2, kernel fusion: the kernel evaluates the position embedding
+ * itself and writes the new key and value into caches allocated ahead) -------------------
  * One decode step of one sequence.  q [H,D], k, v [Hkv,D] fp16: the projections of the token at
  * position pos (0-based).  k_cache, v_cache [Hkv][Lmax][D] fp16, pre-allocated by the caller,
  * rows < pos filled by earlier calls.  The call rotates q and k by the rotary embedding of pos

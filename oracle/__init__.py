@@ -426,8 +426,8 @@ def unpack_w2(qweight, scales_p, zeros_p, N: int, K: int, group: int = GROUP_W2)
 
 def rope_rotate(x, pos: int, theta: float = 10000.0) -> np.ndarray:
     """Rotary position embedding of x [..., D] (fp64): the pairs (i, i + D/2) are rotated by the
-    angle pos * theta^(-2 i / D) (the half-split pairing of Llama-style models; the paper only
-    says the positional embedding is computed on the fly inside the attention kernel)."""
+    angle pos * theta^(-2 i / D) (the half-split pairing of Llama-style models; Sec. 4.2 only
+    says that the attention kernel evaluates the position embedding itself)."""
     x = np.asarray(x, dtype=np.float64)
     D = x.shape[-1]
     i = np.arange(D // 2, dtype=np.float64)
@@ -438,7 +438,7 @@ def rope_rotate(x, pos: int, theta: float = 10000.0) -> np.ndarray:
 
 
 def decode_attention(q, k, v, k_cache, v_cache, pos: int, theta: float = 10000.0):
-    """Sec. 4.2 "Kernel fusion" (attention): one decode step of one sequence.  q [H,D], k, v
+    """Sec. 4.2, kernel fusion (attention): one decode step of one sequence.  q [H,D], k, v
     [Hkv,D] fp16 are the projections of the token at position pos; k_cache, v_cache
     [Hkv,Lmax,D] fp16 hold the rotated keys and the values of positions < pos.  Rotates q and k,
     stores fp16(k_rot) and v in row pos of the caches (returned as new arrays), and returns

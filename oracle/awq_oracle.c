@@ -132,8 +132,8 @@ int awq_oracle_apply_inv_scale(const uint16_t *x, const float *s, int64_t M,
  * codes  [N,K] one code per byte, 0..15
  * scales [N,G] binary16 bits, G = K/128
  * zeros  [N,G] one zero point per byte, 0..15                                   */
-/* ---------- normalisation fused with the inverse scale (Sec. 4.2 "Kernel fusion": all
- * operators of the layer normalisation in one kernel; Sec. 3.2: the diag(s)^-1 factor of Eq. 4
+/* ---------- normalisation fused with the inverse scale (Sec. 4.2, kernel fusion: the
+ * operators of a layer normalisation as one kernel; Sec. 3.2: the diag(s)^-1 factor of Eq. 4
  * belongs to the operator that produces x).  RMS form, as the Llama-2-shaped layers
  * of the workloads use it:
  *   xs[m,k] = fp16( x[m,k] / sqrt(mean_k x[m,k]^2 + eps) * gamma[k] / s[k] ),  binary64 inside.

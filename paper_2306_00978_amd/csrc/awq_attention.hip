@@ -1,7 +1,7 @@
 // awq_decode_attention for gfx950: one decode step of the attention layer.
 //
-// AWQ Sec. 4.2, "Kernel fusion": the positional embedding is computed on the fly inside the
-// attention kernel, the KV caches are pre-allocated and updated by the same kernel.  One call
+// Sec. 4.2, kernel fusion: the attention kernel evaluates the position embedding itself and
+// writes the new key and value into caches that were allocated ahead.  One call
 // takes the q, k, v rows the (fused) QKV projection produced for the current token, rotates q
 // and k by the rotary embedding of the token's position, stores the rotated key and the value
 // in the caches, and returns softmax(q K^T / sqrt(D)) V over all positions so far.
