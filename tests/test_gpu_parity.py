@@ -266,8 +266,11 @@ def test_decode_every_m(awq, small, M):
 @pytest.mark.parametrize("M", [24, 100])
 def test_small_prefill_full_size_blocks_of_16(awq, M):
     """17..128 tokens run through the decode kernels in blocks of 16 (the last block moved back):
-    full-size shapes, every row against the oracle, twice bit for bit alike."""
-    for N, K in [(4096, 4096), (4096, 11008)]:
+    full-size shapes (4096 x 4096 through the register-resident kernel, the two larger ones through
+    the kernel that stages the activations in LDS, where the rows the last block shares with its
+    neighbour are written by the neighbour alone), every row against the oracle, twice bit for bit
+    alike."""
+    for N, K in [(4096, 4096), (4096, 11008), (11008, 4096)]:
         case, s, xs16, ref, gpu, Wdq = config_case(awq, N, K, 0.02, 1)
         g = np.random.default_rng(M)
         xs = (np.tile(xs16, ((M + 15) // 16, 1))[:M].astype(np.float32)
