@@ -1538,12 +1538,9 @@ int awq_gemv_chain_launch(const GemvProblem *const *problems, const GemvFusedExt
 }
 
 
-// Plans and launches gemv_rows_kernel for `count` linears (any K).  A workgroup takes three row blocks
-// x iters.  Where it works out the paired plan of the streaming kernel is used (two sizes of
-// workgroup per linear, 512 in all, heavy ones paired with light ones on a CU); otherwise one size
-// per linear, chosen so that a compute wave's jobs come close to its share of 512 workgroups.
-// Plan of gemv_rows_kernel.  One workgroup per CU, so at most 256 workgroups; per linear one way
-// of cutting it (whole or split rows, 1..4 row-block steps per workgroup).  A wave's run time is
+// Plans and launches gemv_rows_kernel for `count` linears (any K).  One workgroup per CU, so at most
+// 256 workgroups; per linear one way of cutting it (whole or split rows, 1..ROWS_MAX_ITERS row-block
+// steps per workgroup).  A wave's run time is
 // about (jobs) x (time per job), and the time per job falls with the steps per workgroup, because
 // the cost of taking a chunk of x out of LDS is shared by that many jobs (measured: 1.5 us per job
 // with one step, 0.9 us with three).  The plan is the one with the smallest largest such estimate
