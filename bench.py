@@ -1031,7 +1031,7 @@ def cpu_baseline(W0, calib_by_k, x_by_k, shapes):
     xs = {K: x_by_k[K][:1].cpu().numpy() for K in x_by_k}
     bytes_step = sum(workloads.algorithmic_bytes(1, N, K) for _, N, K in shapes)
     reps, t_total = 0, 0.0
-    while reps < 2 or (t_total < 10.0 and reps < 50):
+    while reps < 2 or (t_total < 10.0 and reps < 200):
         t0 = time.perf_counter()
         for p, (name, N, K) in enumerate(shapes):
             c, sc, z = oracle.unpack(*packed[p], N, K)
