@@ -999,6 +999,33 @@ def main():
                                   "loss_best_over_rtn": round(float(losses[int(best.item())] / losses[0]), 4),
                                   "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
                                   "pct_of_mfma_peak": round(100 * fl / (ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 2)}
+        del wsp, Ws, Xs
+        torch.cuda.empty_cache()
+
+        # steps a0 and a0' at the calibration size of configs[4] (128 sequences x 512 tokens per distinct
+        # layer input): s = mean|X|^0.5 and x / s, two buffers cycled (1 GB and more: nothing stays cached)
+        prep = {}
+        T4 = 128 * 512
+        for Kc in (4096, 11008):
+            Xc = [torch.randn((T4, Kc), device=dev, dtype=torch.float16) for _ in range(2)]
+            sc_ = torch.empty(Kc, dtype=torch.float32, device=dev)
+            yc = torch.empty_like(Xc[0])
+            for name, fn, nbytes in (("act_scale", lambda i: awq.awq_act_scale(Xc[i & 1], 0.5, out=sc_), 2 * T4 * Kc),
+                                     ("apply_inv_scale", lambda i: awq.awq_apply_inv_scale(Xc[i & 1], sc_, out=yc), 4 * T4 * Kc)):
+                for i in range(4):
+                    fn(i)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(10):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) / 10 * 1e3
+                prep[f"{name}_{T4}x{Kc}"] = {"us": round(us, 1), "GB/s": round(nbytes / us / 1e3, 1),
+                                             "pct_of_hbm_peak": round(100 * nbytes / us / 1e3 / HBM_PEAK_GBS, 2)}
+            del Xc, yc
+            torch.cuda.empty_cache()
+        extras["calibration_steps_configs4_size"] = prep
         result["extras"] = extras
 
     if args.copy_probe:

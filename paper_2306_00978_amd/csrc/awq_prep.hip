@@ -8,29 +8,54 @@
 
 namespace {
 
-constexpr int ACT_COLS = 64;     // columns per workgroup (8 lanes x 8 halves = 128 B per row)
-constexpr int ACT_PHASES = 128;  // row phases per workgroup (1024 threads)
-
-// Each workgroup owns 64 columns and walks all T rows; thread (phase, oct) sums |x|
-// of rows phase, phase+128, ... for its eight columns.  The 128 partial sums per
-// column are then added in a fixed tree order, so the result is deterministic.
-// RAW: store the (floored) mean itself instead of its power.
-template <bool RAW>
+// A workgroup (1024 threads) owns COLS columns and walks all T rows; thread (phase, oct) sums |x|
+// of rows phase, phase + PHASES, ... for its eight columns (PHASES = 1024 / (COLS / 8)).  The
+// PHASES partial sums per column are then added in a fixed tree order, so the result is
+// deterministic.  RAW: store the (floored) mean itself instead of its power.
+// COLS: 64 columns (128 B per row) give K / 64 workgroups: 172 for K = 11008 (5.2 TB/s at 65 536
+// rows) but only 64 for K = 4096, a quarter of the chip (2.1 TB/s).  Below K = 8192 a workgroup
+// therefore takes 16 columns (2.5 TB/s for K = 4096; 32 columns: 2.4); so that a 128-byte line is
+// still fetched from memory once, the workgroups are numbered so that each XCD (own L2;
+// workgroups go to the XCDs round-robin by their id) gets a contiguous range of column blocks:
+// the workgroups that share a line sit on one XCD and start one after the other.  For wide K
+// the narrow blocks are slower (K = 11008: 3.2 TB/s).  More loads in flight per thread than eight change nothing: a CU
+// alone takes in about 33 GB/s.  Splitting the rows over workgroups would need a place for partial
+// sums, which the call does not have.
+template <bool RAW, int COLS>
 __global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict__ X,
                                                          int64_t T, int64_t K, float alpha,
-                                                         float *__restrict__ s)
+                                                         float *__restrict__ s, int nblocks)
 {
+    constexpr int OCTS = COLS / 8, PHASES = 1024 / OCTS;
     // all arguments fetched in one round (otherwise one scalar-cache miss per first use)
-    asm volatile("" ::"s"(X), "s"(T), "s"(K), "s"(alpha), "s"(s));
-    __shared__ float red[ACT_PHASES][ACT_COLS];
-    const int oct = threadIdx.x & 7;
-    const int phase = threadIdx.x >> 3;
-    const int64_t col0 = (int64_t)blockIdx.x * ACT_COLS + oct * 8;
+    asm volatile("" ::"s"(X), "s"(T), "s"(K), "s"(alpha), "s"(s), "s"(nblocks));
+    __shared__ float red[PHASES][COLS];
+    const int per_xcd = (nblocks + 7) >> 3;
+    const int cb = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (cb >= nblocks) return;
+    const int oct = threadIdx.x % OCTS;
+    const int phase = threadIdx.x / OCTS;
+    const int64_t col0 = (int64_t)cb * COLS + oct * 8;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (col0 < K) {
         const int64_t K8 = K / 8;
         const uint4 *p = X + col0 / 8;
-        for (int64_t t = phase; t < T; t += ACT_PHASES) {
+        // eight rows requested before the first is added (the requests in flight per thread decide
+        // the rate of a CU); the additions keep the order of the rows
+        constexpr int AHEAD = 8;
+        int64_t t = phase;
+        for (; t + (AHEAD - 1) * PHASES < T; t += AHEAD * PHASES) {
+            uint4 raw[AHEAD];
+#pragma unroll
+            for (int a = 0; a < AHEAD; ++a) raw[a] = p[(t + a * PHASES) * K8];
+#pragma unroll
+            for (int a = 0; a < AHEAD; ++a) {
+                const half_t *h = reinterpret_cast<const half_t *>(&raw[a]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += __builtin_fabsf((float)h[e]);
+            }
+        }
+        for (; t < T; t += PHASES) {
             uint4 raw = p[t * K8];
             const half_t *h = reinterpret_cast<const half_t *>(&raw);
 #pragma unroll
@@ -40,21 +65,35 @@ __global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[phase][oct * 8 + e] = acc[e];
     __syncthreads();
-    for (int half = ACT_PHASES / 2; half >= 1; half >>= 1) {
-        for (int i = threadIdx.x; i < half * ACT_COLS; i += 1024) {
-            const int p = i / ACT_COLS, cidx = i % ACT_COLS;
+    for (int half = PHASES / 2; half >= 1; half >>= 1) {
+        for (int i = threadIdx.x; i < half * COLS; i += 1024) {
+            const int p = i / COLS, cidx = i % COLS;
             red[p][cidx] += red[p + half][cidx];
         }
         __syncthreads();
     }
-    if (threadIdx.x < ACT_COLS) {
-        const int64_t col = (int64_t)blockIdx.x * ACT_COLS + threadIdx.x;
+    if (threadIdx.x < COLS) {
+        const int64_t col = (int64_t)cb * COLS + threadIdx.x;
         if (col < K) {
             float mean = red[0][threadIdx.x] / (float)T;
             mean = fmaxf(mean, 1e-4f);
             s[col] = RAW ? mean : powf(mean, alpha);
         }
     }
+}
+
+// Column-block width by K (the same for the plain and the RAW form, whose results must agree bit
+// for bit).
+template <bool RAW>
+int act_scale_launch(const void *X_f16, int64_t T, int64_t K, float alpha, float *s, hipStream_t stream)
+{
+    const int cols = K >= 8192 ? 64 : 16;
+    const int nblocks = (int)((K + cols - 1) / cols);
+    const dim3 grid(8 * ((nblocks + 7) / 8)), block(1024);
+    const uint4 *X = (const uint4 *)X_f16;
+    if (cols == 64) act_scale_kernel<RAW, 64><<<grid, block, 0, stream>>>(X, T, K, alpha, s, nblocks);
+    else act_scale_kernel<RAW, 16><<<grid, block, 0, stream>>>(X, T, K, alpha, s, nblocks);
+    return awq_launch_status();
 }
 
 __global__ __launch_bounds__(256) void apply_inv_scale_kernel(const uint4 *__restrict__ x,
@@ -215,19 +254,14 @@ extern "C" int awq_act_scale(const void *X_f16, int64_t T, int64_t K, float alph
     if (T <= 0 || K <= 0 || (K % 8) != 0 || K > (int64_t)1 << 30) return AWQ_ERR_BAD_SHAPE;
     if (!(alpha >= 0.0f && alpha <= 1.0f)) return AWQ_ERR_BAD_ARGUMENT;
     if (!awq_aligned16(X_f16) || !awq_aligned16(s)) return AWQ_ERR_MISALIGNED;
-    const int blocks = (int)((K + ACT_COLS - 1) / ACT_COLS);
-    act_scale_kernel<false><<<dim3(blocks), dim3(1024), 0, (hipStream_t)stream>>>(
-        (const uint4 *)X_f16, T, K, alpha, s);
-    return awq_launch_status();
+    return act_scale_launch<false>(X_f16, T, K, alpha, s, (hipStream_t)stream);
 }
 
 // s_X itself: max(mean_t |X[t,k]|, 1e-4), the base of Eq. 5 (used by the scale search, which
 // raises it to every alpha of its grid).  Arguments validated by the caller.
 int awq_act_mean_launch(const void *X_f16, int64_t T, int64_t K, float *mean, hipStream_t stream)
 {
-    const int blocks = (int)((K + ACT_COLS - 1) / ACT_COLS);
-    act_scale_kernel<true><<<dim3(blocks), dim3(1024), 0, stream>>>((const uint4 *)X_f16, T, K, 1.0f, mean);
-    return awq_launch_status();
+    return act_scale_launch<true>(X_f16, T, K, 1.0f, mean, stream);
 }
 
 extern "C" int awq_apply_inv_scale(const void *x_f16, const float *s, int64_t M, int64_t K,
