@@ -574,11 +574,36 @@ def main():
                 f"one_launch_per_{span}_layers": {"launches_per_token_step": n,
                                                   "ms_per_token_step": round(e, 4),
                                                   "GB/s": gbs(bytes_m1 * span * n, e)}}
+        def on_streams(calls, reps, nst):
+            """ms per call with the calls going alternately to nst streams of default priority."""
+            cur = torch.cuda.current_stream()
+            side = [torch.cuda.Stream() for _ in range(nst)]
+            hs = [st.cuda_stream for st in side]
+            a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for timed in (False, True):
+                if timed:
+                    a.record()
+                for st in side:
+                    st.wait_stream(cur)
+                for i in range(reps):
+                    calls[i % len(calls)](hs[i % nst])
+                for st in side:
+                    cur.wait_stream(st)
+                if timed:
+                    b_.record()
+                torch.cuda.synchronize()
+            return a.elapsed_time(b_) / reps
+
         for M in (4, 16):
             w, e, n = time_decode("grouped", M, xsteps, xwarm, use_graph)
             b = step_bytes(M) * n
             extras[f"decode_m{M}_grouped"] = {"us_per_layer": round(e * 1e3 / n, 3), "GB/s": gbs(b, e),
                                               "pct_of_hbm_peak": pct(gbs(b, e))}
+            if n_streams > 1:
+                w, e, n = time_decode("grouped", M, xsteps, xwarm, False, streams=n_streams)
+                extras[f"decode_m{M}_grouped"]["alternating_over_streams"] = {
+                    "streams": n_streams, "us_per_layer": round(e * 1e3 / n, 3), "GB/s": gbs(b, e),
+                    "pct_of_hbm_peak": pct(gbs(b, e))}
         # INT3-g128 variant: the seven projections of a layer as seven launches of its decode
         # kernel, M = 1 (0.39453125 B per weight), L distinct layers cycled
         lay3 = []
@@ -732,6 +757,11 @@ def main():
             extras[f"decode_m{M70}_llama70b_layer_grouped"] = {
                 "bytes_per_launch": b70, "ms_per_launch": round(ms, 5), "GB/s": gbs(b70, ms),
                 "pct_of_hbm_peak": round(100 * gbs(b70, ms) / HBM_PEAK_GBS, 2)}
+            if n_streams > 1:
+                ms2s = on_streams(calls70, reps, n_streams)
+                extras[f"decode_m{M70}_llama70b_layer_grouped"]["alternating_over_streams"] = {
+                    "streams": n_streams, "ms_per_launch": round(ms2s, 5), "GB/s": gbs(b70, ms2s),
+                    "pct_of_hbm_peak": round(100 * gbs(b70, ms2s) / HBM_PEAK_GBS, 2)}
         del lay70
 
         M = workloads.PREFILL_M
