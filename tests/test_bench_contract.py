@@ -38,5 +38,8 @@ def test_bench_prints_one_json_line_with_the_agreed_keys():
     r = d["roofline"]
     assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-3 and "traffic" in r
+    # the step runs on two streams, the kernel's own duration (roofline) comes from the one-stream pass
+    assert d["config"]["streams"] == 2 and d["config"]["one_stream"]["GB/s"] > 0
+    assert abs(r["achieved"] - d["config"]["bytes_per_launch"] / r["avg_launch_us"] / 1e3) < 0.01 * r["achieved"]
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["unit"] == "GB/s" and c["sample"]
