@@ -1055,6 +1055,27 @@ def main():
                                              "pct_of_hbm_peak": round(100 * nbytes / us / 1e3 / HBM_PEAK_GBS, 2)}
             del Xc, yc
             torch.cuda.empty_cache()
+        # the four distinct inputs of a decoder layer (q/k/v share one, o, gate/up share one: K = 4096; down:
+        # K = 11008) in one awq_act_scale_multi call, two sets cycled
+        sets = []
+        for _ in range(2):
+            Xl = [torch.randn((T4, Kc), device=dev, dtype=torch.float16) for Kc in (4096, 4096, 4096, 11008)]
+            sets.append(awq.prepare_act_scale_multi(
+                [(X, torch.empty(X.shape[1], dtype=torch.float32, device=dev)) for X in Xl], 0.5))
+        for i in range(4):
+            sets[i & 1]()
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(10):
+            sets[i & 1]()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 10 * 1e3
+        nb = 2 * T4 * (3 * 4096 + 11008)
+        prep["act_scale_multi_one_layer_4_inputs"] = {"us": round(us, 1), "GB/s": round(nb / us / 1e3, 1),
+                                                      "pct_of_hbm_peak": round(100 * nb / us / 1e3 / HBM_PEAK_GBS, 2)}
+        del sets, Xl
+        torch.cuda.empty_cache()
         extras["calibration_steps_configs4_size"] = prep
         result["extras"] = extras
 

@@ -95,6 +95,20 @@ int awq_packed_sizes(int64_t N, int64_t K, int group, size_t *qweight_bytes,
 int awq_act_scale(const void *X_f16, int64_t T, int64_t K, float alpha, float *s,
                   void *stream);
 
+/* The same computation for up to AWQ_ACT_SCALE_MULTI_MAX matrices in one call (16 per launch),
+ * each result bit for bit that of awq_act_scale on its own.  The sums are per column, so a
+ * launch has K / 64 workgroups per matrix: one matrix of K = 4096 occupies a quarter of the
+ * chip, the four distinct inputs of a decoder layer (Sec. 3.2 calibrates every linear on its own
+ * input) fill it.  The matrices may differ in T and K; outputs must not overlap.  `descs` is a
+ * HOST array, read before the call returns. */
+typedef struct awq_act_scale_desc {
+    const void *X_f16;     /* [T,K] fp16 row-major, device */
+    int64_t T, K;
+    float *s;              /* [K] fp32, device, written */
+} awq_act_scale_desc;
+#define AWQ_ACT_SCALE_MULTI_MAX 64
+int awq_act_scale_multi(const awq_act_scale_desc *descs, int count, float alpha, void *stream);
+
 /* Sec. 3.2, Eq. 4: the diag(s)^-1 X factor, applied once by the producer of x:
  * xs[m,k] = fp16(fp32(x[m,k]) / s[k]) (correctly rounded).  x, xs [M,K] fp16
  * (device; xs may alias x), s [K] fp32 (device).  K % 8 == 0. */

@@ -41,6 +41,7 @@ EXPORTS = [
     "awq_w2a16_linear_multi",
     "awq_last_grouped_plan", "awq_static_scratch_bytes", "awq_w4a16_linear_static",
     "awq_quantize_pack_multi", "awq_w4a16_linear_chain", "awq_blob_header_init", "awq_blob_header_check",
+    "awq_act_scale_multi",
 ]
 MULTI_MAX = 56
 
@@ -82,6 +83,14 @@ class QuantizeDesc(ctypes.Structure):
 
 
 QUANTIZE_MULTI_MAX = 64
+
+
+class ActScaleDesc(ctypes.Structure):
+    """awq_act_scale_desc of the C ABI."""
+    _fields_ = [("X_f16", ctypes.c_void_p), ("T", ctypes.c_int64), ("K", ctypes.c_int64), ("s", ctypes.c_void_p)]
+
+
+ACT_SCALE_MULTI_MAX = 64
 
 
 class FusedDesc(ctypes.Structure):
@@ -160,6 +169,8 @@ def load() -> ctypes.CDLL:
     lib.awq_w3a16_linear_prefill.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
     lib.awq_last_grouped_plan.restype = i32
     lib.awq_last_grouped_plan.argtypes = []
+    lib.awq_act_scale_multi.restype = i32
+    lib.awq_act_scale_multi.argtypes = [ctypes.POINTER(ActScaleDesc), i32, ctypes.c_float, vp]
     lib.awq_quantize_pack_multi.restype = i32
     lib.awq_quantize_pack_multi.argtypes = [ctypes.POINTER(QuantizeDesc), i32, i32, vp]
     lib.awq_blob_header_init.restype = i32
@@ -241,6 +252,37 @@ def awq_act_scale(X: torch.Tensor, alpha: float = 0.5, out: torch.Tensor | None 
     _dev(s, torch.float32, "s")
     _check(load().awq_act_scale(_ptr(X), T, K, float(alpha), _ptr(s), _stream()), "awq_act_scale")
     return s
+
+
+def prepare_act_scale_multi(matrices, alpha: float = 0.5):
+    """Marshal one awq_act_scale_multi call.  `matrices` is a list of (X [T,K] fp16, s [K] fp32);
+    returns a zero-argument callable that enqueues the call on the then-current stream."""
+    if not 1 <= len(matrices) <= ACT_SCALE_MULTI_MAX:
+        raise ValueError(f"1..{ACT_SCALE_MULTI_MAX} matrices per call")
+    descs = (ActScaleDesc * len(matrices))()
+    for i, (X, s) in enumerate(matrices):
+        _dev(X, torch.float16, "X")
+        _dev(s, torch.float32, "s")
+        T, K = X.shape
+        if s.numel() != K:
+            raise ValueError("s must have K elements")
+        descs[i] = ActScaleDesc(X.data_ptr(), T, K, s.data_ptr())
+    fn = load().awq_act_scale_multi
+    count = len(matrices)
+    keep = list(matrices)
+
+    def call(_keep=keep):
+        st = fn(descs, count, float(alpha), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != 0:
+            raise AwqError(st, "awq_act_scale_multi")
+    return call
+
+
+def awq_act_scale_multi(Xs, alpha: float = 0.5):
+    """[X, ...] -> [s, ...]: awq_act_scale of every matrix in one call of the library."""
+    full = [(X, torch.empty(X.shape[1], dtype=torch.float32, device=X.device)) for X in Xs]
+    prepare_act_scale_multi(full, alpha)()
+    return [m[1] for m in full]
 
 
 def awq_apply_inv_scale(x: torch.Tensor, s: torch.Tensor, out: torch.Tensor | None = None):

@@ -6,48 +6,64 @@
 // activations.  Both are plain streaming passes over X (HBM-bound).
 #include "awq_common.h"
 
+#include <algorithm>
+
 namespace {
 
-// A workgroup (1024 threads) owns COLS columns and walks all T rows; thread (phase, oct) sums |x|
-// of rows phase, phase + PHASES, ... for its eight columns (PHASES = 1024 / (COLS / 8)).  The
-// PHASES partial sums per column are then added in a fixed tree order, so the result is
-// deterministic.  RAW: store the (floored) mean itself instead of its power.
-// COLS: 64 columns (128 B per row) give K / 64 workgroups: 172 for K = 11008 (5.2 TB/s at 65 536
-// rows) but only 64 for K = 4096, a quarter of the chip (2.1 TB/s).  Below K = 8192 a workgroup
-// therefore takes 16 columns (2.5 TB/s for K = 4096; 32 columns: 2.4); so that a 128-byte line is
-// still fetched from memory once, the workgroups are numbered so that each XCD (own L2;
-// workgroups go to the XCDs round-robin by their id) gets a contiguous range of column blocks:
-// the workgroups that share a line sit on one XCD and start one after the other.  For wide K
-// the narrow blocks are slower (K = 11008: 3.2 TB/s).  More loads in flight per thread than eight change nothing: a CU
-// alone takes in about 33 GB/s.  Splitting the rows over workgroups would need a place for partial
-// sums, which the call does not have.
-template <bool RAW, int COLS>
-__global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict__ X,
-                                                         int64_t T, int64_t K, float alpha,
-                                                         float *__restrict__ s, int nblocks)
+constexpr int ACT_COLS = 64;     // columns per workgroup (8 lanes x 8 halves = one 128-byte line per row)
+constexpr int ACT_PHASES = 128;  // row phases per workgroup (1024 threads)
+constexpr int ACT_MAX = 16;      // matrices per launch
+
+struct ActProblem {
+    const uint4 *X;
+    float *s;
+    int64_t T, K;
+    int wg_begin, pad;
+};
+struct ActArgs {
+    ActProblem p[ACT_MAX];
+    int count;
+    float alpha;
+};
+
+// Up to 16 matrices per launch.  A workgroup (1024 threads) owns 64 columns of one matrix and walks
+// all its T rows; thread (phase, oct) sums |x| of rows phase, phase + 128, ... for its eight
+// columns.  The 128 partial sums per column are then added in a fixed tree order, so the result is
+// deterministic and does not depend on what else the launch holds.  RAW: store the (floored) mean
+// itself instead of its power.
+// The sums are per column, so the workgroups divide the columns, and a matrix gives K / 64 of
+// them: 172 for K = 11008 (5.2 TB/s at 65 536 rows) but 64 for K = 4096, a quarter of the chip --
+// a CU alone takes in about 33 GB/s whatever the number of loads in flight (2.1-2.2 TB/s).
+// Narrower column blocks (16 columns, the workgroups that share a 128-byte line on one XCD) reach
+// 2.5 TB/s for K = 4096 and are slower for wide K; dividing the rows over workgroups would need
+// a place for partial sums, which the call does not have.  What fills the chip is several
+// matrices per launch (awq_act_scale_multi): a decoder layer has four distinct inputs to calibrate.
+template <bool RAW>
+__global__ __launch_bounds__(1024) void act_scale_kernel(const ActArgs A)
 {
-    constexpr int OCTS = COLS / 8, PHASES = 1024 / OCTS;
-    // all arguments fetched in one round (otherwise one scalar-cache miss per first use)
-    asm volatile("" ::"s"(X), "s"(T), "s"(K), "s"(alpha), "s"(s), "s"(nblocks));
-    __shared__ float red[PHASES][COLS];
-    const int per_xcd = (nblocks + 7) >> 3;
-    const int cb = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (cb >= nblocks) return;
-    const int oct = threadIdx.x % OCTS;
-    const int phase = threadIdx.x / OCTS;
-    const int64_t col0 = (int64_t)cb * COLS + oct * 8;
+    __shared__ float red[ACT_PHASES][ACT_COLS];
+    int pi = 0;
+    for (int i = 1; i < A.count; ++i)
+        if ((int)blockIdx.x >= A.p[i].wg_begin) pi = i;
+    const uint4 *__restrict__ X = A.p[pi].X;
+    float *__restrict__ s = A.p[pi].s;
+    const int64_t T = A.p[pi].T, K = A.p[pi].K;
+    const int cb = (int)blockIdx.x - A.p[pi].wg_begin;
+    const float alpha = A.alpha;
+    const int oct = threadIdx.x & 7;
+    const int phase = threadIdx.x >> 3;
+    const int64_t col0 = (int64_t)cb * ACT_COLS + oct * 8;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (col0 < K) {
         const int64_t K8 = K / 8;
         const uint4 *p = X + col0 / 8;
-        // eight rows requested before the first is added (the requests in flight per thread decide
-        // the rate of a CU); the additions keep the order of the rows
+        // eight rows requested before the first is added; the additions keep the order of the rows
         constexpr int AHEAD = 8;
         int64_t t = phase;
-        for (; t + (AHEAD - 1) * PHASES < T; t += AHEAD * PHASES) {
+        for (; t + (AHEAD - 1) * ACT_PHASES < T; t += AHEAD * ACT_PHASES) {
             uint4 raw[AHEAD];
 #pragma unroll
-            for (int a = 0; a < AHEAD; ++a) raw[a] = p[(t + a * PHASES) * K8];
+            for (int a = 0; a < AHEAD; ++a) raw[a] = p[(t + a * ACT_PHASES) * K8];
 #pragma unroll
             for (int a = 0; a < AHEAD; ++a) {
                 const half_t *h = reinterpret_cast<const half_t *>(&raw[a]);
@@ -55,7 +71,7 @@ __global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict
                 for (int e = 0; e < 8; ++e) acc[e] += __builtin_fabsf((float)h[e]);
             }
         }
-        for (; t < T; t += PHASES) {
+        for (; t < T; t += ACT_PHASES) {
             uint4 raw = p[t * K8];
             const half_t *h = reinterpret_cast<const half_t *>(&raw);
 #pragma unroll
@@ -65,15 +81,15 @@ __global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[phase][oct * 8 + e] = acc[e];
     __syncthreads();
-    for (int half = PHASES / 2; half >= 1; half >>= 1) {
-        for (int i = threadIdx.x; i < half * COLS; i += 1024) {
-            const int p = i / COLS, cidx = i % COLS;
+    for (int half = ACT_PHASES / 2; half >= 1; half >>= 1) {
+        for (int i = threadIdx.x; i < half * ACT_COLS; i += 1024) {
+            const int p = i / ACT_COLS, cidx = i % ACT_COLS;
             red[p][cidx] += red[p + half][cidx];
         }
         __syncthreads();
     }
-    if (threadIdx.x < COLS) {
-        const int64_t col = (int64_t)cb * COLS + threadIdx.x;
+    if (threadIdx.x < ACT_COLS) {
+        const int64_t col = (int64_t)cb * ACT_COLS + threadIdx.x;
         if (col < K) {
             float mean = red[0][threadIdx.x] / (float)T;
             mean = fmaxf(mean, 1e-4f);
@@ -82,18 +98,28 @@ __global__ __launch_bounds__(1024) void act_scale_kernel(const uint4 *__restrict
     }
 }
 
-// Column-block width by K (the same for the plain and the RAW form, whose results must agree bit
-// for bit).
 template <bool RAW>
-int act_scale_launch(const void *X_f16, int64_t T, int64_t K, float alpha, float *s, hipStream_t stream)
+int act_scale_launch(const ActProblem *probs, int count, float alpha, hipStream_t stream)
 {
-    const int cols = K >= 8192 ? 64 : 16;
-    const int nblocks = (int)((K + cols - 1) / cols);
-    const dim3 grid(8 * ((nblocks + 7) / 8)), block(1024);
-    const uint4 *X = (const uint4 *)X_f16;
-    if (cols == 64) act_scale_kernel<RAW, 64><<<grid, block, 0, stream>>>(X, T, K, alpha, s, nblocks);
-    else act_scale_kernel<RAW, 16><<<grid, block, 0, stream>>>(X, T, K, alpha, s, nblocks);
+    ActArgs A = {};
+    int wg = 0;
+    for (int i = 0; i < count; ++i) {
+        A.p[i] = probs[i];
+        A.p[i].wg_begin = wg;
+        wg += (int)((probs[i].K + ACT_COLS - 1) / ACT_COLS);
+    }
+    A.count = count;
+    A.alpha = alpha;
+    act_scale_kernel<RAW><<<dim3(wg), dim3(1024), 0, stream>>>(A);
     return awq_launch_status();
+}
+
+int act_scale_check(const void *X_f16, int64_t T, int64_t K, const float *s)
+{
+    if (!X_f16 || !s) return AWQ_ERR_NULL_POINTER;
+    if (T <= 0 || K <= 0 || (K % 8) != 0 || K > (int64_t)1 << 30) return AWQ_ERR_BAD_SHAPE;
+    if (!awq_aligned16(X_f16) || !awq_aligned16(s)) return AWQ_ERR_MISALIGNED;
+    return AWQ_OK;
 }
 
 __global__ __launch_bounds__(256) void apply_inv_scale_kernel(const uint4 *__restrict__ x,
@@ -250,18 +276,40 @@ extern "C" int awq_rmsnorm_inv_scale(const void *x_f16, const void *gamma_f16, c
 extern "C" int awq_act_scale(const void *X_f16, int64_t T, int64_t K, float alpha, float *s,
                              void *stream)
 {
-    if (!X_f16 || !s) return AWQ_ERR_NULL_POINTER;
-    if (T <= 0 || K <= 0 || (K % 8) != 0 || K > (int64_t)1 << 30) return AWQ_ERR_BAD_SHAPE;
+    const int st = act_scale_check(X_f16, T, K, s);
+    if (st != AWQ_OK) return st;
     if (!(alpha >= 0.0f && alpha <= 1.0f)) return AWQ_ERR_BAD_ARGUMENT;
-    if (!awq_aligned16(X_f16) || !awq_aligned16(s)) return AWQ_ERR_MISALIGNED;
-    return act_scale_launch<false>(X_f16, T, K, alpha, s, (hipStream_t)stream);
+    const ActProblem p = {(const uint4 *)X_f16, s, T, K, 0, 0};
+    return act_scale_launch<false>(&p, 1, alpha, (hipStream_t)stream);
+}
+
+extern "C" int awq_act_scale_multi(const awq_act_scale_desc *descs, int count, float alpha, void *stream)
+{
+    if (!descs) return AWQ_ERR_NULL_POINTER;
+    if (count < 1 || count > AWQ_ACT_SCALE_MULTI_MAX) return AWQ_ERR_BAD_ARGUMENT;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return AWQ_ERR_BAD_ARGUMENT;
+    static_assert(AWQ_ACT_SCALE_MULTI_MAX % ACT_MAX == 0, "whole launches");
+    for (int i = 0; i < count; ++i) {
+        const int st = act_scale_check(descs[i].X_f16, descs[i].T, descs[i].K, descs[i].s);
+        if (st != AWQ_OK) return st;
+    }
+    for (int first = 0; first < count; first += ACT_MAX) {
+        ActProblem p[ACT_MAX];
+        const int n = std::min(ACT_MAX, count - first);
+        for (int i = 0; i < n; ++i)
+            p[i] = {(const uint4 *)descs[first + i].X_f16, descs[first + i].s, descs[first + i].T, descs[first + i].K, 0, 0};
+        const int st = act_scale_launch<false>(p, n, alpha, (hipStream_t)stream);
+        if (st != AWQ_OK) return st;
+    }
+    return AWQ_OK;
 }
 
 // s_X itself: max(mean_t |X[t,k]|, 1e-4), the base of Eq. 5 (used by the scale search, which
 // raises it to every alpha of its grid).  Arguments validated by the caller.
 int awq_act_mean_launch(const void *X_f16, int64_t T, int64_t K, float *mean, hipStream_t stream)
 {
-    return act_scale_launch<true>(X_f16, T, K, 1.0f, mean, stream);
+    const ActProblem p = {(const uint4 *)X_f16, mean, T, K, 0, 0};
+    return act_scale_launch<true>(&p, 1, 1.0f, stream);
 }
 
 extern "C" int awq_apply_inv_scale(const void *x_f16, const float *s, int64_t M, int64_t K,

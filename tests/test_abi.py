@@ -144,6 +144,23 @@ def test_grouped_and_search_calls_validate_before_any_launch(lib):
     assert qm(qdescs(3, s=odd), 3, 128, None) == -4
     assert qm(qdescs(3, W_f16=odd), 3, 128, None) == -4
 
+    def adescs(n, **kw):
+        arr = (awq.ActScaleDesc * max(n, 1))()
+        for i in range(n):
+            d = dict(X_f16=ok, T=64, K=128, s=ok)
+            d.update(kw)
+            arr[i] = awq.ActScaleDesc(**d)
+        return arr
+    am = lib.awq_act_scale_multi
+    assert am(None, 1, 0.5, None) == -1
+    assert am(adescs(1), 0, 0.5, None) == -7
+    assert am(adescs(1), awq.ACT_SCALE_MULTI_MAX + 1, 0.5, None) == -7
+    assert am(adescs(2), 2, 1.5, None) == -7
+    assert am(adescs(2, s=None), 2, 0.5, None) == -1
+    assert am(adescs(2, K=100), 2, 0.5, None) == -2
+    assert am(adescs(2, T=0), 2, 0.5, None) == -2
+    assert am(adescs(2, X_f16=odd), 2, 0.5, None) == -4
+
     def fdescs(n, **kw):
         arr = (awq.FusedDesc * max(n, 1))()
         for i in range(n):

@@ -704,6 +704,33 @@ def test_act_scale_and_inverse_scale(awq, T, K):
     assert np.array_equal(xs_gpu.view(np.uint16), xs_ref.view(np.uint16))
 
 
+def test_act_scale_multi_equals_the_single_calls_and_the_oracle(awq):
+    """awq_act_scale_multi: matrices of different T and K in one call (more than one launch's
+    worth: 19 = 16 + 3), every result bit for bit that of awq_act_scale on the same matrix and
+    within the tolerance of the oracle; nothing written around the outputs."""
+    import torch
+    import oracle
+    g = np.random.default_rng(99)
+    shapes = [(64, 4096), (5, 136), (300, 11008), (1, 8), (2048, 512), (17, 1408), (129, 64)] * 3
+    shapes = shapes[:19]
+    Xs, outs, guards = [], [], []
+    for T, K in shapes:
+        Xs.append((g.standard_normal((T, K)) * g.uniform(0.01, 30.0)).astype(np.float16))
+        whole = torch.full((K + 128,), -3.0, dtype=torch.float32, device="cuda")
+        guards.append(whole)
+        outs.append(whole[64:64 + K])
+    dX = [dev(X) for X in Xs]
+    for alpha in (0.5, 0.0, 0.35):
+        awq.prepare_act_scale_multi(list(zip(dX, outs)), alpha)()
+        torch.cuda.synchronize()
+        for X, dx, s_multi, whole in zip(Xs, dX, outs, guards):
+            s_one = awq.awq_act_scale(dx, alpha)
+            assert torch.equal(s_one.view(torch.int32), s_multi.view(torch.int32))
+            s_ref = oracle.act_scale(X, alpha)
+            assert np.abs(host(s_multi).astype(np.float64) / s_ref - 1.0).max() <= 2e-6
+            assert bool((whole[:64] == -3.0).all()) and bool((whole[64 + X.shape[1]:] == -3.0).all())
+
+
 # ------------------------------------------------------------------- weight clipping
 
 CLIP_RATIOS = [1.0 - 0.05 * i for i in range(11)]

@@ -125,6 +125,13 @@ def test_fused_chain_and_quantize_tables(awq):
     st = lib.awq_w4a16_linear_chain(stages, 4, ctypes.c_int64(M), 128, addr.take(8192), 0, None)
     assert st == AWQ_ERR_HIP, st
 
+    ad = (awq.ActScaleDesc * 64)()
+    for i in range(64):
+        T, K = [(65536, 4096), (64, 11008), (5, 136), (1, 8)][i % 4]
+        ad[i] = awq.ActScaleDesc(addr.take(2 * T * K), T, K, addr.take(4 * K))
+    for count in (1, 4, 16, 17, 64):
+        assert lib.awq_act_scale_multi(ad, count, 0.5, None) == AWQ_ERR_HIP
+
     qd = (awq.QuantizeDesc * 64)()
     for i in range(64):
         N, K = (SHAPES_7B + RAGGED)[i % 19]
