@@ -250,7 +250,9 @@ typedef struct awq_linear_desc {
 
 /* Sec. 4.2 (kernel fusion: several projections in one kernel, because a decode
  * kernel is about as short as a launch): the same computation as `count` calls of
- * awq_w4a16_linear with the same M <= 16, in ONE kernel launch.  The linears are
+ * awq_w4a16_linear with the same M <= 16, in ONE kernel launch (up to four tokens a linear whose
+ * K is too long for the register-resident activations takes a launch of its own; from five
+ * tokens on the activations go through LDS and any K is in the one launch).  The linears are
  * independent (none may read another's output; outputs must not overlap); they may
  * share x (Q/K/V, gate/up) or not.  `descs` is a HOST array of 1..AWQ_MULTI_MAX
  * entries, read before the call returns.  Workspace as for awq_w4a16_linear
