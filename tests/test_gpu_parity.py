@@ -406,6 +406,7 @@ def test_multi_single_entry_and_limits(awq, small_group):
     import torch
     check_multi(awq, small_group[:1], 3)
     check_multi(awq, small_group * 14, 2)                    # 56 entries: the maximum
+    check_multi(awq, small_group * 14, 9)                    # ... through the kernel for more than four tokens
     xs, Wdq, gpu, N = small_group[0]
     y = torch.empty((17, N), dtype=torch.float16, device="cuda")
     with pytest.raises(awq.AwqError) as e:                   # M > 16 is not a decode call
