@@ -536,12 +536,43 @@ def main():
             tot_fl += fl
             tot_ms += ms
             del y
+        # reference point, not part of the path: the vendor library's dense fp16 product (torch.matmul,
+        # weights already fp16, nothing to dequantize) on the same shapes, the same activations and
+        # weights of the same distribution, several matrices cycled
+        dense = {}
+        d_fl, d_ms = 0, 0.0
+        try:
+            for p in (0, 4, 6):
+                name, N, K = shapes[p]
+                Wd = [(torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
+                       * workloads.SIGMA_7B).to(torch.float16) for _ in range(8)]
+                yd = torch.empty((M, N), dtype=torch.float16, device=dev)
+                for i in range(100):
+                    torch.matmul(x_by_k[K], Wd[i % 8].t(), out=yd)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(40):
+                    torch.matmul(x_by_k[K], Wd[i % 8].t(), out=yd)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / 40
+                fl = workloads.flops(M, N, K)
+                dense[f"{N}x{K}"] = {"us": round(ms * 1e3, 2), "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1)}
+                d_fl += fl
+                d_ms += ms
+                del Wd, yd
+            dense["TFLOP/s"] = round(d_fl / (d_ms * 1e-3) / 1e12, 1)
+            dense["what"] = "torch.matmul fp16 (the vendor library's dense kernel) on the same shapes and activations"
+        except Exception as exc:                               # a reference only: never fails the run
+            dense = {"unavailable": str(exc)[:200]}
+        torch.cuda.empty_cache()
         tf = tot_fl / (tot_ms * 1e-3) / 1e12
         result["roofline"]["prefill"] = {
             "kernel": "gemm_kernel (prefill, M=2048, configs[2]: 4096x4096, 11008x4096, 4096x11008)",
             "bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4), "flops": tot_fl,
-            "avg_launch_us": round(tot_ms * 1e3 / 3, 2), "shapes": pre}
+            "avg_launch_us": round(tot_ms * 1e3 / 3, 2), "shapes": pre,
+            "dense_fp16_reference": dense}
         result["config"]["prefill_m2048_TFLOP/s"] = round(tf, 1)
         result["config"]["prefill_pct_of_mfma_peak"] = round(100 * tf / MFMA_F16_PEAK_TFLOPS, 2)
     result["config"]["clocks_after_run"] = clocks()
