@@ -460,6 +460,38 @@ def main():
             "alternating_over_streams": {"streams": max(2, args.streams), "us_per_layer": round(e2s * 1e3 / L, 2),
                                          "GB/s": gbs(bytes_step, e2s), "pct_of_hbm_peak": pct(gbs(bytes_step, e2s))},
             "graph_replay": {"us_per_layer": round(eg_ * 1e3 / L, 2), "GB/s": gbs(bytes_step, eg_), "pct_of_hbm_peak": pct(gbs(bytes_step, eg_))}}
+        # reference point, not part of the path: the same layer in fp16 through the vendor library (seven
+        # torch.matmul calls per layer on unquantized weights of the same shapes, four layers cycled:
+        # 1.6 GB, nothing stays cached) -- what Sec. 4.2 measures W4A16 against
+        try:
+            Wf = [[(torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
+                    * workloads.SIGMA_7B).to(torch.float16) for _, N, K in shapes] for _ in range(4)]
+            yf = [torch.empty((1, N), dtype=torch.float16, device=dev) for _, N, K in shapes]
+            xf = [x_by_k[K][:1] for _, N, K in shapes]
+
+            def dense_layer(l):
+                for p in range(len(shapes)):
+                    torch.matmul(xf[p], Wf[l & 3][p].t(), out=yf[p])
+            for l in range(16):
+                dense_layer(l)
+            torch.cuda.synchronize()
+            ef0, ef1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ef0.record()
+            for l in range(64):
+                dense_layer(l)
+            ef1.record()
+            torch.cuda.synchronize()
+            usf = ef0.elapsed_time(ef1) / 64 * 1e3
+            fp16_bytes = sum(2 * N * K + 2 * K + 2 * N for _, N, K in shapes)
+            result["config"]["fp16_dense_reference"] = {
+                "what": "the same layer unquantized: seven torch.matmul calls (fp16 weights, M=1) per layer, one stream",
+                "us_per_layer": round(usf, 2), "fp16_bytes_per_layer": fp16_bytes,
+                "GB/s_of_fp16_bytes": round(fp16_bytes / usf / 1e3, 1),
+                "grouped_w4a16_launch_speedup": round(usf / kernel_us, 2)}
+            del Wf, yf, xf
+        except Exception as exc:                               # a reference only: never fails the run
+            result["config"]["fp16_dense_reference"] = {"unavailable": str(exc)[:200]}
+        torch.cuda.empty_cache()
         w, e, n = time_decode("fused", 1, msteps, mwarm, True)
         result["config"]["dependent_launch_mode"] = {
             "what": "Q,K,V in one launch | o | gate,up in one launch | down: the four launches a decoder's "
